@@ -1,0 +1,218 @@
+/*
+ * earl_dispatch.h - C ABI of the MI355X (gfx950) re-layout library for intermediate RL rollout
+ * batches: the on-device part of the paper's Data Dispatcher (Section 2, "Data Dispatcher").
+ *
+ * The paper states the operation as "plan, then move": the dispatcher looks at the current data
+ * layout and at the parallelism configuration of the consumer, decides which worker needs which
+ * part of every sequence, and sends each part straight from where it was computed to where it is
+ * needed (an all-to-all), instead of gathering the whole batch on one node and scattering it.
+ * The two calls of this library are those two halves:
+ *
+ *   earl_plan_build(lengths, src_layout, dst_layout)   who reads what from where, and where it lands
+ *   earl_dispatch(fields, plan)                        materialise every destination shard
+ *
+ * The batch (Section 1) is a set of per-token tensors ("fields": token ids, masks, log-probabilities,
+ * advantages, auxiliary vectors) over N ragged sequences.  One GPU materialises all D*C destination
+ * shards in its own HBM.
+ *
+ * Conventions for every function:
+ *   - returns an earl_status (int32); never throws, never aborts;
+ *   - "device" pointers are HIP device pointers on the current device, "host" pointers are ordinary
+ *     host memory; the caller owns every buffer it passes; the library allocates no device memory;
+ *   - work is enqueued on the HIP stream passed as `void* hip_stream` (a hipStream_t; NULL = the
+ *     default stream); device buffers must stay valid until that work has finished;
+ *   - calls on the same plan must come from one thread at a time.
+ */
+#ifndef EARL_DISPATCH_H_
+#define EARL_DISPATCH_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  EARL_OK = 0,
+  EARL_INVALID_ARG = 1,        /* null pointer, size out of range, misaligned buffer, L[i] < 1,
+                                  seq_group out of range (the last two are found on the device and
+                                  reported by earl_plan_get_summary / earl_dispatch)              */
+  EARL_SEQ_EXCEEDS_BUDGET = 2, /* some padded sequence is longer than mb_token_budget            */
+  EARL_CAPACITY = 3,           /* workspace or a destination/source buffer is too small          */
+  EARL_HIP_ERROR = 4           /* a HIP runtime call failed; see earl_last_error_message()       */
+} earl_status;
+
+/* Limits (EARL_INVALID_ARG beyond them). */
+#define EARL_MAX_SEQS (1 << 20)       /* N                                   */
+#define EARL_MAX_DP 1024              /* D                                   */
+#define EARL_MAX_SP 64                /* C                                   */
+#define EARL_MAX_SRC_SHARDS 4096      /* S = G*R                             */
+#define EARL_MAX_FIELDS 32            /* fields per earl_dispatch call       */
+#define EARL_MAX_ROW_BYTES (1 << 20)  /* scalar_bytes * width                */
+
+/*
+ * Where the batch lives now ("current data distribution layout", Section 2).  The N sequences are
+ * stored in G groups; group g exists as R identical replicas (e.g. the R tensor-parallel workers of
+ * one rollout engine all hold its outputs), i.e. S = G*R shard buffers per field, replica t of group
+ * g being shard g*R + t.
+ *   seq_group  device int32[N], group holding sequence i; NULL = groups own equal contiguous index
+ *              ranges, g = floor(i*G/N).
+ *   seq_row    device int64[N], first row of sequence i inside its group's buffers; NULL = the
+ *              group's sequences are packed in index order (the library computes the offsets by a
+ *              segmented prefix scan of the lengths).
+ * The plan reads the k-th of a group's n sequences from replica floor(k*R/n), so every row is read
+ * once and each replica serves one contiguous share.
+ */
+typedef struct {
+  int32_t n_groups;     /* G >= 1 */
+  int32_t replication;  /* R >= 1 */
+  const int32_t* seq_group;
+  const int64_t* seq_row;
+} earl_src_layout;
+
+/*
+ * Where the batch has to go ("parallelism configuration", Section 2): dp data-parallel ranks, each
+ * split over sp sequence-parallel ranks; destination shard q = r*sp + c.
+ *   zigzag            1: a sequence is cut into 2*sp chunks and SP rank c holds chunks c and
+ *                     2*sp-1-c (equal causal-attention work); 0: sp contiguous chunks.
+ *   pad_multiple      every chunk is padded to a multiple of this many rows (>= 1).
+ *   balance_policy    0 = longest-first list scheduling on padded lengths (the only policy).
+ *   mb_token_budget   a micro-batch holds whole sequences whose padded lengths sum to at most this.
+ */
+typedef struct {
+  int32_t dp, sp, zigzag, pad_multiple, balance_policy;
+  int64_t mb_token_budget;
+} earl_dst_layout;
+
+/*
+ * One field: `width` scalars of `scalar_bytes` (1, 2, 4 or 8) bytes per token, row-major, rows
+ * contiguous.  All pointer arrays are HOST arrays of DEVICE pointers.
+ *   pad_scalar          padding rows are filled with `width` copies of its low scalar_bytes bytes.
+ *   src_shard_ptrs[S]   shard buffers in the source layout (aligned to scalar_bytes).  A pointer may
+ *                       be NULL if the plan reads no row from that shard.
+ *   dst_shard_ptrs[D*C] destination shards (16-byte aligned; NULL allowed for a shard of 0 rows).
+ *   dst_capacity_rows   rows each destination buffer can hold; EARL_CAPACITY if fewer than needed.
+ *   src_capacity_rows   rows each source buffer holds, or NULL to skip the check.
+ * Source and destination buffers must not overlap.
+ */
+typedef struct {
+  int32_t scalar_bytes;
+  int32_t width;
+  uint64_t pad_scalar;
+  const void* const* src_shard_ptrs;
+  void* const* dst_shard_ptrs;
+  const int64_t* dst_capacity_rows;
+  const int64_t* src_capacity_rows;
+} earl_field;
+
+typedef struct earl_plan earl_plan; /* host object owned by the library */
+
+/*
+ * Host copy of the plan's totals.  The arrays belong to the plan and stay valid until
+ * earl_plan_destroy.  Flat-array sizes are needed to size the buffers of earl_plan_export.
+ */
+typedef struct {
+  int32_t n_seqs, n_src_shards, n_dst_shards, chunks_per_seq; /* N, S, D*C, K               */
+  int32_t n_segments;        /* N*K                                                          */
+  int32_t n_mb_max;          /* largest micro-batch count over DP ranks                      */
+  int32_t cu_seqlens_len;    /* N + sum n_mb                                                 */
+  int32_t mb_table_len;      /* sum (n_mb + 1)                                               */
+  int64_t total_real_rows, total_dst_rows;
+  int64_t rank_load_min, rank_load_max;  /* padded tokens on the least / most loaded DP rank */
+  const int64_t* shard_rows;       /* [D*C] rows of every destination shard                  */
+  const int64_t* src_rows_needed;  /* [S]   rows every source shard buffer must hold         */
+  const int32_t* n_seq;            /* [D]   sequences per DP rank                            */
+  const int32_t* n_mb;             /* [D]   micro-batches per DP rank                        */
+  const int64_t* rank_load;        /* [D]   padded tokens per DP rank                        */
+  const int64_t* a2a_counts;       /* [S][D*C] real rows read from shard s for shard q: the split
+                                      sizes of the all-to-all of Section 2                     */
+} earl_plan_summary;
+
+/* Bytes of device workspace earl_plan_build needs for n_seqs sequences and these layouts. */
+int32_t earl_plan_workspace_bytes(int32_t n_seqs, const earl_src_layout* src,
+                                  const earl_dst_layout* dst, size_t* out_bytes);
+
+/*
+ * Computes the dispatch plan on the device (asynchronously on the stream):
+ *   source row offsets (segmented scan of lengths per group) and the replica each sequence is read
+ *   from; chunk length m = P*ceil(ceil(L/K)/P) with K = 2*sp (zigzag, sp > 1) or sp, padded length
+ *   K*m; longest-first assignment of sequences to DP ranks (ties: lower index, lower rank);
+ *   ascending-index order inside a rank; next-fit micro-batches under the budget; destination row
+ *   offsets; one segment per (sequence, chunk); a2a_counts; cu_seqlens.
+ * lengths_dev: device int32[n_seqs].  workspace_dev: device memory, 256-byte aligned, at least
+ * earl_plan_workspace_bytes() bytes, owned by the caller and in use until earl_plan_destroy (and
+ * until all dispatches of the plan have finished).  *out_plan receives the new plan on EARL_OK.
+ * Errors in the data itself (a length < 1, a group out of range, a sequence over the budget) are
+ * found on the device and reported by the first earl_plan_get_summary / earl_dispatch.
+ */
+int32_t earl_plan_build(const int32_t* lengths_dev, int32_t n_seqs, const earl_src_layout* src,
+                        const earl_dst_layout* dst, void* workspace_dev, size_t workspace_bytes,
+                        void* hip_stream, earl_plan** out_plan);
+
+/* Waits for the plan on its stream (once per plan), copies the totals to the host and returns the
+ * plan's status (EARL_OK, EARL_INVALID_ARG, EARL_SEQ_EXCEEDS_BUDGET, EARL_HIP_ERROR). */
+int32_t earl_plan_get_summary(earl_plan* plan, earl_plan_summary* out);
+
+/*
+ * Copies per-sequence and per-rank plan arrays to HOST buffers (any pointer may be NULL to skip).
+ * Indexed by sequence i, length N: rank, slot (position inside its rank), mb (micro-batch inside
+ * its rank), dst_row (first row in every shard of its rank), seq_shard (shard buffer it is read
+ * from), seq_row (first source row).  seq_ids[N]: sequences of rank 0 in packing order, then rank
+ * 1, ...  mb_seq_start / mb_row_start [mb_table_len]: per rank n_mb+1 entries, slot index / shard
+ * row at which each micro-batch starts, closed by n_seq / shard rows.  cu_seqlens
+ * [cu_seqlens_len]: per rank, per micro-batch, the n+1 cumulative LOCAL row counts (rows on one SP
+ * rank), restarting at 0 in every micro-batch.
+ */
+int32_t earl_plan_export(earl_plan* plan, int32_t* rank, int32_t* slot, int32_t* mb,
+                         int64_t* dst_row, int32_t* seq_shard, int64_t* seq_row, int32_t* seq_ids,
+                         int32_t* mb_seq_start, int64_t* mb_row_start, int32_t* cu_seqlens);
+
+/*
+ * Copies the segment table to HOST buffers of n_segments entries each (NULL to skip).  Segments are
+ * ordered by (destination shard, destination row).  Segment e copies n_real[e] rows from row
+ * src_row[e] of shard buffer src_shard[e] to row dst_row[e] of destination shard dst_shard[e] and
+ * fills the following n_rows[e]-n_real[e] rows with padding; pos0[e] is the logical position of its
+ * first row.  shard_seg_start has D*C+1 entries.
+ */
+int32_t earl_plan_export_segments(earl_plan* plan, int32_t* src_shard, int64_t* src_row,
+                                  int32_t* dst_shard, int64_t* dst_row, int32_t* n_real,
+                                  int32_t* n_rows, int32_t* pos0, int32_t* shard_seg_start);
+
+/*
+ * Materialises every destination shard of every field (asynchronously on the stream; the first call
+ * on a plan waits for the plan as earl_plan_get_summary does).
+ *   fields[n_fields]             0 <= n_fields <= EARL_MAX_FIELDS.
+ *   position_ids_shard_ptrs      host array[D*C] of device int32 buffers (16-byte aligned, at least
+ *                                shard_rows[q] entries), or NULL: logical position of every row,
+ *                                padding rows included.
+ *   cu_seqlens_dev               device int32[cu_seqlens_len] (16-byte aligned) or NULL.
+ * Every check (plan status, alignment, capacities) happens before anything is enqueued: a failed
+ * call writes nothing.  All dispatches of one plan must be issued on the plan's stream or be ordered
+ * after each other by the caller.
+ */
+int32_t earl_dispatch(earl_plan* plan, const earl_field* fields, int32_t n_fields,
+                      int32_t* const* position_ids_shard_ptrs, int32_t* cu_seqlens_dev,
+                      void* hip_stream);
+
+/*
+ * The reverse direction (training layout back to the rollout layout, for the stages that run
+ * between several models): every real row of every destination shard is copied back to the source
+ * row it was read from.  Field descriptors as in earl_dispatch with the roles of the two pointer
+ * arrays unchanged (dst_shard_ptrs is read, src_shard_ptrs is written; src pointers must be aligned
+ * to scalar_bytes).  Rows of the source buffers that the plan does not read are left untouched.
+ */
+int32_t earl_dispatch_inverse(earl_plan* plan, const earl_field* fields, int32_t n_fields,
+                              void* hip_stream);
+
+/* Frees the host object (device memory is the caller's). */
+int32_t earl_plan_destroy(earl_plan* plan);
+
+const char* earl_status_string(int32_t status);
+/* Text of the last failure on this thread (static storage, overwritten by the next failure). */
+const char* earl_last_error_message(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EARL_DISPATCH_H_ */

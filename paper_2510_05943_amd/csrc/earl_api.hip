@@ -1,0 +1,629 @@
+// Host side of the C ABI declared in include/earl_dispatch.h: argument checks, workspace
+// carve-up, kernel launches, and host copies of the plan.  No device memory is allocated here;
+// the only allocations are small host objects and a few pinned staging slots used to hand the
+// per-call parameter block to the re-layout kernel.
+#include "earl_dispatch.h"
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+#include <new>
+#include <vector>
+
+#include "earl_internal.h"
+
+using namespace earl;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int32_t fail(int32_t status, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return status;
+}
+
+#define HIP_TRY(expr)                                                                  \
+  do {                                                                                 \
+    hipError_t e_ = (expr);                                                            \
+    if (e_ != hipSuccess)                                                              \
+      return fail(EARL_HIP_ERROR, "%s failed: %s", #expr, hipGetErrorString(e_));      \
+  } while (0)
+
+constexpr size_t kAlign = 256;
+size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+size_t param_block_bytes(int n_fields, int n_src, int n_dst) {
+  size_t b = align_up(sizeof(DispatchDev));
+  b += align_up(sizeof(FieldDev) * (size_t)n_fields);
+  b += align_up(sizeof(int64_t) * ((size_t)n_fields * n_dst + 1));
+  b += align_up(sizeof(void*) * (size_t)n_fields * ((size_t)n_src + n_dst));
+  return b;
+}
+
+// Byte offsets of every array inside the workspace.
+struct Layout {
+  size_t hdr, shard_rows, src_rows_needed, n_seq, n_mb, rank_load, a2a, summary_end;
+  size_t seq_group, seq_shard, seq_row, m, rank, slot, mb, dst_row;
+  size_t seq_ids, next_start, mb_tmp, mb_seq_start, mb_row_start, cu_seqlens;
+  size_t rank_seq_base, rank_mbt_base, rank_cu_base;
+  size_t seg_src_shard, seg_src_row, seg_dst_row, seg_n_real, seg_n_rows, seg_pos0, seg_dst_shard;
+  size_t shard_seg_start, seg_real_prefix;
+  size_t sort_keys, lab_sum, lab_cnt;
+  size_t params_fwd, params_inv, params_bytes;
+  size_t total;
+};
+
+struct Dims {
+  int32_t N, G, R, S, D, C, K, halves, P, zigzag, n_pow2;
+  int64_t B, n_seg;
+};
+
+Layout make_layout(const Dims& d) {
+  Layout l{};
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    size_t o = off;
+    off += align_up(bytes);
+    return o;
+  };
+  const size_t N = d.N, S = d.S, D = d.D, DC = (size_t)d.D * d.C, NK = (size_t)d.n_seg;
+  l.hdr = take(sizeof(PlanHeader));
+  l.shard_rows = take(8 * DC);
+  l.src_rows_needed = take(8 * S);
+  l.n_seq = take(4 * D);
+  l.n_mb = take(4 * D);
+  l.rank_load = take(8 * D);
+  l.a2a = take(8 * S * DC);
+  l.summary_end = off;
+  l.seq_group = take(4 * N);
+  l.seq_shard = take(4 * N);
+  l.seq_row = take(8 * N);
+  l.m = take(4 * N);
+  l.rank = take(4 * N);
+  l.slot = take(4 * N);
+  l.mb = take(4 * N);
+  l.dst_row = take(8 * N);
+  l.seq_ids = take(4 * N);
+  l.next_start = take(4 * N);
+  l.mb_tmp = take(4 * (N + D));
+  l.mb_seq_start = take(4 * (N + D));
+  l.mb_row_start = take(8 * (N + D));
+  l.cu_seqlens = take(4 * 2 * N);
+  l.rank_seq_base = take(4 * (D + 1));
+  l.rank_mbt_base = take(4 * (D + 1));
+  l.rank_cu_base = take(4 * (D + 1));
+  l.seg_src_shard = take(4 * NK);
+  l.seg_src_row = take(8 * NK);
+  l.seg_dst_row = take(8 * NK);
+  l.seg_n_real = take(4 * NK);
+  l.seg_n_rows = take(4 * NK);
+  l.seg_pos0 = take(4 * NK);
+  l.seg_dst_shard = take(4 * NK);
+  l.shard_seg_start = take(4 * (DC + 1));
+  l.seg_real_prefix = take(8 * (NK + 1));
+  l.sort_keys = take(8 * (size_t)d.n_pow2);
+  const size_t lmax = (size_t)(d.G > d.D ? d.G : d.D);
+  const size_t tab = (2 * (size_t)kPlanWaves + 1) * lmax;
+  l.lab_sum = take(8 * tab);
+  l.lab_cnt = take(4 * tab);
+  l.params_bytes = param_block_bytes(EARL_MAX_FIELDS + 2, d.S, (int)DC);
+  l.params_fwd = take(l.params_bytes);
+  l.params_inv = take(l.params_bytes);
+  l.total = off;
+  return l;
+}
+
+int32_t check_layouts(int32_t n_seqs, const earl_src_layout* src, const earl_dst_layout* dst,
+                      Dims* out) {
+  if (!src || !dst) return fail(EARL_INVALID_ARG, "null layout");
+  if (n_seqs < 1 || n_seqs > EARL_MAX_SEQS)
+    return fail(EARL_INVALID_ARG, "n_seqs %d outside [1, %d]", n_seqs, EARL_MAX_SEQS);
+  if (src->n_groups < 1 || src->replication < 1 ||
+      (int64_t)src->n_groups * src->replication > EARL_MAX_SRC_SHARDS)
+    return fail(EARL_INVALID_ARG, "source layout: need 1 <= groups*replication <= %d",
+                EARL_MAX_SRC_SHARDS);
+  if (dst->dp < 1 || dst->dp > EARL_MAX_DP) return fail(EARL_INVALID_ARG, "dp out of range");
+  if (dst->sp < 1 || dst->sp > EARL_MAX_SP) return fail(EARL_INVALID_ARG, "sp out of range");
+  if (dst->zigzag != 0 && dst->zigzag != 1) return fail(EARL_INVALID_ARG, "zigzag must be 0 or 1");
+  if (dst->pad_multiple < 1) return fail(EARL_INVALID_ARG, "pad_multiple must be >= 1");
+  if (dst->balance_policy != 0) return fail(EARL_INVALID_ARG, "unknown balance_policy");
+  if (dst->mb_token_budget < 1) return fail(EARL_INVALID_ARG, "mb_token_budget must be >= 1");
+  Dims d{};
+  d.N = n_seqs;
+  d.G = src->n_groups;
+  d.R = src->replication;
+  d.S = d.G * d.R;
+  d.D = dst->dp;
+  d.C = dst->sp;
+  d.zigzag = dst->zigzag;
+  d.K = (dst->zigzag && dst->sp > 1) ? 2 * dst->sp : dst->sp;
+  d.halves = d.K / d.C;
+  d.P = dst->pad_multiple;
+  d.B = dst->mb_token_budget;
+  d.n_seg = (int64_t)d.N * d.K;
+  if (d.n_seg > (int64_t)1 << 27) return fail(EARL_INVALID_ARG, "n_seqs * chunks exceeds 2^27");
+  if ((int64_t)d.S * d.D * d.C > (int64_t)1 << 24)
+    return fail(EARL_INVALID_ARG, "source shards * destination shards exceeds 2^24");
+  d.n_pow2 = 1;
+  while (d.n_pow2 < d.N) d.n_pow2 <<= 1;
+  *out = d;
+  return EARL_OK;
+}
+
+// Pinned staging slots for the per-call parameter block (host -> workspace copy on the stream).
+struct StageSlot {
+  void* host = nullptr;
+  hipEvent_t done = nullptr;
+  bool in_flight = false;
+};
+constexpr int kStageSlots = 8;
+constexpr size_t kStageBytes = 256 * 1024;
+std::mutex g_stage_mu;
+StageSlot g_stage[kStageSlots];
+int g_stage_next = 0;
+
+}  // namespace
+
+struct earl_plan {
+  Dims d;
+  Layout l;
+  PlanDev dev;
+  unsigned char* ws;
+  hipStream_t stream;
+  bool summary_ready;
+  int32_t status;
+  bool inverse_ready;
+  std::vector<unsigned char> summary;   // host copy of the workspace's summary block
+  PlanHeader hdr;
+};
+
+namespace {
+
+int32_t ensure_summary(earl_plan* p) {
+  if (p->summary_ready) return p->status;
+  p->summary.resize(p->l.summary_end);
+  HIP_TRY(hipMemcpyAsync(p->summary.data(), p->ws, p->l.summary_end, hipMemcpyDeviceToHost,
+                         p->stream));
+  HIP_TRY(hipStreamSynchronize(p->stream));
+  std::memcpy(&p->hdr, p->summary.data() + p->l.hdr, sizeof(PlanHeader));
+  p->status = p->hdr.status;
+  p->summary_ready = true;
+  if (p->status == EARL_INVALID_ARG)
+    fail(p->status, "sequence %d: length < 1, group out of range or negative row offset",
+         p->hdr.bad_index);
+  else if (p->status == EARL_SEQ_EXCEEDS_BUDGET)
+    fail(p->status, "sequence %d: padded length exceeds the micro-batch budget", p->hdr.bad_index);
+  return p->status;
+}
+
+template <class Tv>
+const Tv* summary_ptr(const earl_plan* p, size_t off) {
+  return reinterpret_cast<const Tv*>(p->summary.data() + off);
+}
+
+// Copies a host-built parameter block into the workspace, ordered on the stream.
+int32_t upload_params(earl_plan* p, const std::vector<unsigned char>& block, size_t ws_off,
+                      hipStream_t stream) {
+  if (block.size() > kStageBytes) {
+    // too large for a staging slot: blocking copy
+    HIP_TRY(hipStreamSynchronize(stream));
+    HIP_TRY(hipMemcpy(p->ws + ws_off, block.data(), block.size(), hipMemcpyHostToDevice));
+    return EARL_OK;
+  }
+  std::lock_guard<std::mutex> lock(g_stage_mu);
+  StageSlot& s = g_stage[g_stage_next];
+  g_stage_next = (g_stage_next + 1) % kStageSlots;
+  if (!s.host) {
+    HIP_TRY(hipHostMalloc(&s.host, kStageBytes, hipHostMallocDefault));
+    HIP_TRY(hipEventCreateWithFlags(&s.done, hipEventDisableTiming));
+  }
+  if (s.in_flight) HIP_TRY(hipEventSynchronize(s.done));
+  std::memcpy(s.host, block.data(), block.size());
+  HIP_TRY(hipMemcpyAsync(p->ws + ws_off, s.host, block.size(), hipMemcpyHostToDevice, stream));
+  HIP_TRY(hipEventRecord(s.done, stream));
+  s.in_flight = true;
+  return EARL_OK;
+}
+
+struct BlockBuilder {
+  std::vector<unsigned char> bytes;
+  DispatchDev hd{};
+  FieldDev* fields() { return reinterpret_cast<FieldDev*>(bytes.data() + hd.fields_ofs); }
+  int64_t* tile_start() { return reinterpret_cast<int64_t*>(bytes.data() + hd.tile_start_ofs); }
+  const void** ptrs() { return reinterpret_cast<const void**>(bytes.data() + hd.ptrs_ofs); }
+  void init(int n_fields, int n_tile_cols, int n_src, int n_dst) {
+    hd.n_fields = n_fields;
+    hd.n_dst = n_tile_cols;
+    hd.n_src = n_src;
+    size_t off = align_up(sizeof(DispatchDev));
+    hd.fields_ofs = (uint32_t)off;
+    off += align_up(sizeof(FieldDev) * (size_t)n_fields);
+    hd.tile_start_ofs = (uint32_t)off;
+    off += align_up(sizeof(int64_t) * ((size_t)n_fields * n_tile_cols + 1));
+    hd.ptrs_ofs = (uint32_t)off;
+    off += align_up(sizeof(void*) * (size_t)n_fields * ((size_t)n_src + n_dst));
+    hd.total_bytes = (uint32_t)off;
+    bytes.assign(off, 0);
+    std::memcpy(bytes.data(), &hd, sizeof(hd));
+  }
+};
+
+uint64_t replicate_scalar(uint64_t v, int sb) {
+  if (sb >= 8) return v;
+  const uint64_t mask = (1ull << (8 * sb)) - 1ull;
+  uint64_t x = v & mask;
+  for (int b = sb; b < 8; b *= 2) x |= x << (8 * b);
+  return x;
+}
+
+int32_t check_field(const earl_plan* p, const earl_field& f, int idx, bool inverse) {
+  const int sb = f.scalar_bytes;
+  if (sb != 1 && sb != 2 && sb != 4 && sb != 8)
+    return fail(EARL_INVALID_ARG, "field %d: scalar_bytes must be 1, 2, 4 or 8", idx);
+  if (f.width < 1 || (int64_t)f.width * sb > EARL_MAX_ROW_BYTES)
+    return fail(EARL_INVALID_ARG, "field %d: row bytes outside [1, %d]", idx, EARL_MAX_ROW_BYTES);
+  if (!f.src_shard_ptrs || !f.dst_shard_ptrs || !f.dst_capacity_rows)
+    return fail(EARL_INVALID_ARG, "field %d: null pointer array", idx);
+  const int64_t* shard_rows = summary_ptr<int64_t>(p, p->l.shard_rows);
+  const int64_t* need = summary_ptr<int64_t>(p, p->l.src_rows_needed);
+  const int n_dst = p->d.D * p->d.C;
+  for (int q = 0; q < n_dst; ++q) {
+    if (shard_rows[q] == 0) continue;
+    if (!f.dst_shard_ptrs[q]) return fail(EARL_INVALID_ARG, "field %d: destination %d is null", idx, q);
+    if (reinterpret_cast<uintptr_t>(f.dst_shard_ptrs[q]) % (inverse ? sb : kVecBytes))
+      return fail(EARL_INVALID_ARG, "field %d: destination %d is misaligned", idx, q);
+    if (f.dst_capacity_rows[q] < shard_rows[q])
+      return fail(EARL_CAPACITY, "field %d: destination %d holds %lld rows, %lld needed", idx, q,
+                  (long long)f.dst_capacity_rows[q], (long long)shard_rows[q]);
+  }
+  for (int s = 0; s < p->d.S; ++s) {
+    if (need[s] == 0) continue;
+    if (!f.src_shard_ptrs[s]) return fail(EARL_INVALID_ARG, "field %d: source %d is null", idx, s);
+    if (reinterpret_cast<uintptr_t>(f.src_shard_ptrs[s]) % sb)
+      return fail(EARL_INVALID_ARG, "field %d: source %d is misaligned", idx, s);
+    if (f.src_capacity_rows && f.src_capacity_rows[s] < need[s])
+      return fail(EARL_CAPACITY, "field %d: source %d holds %lld rows, %lld needed", idx, s,
+                  (long long)f.src_capacity_rows[s], (long long)need[s]);
+  }
+  return EARL_OK;
+}
+
+CopyArgs copy_args(const earl_plan* p, size_t params_off, int64_t n_tiles) {
+  CopyArgs a{};
+  a.params = reinterpret_cast<const DispatchDev*>(p->ws + params_off);
+  a.shard_rows = p->dev.shard_rows;
+  a.shard_seg_start = p->dev.shard_seg_start;
+  a.seg_dst_row = p->dev.seg_dst_row;
+  a.seg_src_row = p->dev.seg_src_row;
+  a.seg_src_shard = p->dev.seg_src_shard;
+  a.seg_n_real = p->dev.seg_n_real;
+  a.seg_n_rows = p->dev.seg_n_rows;
+  a.seg_pos0 = p->dev.seg_pos0;
+  a.n_tiles = n_tiles;
+  return a;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t earl_plan_workspace_bytes(int32_t n_seqs, const earl_src_layout* src,
+                                  const earl_dst_layout* dst, size_t* out_bytes) {
+  if (!out_bytes) return fail(EARL_INVALID_ARG, "out_bytes is null");
+  Dims d;
+  int32_t st = check_layouts(n_seqs, src, dst, &d);
+  if (st != EARL_OK) return st;
+  *out_bytes = make_layout(d).total;
+  return EARL_OK;
+}
+
+int32_t earl_plan_build(const int32_t* lengths_dev, int32_t n_seqs, const earl_src_layout* src,
+                        const earl_dst_layout* dst, void* workspace_dev, size_t workspace_bytes,
+                        void* hip_stream, earl_plan** out_plan) {
+  if (!out_plan) return fail(EARL_INVALID_ARG, "out_plan is null");
+  *out_plan = nullptr;
+  if (!lengths_dev || !workspace_dev) return fail(EARL_INVALID_ARG, "null device pointer");
+  Dims d;
+  int32_t st = check_layouts(n_seqs, src, dst, &d);
+  if (st != EARL_OK) return st;
+  if (reinterpret_cast<uintptr_t>(workspace_dev) % kAlign)
+    return fail(EARL_INVALID_ARG, "workspace must be %zu-byte aligned", kAlign);
+  const Layout l = make_layout(d);
+  if (workspace_bytes < l.total)
+    return fail(EARL_CAPACITY, "workspace has %zu bytes, %zu needed", workspace_bytes, l.total);
+
+  earl_plan* p = new (std::nothrow) earl_plan();
+  if (!p) return fail(EARL_HIP_ERROR, "out of host memory");
+  p->d = d;
+  p->l = l;
+  p->ws = static_cast<unsigned char*>(workspace_dev);
+  p->stream = static_cast<hipStream_t>(hip_stream);
+  p->summary_ready = false;
+  p->status = EARL_OK;
+  p->inverse_ready = false;
+
+  PlanDev& v = p->dev;
+  unsigned char* w = p->ws;
+  v.lengths = lengths_dev;
+  v.seq_group_in = src->seq_group;
+  v.seq_row_in = src->seq_row;
+  v.N = d.N; v.G = d.G; v.R = d.R; v.S = d.S; v.D = d.D; v.C = d.C; v.K = d.K;
+  v.halves = d.halves; v.P = d.P; v.n_pow2 = d.n_pow2; v.B = d.B;
+  v.hdr = reinterpret_cast<PlanHeader*>(w + l.hdr);
+  v.shard_rows = reinterpret_cast<int64_t*>(w + l.shard_rows);
+  v.src_rows_needed = reinterpret_cast<int64_t*>(w + l.src_rows_needed);
+  v.n_seq = reinterpret_cast<int32_t*>(w + l.n_seq);
+  v.n_mb = reinterpret_cast<int32_t*>(w + l.n_mb);
+  v.rank_load = reinterpret_cast<int64_t*>(w + l.rank_load);
+  v.a2a = reinterpret_cast<int64_t*>(w + l.a2a);
+  v.seq_group = reinterpret_cast<int32_t*>(w + l.seq_group);
+  v.seq_shard = reinterpret_cast<int32_t*>(w + l.seq_shard);
+  v.seq_row = reinterpret_cast<int64_t*>(w + l.seq_row);
+  v.m = reinterpret_cast<int32_t*>(w + l.m);
+  v.rank = reinterpret_cast<int32_t*>(w + l.rank);
+  v.slot = reinterpret_cast<int32_t*>(w + l.slot);
+  v.mb = reinterpret_cast<int32_t*>(w + l.mb);
+  v.dst_row = reinterpret_cast<int64_t*>(w + l.dst_row);
+  v.seq_ids = reinterpret_cast<int32_t*>(w + l.seq_ids);
+  v.next_start = reinterpret_cast<int32_t*>(w + l.next_start);
+  v.mb_tmp = reinterpret_cast<int32_t*>(w + l.mb_tmp);
+  v.mb_seq_start = reinterpret_cast<int32_t*>(w + l.mb_seq_start);
+  v.mb_row_start = reinterpret_cast<int64_t*>(w + l.mb_row_start);
+  v.cu_seqlens = reinterpret_cast<int32_t*>(w + l.cu_seqlens);
+  v.rank_seq_base = reinterpret_cast<int32_t*>(w + l.rank_seq_base);
+  v.rank_mbt_base = reinterpret_cast<int32_t*>(w + l.rank_mbt_base);
+  v.rank_cu_base = reinterpret_cast<int32_t*>(w + l.rank_cu_base);
+  v.seg_src_shard = reinterpret_cast<int32_t*>(w + l.seg_src_shard);
+  v.seg_src_row = reinterpret_cast<int64_t*>(w + l.seg_src_row);
+  v.seg_dst_row = reinterpret_cast<int64_t*>(w + l.seg_dst_row);
+  v.seg_n_real = reinterpret_cast<int32_t*>(w + l.seg_n_real);
+  v.seg_n_rows = reinterpret_cast<int32_t*>(w + l.seg_n_rows);
+  v.seg_pos0 = reinterpret_cast<int32_t*>(w + l.seg_pos0);
+  v.seg_dst_shard = reinterpret_cast<int32_t*>(w + l.seg_dst_shard);
+  v.shard_seg_start = reinterpret_cast<int32_t*>(w + l.shard_seg_start);
+  v.sort_keys = reinterpret_cast<uint64_t*>(w + l.sort_keys);
+  v.lab_sum = reinterpret_cast<int64_t*>(w + l.lab_sum);
+  v.lab_cnt = reinterpret_cast<int32_t*>(w + l.lab_cnt);
+
+  launch_plan(v, p->stream);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) {
+    delete p;
+    return fail(EARL_HIP_ERROR, "plan kernel launch failed: %s", hipGetErrorString(e));
+  }
+  *out_plan = p;
+  return EARL_OK;
+}
+
+int32_t earl_plan_get_summary(earl_plan* p, earl_plan_summary* out) {
+  if (!p || !out) return fail(EARL_INVALID_ARG, "null argument");
+  std::memset(out, 0, sizeof(*out));
+  const int32_t st = ensure_summary(p);
+  if (st != EARL_OK) return st;
+  out->n_seqs = p->d.N;
+  out->n_src_shards = p->d.S;
+  out->n_dst_shards = p->d.D * p->d.C;
+  out->chunks_per_seq = p->d.K;
+  out->n_segments = p->hdr.n_segments;
+  out->n_mb_max = p->hdr.n_mb_max;
+  out->cu_seqlens_len = p->hdr.cu_seqlens_len;
+  out->mb_table_len = p->hdr.mb_table_len;
+  out->total_real_rows = p->hdr.total_real_rows;
+  out->total_dst_rows = p->hdr.total_dst_rows;
+  out->rank_load_min = p->hdr.rank_load_min;
+  out->rank_load_max = p->hdr.rank_load_max;
+  out->shard_rows = summary_ptr<int64_t>(p, p->l.shard_rows);
+  out->src_rows_needed = summary_ptr<int64_t>(p, p->l.src_rows_needed);
+  out->n_seq = summary_ptr<int32_t>(p, p->l.n_seq);
+  out->n_mb = summary_ptr<int32_t>(p, p->l.n_mb);
+  out->rank_load = summary_ptr<int64_t>(p, p->l.rank_load);
+  out->a2a_counts = summary_ptr<int64_t>(p, p->l.a2a);
+  return EARL_OK;
+}
+
+int32_t earl_plan_export(earl_plan* p, int32_t* rank, int32_t* slot, int32_t* mb, int64_t* dst_row,
+                         int32_t* seq_shard, int64_t* seq_row, int32_t* seq_ids,
+                         int32_t* mb_seq_start, int64_t* mb_row_start, int32_t* cu_seqlens) {
+  if (!p) return fail(EARL_INVALID_ARG, "null plan");
+  const int32_t st = ensure_summary(p);
+  if (st != EARL_OK) return st;
+  const size_t N = p->d.N;
+  auto get = [&](void* dst, const void* src, size_t bytes) -> hipError_t {
+    if (!dst || bytes == 0) return hipSuccess;
+    return hipMemcpy(dst, src, bytes, hipMemcpyDeviceToHost);
+  };
+  HIP_TRY(get(rank, p->dev.rank, 4 * N));
+  HIP_TRY(get(slot, p->dev.slot, 4 * N));
+  HIP_TRY(get(mb, p->dev.mb, 4 * N));
+  HIP_TRY(get(dst_row, p->dev.dst_row, 8 * N));
+  HIP_TRY(get(seq_shard, p->dev.seq_shard, 4 * N));
+  HIP_TRY(get(seq_row, p->dev.seq_row, 8 * N));
+  HIP_TRY(get(seq_ids, p->dev.seq_ids, 4 * N));
+  HIP_TRY(get(mb_seq_start, p->dev.mb_seq_start, 4 * (size_t)p->hdr.mb_table_len));
+  HIP_TRY(get(mb_row_start, p->dev.mb_row_start, 8 * (size_t)p->hdr.mb_table_len));
+  HIP_TRY(get(cu_seqlens, p->dev.cu_seqlens, 4 * (size_t)p->hdr.cu_seqlens_len));
+  return EARL_OK;
+}
+
+int32_t earl_plan_export_segments(earl_plan* p, int32_t* src_shard, int64_t* src_row,
+                                  int32_t* dst_shard, int64_t* dst_row, int32_t* n_real,
+                                  int32_t* n_rows, int32_t* pos0, int32_t* shard_seg_start) {
+  if (!p) return fail(EARL_INVALID_ARG, "null plan");
+  const int32_t st = ensure_summary(p);
+  if (st != EARL_OK) return st;
+  const size_t E = (size_t)p->hdr.n_segments;
+  auto get = [&](void* dst, const void* src, size_t bytes) -> hipError_t {
+    if (!dst || bytes == 0) return hipSuccess;
+    return hipMemcpy(dst, src, bytes, hipMemcpyDeviceToHost);
+  };
+  HIP_TRY(get(src_shard, p->dev.seg_src_shard, 4 * E));
+  HIP_TRY(get(src_row, p->dev.seg_src_row, 8 * E));
+  HIP_TRY(get(dst_shard, p->dev.seg_dst_shard, 4 * E));
+  HIP_TRY(get(dst_row, p->dev.seg_dst_row, 8 * E));
+  HIP_TRY(get(n_real, p->dev.seg_n_real, 4 * E));
+  HIP_TRY(get(n_rows, p->dev.seg_n_rows, 4 * E));
+  HIP_TRY(get(pos0, p->dev.seg_pos0, 4 * E));
+  HIP_TRY(get(shard_seg_start, p->dev.shard_seg_start, 4 * ((size_t)p->d.D * p->d.C + 1)));
+  return EARL_OK;
+}
+
+int32_t earl_dispatch(earl_plan* p, const earl_field* fields, int32_t n_fields,
+                      int32_t* const* position_ids_shard_ptrs, int32_t* cu_seqlens_dev,
+                      void* hip_stream) {
+  if (!p) return fail(EARL_INVALID_ARG, "null plan");
+  if (n_fields < 0 || n_fields > EARL_MAX_FIELDS || (n_fields > 0 && !fields))
+    return fail(EARL_INVALID_ARG, "n_fields outside [0, %d] or null fields", EARL_MAX_FIELDS);
+  int32_t st = ensure_summary(p);
+  if (st != EARL_OK) return st;
+  const int n_dst = p->d.D * p->d.C, S = p->d.S;
+  const int64_t* shard_rows = summary_ptr<int64_t>(p, p->l.shard_rows);
+  for (int f = 0; f < n_fields; ++f) {
+    st = check_field(p, fields[f], f, false);
+    if (st != EARL_OK) return st;
+  }
+  if (position_ids_shard_ptrs) {
+    for (int q = 0; q < n_dst; ++q) {
+      if (shard_rows[q] == 0) continue;
+      if (!position_ids_shard_ptrs[q] ||
+          reinterpret_cast<uintptr_t>(position_ids_shard_ptrs[q]) % kVecBytes)
+        return fail(EARL_INVALID_ARG, "position ids of shard %d: null or misaligned", q);
+    }
+  }
+  if (cu_seqlens_dev && reinterpret_cast<uintptr_t>(cu_seqlens_dev) % kVecBytes)
+    return fail(EARL_INVALID_ARG, "cu_seqlens buffer is misaligned");
+
+  const int extra = (position_ids_shard_ptrs ? 1 : 0) + (cu_seqlens_dev ? 1 : 0);
+  const int F = n_fields + extra;
+  if (F == 0) return EARL_OK;
+  BlockBuilder b;
+  b.init(F, n_dst, S, n_dst);
+  FieldDev* fd = b.fields();
+  int64_t* ts = b.tile_start();
+  const void** ptrs = b.ptrs();
+  uint32_t pi = 0;
+  int64_t tiles = 0;
+  for (int f = 0; f < F; ++f) {
+    FieldDev& d = fd[f];
+    d.src_ptr_index = pi;
+    d.dst_ptr_index = pi + S;
+    if (f < n_fields) {
+      const earl_field& uf = fields[f];
+      d.kind = kFieldCopy;
+      d.scalar_bytes = uf.scalar_bytes;
+      d.row_bytes = uf.scalar_bytes * uf.width;
+      d.pad_scalar = replicate_scalar(uf.pad_scalar, uf.scalar_bytes);
+      for (int s = 0; s < S; ++s) ptrs[pi + s] = uf.src_shard_ptrs[s];
+      for (int q = 0; q < n_dst; ++q) ptrs[pi + S + q] = uf.dst_shard_ptrs[q];
+    } else if (position_ids_shard_ptrs && f == n_fields) {
+      d.kind = kFieldPositionIds;
+      d.scalar_bytes = 4;
+      d.row_bytes = 4;
+      d.pad_scalar = 0;
+      for (int q = 0; q < n_dst; ++q) ptrs[pi + S + q] = position_ids_shard_ptrs[q];
+    } else {
+      d.kind = kFieldLinear;
+      d.scalar_bytes = 4;
+      d.row_bytes = 4;
+      d.pad_scalar = 4ull * (uint64_t)p->hdr.cu_seqlens_len;
+      ptrs[pi] = p->dev.cu_seqlens;
+      ptrs[pi + S] = cu_seqlens_dev;
+    }
+    pi += S + n_dst;
+    for (int q = 0; q < n_dst; ++q) {
+      ts[(size_t)f * n_dst + q] = tiles;
+      int64_t bytes = d.kind == kFieldLinear ? (q == 0 ? (int64_t)d.pad_scalar : 0)
+                                             : shard_rows[q] * (int64_t)d.row_bytes;
+      tiles += (bytes + kTileBytes - 1) / kTileBytes;
+    }
+  }
+  ts[(size_t)F * n_dst] = tiles;
+  if (tiles > 0x7fffffffll) return fail(EARL_INVALID_ARG, "too many tiles for one launch");
+  if (tiles == 0) return EARL_OK;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  st = upload_params(p, b.bytes, p->l.params_fwd, stream);
+  if (st != EARL_OK) return st;
+  launch_copy(copy_args(p, p->l.params_fwd, tiles), stream);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess)
+    return fail(EARL_HIP_ERROR, "re-layout kernel launch failed: %s", hipGetErrorString(e));
+  return EARL_OK;
+}
+
+int32_t earl_dispatch_inverse(earl_plan* p, const earl_field* fields, int32_t n_fields,
+                              void* hip_stream) {
+  if (!p) return fail(EARL_INVALID_ARG, "null plan");
+  if (n_fields < 0 || n_fields > EARL_MAX_FIELDS || (n_fields > 0 && !fields))
+    return fail(EARL_INVALID_ARG, "n_fields outside [0, %d] or null fields", EARL_MAX_FIELDS);
+  int32_t st = ensure_summary(p);
+  if (st != EARL_OK) return st;
+  const int n_dst = p->d.D * p->d.C, S = p->d.S;
+  for (int f = 0; f < n_fields; ++f) {
+    st = check_field(p, fields[f], f, true);
+    if (st != EARL_OK) return st;
+  }
+  if (n_fields == 0 || p->hdr.total_real_rows == 0) return EARL_OK;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  int64_t* prefix = reinterpret_cast<int64_t*>(p->ws + p->l.seg_real_prefix);
+  if (!p->inverse_ready) {
+    launch_real_prefix(p->dev.seg_n_real, prefix, p->hdr.n_segments, stream);
+    p->inverse_ready = true;
+  }
+  BlockBuilder b;
+  b.init(n_fields, 1, S, n_dst);
+  FieldDev* fd = b.fields();
+  int64_t* ts = b.tile_start();
+  const void** ptrs = b.ptrs();
+  uint32_t pi = 0;
+  int64_t tiles = 0;
+  for (int f = 0; f < n_fields; ++f) {
+    const earl_field& uf = fields[f];
+    FieldDev& d = fd[f];
+    d.kind = kFieldCopy;
+    d.scalar_bytes = uf.scalar_bytes;
+    d.row_bytes = uf.scalar_bytes * uf.width;
+    d.pad_scalar = 0;
+    d.src_ptr_index = pi;
+    d.dst_ptr_index = pi + S;
+    for (int s = 0; s < S; ++s) ptrs[pi + s] = uf.src_shard_ptrs[s];
+    for (int q = 0; q < n_dst; ++q) ptrs[pi + S + q] = uf.dst_shard_ptrs[q];
+    pi += S + n_dst;
+    ts[f] = tiles;
+    const int64_t bytes = p->hdr.total_real_rows * (int64_t)d.row_bytes;
+    tiles += (bytes + kTileBytes - 1) / kTileBytes;
+  }
+  ts[n_fields] = tiles;
+  if (tiles > 0x7fffffffll) return fail(EARL_INVALID_ARG, "too many tiles for one launch");
+  st = upload_params(p, b.bytes, p->l.params_inv, stream);
+  if (st != EARL_OK) return st;
+  launch_copy_inverse(copy_args(p, p->l.params_inv, tiles), prefix, p->dev.seg_dst_shard,
+                      p->hdr.n_segments, stream);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess)
+    return fail(EARL_HIP_ERROR, "inverse kernel launch failed: %s", hipGetErrorString(e));
+  return EARL_OK;
+}
+
+int32_t earl_plan_destroy(earl_plan* p) {
+  delete p;
+  return EARL_OK;
+}
+
+const char* earl_status_string(int32_t status) {
+  switch (status) {
+    case EARL_OK: return "ok";
+    case EARL_INVALID_ARG: return "invalid argument";
+    case EARL_SEQ_EXCEEDS_BUDGET: return "a padded sequence exceeds the micro-batch token budget";
+    case EARL_CAPACITY: return "a buffer is too small";
+    case EARL_HIP_ERROR: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+const char* earl_last_error_message(void) { return g_err; }
+
+}  // extern "C"

@@ -1,0 +1,140 @@
+// Internal definitions shared by the host API and the gfx950 kernels of the re-layout library.
+// Nothing here is part of the C ABI (see include/earl_dispatch.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace earl {
+
+constexpr int kWave = 64;            // CDNA wavefront width
+constexpr int kPlanThreads = 1024;   // the plan runs in one workgroup of 16 wavefronts
+constexpr int kPlanWaves = kPlanThreads / kWave;
+constexpr int kMaxDp = 1024;         // one DP rank per plan thread
+
+// Labels (source groups, DP ranks) whose per-wave scan tables fit the workgroup's LDS; larger
+// label counts use the same code on tables in the workspace.
+constexpr int kLdsLabels = 256;
+// Sort keys kept in LDS up to this many (power of two); more go to the workspace.
+constexpr int kLdsSortKeys = 8192;
+
+constexpr int kCopyThreads = 256;    // re-layout kernel workgroup (4 wavefronts)
+constexpr int kVecBytes = 16;        // one global_load/store_dwordx4 per lane
+constexpr int kTileBytes = 64 * 1024;  // destination bytes handled by one workgroup
+
+// First bytes of the workspace; copied to the host together with the arrays that follow it.
+struct PlanHeader {
+  int32_t status;
+  int32_t bad_index;       // a sequence index that caused status != 0 (diagnostic)
+  int32_t n_segments;
+  int32_t n_mb_max;
+  int32_t cu_seqlens_len;
+  int32_t mb_table_len;
+  int32_t pad_[2];
+  int64_t total_real_rows;
+  int64_t total_dst_rows;
+  int64_t rank_load_min;
+  int64_t rank_load_max;
+  int64_t reserved_[10];
+};
+static_assert(sizeof(PlanHeader) == 144, "PlanHeader layout");
+
+// Everything the plan kernel needs: problem sizes and pointers into the caller's workspace.
+struct PlanDev {
+  // inputs
+  const int32_t* lengths;
+  const int32_t* seq_group_in;   // may be null
+  const int64_t* seq_row_in;     // may be null
+  int32_t N, G, R, S, D, C, K, halves, P;
+  int32_t n_pow2;                // N rounded up to a power of two (sort size)
+  int64_t B;
+  // summary block (contiguous, copied to the host in one piece)
+  PlanHeader* hdr;
+  int64_t* shard_rows;           // [D*C]
+  int64_t* src_rows_needed;      // [S]
+  int32_t* n_seq;                // [D]
+  int32_t* n_mb;                 // [D]
+  int64_t* rank_load;            // [D]
+  int64_t* a2a;                  // [S*D*C]
+  // per sequence
+  int32_t* seq_group;            // [N]
+  int32_t* seq_shard;            // [N]
+  int64_t* seq_row;              // [N]
+  int32_t* m;                    // [N] chunk length
+  int32_t* rank;                 // [N]
+  int32_t* slot;                 // [N]
+  int32_t* mb;                   // [N]
+  int64_t* dst_row;              // [N]
+  // per rank / packed order
+  int32_t* seq_ids;              // [N]
+  int32_t* next_start;           // [N] scratch: first slot of the following micro-batch
+  int32_t* mb_tmp;               // [N+D] scratch
+  int32_t* mb_seq_start;         // [N+D]
+  int64_t* mb_row_start;         // [N+D]
+  int32_t* cu_seqlens;           // [2N]
+  int32_t* rank_seq_base;        // [D+1]
+  int32_t* rank_mbt_base;        // [D+1]
+  int32_t* rank_cu_base;         // [D+1]
+  // segment table, ordered by (destination shard, destination row)
+  int32_t* seg_src_shard;        // [N*K]
+  int64_t* seg_src_row;
+  int64_t* seg_dst_row;
+  int32_t* seg_n_real;
+  int32_t* seg_n_rows;
+  int32_t* seg_pos0;
+  int32_t* seg_dst_shard;
+  int32_t* shard_seg_start;      // [D*C+1]
+  // scratch
+  uint64_t* sort_keys;           // [n_pow2]; reused as int64 row offsets in packed order
+  int64_t* lab_sum;              // [2*kPlanWaves*Lmax + Lmax], Lmax = max(G, D)
+  int32_t* lab_cnt;              // same shape
+};
+
+// One field as the re-layout kernel sees it.
+enum FieldKind : int32_t { kFieldCopy = 0, kFieldPositionIds = 1, kFieldLinear = 2 };
+
+struct FieldDev {
+  int32_t kind;
+  int32_t row_bytes;
+  int32_t scalar_bytes;
+  int32_t pad_;
+  uint64_t pad_scalar;      // replicated to fill 8 bytes (kFieldLinear: bytes to copy)
+  uint32_t src_ptr_index;   // first of S entries in DispatchDev::ptrs
+  uint32_t dst_ptr_index;   // first of D*C entries in DispatchDev::ptrs
+};
+
+// Parameter block of one dispatch call, in device memory.
+//   tile_start[f*n_dst + q] = first tile of (field f, shard q); tile_start[n_fields*n_dst] = total
+struct DispatchDev {
+  int32_t n_fields;
+  int32_t n_dst;
+  int32_t n_src;
+  int32_t pad_;
+  uint32_t fields_ofs;      // byte offsets from the start of the block
+  uint32_t tile_start_ofs;
+  uint32_t ptrs_ofs;
+  uint32_t total_bytes;
+};
+
+struct CopyArgs {
+  const DispatchDev* params;
+  const int64_t* shard_rows;       // [n_dst]
+  const int32_t* shard_seg_start;  // [n_dst+1]
+  const int64_t* seg_dst_row;
+  const int64_t* seg_src_row;
+  const int32_t* seg_src_shard;
+  const int32_t* seg_n_real;
+  const int32_t* seg_n_rows;
+  const int32_t* seg_pos0;
+  int64_t n_tiles;
+};
+
+void launch_plan(const PlanDev& p, hipStream_t stream);
+void launch_copy(const CopyArgs& a, hipStream_t stream);
+// seg_real_prefix[e] = real rows of the segments before e (n_seg+1 entries)
+void launch_real_prefix(const int32_t* seg_n_real, int64_t* prefix, int n_seg, hipStream_t stream);
+void launch_copy_inverse(const CopyArgs& a, const int64_t* seg_real_prefix,
+                         const int32_t* seg_dst_shard, int n_seg, hipStream_t stream);
+
+}  // namespace earl

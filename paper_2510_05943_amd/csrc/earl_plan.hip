@@ -1,0 +1,605 @@
+// Dispatch plan on the device: one workgroup of 16 wavefronts on gfx950.
+//
+// The paper's Data Dispatcher (Section 2) chooses, from the current data layout and the
+// consumer's parallelism configuration, where every part of every sequence has to go, so that
+// it can be sent there directly.  This kernel is that decision for one batch: source row
+// offsets, replica choice, padded chunk geometry, length-balanced DP-rank assignment, packing
+// order, micro-batches, destination offsets, the segment table and the all-to-all counts.
+// Everything is integer arithmetic with explicit tie-breaks, so the result is unique.
+//
+// N is a few thousand at most in practice and the longest dependency chain (the list
+// scheduling of N sequences) is serial by definition, so the whole plan runs in a single
+// workgroup: phases are separated by workgroup barriers, wide phases use all 1024 lanes, the
+// serial chain runs in wavefront 0 with the rank loads held one per lane and the arg-min taken
+// by DPP cross-lane operations.
+#include "earl_internal.h"
+
+namespace earl {
+namespace {
+
+constexpr int T = kPlanThreads;
+
+// ---------------------------------------------------------------------------------------
+// wavefront primitives
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
+__device__ __forceinline__ int wave_id() { return threadIdx.x >> 6; }
+
+template <int kCtrl, int kRowMask>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t old, uint32_t src) {
+  return (uint32_t)__builtin_amdgcn_update_dpp((int)old, (int)src, kCtrl, kRowMask, 0xf, false);
+}
+
+// DPP controls of the GFX9 family.
+constexpr int kDppQuadXor1 = 0xB1;      // quad_perm:[1,0,3,2]
+constexpr int kDppQuadXor2 = 0x4E;      // quad_perm:[2,3,0,1]
+constexpr int kDppRowHalfMirror = 0x141;
+constexpr int kDppRowMirror = 0x140;
+constexpr int kDppRowBcast15 = 0x142;
+constexpr int kDppRowBcast31 = 0x143;
+constexpr int kDppRowShr = 0x110;       // + n
+
+// Minimum of x over the 64 lanes (result valid in every lane: read back from lane 63).
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t x) {
+  uint32_t y;
+  y = dpp_u32<kDppQuadXor1, 0xf>(x, x); x = y < x ? y : x;
+  y = dpp_u32<kDppQuadXor2, 0xf>(x, x); x = y < x ? y : x;
+  y = dpp_u32<kDppRowHalfMirror, 0xf>(x, x); x = y < x ? y : x;
+  y = dpp_u32<kDppRowMirror, 0xf>(x, x); x = y < x ? y : x;
+  y = dpp_u32<kDppRowBcast15, 0xa>(x, x); x = y < x ? y : x;
+  y = dpp_u32<kDppRowBcast31, 0xc>(x, x); x = y < x ? y : x;
+  return (uint32_t)__builtin_amdgcn_readlane((int)x, 63);
+}
+
+// Inclusive prefix sum over the 64 lanes: Hillis-Steele inside each row of 16 lanes with
+// row_shr, then the row totals are carried across rows with row_bcast.
+template <int kCtrl, int kRowMask>
+__device__ __forceinline__ int64_t dpp_add_i64(int64_t x) {
+  uint32_t lo = dpp_u32<kCtrl, kRowMask>(0u, (uint32_t)x);
+  uint32_t hi = dpp_u32<kCtrl, kRowMask>(0u, (uint32_t)((uint64_t)x >> 32));
+  return x + (int64_t)(((uint64_t)hi << 32) | lo);
+}
+__device__ __forceinline__ int64_t wave_incl_scan_i64(int64_t x) {
+  x = dpp_add_i64<kDppRowShr + 1, 0xf>(x);
+  x = dpp_add_i64<kDppRowShr + 2, 0xf>(x);
+  x = dpp_add_i64<kDppRowShr + 4, 0xf>(x);
+  x = dpp_add_i64<kDppRowShr + 8, 0xf>(x);
+  x = dpp_add_i64<kDppRowBcast15, 0xa>(x);
+  x = dpp_add_i64<kDppRowBcast31, 0xc>(x);
+  return x;
+}
+__device__ __forceinline__ int64_t readlane_i64(int64_t x, int l) {
+  uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)x, l);
+  uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)((uint64_t)x >> 32), l);
+  return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+
+// ---------------------------------------------------------------------------------------
+// workgroup primitives (every thread of the workgroup must call them)
+// ---------------------------------------------------------------------------------------
+struct BlockScratch {
+  int64_t wave_tot[kPlanWaves];
+  int64_t total;
+};
+
+// Exclusive prefix sum of one value per thread; returns the prefix, writes the total.
+__device__ int64_t block_excl_scan(int64_t v, BlockScratch& s, int64_t* total) {
+  int64_t incl = wave_incl_scan_i64(v);
+  if (lane_id() == kWave - 1) s.wave_tot[wave_id()] = incl;
+  __syncthreads();
+  if (wave_id() == 0) {
+    int64_t t = lane_id() < kPlanWaves ? s.wave_tot[lane_id()] : 0;
+    int64_t ti = wave_incl_scan_i64(t);
+    if (lane_id() < kPlanWaves) s.wave_tot[lane_id()] = ti - t;
+    if (lane_id() == kPlanWaves - 1) s.total = ti;
+  }
+  __syncthreads();
+  int64_t r = incl - v + s.wave_tot[wave_id()];
+  *total = s.total;
+  __syncthreads();
+  return r;
+}
+
+__device__ int64_t block_reduce_max(int64_t v, BlockScratch& s) {
+  for (int d = 32; d > 0; d >>= 1) {
+    int64_t o = __shfl_xor(v, d);
+    v = o > v ? o : v;
+  }
+  if (lane_id() == 0) s.wave_tot[wave_id()] = v;
+  __syncthreads();
+  int64_t r = s.wave_tot[0];
+  for (int w = 1; w < kPlanWaves; ++w) r = s.wave_tot[w] > r ? s.wave_tot[w] : r;
+  __syncthreads();
+  return r;
+}
+
+__device__ int64_t block_reduce_min(int64_t v, BlockScratch& s) {
+  return -block_reduce_max(-v, s);
+}
+
+// ---------------------------------------------------------------------------------------
+// Segmented prefix scan by label, in index order.
+//
+// For every i in [0, N): cnt(i) = #{ j < i : lab(j) == lab(i) } and
+// sum(i) = sum of val(j) over the same j.  With lab = source group and val = length this gives
+// the packed source row offset of every sequence; with lab = DP rank and val = rows per SP rank
+// it gives the position of a sequence inside its rank and its destination row offset.
+//
+// A chunk of 1024 consecutive indices is handled per step: each wavefront loops over the
+// distinct labels among its 64 lanes (ballot / readlane) and scans the matching lanes; the
+// per-(wavefront, label) totals are combined through a table (LDS or workspace) and a running
+// carry per label.  tab_* are [2][kPlanWaves][n_labels] (contribution, prefix) followed by the
+// carry [n_labels]; all zero on entry, and the carry holds the per-label totals on exit.
+// ---------------------------------------------------------------------------------------
+template <class LabF, class ValF, class OutF>
+__device__ void label_scan(int N, int n_labels, LabF lab, ValF val, OutF out, int64_t* tab_sum,
+                           int32_t* tab_cnt) {
+  const int lane = lane_id(), wave = wave_id();
+  const size_t plane = (size_t)kPlanWaves * n_labels;
+  int64_t* tot_sum = tab_sum;
+  int64_t* pre_sum = tab_sum + plane;
+  int64_t* carry_sum = tab_sum + 2 * plane;
+  int32_t* tot_cnt = tab_cnt;
+  int32_t* pre_cnt = tab_cnt + plane;
+  int32_t* carry_cnt = tab_cnt + 2 * plane;
+
+  for (int base = 0; base < N; base += T) {
+    const int i = base + (int)threadIdx.x;
+    const bool active = i < N;
+    const int l = active ? lab(i) : -1;
+    const int64_t v = active ? val(i) : 0;
+    int32_t my_cnt = 0;
+    int64_t my_sum = 0;
+    uint64_t remaining = __ballot(active);
+    while (remaining) {
+      const int leader = __builtin_ctzll(remaining);
+      const int cur = __builtin_amdgcn_readlane(l, leader);
+      const bool mine = active && l == cur;
+      const uint64_t mask = __ballot(mine);
+      const int64_t incl = wave_incl_scan_i64(mine ? v : 0);
+      if (mine) {
+        my_cnt = __builtin_popcountll(mask & ((1ull << lane) - 1ull));
+        my_sum = incl - v;
+      }
+      const int64_t wtot = readlane_i64(incl, kWave - 1);
+      if (lane == leader) {
+        tot_sum[(size_t)wave * n_labels + cur] = wtot;
+        tot_cnt[(size_t)wave * n_labels + cur] = __builtin_popcountll(mask);
+      }
+      remaining &= ~mask;
+    }
+    __syncthreads();
+    for (int c = threadIdx.x; c < n_labels; c += T) {
+      int64_t as = carry_sum[c];
+      int32_t ac = carry_cnt[c];
+      for (int w = 0; w < kPlanWaves; ++w) {
+        const size_t x = (size_t)w * n_labels + c;
+        const int64_t s = tot_sum[x];
+        const int32_t n = tot_cnt[x];
+        pre_sum[x] = as;
+        pre_cnt[x] = ac;
+        tot_sum[x] = 0;
+        tot_cnt[x] = 0;
+        as += s;
+        ac += n;
+      }
+      carry_sum[c] = as;
+      carry_cnt[c] = ac;
+    }
+    __syncthreads();
+    if (active) {
+      const size_t x = (size_t)wave * n_labels + l;
+      out(i, my_cnt + pre_cnt[x], my_sum + pre_sum[x]);
+    }
+  }
+  __syncthreads();
+}
+
+// ---------------------------------------------------------------------------------------
+// Bitonic sort of n (power of two) unique 64-bit keys, ascending.
+// ---------------------------------------------------------------------------------------
+__device__ void bitonic_sort(uint64_t* keys, int n) {
+  for (int k = 2; k <= n; k <<= 1) {
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      for (int t = threadIdx.x; t < (n >> 1); t += T) {
+        const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
+        const int x = i | j;
+        const uint64_t a = keys[i], b = keys[x];
+        const bool up = (i & k) == 0;
+        if ((a > b) == up) {
+          keys[i] = b;
+          keys[x] = a;
+        }
+      }
+      __syncthreads();
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Longest-first list scheduling in wavefront 0.
+//
+// keys[] holds the sequences sorted by (padded length descending, index ascending); the low
+// word is the index, the high word is 0x7fffffff - padded length.  Each lane owns the loads of
+// a block of consecutive ranks, so a lower lane always means lower ranks and ties resolve to
+// the lowest rank by taking the first lane that holds the minimum.  Loads are compared as
+// 32-bit distances from a running uniform base (the greedy rule keeps max - min load within one
+// padded length, which is < 2^31), so the arg-min is six v_min_u32 DPP steps.
+// ---------------------------------------------------------------------------------------
+__device__ void lpt_wave0(const PlanDev& p, const uint64_t* keys, int64_t* lds_load) {
+  const int lane = lane_id();
+  const int D = p.D, N = p.N;
+  const int kper = (D + kWave - 1) / kWave;
+  const int r_lo = lane * kper;
+  const int r_hi = min(D, r_lo + kper);
+  const bool owner = r_lo < D;
+  for (int r = r_lo; r < r_hi; ++r) lds_load[r] = 0;
+  int64_t best = 0;     // smallest load among this lane's ranks
+  int best_r = r_lo;    // the lowest rank that has it
+  int64_t base = 0;     // uniform: the minimum load over all ranks before the current step
+
+  for (int start = 0; start < N; start += kWave) {
+    const int i = start + lane;
+    const uint64_t key = i < N ? keys[i] : ~0ull;
+    const int32_t lp = 0x7fffffff - (int32_t)(key >> 32);
+    const int32_t idx = (int32_t)(key & 0xffffffffu);
+    int my_rank = 0;
+    const int cnt = min(kWave, N - start);
+    for (int s = 0; s < cnt; ++s) {
+      const int32_t lp_s = __builtin_amdgcn_readlane(lp, s);
+      const uint32_t rel = owner ? (uint32_t)(best - base) : 0xffffffffu;
+      const uint32_t mn = wave_min_u32(rel);
+      const uint64_t at_min = __ballot(rel == mn);
+      const int wl = __builtin_ctzll(at_min);
+      const int r = __builtin_amdgcn_readlane(best_r, wl);
+      base += mn;
+      if (lane == wl) {
+        if (kper == 1) {
+          best += lp_s;
+        } else {
+          lds_load[r] += lp_s;
+          best = lds_load[r_lo];
+          best_r = r_lo;
+          for (int q = r_lo + 1; q < r_hi; ++q) {
+            const int64_t v = lds_load[q];
+            if (v < best) { best = v; best_r = q; }
+          }
+        }
+      }
+      if (lane == s) my_rank = r;
+    }
+    if (i < N) p.rank[idx] = my_rank;
+  }
+  if (kper == 1) {
+    if (owner) p.rank_load[lane] = best;
+  } else {
+    for (int r = r_lo; r < r_hi; ++r) p.rank_load[r] = lds_load[r];
+  }
+}
+
+// LDS carve-up: the sort keys and the label-scan tables are never live at the same time.
+constexpr size_t kLdsTabSumBytes = sizeof(int64_t) * (2 * kPlanWaves + 1) * kLdsLabels;
+constexpr size_t kLdsTabCntBytes = sizeof(int32_t) * (2 * kPlanWaves + 1) * kLdsLabels;
+constexpr size_t kLdsSortBytes = sizeof(uint64_t) * kLdsSortKeys;
+constexpr size_t kLdsUnionBytes =
+    (kLdsTabSumBytes + kLdsTabCntBytes) > kLdsSortBytes ? (kLdsTabSumBytes + kLdsTabCntBytes)
+                                                        : kLdsSortBytes;
+
+__device__ __forceinline__ void zero_tables(int64_t* tab_sum, int32_t* tab_cnt, int n_labels) {
+  const size_t n = (size_t)(2 * kPlanWaves + 1) * n_labels;
+  for (size_t x = threadIdx.x; x < n; x += T) {
+    tab_sum[x] = 0;
+    tab_cnt[x] = 0;
+  }
+  __syncthreads();
+}
+
+__global__ __launch_bounds__(kPlanThreads) void plan_kernel(const PlanDev p) {
+  __shared__ __align__(16) unsigned char lds_union[kLdsUnionBytes];
+  __shared__ int64_t lds_load[kMaxDp];
+  __shared__ BlockScratch bs;
+  __shared__ int s_invalid, s_exceeds, s_bad;
+
+  const int tid = threadIdx.x;
+  const int N = p.N, G = p.G, R = p.R, S = p.S, D = p.D, C = p.C, K = p.K, P = p.P;
+  const int halves = p.halves;
+  const int n_dst = D * C;
+  const int64_t B = p.B;
+
+  // ---- phase 0: clear accumulators --------------------------------------------------------
+  if (tid == 0) { s_invalid = 0; s_exceeds = 0; s_bad = -1; }
+  for (int64_t x = tid; x < (int64_t)S * n_dst; x += T) p.a2a[x] = 0;
+  for (int x = tid; x < S; x += T) p.src_rows_needed[x] = 0;
+  for (int x = tid; x < n_dst; x += T) p.shard_rows[x] = 0;
+  for (int x = tid; x < D; x += T) { p.n_seq[x] = 0; p.n_mb[x] = 0; p.rank_load[x] = 0; }
+  __syncthreads();
+
+  // ---- phase 1: validation and padded chunk geometry --------------------------------------
+  // K equal chunks per sequence, each the smallest multiple of P that covers ceil(L/K) rows.
+  const int64_t lp_cap = B < 0x7fffffffll ? B : 0x7fffffffll;
+  int64_t real_rows = 0;
+  for (int i = tid; i < N; i += T) {
+    int32_t L = p.lengths[i];
+    bool invalid = false;
+    if (L < 1) { invalid = true; L = 1; }
+    int64_t g = p.seq_group_in ? (int64_t)p.seq_group_in[i] : ((int64_t)i * G) / N;
+    if (g < 0 || g >= G) { invalid = true; g = 0; }
+    if (p.seq_row_in && p.seq_row_in[i] < 0) invalid = true;
+    const int64_t per = ((int64_t)L + K - 1) / K;
+    int64_t m = (int64_t)P * ((per + P - 1) / P);
+    const bool exceeds = m * K > lp_cap;
+    if (exceeds) m = 1;
+    p.seq_group[i] = (int32_t)g;
+    p.m[i] = (int32_t)m;
+    real_rows += L;
+    if (invalid) { s_invalid = 1; s_bad = i; }
+    else if (exceeds) { s_exceeds = 1; atomicMax(&s_bad, i); }
+  }
+  __syncthreads();
+  if (s_invalid || s_exceeds) {
+    if (tid == 0) {
+      PlanHeader h = {};
+      h.status = s_invalid ? 1 : 2;
+      h.bad_index = s_bad;
+      *p.hdr = h;
+    }
+    return;
+  }
+  {
+    int64_t tot;
+    block_excl_scan(real_rows, bs, &tot);
+    real_rows = tot;
+  }
+
+  // Scan tables: LDS when the label count fits, else the workspace.
+  const int lmax = G > D ? G : D;
+  int64_t* tab_sum;
+  int32_t* tab_cnt;
+  if (lmax <= kLdsLabels) {
+    tab_sum = reinterpret_cast<int64_t*>(lds_union);
+    tab_cnt = reinterpret_cast<int32_t*>(lds_union + kLdsTabSumBytes);
+  } else {
+    tab_sum = p.lab_sum;
+    tab_cnt = p.lab_cnt;
+  }
+
+  // ---- phase 2: source offsets and replica choice ------------------------------------------
+  // Packed row offset = exclusive scan of L over the group's earlier members; the k-th of a
+  // group's n members is read from replica floor(k*R/n) ("from their computation origins").
+  zero_tables(tab_sum, tab_cnt, G);
+  label_scan(
+      N, G, [&](int i) { return p.seq_group[i]; }, [&](int i) { return (int64_t)p.lengths[i]; },
+      [&](int i, int32_t k, int64_t row) {
+        p.slot[i] = k;
+        p.seq_row[i] = p.seq_row_in ? p.seq_row_in[i] : row;
+      },
+      tab_sum, tab_cnt);
+  {
+    const int32_t* group_cnt = tab_cnt + 2 * (size_t)kPlanWaves * G;
+    for (int i = tid; i < N; i += T) {
+      const int g = p.seq_group[i];
+      const int64_t t = ((int64_t)p.slot[i] * R) / group_cnt[g];
+      const int s = g * R + (int)t;
+      p.seq_shard[i] = s;
+      atomicMax(reinterpret_cast<unsigned long long*>(&p.src_rows_needed[s]),
+                (unsigned long long)(p.seq_row[i] + p.lengths[i]));
+    }
+  }
+  __syncthreads();
+
+  // ---- phase 3: sort by (padded length desc, index asc), then list scheduling --------------
+  uint64_t* keys = p.n_pow2 <= kLdsSortKeys ? reinterpret_cast<uint64_t*>(lds_union) : p.sort_keys;
+  for (int i = tid; i < p.n_pow2; i += T) {
+    uint64_t key = ~0ull;
+    if (i < N) {
+      const int64_t lp = (int64_t)p.m[i] * K;
+      key = ((uint64_t)(0x7fffffffll - lp) << 32) | (uint32_t)i;
+    }
+    keys[i] = key;
+  }
+  __syncthreads();
+  bitonic_sort(keys, p.n_pow2);
+  if (wave_id() == 0) lpt_wave0(p, keys, lds_load);
+  __syncthreads();
+
+  // ---- phase 4: packing order, destination offsets, micro-batches --------------------------
+  zero_tables(tab_sum, tab_cnt, D);
+  label_scan(
+      N, D, [&](int i) { return p.rank[i]; },
+      [&](int i) { return (int64_t)p.m[i] * halves; },
+      [&](int i, int32_t k, int64_t row) {
+        p.slot[i] = k;
+        p.dst_row[i] = row;
+      },
+      tab_sum, tab_cnt);
+  const int64_t* rank_rows = tab_sum + 2 * (size_t)kPlanWaves * D;
+  const int32_t* rank_cnt = tab_cnt + 2 * (size_t)kPlanWaves * D;
+  int64_t load_max = 0, load_min = 0;
+  {
+    // D <= 1024: one rank per thread.
+    const int32_t ns = tid < D ? rank_cnt[tid] : 0;
+    int64_t tot;
+    const int64_t ex = block_excl_scan(ns, bs, &tot);
+    if (tid < D) {
+      p.rank_seq_base[tid] = (int32_t)ex;
+      p.n_seq[tid] = ns;
+      for (int c = 0; c < C; ++c) p.shard_rows[(size_t)tid * C + c] = rank_rows[tid];
+    }
+    if (tid == 0) p.rank_seq_base[D] = N;
+    const int64_t ld = tid < D ? p.rank_load[tid] : 0;
+    load_max = block_reduce_max(tid < D ? ld : INT64_MIN, bs);
+    load_min = block_reduce_min(tid < D ? ld : INT64_MAX, bs);
+  }
+  __syncthreads();
+  // sequences of a rank in ascending index; row_packed[pos] = destination row of the pos-th
+  int64_t* row_packed = reinterpret_cast<int64_t*>(p.sort_keys);
+  for (int i = tid; i < N; i += T) {
+    const int pos = p.rank_seq_base[p.rank[i]] + p.slot[i];
+    p.seq_ids[pos] = i;
+    row_packed[pos] = p.dst_row[i];
+  }
+  __syncthreads();
+  // Next-fit: the micro-batch that starts at slot s ends before the first slot u whose
+  // inclusive padded prefix exceeds prefix(s) + B.  Padded prefix = C * destination row.
+  for (int pos = tid; pos < N; pos += T) {
+    const int r = p.rank[p.seq_ids[pos]];
+    const int base = p.rank_seq_base[r];
+    const int n = rank_cnt[r];
+    const int s = pos - base;
+    const int64_t limit = row_packed[pos] * C + B;
+    int lo = s + 1, hi = n + 1;   // smallest u in [s+1, n] with E(u) > limit, else n+1
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      const int64_t e = (mid < n ? row_packed[base + mid] : rank_rows[r]) * C;
+      if (e > limit) hi = mid; else lo = mid + 1;
+    }
+    p.next_start[pos] = lo <= n ? lo - 1 : n;
+  }
+  __syncthreads();
+  for (int r = tid; r < D; r += T) {
+    const int base = p.rank_seq_base[r];
+    const int n = rank_cnt[r];
+    int s = 0, b = 0;
+    while (s < n) {
+      p.mb_tmp[base + r + b] = s;
+      s = p.next_start[base + s];
+      ++b;
+    }
+    p.mb_tmp[base + r + b] = n;
+    p.n_mb[r] = b;
+  }
+  __syncthreads();
+  int n_mb_max = 0;
+  int64_t mb_table_len = 0, cu_len = 0;
+  {
+    const int32_t nm = tid < D ? p.n_mb[tid] : 0;
+    const int32_t ns = tid < D ? rank_cnt[tid] : 0;
+    const int64_t ex1 = block_excl_scan(tid < D ? nm + 1 : 0, bs, &mb_table_len);
+    const int64_t ex2 = block_excl_scan(tid < D ? nm + ns : 0, bs, &cu_len);
+    if (tid < D) {
+      p.rank_mbt_base[tid] = (int32_t)ex1;
+      p.rank_cu_base[tid] = (int32_t)ex2;
+    }
+    if (tid == 0) {
+      p.rank_mbt_base[D] = (int32_t)mb_table_len;
+      p.rank_cu_base[D] = (int32_t)cu_len;
+    }
+    n_mb_max = (int)block_reduce_max(nm, bs);
+  }
+  __syncthreads();
+  // compact the per-rank micro-batch tables
+  for (int x = tid; x < N + D; x += T) {
+    int lo = 0, hi = D;   // last rank r with rank_seq_base[r] + r <= x
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (p.rank_seq_base[mid] + mid <= x) lo = mid; else hi = mid;
+    }
+    const int r = lo;
+    const int b = x - (p.rank_seq_base[r] + r);
+    if (b <= p.n_mb[r]) {
+      const int s = p.mb_tmp[x];
+      const int n = rank_cnt[r];
+      const int o = p.rank_mbt_base[r] + b;
+      p.mb_seq_start[o] = s;
+      p.mb_row_start[o] = s < n ? row_packed[p.rank_seq_base[r] + s] : rank_rows[r];
+    }
+  }
+  __syncthreads();
+  // micro-batch of every sequence; cu_seqlens (local rows, restarting in every micro-batch)
+  for (int pos = tid; pos < N; pos += T) {
+    const int i = p.seq_ids[pos];
+    const int r = p.rank[i];
+    const int s = pos - p.rank_seq_base[r];
+    const int32_t* starts = p.mb_seq_start + p.rank_mbt_base[r];
+    int lo = 0, hi = p.n_mb[r];   // last b with starts[b] <= s
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (starts[mid] <= s) lo = mid; else hi = mid;
+    }
+    p.mb[i] = lo;
+    p.cu_seqlens[p.rank_cu_base[r] + s + lo] =
+        (int32_t)(row_packed[pos] - p.mb_row_start[p.rank_mbt_base[r] + lo]);
+  }
+  for (int x = tid; x < (int)mb_table_len; x += T) {
+    int lo = 0, hi = D;   // last rank r with rank_mbt_base[r] <= x
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (p.rank_mbt_base[mid] <= x) lo = mid; else hi = mid;
+    }
+    const int r = lo;
+    const int b = x - p.rank_mbt_base[r];
+    if (b < p.n_mb[r]) {
+      const int64_t rows = p.mb_row_start[x + 1] - p.mb_row_start[x];
+      if (rows > 0x7fffffffll) s_invalid = 1;   // cu_seqlens entries are int32
+      p.cu_seqlens[p.rank_cu_base[r] + p.mb_seq_start[x + 1] + b] = (int32_t)rows;
+    }
+  }
+
+  // ---- phase 5: segment table and all-to-all counts ----------------------------------------
+  // One segment per (sequence, chunk): m rows contiguous in both layouts.  SP rank c holds chunk
+  // c and, with zigzag, chunk 2C-1-c right after it.
+  const int64_t n_seg = (int64_t)N * K;
+  for (int64_t t = tid; t < n_seg; t += T) {
+    const int pos = (int)(t / K);
+    const int rem = (int)(t - (int64_t)pos * K);
+    const int c = rem / halves;
+    const int h = rem - c * halves;
+    const int i = p.seq_ids[pos];
+    const int r = p.rank[i];
+    const int base = p.rank_seq_base[r];
+    const int n = rank_cnt[r];
+    const int64_t e = (int64_t)halves * ((int64_t)C * base + (int64_t)c * n + (pos - base)) + h;
+    const int32_t mi = p.m[i];
+    const int kappa = h == 0 ? c : 2 * C - 1 - c;
+    const int64_t p0 = (int64_t)kappa * mi;
+    int64_t n_real = (int64_t)p.lengths[i] - p0;
+    n_real = n_real < 0 ? 0 : (n_real > mi ? mi : n_real);
+    const int s = p.seq_shard[i];
+    p.seg_src_shard[e] = s;
+    p.seg_src_row[e] = p.seq_row[i] + p0;
+    p.seg_dst_row[e] = p.dst_row[i] + (int64_t)h * mi;
+    p.seg_n_real[e] = (int32_t)n_real;
+    p.seg_n_rows[e] = mi;
+    p.seg_pos0[e] = (int32_t)p0;
+    p.seg_dst_shard[e] = r * C + c;
+    if (n_real > 0)
+      atomicAdd(reinterpret_cast<unsigned long long*>(&p.a2a[(size_t)s * n_dst + r * C + c]),
+                (unsigned long long)n_real);
+  }
+  for (int q = tid; q <= n_dst; q += T) {
+    int64_t v = n_seg;
+    if (q < n_dst) {
+      const int r = q / C, c = q - r * C;
+      v = (int64_t)halves * ((int64_t)C * p.rank_seq_base[r] + (int64_t)c * rank_cnt[r]);
+    }
+    p.shard_seg_start[q] = (int32_t)v;
+  }
+  int64_t dst_rows = 0;
+  {
+    int64_t tot;
+    block_excl_scan(tid < D ? rank_rows[tid] * C : 0, bs, &tot);
+    dst_rows = tot;
+  }
+  if (tid == 0) {
+    PlanHeader h = {};
+    h.status = s_invalid ? 1 : 0;
+    h.bad_index = -1;
+    h.n_segments = (int32_t)n_seg;
+    h.n_mb_max = n_mb_max;
+    h.cu_seqlens_len = (int32_t)cu_len;
+    h.mb_table_len = (int32_t)mb_table_len;
+    h.total_real_rows = real_rows;
+    h.total_dst_rows = dst_rows;
+    h.rank_load_min = load_min;
+    h.rank_load_max = load_max;
+    *p.hdr = h;
+  }
+}
+
+}  // namespace
+
+void launch_plan(const PlanDev& p, hipStream_t stream) {
+  hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, stream, p);
+}
+
+}  // namespace earl

@@ -108,6 +108,20 @@ class Workload:
         return int(self.lengths[self.seq_group == g].astype(np.int64).sum())
 
     # ---- field values -------------------------------------------------------------------
+    def hidden_pool(self, width: int) -> np.ndarray:
+        """The pool of distinct N(0,1) bf16 rows the wide field is drawn from."""
+        return self._hidden_pool(width)
+
+    def hidden_rows_index(self, g: int) -> np.ndarray:
+        """Pool row of every row of group g's buffer of the wide field, in buffer order, so
+        that the buffer can be materialised by any gather (pool[index]), e.g. on the device."""
+        members = self.group_members(g)
+        lens = self.lengths[members].astype(np.int64)
+        seq = np.repeat(members.astype(np.int64), lens)
+        starts = np.cumsum(lens) - lens
+        pos = np.arange(int(lens.sum()), dtype=np.int64) - np.repeat(starts, lens)
+        return self.hidden_pool_index(seq, pos)
+
     def _hidden_pool(self, width: int) -> np.ndarray:
         if width not in self._pool:
             rng = _stream(self.seed, self.name, "hidden_pool", width)
@@ -153,10 +167,7 @@ class Workload:
             per_seq = rng.standard_normal(len(members)).astype(np.float32)
             out = np.repeat(per_seq, lens).view(np.uint32)
         elif field.kind == "hidden":
-            seq = np.repeat(members.astype(np.int64), lens)
-            starts = np.cumsum(lens) - lens
-            pos = np.arange(rows, dtype=np.int64) - np.repeat(starts, lens)
-            out = self._hidden_pool(field.width)[self.hidden_pool_index(seq, pos)]
+            out = self._hidden_pool(field.width)[self.hidden_rows_index(g)]
         elif field.kind == "bytes":
             out = rng.integers(0, 256, size=(rows, field.row_bytes),
                                dtype=np.uint8).view(field.np_dtype)

@@ -1,0 +1,91 @@
+"""The C-ABI library loads and exports what include/earl_dispatch.h declares; host-side argument
+checks answer without touching a GPU."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2510_05943_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "earl_dispatch.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(earl_[a-z_]+)\s*\(", text)))
+
+
+def test_header_functions_are_exported():
+    lib = B.load_library()
+    names = declared_functions()
+    assert set(names) == set(B.EXPORTED)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_status_strings():
+    lib = B.load_library()
+    seen = {lib.earl_status_string(s).decode() for s in range(5)}
+    assert len(seen) == 5
+    assert lib.earl_status_string(99).decode() == "unknown status"
+
+
+def test_workspace_bytes_validation_and_growth():
+    src, dst = B.SrcLayout(8), B.DstLayout(dp=8, sp=4, zigzag=1, mb_token_budget=131072)
+    small = B.plan_workspace_bytes(64, src, dst)
+    big = B.plan_workspace_bytes(2048, src, dst)
+    assert 0 < small < big < 64 << 20
+    bad = [
+        (0, src, dst),
+        ((1 << 20) + 1, src, dst),
+        (64, B.SrcLayout(0), dst),
+        (64, B.SrcLayout(8, 0), dst),
+        (64, B.SrcLayout(4096, 2), dst),
+        (64, src, B.DstLayout(dp=0)),
+        (64, src, B.DstLayout(dp=1025)),
+        (64, src, B.DstLayout(dp=1, sp=0)),
+        (64, src, B.DstLayout(dp=1, sp=65)),
+        (64, src, B.DstLayout(dp=1, zigzag=2)),
+        (64, src, B.DstLayout(dp=1, pad_multiple=0)),
+        (64, src, B.DstLayout(dp=1, mb_token_budget=0)),
+        (64, src, B.DstLayout(dp=1, balance_policy=7)),
+    ]
+    for n, s, d in bad:
+        with pytest.raises(B.EarlError) as e:
+            B.plan_workspace_bytes(n, s, d)
+        assert e.value.status == B.EARL_INVALID_ARG
+
+
+def test_plan_build_rejects_bad_host_arguments_without_a_gpu():
+    lib = B.load_library()
+    src, dst = B.SrcLayout(1).c(), B.DstLayout(dp=1).c()
+    handle = C.c_void_p(0x1234)
+    # null lengths / null workspace / misaligned workspace / small workspace
+    assert lib.earl_plan_build(None, 4, C.byref(src), C.byref(dst), 256, 1 << 20, None,
+                               C.byref(handle)) == B.EARL_INVALID_ARG
+    assert handle.value is None
+    assert lib.earl_plan_build(256, 4, C.byref(src), C.byref(dst), None, 1 << 20, None,
+                               C.byref(handle)) == B.EARL_INVALID_ARG
+    assert lib.earl_plan_build(256, 4, C.byref(src), C.byref(dst), 256 + 8, 1 << 20, None,
+                               C.byref(handle)) == B.EARL_INVALID_ARG
+    assert lib.earl_plan_build(256, 4, C.byref(src), C.byref(dst), 256, 16, None,
+                               C.byref(handle)) == B.EARL_CAPACITY
+    assert b"workspace" in lib.earl_last_error_message()
+    assert lib.earl_plan_build(256, 4, C.byref(src), C.byref(dst), 256, 1 << 20, None,
+                               None) == B.EARL_INVALID_ARG
+    # null plan handles
+    assert lib.earl_dispatch(None, None, 0, None, None, None) == B.EARL_INVALID_ARG
+    assert lib.earl_dispatch_inverse(None, None, 0, None) == B.EARL_INVALID_ARG
+    assert lib.earl_plan_get_summary(None, None) == B.EARL_INVALID_ARG
+    assert lib.earl_plan_destroy(None) == B.EARL_OK
+
+
+def test_product_path_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2510_05943_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for fn in files:
+            if fn.endswith((".py", ".hip", ".h")):
+                text = open(os.path.join(dirpath, fn)).read()
+                assert "oracle" not in text.replace("the CPU oracle's tests", ""), fn

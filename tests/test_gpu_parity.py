@@ -1,0 +1,345 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle, bit for bit.
+
+Everything here is integer or byte work, so the bar is exact equality on every output: plan
+arrays, segment table, all-to-all counts, every destination shard of every field, position ids
+and cu_seqlens.  Sizes span several 64 KiB tiles per shard and ragged tails; edge cases cover
+empty ranks, single-row sequences, odd row widths, explicit source offsets, replicated
+sources, large label counts and the error paths.
+"""
+import numpy as np
+import pytest
+
+import checkers
+from oracle import earl_oracle as O
+from paper_2510_05943_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def H():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.fail("no GPU visible: the GPU parity tests need a real MI355X")
+    import gpu_harness
+    return gpu_harness
+
+
+def oracle_plan(w, seq_row=None):
+    return O.build_plan(w.lengths, n_groups=w.n_groups, replication=w.replication,
+                        seq_group=w.seq_group, seq_row=seq_row, dp=w.dp, sp=w.sp, zigzag=w.zigzag,
+                        pad_multiple=w.pad_multiple, mb_token_budget=w.mb_token_budget)
+
+
+PLAN_KEYS = ("rank", "slot", "mb", "dst_row", "seq_shard", "seq_row", "seq_ids", "mb_seq_start",
+             "mb_row_start", "cu_seqlens", "n_seq", "n_mb", "shard_rows", "a2a_counts",
+             "rank_load")
+SEG_KEYS = ("src_shard", "src_row", "dst_shard", "dst_row", "n_real", "n_rows", "pos0")
+
+
+def assert_plan_equal(res, plan):
+    for k in PLAN_KEYS:
+        want = getattr(plan, k)
+        got = res[k]
+        assert got.shape == np.asarray(want).shape, (k, got.shape, np.asarray(want).shape)
+        assert np.array_equal(got, want), k
+    for k in SEG_KEYS:
+        assert np.array_equal(res["segments"][k], getattr(plan, "seg_" + k)), "seg_" + k
+    assert np.array_equal(res["segments"]["shard_seg_start"], plan.shard_seg_start)
+    assert res["total_real_rows"] == plan.total_real_rows
+    assert res["total_dst_rows"] == plan.total_dst_rows
+    assert res["n_segments"] == plan.N * plan.K
+    assert res["n_mb_max"] == int(plan.n_mb.max())
+    assert res["cu_seqlens_len"] == len(plan.cu_seqlens)
+    assert res["mb_table_len"] == len(plan.mb_seq_start)
+    assert res["rank_load_min"] == int(plan.rank_load.min())
+    assert res["rank_load_max"] == int(plan.rank_load.max())
+    need = np.zeros(plan.S, np.int64)
+    for i in range(plan.N):
+        s = int(plan.seq_shard[i])
+        need[s] = max(need[s], int(plan.seq_row[i]) + int(plan.L[i]))
+    assert np.array_equal(res["src_rows_needed"], need)
+
+
+def assert_dispatch_equal(w, plan, out, shards_host, fields):
+    for q in range(plan.D * plan.C):
+        assert np.array_equal(out["position_ids"][q], O.position_ids_shard(plan, q)), ("pos", q)
+    assert np.array_equal(out["cu_seqlens"], plan.cu_seqlens)
+    for f in fields:
+        for q in range(plan.D * plan.C):
+            want = O.dispatch_field_shard(plan, q, shards_host[f.name], f.np_dtype, f.width,
+                                          f.pad_scalar)
+            got = out["fields"][f.name][q]
+            assert got.shape == want.shape, (f.name, q)
+            assert np.array_equal(got, want), (f.name, q)
+
+
+# ---------------------------------------------------------------------------------------
+# the five workloads
+# ---------------------------------------------------------------------------------------
+@pytest.mark.parametrize("seed", [0, 1, 2])
+@pytest.mark.parametrize("name", synth.CONFIG_NAMES)
+def test_plan_parity_full_size(H, name, seed):
+    w = synth.make_workload(name, seed=seed)
+    plan = H.build_plan(w)
+    res = H.plan_result(plan)
+    assert_plan_equal(res, oracle_plan(w))
+    H.B.plan_destroy(plan)
+
+
+@pytest.mark.parametrize("name,seed,scale", [
+    ("tiny", 0, 1.0), ("tiny", 1, 1.0), ("tiny", 2, 1.0),
+    ("mid", 0, 1.0), ("mid", 1, 0.25),
+    ("agentic", 0, 1.0), ("agentic", 2, 0.25),
+    ("heavy", 0, 0.01), ("heavy", 1, 0.02),
+    ("longctx", 0, 0.04),
+])
+def test_dispatch_parity(H, name, seed, scale):
+    w = synth.make_workload(name, seed=seed, scale=scale)
+    oplan = oracle_plan(w)
+    plan = H.build_plan(w)
+    assert_plan_equal(H.plan_result(plan), oplan)
+    groups, shards = H.host_sources(w, w.fields)
+    out = H.run_dispatch(w, plan, w.fields, src_host=shards)
+    assert_dispatch_equal(w, oplan, out, shards, w.fields)
+    H.B.plan_destroy(plan)
+
+
+def test_dispatch_is_deterministic_and_field_order_free(H):
+    w = synth.make_workload("mid", seed=3, scale=0.25)
+    plan = H.build_plan(w)
+    _, shards = H.host_sources(w, w.fields)
+    a = H.run_dispatch(w, plan, w.fields, src_host=shards)
+    b = H.run_dispatch(w, plan, tuple(reversed(w.fields)), src_host=shards)
+    one = H.run_dispatch(w, plan, w.fields[:1], src_host=shards, want_position_ids=False,
+                         want_cu=False)
+    for f in w.fields:
+        for x, y in zip(a["fields"][f.name], b["fields"][f.name]):
+            assert np.array_equal(x, y)
+    for x, y in zip(a["fields"][w.fields[0].name], one["fields"][w.fields[0].name]):
+        assert np.array_equal(x, y)
+    H.B.plan_destroy(plan)
+
+
+def test_replicas_are_read_only_where_the_plan_says(H):
+    """Rows of a replica outside its share are poisoned; the result must not change."""
+    w = synth.make_workload("agentic", seed=1, scale=0.25)
+    oplan = oracle_plan(w)
+    plan = H.build_plan(w)
+    _, shards = H.host_sources(w, w.fields)
+    poisoned = {}
+    for f in w.fields:
+        bufs = [np.full_like(b, 0xA5) for b in shards[f.name]]
+        for i in range(w.n_seqs):
+            s, r0, n = int(oplan.seq_shard[i]), int(oplan.seq_row[i]), int(w.lengths[i])
+            bufs[s][r0:r0 + n] = shards[f.name][s][r0:r0 + n]
+        poisoned[f.name] = bufs
+    out = H.run_dispatch(w, plan, w.fields, src_host=poisoned)
+    assert_dispatch_equal(w, oplan, out, shards, w.fields)
+    H.B.plan_destroy(plan)
+
+
+# ---------------------------------------------------------------------------------------
+# small random batches: odd widths, every layout option, trace-back check and inverse
+# ---------------------------------------------------------------------------------------
+def small_cases():
+    rng = np.random.default_rng(11)
+    cases = []
+    for t in range(24):
+        N = int(rng.integers(1, 14))
+        G = int(rng.integers(1, 4))
+        R = int(rng.choice([1, 1, 2, 4]))
+        D = int(rng.integers(1, 4))
+        C = int(rng.choice([1, 2, 3, 4]))
+        z = int(rng.integers(0, 2))
+        P = int(rng.choice([1, 1, 2, 8]))
+        L = rng.integers(1, 60, size=N)
+        K = 2 * C if (z and C > 1) else C
+        worst = K * P * (-(-(-(-int(L.max()) // K)) // P))
+        B = int(worst + rng.integers(0, 3 * worst))
+        grp = rng.integers(0, G, size=N) if t % 2 else None
+        cases.append(dict(L=L, G=G, R=R, D=D, C=C, z=z, P=P, B=B, grp=grp, seed=t))
+    return cases
+
+
+ODD_FIELDS = (synth.F_ID, synth.F_MASK, synth.bytes_field("wide", 2, 24, 0xBEEF),
+              synth.bytes_field("odd", 4, 3, 0x01020304), synth.bytes_field("b8", 8, 1, 0x1122334455667788),
+              synth.bytes_field("b6", 2, 3, 0x7777), synth.bytes_field("row16", 4, 4, 0xABCD0123),
+              synth.bytes_field("bf16x64", 2, 64, 0x3F80))
+
+
+@pytest.mark.parametrize("case", small_cases(), ids=lambda c: f"case{c['seed']}")
+def test_small_batches(H, case):
+    w = synth.custom_workload(case["L"], n_groups=case["G"], replication=case["R"],
+                              seq_group=case["grp"], dp=case["D"], sp=case["C"], zigzag=case["z"],
+                              pad_multiple=case["P"], mb_token_budget=case["B"], fields=ODD_FIELDS,
+                              seed=case["seed"])
+    oplan = oracle_plan(w)
+    plan = H.build_plan(w, explicit_groups=bool(case["seed"] % 4 == 1))
+    res = H.plan_result(plan)
+    assert_plan_equal(res, oplan)
+    groups, shards = H.host_sources(w, w.fields)
+    out = H.run_dispatch(w, plan, w.fields, src_host=shards)
+    assert_dispatch_equal(w, oplan, out, shards, w.fields)
+    # the result explains itself: every row traces back to its source token
+    res["position_ids"] = out["position_ids"]
+    res["cu_seqlens"] = out["cu_seqlens"]
+    checkers.check_structure(res, w.lengths, w.dp, w.sp, oplan.K, w.pad_multiple, w.mb_token_budget)
+    src_row = checkers.packed_source_rows(w.lengths, w.seq_group, w.n_groups)
+    for f in w.fields:
+        pad = np.full((f.width,), f.pad_scalar & ((1 << (8 * f.scalar_bytes)) - 1), f.np_dtype)
+        checkers.check_self_describing(res, w.lengths, w.dp, w.sp, groups[f.name], w.seq_group,
+                                       src_row, out["fields"][f.name], pad)
+    # inverse: back to the rollout layout, untouched where nothing was read
+    import torch
+    back = {f.name: [torch.full_like(t, 0x5A) for t in out["src_dev"][f.name]] for f in w.fields}
+    bfields = [H.B.Field(f.scalar_bytes, f.width, f.pad_scalar, back[f.name], out["dev"][f.name])
+               for f in w.fields]
+    H.B.dispatch_inverse(plan, bfields)
+    torch.cuda.synchronize()
+    for f in w.fields:
+        want = [np.full_like(b, 0x5A) for b in shards[f.name]]
+        O.inverse_field(oplan, out["fields"][f.name], want)
+        for s in range(w.n_shards):
+            got = back[f.name][s].cpu().numpy().view(f.np_dtype).reshape(-1, f.width)
+            assert np.array_equal(got, want[s]), (f.name, s)
+    H.B.plan_destroy(plan)
+
+
+def test_explicit_source_rows_with_gaps(H):
+    rng = np.random.default_rng(21)
+    L = rng.integers(1, 300, size=37)
+    w = synth.custom_workload(L, n_groups=3, dp=3, sp=2, zigzag=1, pad_multiple=4,
+                              mb_token_budget=4096, fields=(synth.F_ID, synth.F_MASK,
+                                                            synth.bytes_field("h", 2, 40, 0)))
+    # every sequence starts 5 rows after the previous one ends, inside its group's buffer
+    packed = checkers.packed_source_rows(w.lengths, w.seq_group, w.n_groups)
+    k_in_group = np.zeros(len(L), np.int64)
+    for g in range(3):
+        idx = np.nonzero(w.seq_group == g)[0]
+        k_in_group[idx] = np.arange(len(idx))
+    seq_row = packed + 5 * (k_in_group + 1)
+    oplan = oracle_plan(w, seq_row=seq_row)
+    plan = H.build_plan(w, seq_row=seq_row)
+    assert_plan_equal(H.plan_result(plan), oplan)
+    shards = {}
+    for f in w.fields:
+        bufs = []
+        for g in range(3):
+            packed_buf = w.group_buffer(f, g)
+            idx = np.nonzero(w.seq_group == g)[0]
+            rows = int(seq_row[idx[-1]] + L[idx[-1]]) if len(idx) else 0
+            buf = np.full((rows, f.width), 0xEE, f.np_dtype)
+            for i in idx:
+                buf[seq_row[i]:seq_row[i] + L[i]] = packed_buf[packed[i]:packed[i] + L[i]]
+            bufs.append(buf)
+        shards[f.name] = bufs
+    out = H.run_dispatch(w, plan, w.fields, src_host=shards)
+    assert_dispatch_equal(w, oplan, out, shards, w.fields)
+    H.B.plan_destroy(plan)
+
+
+# ---------------------------------------------------------------------------------------
+# plan-only edge cases (no field data needed)
+# ---------------------------------------------------------------------------------------
+@pytest.mark.parametrize("desc,kw", [
+    ("one_sequence", dict(L=[1], dp=1, sp=1)),
+    ("one_sequence_many_ranks", dict(L=[77], dp=7, sp=4, zigzag=1, pad=8, B=1024)),
+    ("all_length_one", dict(L=[1] * 300, dp=3, sp=2, zigzag=1, B=8)),
+    ("fewer_sequences_than_ranks", dict(L=[5, 9, 2], dp=5, sp=2, zigzag=1, B=100)),
+    ("dp_100", dict(L=list(range(1, 1301)), dp=100, sp=1, B=100000)),
+    ("dp_1024", dict(L=[(i * 7919) % 997 + 1 for i in range(3000)], dp=1024, sp=1, B=100000)),
+    ("groups_300", dict(L=[(i * 31) % 50 + 1 for i in range(2500)], G=300, dp=4, sp=2, B=1 << 20)),
+    ("replicated_5x3", dict(L=[(i * 17) % 90 + 1 for i in range(157)], G=5, R=3, dp=2, sp=3, B=4096)),
+    ("n_9000_global_sort", dict(L=[(i * 2654435761) % 4000 + 1 for i in range(9000)], dp=16, sp=2,
+                                zigzag=1, pad=16, B=20000)),
+    ("loads_beyond_32_bits", dict(L=[1 << 30] * 5 + [(1 << 30) - 12345] * 6, dp=3, sp=1, B=(1 << 31) - 1)),
+    ("equal_lengths_round_robin", dict(L=[64] * 96, dp=8, sp=2, B=1 << 20)),
+    ("budget_exactly_one_sequence", dict(L=[16] * 40, dp=2, sp=2, zigzag=1, B=16)),
+])
+def test_plan_edge_cases(H, desc, kw):
+    w = synth.custom_workload(kw["L"], n_groups=kw.get("G", 1), replication=kw.get("R", 1),
+                              dp=kw["dp"], sp=kw["sp"], zigzag=kw.get("zigzag", 0),
+                              pad_multiple=kw.get("pad", 1), mb_token_budget=kw.get("B", 1 << 40))
+    if kw.get("G", 1) > 1:
+        rng = np.random.default_rng(len(kw["L"]))
+        w.seq_group = rng.integers(0, kw["G"], size=len(kw["L"])).astype(np.int32)
+    plan = H.build_plan(w)
+    assert_plan_equal(H.plan_result(plan), oracle_plan(w))
+    H.B.plan_destroy(plan)
+
+
+def test_dispatch_with_empty_ranks_and_no_fields(H):
+    w = synth.custom_workload([5, 9, 2], dp=5, sp=2, zigzag=1, mb_token_budget=100,
+                              fields=(synth.F_ID, synth.F_MASK))
+    oplan = oracle_plan(w)
+    plan = H.build_plan(w)
+    _, shards = H.host_sources(w, w.fields)
+    out = H.run_dispatch(w, plan, w.fields, src_host=shards)
+    assert_dispatch_equal(w, oplan, out, shards, w.fields)
+    H.B.dispatch(plan, [], position_ids=None, cu_seqlens=None)     # nothing to do is not an error
+    H.B.plan_destroy(plan)
+
+
+# ---------------------------------------------------------------------------------------
+# error paths: detected on the device or on the host, nothing is written
+# ---------------------------------------------------------------------------------------
+def test_errors(H):
+    import torch
+    B = H.B
+    # a zero length
+    w = synth.custom_workload([4, 0, 7], dp=2)
+    plan = H.build_plan(w)
+    with pytest.raises(B.EarlError) as e:
+        B.plan_get_summary(plan)
+    assert e.value.status == B.EARL_INVALID_ARG
+    B.plan_destroy(plan)
+    # a group id out of range
+    w = synth.custom_workload([4, 5, 7], n_groups=2, dp=2)
+    w.seq_group = np.array([0, 2, 1], np.int32)
+    plan = H.build_plan(w)
+    with pytest.raises(B.EarlError) as e:
+        B.plan_get_summary(plan)
+    assert e.value.status == B.EARL_INVALID_ARG
+    B.plan_destroy(plan)
+    # a sequence over the budget
+    w = synth.custom_workload([10, 200], dp=1, sp=2, zigzag=1, mb_token_budget=199)
+    plan = H.build_plan(w)
+    with pytest.raises(B.EarlError) as e:
+        B.plan_get_summary(plan)
+    assert e.value.status == B.EARL_SEQ_EXCEEDS_BUDGET
+    with pytest.raises(B.EarlError) as e:
+        B.dispatch(plan, [])
+    assert e.value.status == B.EARL_SEQ_EXCEEDS_BUDGET
+    B.plan_destroy(plan)
+    # capacity, alignment and field-shape errors leave the destination untouched
+    w = synth.custom_workload([33, 18, 90, 7], dp=2, sp=2, zigzag=1, mb_token_budget=4096,
+                              fields=(synth.F_ID,))
+    plan = H.build_plan(w)
+    sm = B.plan_get_summary(plan)
+    f = synth.F_ID
+    _, shards = H.host_sources(w, w.fields)
+    srcs = [H.to_dev(a) for a in shards[f.name]]
+    rows = [int(x) for x in sm["shard_rows"]]
+    good = [torch.full((r * 4 + 64,), 0xCD, dtype=torch.uint8, device="cuda") for r in rows]
+
+    def attempt(dsts, sb=4, width=1, srcs_=None):
+        with pytest.raises(B.EarlError) as e:
+            B.dispatch(plan, [B.Field(sb, width, 0, srcs_ or srcs, dsts)])
+        torch.cuda.synchronize()
+        for t in good:
+            assert bool((t == 0xCD).all().item())
+        return e.value.status
+
+    small = [t[:max(0, r * 4 - 4)] for t, r in zip(good, rows)]
+    assert attempt(small) == B.EARL_CAPACITY
+    assert attempt([t[4:] for t in good]) == B.EARL_INVALID_ARG          # not 16-byte aligned
+    assert attempt([t[:r * 4] for t, r in zip(good, rows)], sb=3) == B.EARL_INVALID_ARG
+    assert attempt([t[:r * 4] for t, r in zip(good, rows)], width=0) == B.EARL_INVALID_ARG
+    assert attempt([t[:r * 4] for t, r in zip(good, rows)],
+                   srcs_=[s[:-1] for s in srcs]) == B.EARL_CAPACITY       # source too short
+    assert attempt([None] + [t[:r * 4] for t, r in zip(good[1:], rows[1:])]) == B.EARL_INVALID_ARG
+    # and the same plan still works afterwards
+    out = H.run_dispatch(w, plan, w.fields, src_host=shards)
+    assert_dispatch_equal(w, oracle_plan(w), out, shards, w.fields)
+    B.plan_destroy(plan)
