@@ -1,0 +1,231 @@
+#!/usr/bin/env python3
+"""Benchmark of the re-layout hot path on one MI355X.
+
+A step is one pass of the whole path over one synthetic rollout batch that is already resident
+in HBM: earl_plan_build (source offsets, padded geometry, rank assignment, packing,
+micro-batches, segment table) followed by earl_dispatch (every field, every destination shard,
+position ids, cu_seqlens).  The default workload is "heavy" (2048 sequences, about 12.4 M tokens,
+2065 bytes per token, DP8 x SP4 zigzag: the largest of the five workloads by bytes moved);
+`--workload longctx` is the largest by tokens.
+
+Prints ONE JSON line:  value = real tokens re-laid-out per second over the timed steps
+(plan + dispatch, whole job); `roofline` prices the re-layout kernel alone against the 8 TB/s
+HBM peak with algorithmic bytes (each real source row read once, each destination row written
+once, 4 bytes of position id per destination row) over its HIP-event duration; `cpu_baseline`
+is the CPU oracle timed on a bounded sample of the same workload on the host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import hashlib
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+# HBM traffic of one re-layout kernel launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# (scaled by a plain copy kernel of known size, see profiles/), keyed by the sha256 of the kernel
+# source the counters were taken on.  A changed kernel reports null until re-measured.
+MEASURED_TRAFFIC = {
+    # "<sha256 of csrc/earl_copy.hip>": {"heavy": bytes_per_launch, "longctx": ...},
+}
+
+WORKLOAD_NOTES = {
+    "tiny": "c1 tiny: 64 seqs U[16,512], 4 src shards, 4 fields (13 B/token), DP2 SP1, budget 4096",
+    "mid": "c2 mid: 1024 seqs lognormal(2048,0.8) in [64,8192], 8 src shards, 5 fields (17 B/token), "
+           "DP8 SP2 zigzag, pad 64, budget 16384",
+    "agentic": "c3 agentic multi-turn: 512 episodes x 2-12 turns, TP4xDP2 replicated source "
+               "(8 shards), 5 fields (17 B/token), DP4 SP4, budget 65536",
+    "heavy": "c4 heavy intermediates: 2048 seqs lognormal(4096,0.9) in [128,32768] (~12.4M tokens), "
+             "8 src shards, 5 scalar fields + bf16[1024] (2065 B/token), DP8 SP4 zigzag, budget 131072",
+    "longctx": "c5 long-context: 256 seqs U[32768,131072] (~21.9M tokens), 8 src shards, 5 scalar "
+               "fields + bf16[512] (1041 B/token), DP2 SP8 zigzag, pad 128, budget 262144",
+}
+
+
+def kernel_source_hash() -> str:
+    path = os.path.join(ROOT, "paper_2510_05943_amd", "csrc", "earl_copy.hip")
+    with open(path, "rb") as f:
+        return hashlib.sha256(f.read()).hexdigest()
+
+
+def stage_workload(w, torch, B):
+    """Uploads every source shard buffer; the wide bf16 field is gathered from its pool on the
+    device (same bytes as the host generator: pool[index])."""
+    signed = {1: np.uint8, 2: np.int16, 4: np.int32, 8: np.int64}
+
+    def dev(a):
+        a = np.ascontiguousarray(a)
+        return torch.from_numpy(a.view(signed[a.dtype.itemsize])).cuda()
+
+    src = {}
+    for f in w.fields:
+        groups = []
+        for g in range(w.n_groups):
+            if f.kind == "hidden":
+                pool = dev(w.hidden_pool(f.width))
+                idx = torch.from_numpy(w.hidden_rows_index(g)).cuda()
+                groups.append(pool.index_select(0, idx))
+                del idx
+            else:
+                groups.append(dev(w.group_buffer(f, g)))
+        # replicas are separate buffers holding the same bytes
+        src[f.name] = [groups[s // w.replication] if s % w.replication == 0
+                       else groups[s // w.replication].clone() for s in range(w.n_shards)]
+    return src
+
+
+def run_gpu(args, torch, B, synth):
+    w = synth.make_workload(args.workload, seed=args.seed)
+    t0 = time.time()
+    src = stage_workload(w, torch, B)
+    torch.cuda.synchronize()
+    stage_s = time.time() - t0
+
+    stream = torch.cuda.current_stream()
+    src_l = B.SrcLayout(w.n_groups, w.replication)
+    dst_l = B.DstLayout(w.dp, w.sp, w.zigzag, w.pad_multiple, w.mb_token_budget)
+    lengths = torch.from_numpy(w.lengths.astype(np.int32)).cuda()
+    ws = torch.empty(B.plan_workspace_bytes(w.n_seqs, src_l, dst_l), dtype=torch.uint8, device="cuda")
+
+    # sizes of the destination shards come from a first plan
+    plan = B.plan_build(lengths, w.n_seqs, src_l, dst_l, ws, stream=stream)
+    sm = B.plan_get_summary(plan)
+    B.plan_destroy(plan)
+    shard_rows = [int(r) for r in sm["shard_rows"]]
+    fields = []
+    for f in w.fields:
+        dsts = [torch.empty((r * f.row_bytes,), dtype=torch.uint8, device="cuda") for r in shard_rows]
+        fields.append(B.Field(f.scalar_bytes, f.width, f.pad_scalar, src[f.name], dsts))
+    pos = [torch.empty((r,), dtype=torch.int32, device="cuda") for r in shard_rows]
+    cu = torch.empty((sm["cu_seqlens_len"],), dtype=torch.int32, device="cuda")
+
+    row_bytes = sum(f.row_bytes for f in w.fields)
+    algo_bytes = (row_bytes * sm["total_real_rows"] + row_bytes * sm["total_dst_rows"]
+                  + 4 * sm["total_dst_rows"])
+
+    def step(ev=None):
+        p = B.plan_build(lengths, w.n_seqs, src_l, dst_l, ws, stream=stream)
+        B.plan_get_summary(p)          # the consumer needs the shard sizes before it can dispatch
+        if ev is not None:
+            ev[0].record(stream)
+        B.dispatch(p, fields, position_ids=pos, cu_seqlens=cu, stream=stream)
+        if ev is not None:
+            ev[1].record(stream)
+        return p
+
+    plans = [step() for _ in range(args.warmup)]
+    torch.cuda.synchronize()
+    for p in plans:
+        B.plan_destroy(p)
+
+    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+              for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    plans = [step(events[k]) for k in range(args.steps)]
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for p in plans:
+        B.plan_destroy(p)
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    kern_ms = [a.elapsed_time(b) for a, b in events]
+    kern_avg_ms = float(np.mean(kern_ms))
+    achieved = algo_bytes / (kern_avg_ms * 1e-3) / 1e9
+    traffic = MEASURED_TRAFFIC.get(kernel_source_hash(), {}).get(args.workload)
+    return dict(w=w, sm=sm, ms_per_step=ms_per_step, kern_avg_ms=kern_avg_ms,
+                kern_min_ms=float(np.min(kern_ms)), achieved=achieved, algo_bytes=algo_bytes,
+                traffic=traffic, stage_s=stage_s, row_bytes=row_bytes)
+
+
+def run_cpu_baseline(args, synth):
+    """The oracle as it stands (single thread: Python loops + numpy slice copies), on a reduced
+    sequence count of the same workload; forward path only (plan, all fields, all shards,
+    position ids)."""
+    from oracle import earl_oracle as O
+    scale = {"tiny": 1.0, "mid": 1.0, "agentic": 1.0, "heavy": 1.0 / 16, "longctx": 1.0 / 16}[args.workload]
+    w = synth.make_workload(args.workload, seed=args.seed, scale=scale)
+    host = {f.name: [w.group_buffer(f, s // w.replication) for s in range(w.n_shards)]
+            for f in w.fields}
+    t0 = time.perf_counter()
+    plan = O.build_plan(w.lengths, n_groups=w.n_groups, replication=w.replication,
+                        seq_group=w.seq_group, dp=w.dp, sp=w.sp, zigzag=w.zigzag,
+                        pad_multiple=w.pad_multiple, mb_token_budget=w.mb_token_budget)
+    for q in range(w.dp * w.sp):
+        O.position_ids_shard(plan, q)
+        for f in w.fields:
+            O.dispatch_field_shard(plan, q, host[f.name], f.np_dtype, f.width, f.pad_scalar)
+    dt = time.perf_counter() - t0
+    return {"value": w.total_tokens / dt, "unit": "tokens/s", "cores": 1, "kind": "oracle",
+            "sample": f"{w.n_seqs} of the workload's sequences ({w.total_tokens} tokens), all fields, "
+                      f"all {w.dp * w.sp} destination shards, plan + dispatch, {dt:.2f} s of one core "
+                      f"(host has {os.cpu_count()} logical cpus)"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="heavy", choices=list(WORKLOAD_NOTES))
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU's share of the re-layout (all destination shards in one "
+              "HBM); there is no multi-GPU path in this build: run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2510_05943_amd import binding as B
+    from paper_2510_05943_amd import synth
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    B.load_library()
+    torch.cuda.set_device(0)
+
+    r = run_gpu(args, torch, B, synth)
+    w, sm = r["w"], r["sm"]
+    line = {
+        "metric": "re-layout throughput: tokens/s and achieved HBM GB/s (% of peak) at 1 GPU",
+        "value": sm["total_real_rows"] / (r["ms_per_step"] * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": r["ms_per_step"],
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u8",
+        "data": "synthetic",
+        "config": {"workload": WORKLOAD_NOTES[args.workload], "name": args.workload,
+                   "seed": args.seed, "n_seqs": w.n_seqs, "real_tokens": sm["total_real_rows"],
+                   "dst_rows": sm["total_dst_rows"], "bytes_per_token_row": r["row_bytes"],
+                   "dst_shards": w.dp * w.sp, "src_shards": w.n_shards,
+                   "step": "earl_plan_build + earl_plan_get_summary + earl_dispatch"},
+        "whole_path_GBps": r["algo_bytes"] / (r["ms_per_step"] * 1e-3) / 1e9,
+        "roofline": {"bound": "hbm", "achieved": r["achieved"], "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": r["achieved"] / HBM_PEAK_GBPS, "traffic": r["traffic"],
+                     "kernel": "relayout_kernel", "algorithmic_bytes_per_launch": r["algo_bytes"],
+                     "kernel_ms_avg": r["kern_avg_ms"], "kernel_ms_min": r["kern_min_ms"]},
+        "input_staging_s": r["stage_s"],
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = run_cpu_baseline(args, synth)
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -453,7 +453,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const PlanDev p) {
       const int64_t e = (mid < n ? row_packed[base + mid] : rank_rows[r]) * C;
       if (e > limit) hi = mid; else lo = mid + 1;
     }
-    p.next_start[pos] = lo <= n ? lo - 1 : n;
+    const int nxt = lo <= n ? lo - 1 : n;
+    p.next_start[pos] = nxt > s ? nxt : s + 1;   // a micro-batch always holds its first sequence
   }
   __syncthreads();
   for (int r = tid; r < D; r += T) {
