@@ -19,9 +19,9 @@ constexpr int kLdsLabels = 256;
 // Sort keys kept in LDS up to this many (power of two); more go to the workspace.
 constexpr int kLdsSortKeys = 8192;
 
-constexpr int kCopyThreads = 256;    // re-layout kernel workgroup (4 wavefronts)
+constexpr int kCopyThreads = 256;    // re-layout kernel workgroup (4 wavefronts, one tile each)
 constexpr int kVecBytes = 16;        // one global_load/store_dwordx4 per lane
-constexpr int kTileBytes = 64 * 1024;  // destination bytes handled by one workgroup
+constexpr int kTileBytes = kWave * kVecBytes;  // destination bytes handled by one wavefront
 
 // First bytes of the workspace; copied to the host together with the arrays that follow it.
 struct PlanHeader {
