@@ -38,9 +38,10 @@ constexpr size_t kAlign = 256;
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 size_t param_block_bytes(int n_fields, int n_src, int n_dst) {
+  const size_t n_recs = (size_t)n_fields * n_dst;
   size_t b = align_up(sizeof(DispatchDev));
-  b += align_up(sizeof(FieldDev) * (size_t)n_fields);
-  b += align_up(sizeof(int64_t) * ((size_t)n_fields * n_dst + 1));
+  b += align_up(sizeof(int64_t) * (n_recs + 1));
+  b += align_up(sizeof(TileRec) * n_recs);
   b += align_up(sizeof(void*) * (size_t)n_fields * ((size_t)n_src + n_dst));
   return b;
 }
@@ -51,7 +52,7 @@ struct Layout {
   size_t seq_group, seq_shard, seq_row, m, rank, slot, mb, dst_row;
   size_t seq_ids, next_start, mb_tmp, mb_seq_start, mb_row_start, cu_seqlens;
   size_t rank_seq_base, rank_mbt_base, rank_cu_base;
-  size_t seg_src_shard, seg_src_row, seg_dst_row, seg_n_real, seg_n_rows, seg_pos0, seg_dst_shard;
+  size_t segs, seg_dst_shard;
   size_t shard_seg_start, seg_real_prefix;
   size_t sort_keys, lab_sum, lab_cnt;
   size_t params_fwd, params_inv, params_bytes;
@@ -97,12 +98,7 @@ Layout make_layout(const Dims& d) {
   l.rank_seq_base = take(4 * (D + 1));
   l.rank_mbt_base = take(4 * (D + 1));
   l.rank_cu_base = take(4 * (D + 1));
-  l.seg_src_shard = take(4 * NK);
-  l.seg_src_row = take(8 * NK);
-  l.seg_dst_row = take(8 * NK);
-  l.seg_n_real = take(4 * NK);
-  l.seg_n_rows = take(4 * NK);
-  l.seg_pos0 = take(4 * NK);
+  l.segs = take(sizeof(SegRec) * NK);
   l.seg_dst_shard = take(4 * NK);
   l.shard_seg_start = take(4 * (DC + 1));
   l.seg_real_prefix = take(8 * (NK + 1));
@@ -178,6 +174,7 @@ struct earl_plan {
   bool summary_ready;
   int32_t status;
   bool inverse_ready;
+  std::vector<int32_t> seg_starts;      // first segment of every destination shard (+ total)
   std::vector<unsigned char> summary;   // host copy of the workspace's summary block
   PlanHeader hdr;
 };
@@ -193,6 +190,20 @@ int32_t ensure_summary(earl_plan* p) {
   std::memcpy(&p->hdr, p->summary.data() + p->l.hdr, sizeof(PlanHeader));
   p->status = p->hdr.status;
   p->summary_ready = true;
+  if (p->status == EARL_OK) {
+    // Segments are ordered by (rank, SP rank, position in rank, half): the first segment of
+    // every destination shard follows from the per-rank sequence counts.
+    const int32_t* n_seq = reinterpret_cast<const int32_t*>(p->summary.data() + p->l.n_seq);
+    const int D = p->d.D, C = p->d.C, halves = p->d.halves;
+    p->seg_starts.resize((size_t)D * C + 1);
+    int64_t base = 0;
+    for (int r = 0; r < D; ++r) {
+      for (int c = 0; c < C; ++c)
+        p->seg_starts[(size_t)r * C + c] = (int32_t)(halves * (C * base + (int64_t)c * n_seq[r]));
+      base += n_seq[r];
+    }
+    p->seg_starts[(size_t)D * C] = (int32_t)(halves * C * base);
+  }
   if (p->status == EARL_INVALID_ARG)
     fail(p->status, "sequence %d: length < 1, group out of range or negative row offset",
          p->hdr.bad_index);
@@ -233,18 +244,16 @@ int32_t upload_params(earl_plan* p, const std::vector<unsigned char>& block, siz
 struct BlockBuilder {
   std::vector<unsigned char> bytes;
   DispatchDev hd{};
-  FieldDev* fields() { return reinterpret_cast<FieldDev*>(bytes.data() + hd.fields_ofs); }
   int64_t* tile_start() { return reinterpret_cast<int64_t*>(bytes.data() + hd.tile_start_ofs); }
+  TileRec* recs() { return reinterpret_cast<TileRec*>(bytes.data() + hd.recs_ofs); }
   const void** ptrs() { return reinterpret_cast<const void**>(bytes.data() + hd.ptrs_ofs); }
-  void init(int n_fields, int n_tile_cols, int n_src, int n_dst) {
-    hd.n_fields = n_fields;
-    hd.n_dst = n_tile_cols;
-    hd.n_src = n_src;
+  void init(int n_recs, int n_fields, int n_src, int n_dst) {
+    hd.n_recs = n_recs;
     size_t off = align_up(sizeof(DispatchDev));
-    hd.fields_ofs = (uint32_t)off;
-    off += align_up(sizeof(FieldDev) * (size_t)n_fields);
     hd.tile_start_ofs = (uint32_t)off;
-    off += align_up(sizeof(int64_t) * ((size_t)n_fields * n_tile_cols + 1));
+    off += align_up(sizeof(int64_t) * ((size_t)n_recs + 1));
+    hd.recs_ofs = (uint32_t)off;
+    off += align_up(sizeof(TileRec) * (size_t)n_recs);
     hd.ptrs_ofs = (uint32_t)off;
     off += align_up(sizeof(void*) * (size_t)n_fields * ((size_t)n_src + n_dst));
     hd.total_bytes = (uint32_t)off;
@@ -296,14 +305,7 @@ int32_t check_field(const earl_plan* p, const earl_field& f, int idx, bool inver
 CopyArgs copy_args(const earl_plan* p, size_t params_off, int64_t n_tiles) {
   CopyArgs a{};
   a.params = reinterpret_cast<const DispatchDev*>(p->ws + params_off);
-  a.shard_rows = p->dev.shard_rows;
-  a.shard_seg_start = p->dev.shard_seg_start;
-  a.seg_dst_row = p->dev.seg_dst_row;
-  a.seg_src_row = p->dev.seg_src_row;
-  a.seg_src_shard = p->dev.seg_src_shard;
-  a.seg_n_real = p->dev.seg_n_real;
-  a.seg_n_rows = p->dev.seg_n_rows;
-  a.seg_pos0 = p->dev.seg_pos0;
+  a.segs = p->dev.segs;
   a.n_tiles = n_tiles;
   return a;
 }
@@ -378,12 +380,7 @@ int32_t earl_plan_build(const int32_t* lengths_dev, int32_t n_seqs, const earl_s
   v.rank_seq_base = reinterpret_cast<int32_t*>(w + l.rank_seq_base);
   v.rank_mbt_base = reinterpret_cast<int32_t*>(w + l.rank_mbt_base);
   v.rank_cu_base = reinterpret_cast<int32_t*>(w + l.rank_cu_base);
-  v.seg_src_shard = reinterpret_cast<int32_t*>(w + l.seg_src_shard);
-  v.seg_src_row = reinterpret_cast<int64_t*>(w + l.seg_src_row);
-  v.seg_dst_row = reinterpret_cast<int64_t*>(w + l.seg_dst_row);
-  v.seg_n_real = reinterpret_cast<int32_t*>(w + l.seg_n_real);
-  v.seg_n_rows = reinterpret_cast<int32_t*>(w + l.seg_n_rows);
-  v.seg_pos0 = reinterpret_cast<int32_t*>(w + l.seg_pos0);
+  v.segs = reinterpret_cast<SegRec*>(w + l.segs);
   v.seg_dst_shard = reinterpret_cast<int32_t*>(w + l.seg_dst_shard);
   v.shard_seg_start = reinterpret_cast<int32_t*>(w + l.shard_seg_start);
   v.sort_keys = reinterpret_cast<uint64_t*>(w + l.sort_keys);
@@ -457,18 +454,22 @@ int32_t earl_plan_export_segments(earl_plan* p, int32_t* src_shard, int64_t* src
   const int32_t st = ensure_summary(p);
   if (st != EARL_OK) return st;
   const size_t E = (size_t)p->hdr.n_segments;
-  auto get = [&](void* dst, const void* src, size_t bytes) -> hipError_t {
-    if (!dst || bytes == 0) return hipSuccess;
-    return hipMemcpy(dst, src, bytes, hipMemcpyDeviceToHost);
-  };
-  HIP_TRY(get(src_shard, p->dev.seg_src_shard, 4 * E));
-  HIP_TRY(get(src_row, p->dev.seg_src_row, 8 * E));
-  HIP_TRY(get(dst_shard, p->dev.seg_dst_shard, 4 * E));
-  HIP_TRY(get(dst_row, p->dev.seg_dst_row, 8 * E));
-  HIP_TRY(get(n_real, p->dev.seg_n_real, 4 * E));
-  HIP_TRY(get(n_rows, p->dev.seg_n_rows, 4 * E));
-  HIP_TRY(get(pos0, p->dev.seg_pos0, 4 * E));
-  HIP_TRY(get(shard_seg_start, p->dev.shard_seg_start, 4 * ((size_t)p->d.D * p->d.C + 1)));
+  const size_t n_dst = (size_t)p->d.D * p->d.C;
+  std::vector<SegRec> segs(E);
+  std::vector<int32_t> starts(n_dst + 1);
+  if (E) HIP_TRY(hipMemcpy(segs.data(), p->dev.segs, sizeof(SegRec) * E, hipMemcpyDeviceToHost));
+  HIP_TRY(hipMemcpy(starts.data(), p->dev.shard_seg_start, 4 * (n_dst + 1), hipMemcpyDeviceToHost));
+  if (dst_shard && E)
+    HIP_TRY(hipMemcpy(dst_shard, p->dev.seg_dst_shard, 4 * E, hipMemcpyDeviceToHost));
+  for (size_t e = 0; e < E; ++e) {
+    if (src_shard) src_shard[e] = segs[e].src_shard;
+    if (src_row) src_row[e] = segs[e].src_row;
+    if (dst_row) dst_row[e] = segs[e].dst_row;
+    if (n_real) n_real[e] = segs[e].n_real;
+    if (n_rows) n_rows[e] = segs[e].n_rows;
+    if (pos0) pos0[e] = segs[e].pos0;
+  }
+  if (shard_seg_start) std::memcpy(shard_seg_start, starts.data(), 4 * (n_dst + 1));
   return EARL_OK;
 }
 
@@ -501,45 +502,50 @@ int32_t earl_dispatch(earl_plan* p, const earl_field* fields, int32_t n_fields,
   const int F = n_fields + extra;
   if (F == 0) return EARL_OK;
   BlockBuilder b;
-  b.init(F, n_dst, S, n_dst);
-  FieldDev* fd = b.fields();
+  b.init(F * n_dst, F, S, n_dst);
   int64_t* ts = b.tile_start();
+  TileRec* recs = b.recs();
   const void** ptrs = b.ptrs();
   uint32_t pi = 0;
   int64_t tiles = 0;
   for (int f = 0; f < F; ++f) {
-    FieldDev& d = fd[f];
-    d.src_ptr_index = pi;
-    d.dst_ptr_index = pi + S;
+    TileRec proto{};
+    proto.src_ptr_index = pi;
+    proto.dst_ptr_index = pi + S;
     if (f < n_fields) {
       const earl_field& uf = fields[f];
-      d.kind = kFieldCopy;
-      d.scalar_bytes = uf.scalar_bytes;
-      d.row_bytes = uf.scalar_bytes * uf.width;
-      d.pad_scalar = replicate_scalar(uf.pad_scalar, uf.scalar_bytes);
+      proto.kind = kFieldCopy;
+      proto.scalar_bytes = uf.scalar_bytes;
+      proto.row_bytes = uf.scalar_bytes * uf.width;
+      proto.pad_scalar = replicate_scalar(uf.pad_scalar, uf.scalar_bytes);
       for (int s = 0; s < S; ++s) ptrs[pi + s] = uf.src_shard_ptrs[s];
       for (int q = 0; q < n_dst; ++q) ptrs[pi + S + q] = uf.dst_shard_ptrs[q];
     } else if (position_ids_shard_ptrs && f == n_fields) {
-      d.kind = kFieldPositionIds;
-      d.scalar_bytes = 4;
-      d.row_bytes = 4;
-      d.pad_scalar = 0;
+      proto.kind = kFieldPositionIds;
+      proto.scalar_bytes = 4;
+      proto.row_bytes = 4;
       for (int q = 0; q < n_dst; ++q) ptrs[pi + S + q] = position_ids_shard_ptrs[q];
     } else {
-      d.kind = kFieldLinear;
-      d.scalar_bytes = 4;
-      d.row_bytes = 4;
-      d.pad_scalar = 4ull * (uint64_t)p->hdr.cu_seqlens_len;
+      proto.kind = kFieldLinear;
+      proto.scalar_bytes = 4;
+      proto.row_bytes = 4;
       ptrs[pi] = p->dev.cu_seqlens;
       ptrs[pi + S] = cu_seqlens_dev;
     }
-    pi += S + n_dst;
     for (int q = 0; q < n_dst; ++q) {
+      TileRec& r = recs[(size_t)f * n_dst + q];
+      r = proto;
+      r.tile_first = tiles;
+      r.dst = const_cast<void*>(ptrs[pi + S + q]);
+      r.e_begin = p->seg_starts[q];
+      r.e_end = p->seg_starts[q + 1];
+      r.end_bytes = proto.kind == kFieldLinear
+                        ? (q == 0 ? 4ll * p->hdr.cu_seqlens_len : 0)
+                        : shard_rows[q] * (int64_t)proto.row_bytes;
       ts[(size_t)f * n_dst + q] = tiles;
-      int64_t bytes = d.kind == kFieldLinear ? (q == 0 ? (int64_t)d.pad_scalar : 0)
-                                             : shard_rows[q] * (int64_t)d.row_bytes;
-      tiles += (bytes + kTileBytes - 1) / kTileBytes;
+      tiles += (r.end_bytes + kTileBytes - 1) / kTileBytes;
     }
+    pi += S + n_dst;
   }
   ts[(size_t)F * n_dst] = tiles;
   if (tiles > 0x7fffffffll) return fail(EARL_INVALID_ARG, "too many tiles for one launch");
@@ -570,31 +576,31 @@ int32_t earl_dispatch_inverse(earl_plan* p, const earl_field* fields, int32_t n_
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   int64_t* prefix = reinterpret_cast<int64_t*>(p->ws + p->l.seg_real_prefix);
   if (!p->inverse_ready) {
-    launch_real_prefix(p->dev.seg_n_real, prefix, p->hdr.n_segments, stream);
+    launch_real_prefix(p->dev.segs, prefix, p->hdr.n_segments, stream);
     p->inverse_ready = true;
   }
   BlockBuilder b;
-  b.init(n_fields, 1, S, n_dst);
-  FieldDev* fd = b.fields();
+  b.init(n_fields, n_fields, S, n_dst);
   int64_t* ts = b.tile_start();
+  TileRec* recs = b.recs();
   const void** ptrs = b.ptrs();
   uint32_t pi = 0;
   int64_t tiles = 0;
   for (int f = 0; f < n_fields; ++f) {
     const earl_field& uf = fields[f];
-    FieldDev& d = fd[f];
-    d.kind = kFieldCopy;
-    d.scalar_bytes = uf.scalar_bytes;
-    d.row_bytes = uf.scalar_bytes * uf.width;
-    d.pad_scalar = 0;
-    d.src_ptr_index = pi;
-    d.dst_ptr_index = pi + S;
+    TileRec& r = recs[f];
+    r.kind = kFieldCopy;
+    r.scalar_bytes = uf.scalar_bytes;
+    r.row_bytes = uf.scalar_bytes * uf.width;
+    r.src_ptr_index = pi;
+    r.dst_ptr_index = pi + S;
     for (int s = 0; s < S; ++s) ptrs[pi + s] = uf.src_shard_ptrs[s];
     for (int q = 0; q < n_dst; ++q) ptrs[pi + S + q] = uf.dst_shard_ptrs[q];
     pi += S + n_dst;
+    r.tile_first = tiles;
+    r.end_bytes = p->hdr.total_real_rows * (int64_t)r.row_bytes;
     ts[f] = tiles;
-    const int64_t bytes = p->hdr.total_real_rows * (int64_t)d.row_bytes;
-    tiles += (bytes + kTileBytes - 1) / kTileBytes;
+    tiles += (r.end_bytes + kTileBytes - 1) / kTileBytes;
   }
   ts[n_fields] = tiles;
   if (tiles > 0x7fffffffll) return fail(EARL_INVALID_ARG, "too many tiles for one launch");

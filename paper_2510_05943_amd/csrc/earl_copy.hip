@@ -4,20 +4,21 @@
 // straight from the buffers it was computed into, to the layout the consumer needs; Section 1:
 // the volume of these batches is the bottleneck).  The path is pure data movement, bound by HBM
 // bandwidth, and its shape follows what was measured on MI355X for plain copies:
-//   * the chip streams fastest when every wavefront does ONE 16-byte load and ONE 16-byte store
-//     per lane and then ends: stores are fire-and-forget (nothing waits for their
+//   * the chip streams fastest when every lane does ONE 16-byte load and ONE 16-byte store and
+//     the wavefront then ends: stores are fire-and-forget (nothing waits for their
 //     acknowledgement) and the wavefronts in flight always cover one compact, advancing window
 //     of addresses.  Loops over large tiles, persistent grids and deeper unrolling all measured
-//     15-30 % slower.  So a wavefront owns exactly 1 KiB of one destination shard of one field;
+//     15-30 % slower.  So a workgroup owns exactly 4 KiB of one destination shard of one field;
+//   * with so little work per wavefront the kernel is instruction-bound unless the search for
+//     "which field, which shard, which segment" is almost free: wavefront 0 does it once per
+//     workgroup with lane-parallel probes (a ballot counts the hits, no divisions, all compares
+//     in bytes) and hands the result to the other wavefronts through LDS;
 //   * work is cut on the DESTINATION, every lane owns one whole 16-byte destination vector:
-//     stores are aligned global_store_dwordx4 and no two wavefronts share a cache line;
+//     stores are aligned global_store_dwordx4 and no two workgroups share a cache line;
 //   * a vector inside the real part of a segment is one (possibly unaligned)
 //     global_load_dwordx4 from the source shard; padding vectors are stored without a load;
 //     vectors that straddle a segment edge are moved scalar by scalar;
 //   * loads and stores carry the non-temporal hint: every byte is touched once;
-//   * finding (field, shard, segment) for a wavefront is done by the 64 lanes together
-//     (each lane probes one table entry, a ballot counts the hits), so the dependent chain is a
-//     handful of cache-resident loads, which the measurements show to be free at this occupancy;
 //   * position ids and cu_seqlens are further "fields" of the same launch.
 #include "earl_internal.h"
 
@@ -55,32 +56,6 @@ __device__ __forceinline__ void store_scalar(u8* p, uint64_t v, int sb) {
   }
 }
 
-// Last index x in [lo, hi) with key[x] <= v (key ascending, key[lo] <= v); one lane on its own.
-template <class Tk>
-__device__ __forceinline__ int last_le(const Tk* key, int lo, int hi, Tk v) {
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if (key[mid] <= v) lo = mid; else hi = mid;
-  }
-  return lo;
-}
-
-// The same search done by the 64 lanes of a wavefront together (v is wavefront-uniform): every
-// round each lane probes one of 64 evenly spaced entries and a ballot narrows the range 64-fold.
-__device__ __forceinline__ int wave_last_le(const int64_t* key, int lo, int hi, int64_t v, int lane) {
-  int len = hi - lo;
-  while (len > 1) {
-    const int stride = (len + kWave - 1) / kWave;
-    const int idx = lo + lane * stride;
-    const bool hit = idx < lo + len && key[idx] <= v;
-    const int cnt = __builtin_popcountll(__ballot(hit));   // >= 1: key[lo] <= v
-    const int nlo = lo + (cnt - 1) * stride;
-    len = (lo + len - nlo) < stride ? (lo + len - nlo) : stride;
-    lo = nlo;
-  }
-  return lo;
-}
-
 // Number of entries of the ascending table t[0..n) that are <= v, n <= 256, counted by the
 // wavefront: lane l looks at entries 4l..4l+3.
 __device__ __forceinline__ int wave_count_le_256(const int64_t* t, int n, int64_t v, int lane) {
@@ -94,92 +69,147 @@ __device__ __forceinline__ int wave_count_le_256(const int64_t* t, int n, int64_
          __builtin_popcountll(__ballot(c >= 3)) + __builtin_popcountll(__ballot(c >= 4));
 }
 
-// The segment a lane is currently copying from, as destination byte ranges of its shard.
+// Last record x in [lo, hi) of `table` with table[x] <= v, one lane on its own.
+__device__ __forceinline__ int last_le(const int64_t* table, int lo, int hi, int64_t v) {
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (table[mid] <= v) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+// Last segment e in [lo, hi) whose first destination byte (dst_row * w) is <= byte; requires
+// that of segment lo to be.  Done by the 64 lanes together: every round each lane probes one of
+// 64 evenly spaced segments and a ballot narrows the range 64-fold.
+__device__ __forceinline__ int wave_find_segment(const SegRec* segs, int lo, int hi, int64_t byte,
+                                                 int64_t w, int lane) {
+  int len = hi - lo;
+  while (len > 1) {
+    const int stride = (len + kWave - 1) >> 6;
+    const int idx = lo + lane * stride;
+    const bool hit = idx < lo + len && segs[idx].dst_row * w <= byte;
+    const int cnt = __builtin_popcountll(__ballot(hit));   // >= 1
+    const int nlo = lo + (cnt - 1) * stride;
+    const int rest = lo + len - nlo;
+    len = rest < stride ? rest : stride;
+    lo = nlo;
+  }
+  return lo;
+}
+// The same by one lane.
+__device__ __forceinline__ int find_segment(const SegRec* segs, int lo, int hi, int64_t byte,
+                                            int64_t w) {
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (segs[mid].dst_row * w <= byte) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+// A segment as destination byte ranges of its shard, plus where its bytes come from.
 struct SegCursor {
   int64_t lo, real_hi, hi;   // [lo, real_hi) real rows, [real_hi, hi) padding rows
   const u8* src;             // source byte that lands on destination byte lo
-  int64_t dst_row;
   int32_t pos0;
   int e;
 };
 
-struct TileCtx {
-  const CopyArgs* a;
-  const void* const* src_ptrs;   // this field's S source shard pointers (null for position ids)
-  int64_t w;                     // row bytes
-  int e_end;                     // end of this destination shard's segments
+// What wavefront 0 decodes for the whole workgroup.
+struct TileInfo {
+  u8* dst;
+  int64_t lo;                // first destination byte of the tile
+  int64_t end;               // bytes of the destination shard
+  uint64_t pad_scalar;
+  const void* const* src_ptrs;
+  SegCursor seg;             // segment holding byte lo
+  int32_t e_end;
+  int32_t row_bytes;
+  int32_t scalar_bytes;
+  int32_t kind;
 };
 
-__device__ __forceinline__ void load_segment(const TileCtx& t, int e, SegCursor& sc) {
-  const CopyArgs& a = *t.a;
-  const int64_t d = a.seg_dst_row[e];
+__device__ __forceinline__ void load_segment(const SegRec* segs, const void* const* src_ptrs,
+                                             int64_t w, int e, SegCursor& sc) {
+  const SegRec r = segs[e];
   sc.e = e;
-  sc.dst_row = d;
-  sc.lo = d * t.w;
-  sc.real_hi = (d + a.seg_n_real[e]) * t.w;
-  sc.hi = (d + a.seg_n_rows[e]) * t.w;
-  sc.pos0 = a.seg_pos0[e];
-  sc.src = t.src_ptrs
-               ? static_cast<const u8*>(t.src_ptrs[a.seg_src_shard[e]]) + a.seg_src_row[e] * t.w
-               : nullptr;
+  sc.lo = r.dst_row * w;
+  sc.real_hi = (r.dst_row + r.n_real) * w;
+  sc.hi = (r.dst_row + r.n_rows) * w;
+  sc.pos0 = r.pos0;
+  sc.src = src_ptrs ? static_cast<const u8*>(src_ptrs[r.src_shard]) + r.src_row * w : nullptr;
 }
 
 // Moves a lane's cursor to the segment that holds destination byte o >= sc.lo.
-__device__ __forceinline__ void seek(const TileCtx& t, int64_t o, SegCursor& sc) {
+__device__ __forceinline__ void seek(const SegRec* segs, const TileInfo& t, int64_t o, SegCursor& sc) {
   if (o < sc.hi) return;
+  const int64_t w = t.row_bytes;
   int e = sc.e + 1;
-  if (e + 1 < t.e_end && (t.a->seg_dst_row[e + 1]) * t.w <= o)
-    e = last_le<int64_t>(t.a->seg_dst_row, e + 1, t.e_end, o / t.w);
-  load_segment(t, e, sc);
+  if (e + 1 < t.e_end && segs[e + 1].dst_row * w <= o) e = find_segment(segs, e + 1, t.e_end, o, w);
+  load_segment(segs, t.src_ptrs, w, e, sc);
 }
 
 // One 16-byte destination vector that is not a plain copy or a plain fill: element by element.
-__device__ void slow_vector(const TileCtx& t, const FieldDev& fd, u8* dst, int64_t o, int64_t end,
-                            SegCursor sc) {
-  const int sb = fd.scalar_bytes;
-  for (int64_t b = o; b < o + kVecBytes && b < end; b += sb) {
-    seek(t, b, sc);
-    if (fd.kind == kFieldPositionIds) {
-      const int64_t row = b / t.w;
-      store_scalar(dst + b, (uint64_t)(uint32_t)(sc.pos0 + (int32_t)(row - sc.dst_row)), 4);
+__device__ __noinline__ void slow_vector(const SegRec* segs, const TileInfo& t, int64_t o,
+                                         SegCursor sc) {
+  const int sb = t.scalar_bytes;
+  for (int64_t b = o; b < o + kVecBytes && b < t.end; b += sb) {
+    seek(segs, t, b, sc);
+    if (t.kind == kFieldPositionIds) {
+      store_scalar(t.dst + b, (uint64_t)(uint32_t)(sc.pos0 + (int32_t)((b - sc.lo) >> 2)), 4);
     } else if (b < sc.real_hi) {
-      store_scalar(dst + b, load_scalar(sc.src + (b - sc.lo), sb), sb);
+      store_scalar(t.dst + b, load_scalar(sc.src + (b - sc.lo), sb), sb);
     } else {
-      store_scalar(dst + b, fd.pad_scalar, sb);
+      store_scalar(t.dst + b, t.pad_scalar, sb);
     }
   }
 }
 
-// One wavefront = one tile of kTileBytes destination bytes; kWaves tiles per workgroup.
-template <int kWaves>
-__global__ __launch_bounds__(kWaves * kWave) void relayout_kernel(const CopyArgs a) {
+__global__ __launch_bounds__(kCopyThreads) void relayout_kernel(const CopyArgs a) {
+  __shared__ TileInfo s_tile;
   const int lane = threadIdx.x & (kWave - 1);
-  const int64_t tile = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6);
-  if (tile >= a.n_tiles) return;
+  const int64_t tile = blockIdx.x;
 
-  const u8* params = reinterpret_cast<const u8*>(a.params);
-  const DispatchDev hd = *a.params;
-  const FieldDev* fields = reinterpret_cast<const FieldDev*>(params + hd.fields_ofs);
-  const int64_t* tile_start = reinterpret_cast<const int64_t*>(params + hd.tile_start_ofs);
-  const void* const* ptrs = reinterpret_cast<const void* const*>(params + hd.ptrs_ofs);
+  if (threadIdx.x < kWave) {
+    const u8* params = reinterpret_cast<const u8*>(a.params);
+    const DispatchDev hd = *a.params;
+    const int64_t* tile_start = reinterpret_cast<const int64_t*>(params + hd.tile_start_ofs);
+    const TileRec* recs = reinterpret_cast<const TileRec*>(params + hd.recs_ofs);
+    const void* const* ptrs = reinterpret_cast<const void* const*>(params + hd.ptrs_ofs);
+    // (field, shard) of this tile: last record whose first tile is <= tile
+    const int x = hd.n_recs <= 256 ? wave_count_le_256(tile_start, hd.n_recs, tile, lane) - 1
+                                   : last_le(tile_start, 0, hd.n_recs, tile);
+    const TileRec rec = recs[x];
+    TileInfo t;
+    t.dst = static_cast<u8*>(rec.dst);
+    t.lo = (tile - rec.tile_first) * (int64_t)kTileBytes;
+    t.end = rec.end_bytes;
+    t.pad_scalar = rec.pad_scalar;
+    t.src_ptrs = rec.kind == kFieldPositionIds ? nullptr : ptrs + rec.src_ptr_index;
+    t.e_end = rec.e_end;
+    t.row_bytes = rec.row_bytes;
+    t.scalar_bytes = rec.scalar_bytes;
+    t.kind = rec.kind;
+    if (rec.kind == kFieldLinear) {
+      t.seg = SegCursor{0, rec.end_bytes, rec.end_bytes, static_cast<const u8*>(t.src_ptrs[0]), 0, 0};
+    } else {
+      const int e0 = wave_find_segment(a.segs, rec.e_begin, rec.e_end, t.lo, rec.row_bytes, lane);
+      load_segment(a.segs, t.src_ptrs, rec.row_bytes, e0, t.seg);
+    }
+    if (lane == 0) s_tile = t;
+  }
+  __syncthreads();
 
-  // (field, shard) of this tile: last entry of tile_start that is <= tile
-  const int n_fq = hd.n_fields * hd.n_dst;
-  const int x = n_fq <= 256 ? wave_count_le_256(tile_start, n_fq, tile, lane) - 1
-                            : last_le<int64_t>(tile_start, 0, n_fq, tile);
-  const int f = x / hd.n_dst;
-  const int q = x - f * hd.n_dst;
-  const FieldDev fd = fields[f];
-  const int64_t w = fd.row_bytes;
-  u8* dst = static_cast<u8*>(const_cast<void*>(ptrs[fd.dst_ptr_index + q]));
-  const int64_t lo = (tile - tile_start[x]) * (int64_t)kTileBytes;
-  const int64_t o = lo + (int64_t)lane * kVecBytes;   // this lane's destination vector
+  const int64_t o = s_tile.lo + (int64_t)threadIdx.x * kVecBytes;   // this lane's vector
+  const int64_t end = s_tile.end;
+  if (o >= end) return;
+  u8* dst = s_tile.dst;
+  const int kind = s_tile.kind;
+  const int64_t o_end = o + kVecBytes;
 
-  if (fd.kind == kFieldLinear) {
-    // a flat copy (cu_seqlens): shard 0 only, pad_scalar = bytes to copy
-    const u8* src = static_cast<const u8*>(ptrs[fd.src_ptr_index]);
-    const int64_t end = (int64_t)fd.pad_scalar;
-    if (o + kVecBytes <= end) {
+  if (kind == kFieldLinear) {
+    // a flat copy (cu_seqlens)
+    const u8* src = s_tile.seg.src;
+    if (o_end <= end) {
       store16(dst + o, load16(src + o));
     } else {
       for (int64_t b = o; b < end; b += 4)
@@ -188,34 +218,44 @@ __global__ __launch_bounds__(kWaves * kWave) void relayout_kernel(const CopyArgs
     return;
   }
 
-  const int64_t end = a.shard_rows[q] * w;   // bytes of this destination shard
-  TileCtx t;
-  t.a = &a;
-  t.src_ptrs = fd.kind == kFieldCopy ? ptrs + fd.src_ptr_index : nullptr;
-  t.w = w;
-  t.e_end = a.shard_seg_start[q + 1];
-  const int e0 = wave_last_le(a.seg_dst_row, a.shard_seg_start[q], t.e_end, lo / w, lane);
-  if (o >= end) return;
-
-  SegCursor sc;
-  load_segment(t, e0, sc);
-  seek(t, o, sc);
-  const int64_t o_end = o + kVecBytes;
-  if (fd.kind == kFieldPositionIds) {
-    if (o_end <= sc.hi) {
-      const uint32_t p0 = (uint32_t)(sc.pos0 + (int32_t)(o / 4 - sc.dst_row));
-      store16(dst + o, u32x4{p0, p0 + 1, p0 + 2, p0 + 3});
+  // fast paths against the segment decoded for the tile (uniform values from LDS)
+  const int64_t s_lo = s_tile.seg.lo, s_real_hi = s_tile.seg.real_hi, s_hi = s_tile.seg.hi;
+  if (kind == kFieldCopy) {
+    if (o_end <= s_real_hi) {
+      store16(dst + o, load16(s_tile.seg.src + (o - s_lo)));
       return;
     }
-  } else if (o_end <= sc.real_hi) {
-    store16(dst + o, load16(sc.src + (o - sc.lo)));
-    return;
-  } else if (o >= sc.real_hi && o_end <= sc.hi) {
-    const uint32_t p_lo = (uint32_t)fd.pad_scalar, p_hi = (uint32_t)(fd.pad_scalar >> 32);
-    store16(dst + o, u32x4{p_lo, p_hi, p_lo, p_hi});
+    if (o >= s_real_hi && o_end <= s_hi) {
+      const uint64_t p = s_tile.pad_scalar;
+      store16(dst + o, u32x4{(uint32_t)p, (uint32_t)(p >> 32), (uint32_t)p, (uint32_t)(p >> 32)});
+      return;
+    }
+  } else if (o_end <= s_hi) {
+    const uint32_t p0 = (uint32_t)(s_tile.seg.pos0 + (int32_t)((o - s_lo) >> 2));
+    store16(dst + o, u32x4{p0, p0 + 1, p0 + 2, p0 + 3});
     return;
   }
-  slow_vector(t, fd, dst, o, end, sc);
+
+  // this lane's vector lies beyond the tile's first segment or straddles an edge
+  const TileInfo t = s_tile;
+  SegCursor sc = t.seg;
+  seek(a.segs, t, o, sc);
+  if (kind == kFieldCopy) {
+    if (o_end <= sc.real_hi) {
+      store16(dst + o, load16(sc.src + (o - sc.lo)));
+      return;
+    }
+    if (o >= sc.real_hi && o_end <= sc.hi) {
+      const uint64_t p = t.pad_scalar;
+      store16(dst + o, u32x4{(uint32_t)p, (uint32_t)(p >> 32), (uint32_t)p, (uint32_t)(p >> 32)});
+      return;
+    }
+  } else if (o_end <= sc.hi) {
+    const uint32_t p0 = (uint32_t)(sc.pos0 + (int32_t)((o - sc.lo) >> 2));
+    store16(dst + o, u32x4{p0, p0 + 1, p0 + 2, p0 + 3});
+    return;
+  }
+  slow_vector(a.segs, t, o, sc);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -227,7 +267,7 @@ __global__ __launch_bounds__(kWaves * kWave) void relayout_kernel(const CopyArgs
 // shards) are both contiguous inside a segment; vectors that would cross a segment edge are
 // moved scalar by scalar.  Same one-load-one-store-per-lane shape as the forward kernel.
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kPlanThreads) void real_prefix_kernel(const int32_t* seg_n_real,
+__global__ __launch_bounds__(kPlanThreads) void real_prefix_kernel(const SegRec* segs,
                                                                     int64_t* prefix, int n_seg) {
   // one workgroup: each thread sums a contiguous run, the runs are scanned, then written out
   __shared__ int64_t wave_tot[kPlanWaves];
@@ -236,7 +276,7 @@ __global__ __launch_bounds__(kPlanThreads) void real_prefix_kernel(const int32_t
   const int b = (int64_t)tid * per < n_seg ? tid * per : n_seg;
   const int e = b + per < n_seg ? b + per : n_seg;
   int64_t s = 0;
-  for (int x = b; x < e; ++x) s += seg_n_real[x];
+  for (int x = b; x < e; ++x) s += segs[x].n_real;
   int64_t incl = s;
   for (int d = 1; d < kWave; d <<= 1) {
     const int64_t o = __shfl_up(incl, d);
@@ -248,52 +288,88 @@ __global__ __launch_bounds__(kPlanThreads) void real_prefix_kernel(const int32_t
   for (int wv = 0; wv < (tid >> 6); ++wv) acc += wave_tot[wv];
   for (int x = b; x < e; ++x) {
     prefix[x] = acc;
-    acc += seg_n_real[x];
+    acc += segs[x].n_real;
   }
   if (tid == kPlanThreads - 1) prefix[n_seg] = acc;
 }
 
-template <int kWaves>
-__global__ __launch_bounds__(kWaves * kWave) void inverse_kernel(const CopyArgs a,
-                                                                 const int64_t* seg_real_prefix,
-                                                                 const int32_t* seg_dst_shard,
-                                                                 int n_seg) {
+struct InvInfo {
+  int64_t lo;        // first stream byte of the tile
+  int64_t total;     // bytes of the real-row stream of this field
+  const void* const* src_ptrs;
+  const void* const* dst_ptrs;
+  int32_t e0;
+  int32_t row_bytes;
+  int32_t scalar_bytes;
+};
+
+__global__ __launch_bounds__(kCopyThreads) void inverse_kernel(const CopyArgs a,
+                                                               const int64_t* seg_real_prefix,
+                                                               const int32_t* seg_dst_shard,
+                                                               int n_seg) {
+  __shared__ InvInfo s_inv;
   const int lane = threadIdx.x & (kWave - 1);
-  const int64_t tile = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6);
-  if (tile >= a.n_tiles) return;
+  const int64_t tile = blockIdx.x;
+  if (threadIdx.x < kWave) {
+    const u8* params = reinterpret_cast<const u8*>(a.params);
+    const DispatchDev hd = *a.params;
+    const int64_t* tile_start = reinterpret_cast<const int64_t*>(params + hd.tile_start_ofs);
+    const TileRec* recs = reinterpret_cast<const TileRec*>(params + hd.recs_ofs);
+    const void* const* ptrs = reinterpret_cast<const void* const*>(params + hd.ptrs_ofs);
+    // one record per field here (at most EARL_MAX_FIELDS of them)
+    const int f = wave_count_le_256(tile_start, hd.n_recs, tile, lane) - 1;
+    const TileRec rec = recs[f];
+    InvInfo t;
+    t.lo = (tile - rec.tile_first) * (int64_t)kTileBytes;
+    t.total = rec.end_bytes;
+    t.src_ptrs = ptrs + rec.src_ptr_index;
+    t.dst_ptrs = ptrs + rec.dst_ptr_index;
+    t.row_bytes = rec.row_bytes;
+    t.scalar_bytes = rec.scalar_bytes;
+    // last segment whose prefix (in bytes) is <= lo: 64-ary search by the wavefront; empty
+    // segments share a prefix with their successor, and taking the last one skips them
+    int lo = 0, len = n_seg;
+    const int64_t w = rec.row_bytes;
+    while (len > 1) {
+      const int stride = (len + kWave - 1) >> 6;
+      const int idx = lo + lane * stride;
+      const bool hit = idx < lo + len && seg_real_prefix[idx] * w <= t.lo;
+      const int cnt = __builtin_popcountll(__ballot(hit));
+      const int nlo = lo + (cnt - 1) * stride;
+      const int rest = lo + len - nlo;
+      len = rest < stride ? rest : stride;
+      lo = nlo;
+    }
+    t.e0 = lo;
+    if (lane == 0) s_inv = t;
+  }
+  __syncthreads();
 
-  const u8* params = reinterpret_cast<const u8*>(a.params);
-  const DispatchDev hd = *a.params;
-  const FieldDev* fields = reinterpret_cast<const FieldDev*>(params + hd.fields_ofs);
-  const int64_t* tile_start = reinterpret_cast<const int64_t*>(params + hd.tile_start_ofs);
-  const void* const* ptrs = reinterpret_cast<const void* const*>(params + hd.ptrs_ofs);
+  const InvInfo t = s_inv;
+  const int64_t w = t.row_bytes;
+  const int sb = t.scalar_bytes;
+  const int64_t o = t.lo + (int64_t)threadIdx.x * kVecBytes;
+  if (o >= t.total) return;
 
-  // one tile_start entry per field here (at most EARL_MAX_FIELDS of them)
-  const int f = wave_count_le_256(tile_start, hd.n_fields, tile, lane) - 1;
-  const FieldDev fd = fields[f];
-  const int64_t w = fd.row_bytes;
-  const int sb = fd.scalar_bytes;
-  const int64_t total = seg_real_prefix[n_seg] * w;   // bytes of the real-row stream
-  const int64_t lo = (tile - tile_start[f]) * (int64_t)kTileBytes;
-  const int64_t o = lo + (int64_t)lane * kVecBytes;
-  // last segment whose prefix <= first row of the tile; empty segments share a prefix with
-  // their successor, and taking the last one skips them
-  int e = wave_last_le(seg_real_prefix, 0, n_seg, lo / w, lane);
-  if (o >= total) return;
-
+  int e = t.e0;
   int64_t s_lo = 0, s_hi = 0;     // stream byte range of the cached segment
   const u8* from = nullptr;       // training-layout byte of stream byte s_lo
   u8* to = nullptr;               // rollout-layout byte of stream byte s_lo
   auto load_seg = [&]() {
+    const SegRec r = a.segs[e];
     s_lo = seg_real_prefix[e] * w;
-    s_hi = s_lo + (int64_t)a.seg_n_real[e] * w;
-    from = static_cast<const u8*>(ptrs[fd.dst_ptr_index + seg_dst_shard[e]]) + a.seg_dst_row[e] * w;
-    to = static_cast<u8*>(const_cast<void*>(ptrs[fd.src_ptr_index + a.seg_src_shard[e]])) +
-         a.seg_src_row[e] * w;
+    s_hi = s_lo + (int64_t)r.n_real * w;
+    from = static_cast<const u8*>(t.dst_ptrs[seg_dst_shard[e]]) + r.dst_row * w;
+    to = static_cast<u8*>(const_cast<void*>(t.src_ptrs[r.src_shard])) + r.src_row * w;
   };
   auto seek_stream = [&](int64_t b) {
     if (b < s_hi) return;
-    e = last_le<int64_t>(seg_real_prefix, e, n_seg, b / w);
+    int lo = e, hi = n_seg;       // last segment with prefix * w <= b
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (seg_real_prefix[mid] * w <= b) lo = mid; else hi = mid;
+    }
+    e = lo;
     load_seg();
   };
   load_seg();
@@ -301,33 +377,28 @@ __global__ __launch_bounds__(kWaves * kWave) void inverse_kernel(const CopyArgs 
   if (o + kVecBytes <= s_hi) {
     store16_any(to + (o - s_lo), load16(from + (o - s_lo)));
   } else {
-    for (int64_t b = o; b < o + kVecBytes && b < total; b += sb) {
+    for (int64_t b = o; b < o + kVecBytes && b < t.total; b += sb) {
       seek_stream(b);
       store_scalar(to + (b - s_lo), load_scalar(from + (b - s_lo), sb), sb);
     }
   }
 }
 
-constexpr int kCopyWaves = kCopyThreads / kWave;
-
 }  // namespace
 
 void launch_copy(const CopyArgs& a, hipStream_t stream) {
   if (a.n_tiles <= 0) return;
-  const unsigned grid = (unsigned)((a.n_tiles + kCopyWaves - 1) / kCopyWaves);
-  hipLaunchKernelGGL(relayout_kernel<kCopyWaves>, dim3(grid), dim3(kCopyThreads), 0, stream, a);
+  hipLaunchKernelGGL(relayout_kernel, dim3((unsigned)a.n_tiles), dim3(kCopyThreads), 0, stream, a);
 }
 
-void launch_real_prefix(const int32_t* seg_n_real, int64_t* prefix, int n_seg, hipStream_t stream) {
-  hipLaunchKernelGGL(real_prefix_kernel, dim3(1), dim3(kPlanThreads), 0, stream, seg_n_real, prefix,
-                     n_seg);
+void launch_real_prefix(const SegRec* segs, int64_t* prefix, int n_seg, hipStream_t stream) {
+  hipLaunchKernelGGL(real_prefix_kernel, dim3(1), dim3(kPlanThreads), 0, stream, segs, prefix, n_seg);
 }
 
 void launch_copy_inverse(const CopyArgs& a, const int64_t* seg_real_prefix,
                          const int32_t* seg_dst_shard, int n_seg, hipStream_t stream) {
   if (a.n_tiles <= 0) return;
-  const unsigned grid = (unsigned)((a.n_tiles + kCopyWaves - 1) / kCopyWaves);
-  hipLaunchKernelGGL(inverse_kernel<kCopyWaves>, dim3(grid), dim3(kCopyThreads), 0, stream, a,
+  hipLaunchKernelGGL(inverse_kernel, dim3((unsigned)a.n_tiles), dim3(kCopyThreads), 0, stream, a,
                      seg_real_prefix, seg_dst_shard, n_seg);
 }
 

@@ -21,7 +21,7 @@ constexpr int kLdsSortKeys = 8192;
 
 constexpr int kCopyThreads = 256;    // re-layout kernel workgroup (4 wavefronts, one tile each)
 constexpr int kVecBytes = 16;        // one global_load/store_dwordx4 per lane
-constexpr int kTileBytes = kWave * kVecBytes;  // destination bytes handled by one wavefront
+constexpr int kTileBytes = kCopyThreads * kVecBytes;  // destination bytes per workgroup
 
 // First bytes of the workspace; copied to the host together with the arrays that follow it.
 struct PlanHeader {
@@ -39,6 +39,19 @@ struct PlanHeader {
   int64_t reserved_[10];
 };
 static_assert(sizeof(PlanHeader) == 144, "PlanHeader layout");
+
+// One segment: n_rows destination rows starting at dst_row of its shard; the first n_real are
+// copied from row src_row of shard buffer src_shard, the rest is padding; pos0 = logical
+// position of the first row.  32 bytes, so a lane fetches a whole record with two loads.
+struct SegRec {
+  int64_t dst_row;
+  int64_t src_row;
+  int32_t n_real;
+  int32_t n_rows;
+  int32_t src_shard;
+  int32_t pos0;
+};
+static_assert(sizeof(SegRec) == 32, "SegRec layout");
 
 // Everything the plan kernel needs: problem sizes and pointers into the caller's workspace.
 struct PlanDev {
@@ -77,13 +90,8 @@ struct PlanDev {
   int32_t* rank_mbt_base;        // [D+1]
   int32_t* rank_cu_base;         // [D+1]
   // segment table, ordered by (destination shard, destination row)
-  int32_t* seg_src_shard;        // [N*K]
-  int64_t* seg_src_row;
-  int64_t* seg_dst_row;
-  int32_t* seg_n_real;
-  int32_t* seg_n_rows;
-  int32_t* seg_pos0;
-  int32_t* seg_dst_shard;
+  SegRec* segs;                  // [N*K]
+  int32_t* seg_dst_shard;        // [N*K]
   int32_t* shard_seg_start;      // [D*C+1]
   // scratch
   uint64_t* sort_keys;           // [n_pow2]; reused as int64 row offsets in packed order
@@ -91,49 +99,47 @@ struct PlanDev {
   int32_t* lab_cnt;              // same shape
 };
 
-// One field as the re-layout kernel sees it.
+// What a tile of the re-layout kernel copies.
 enum FieldKind : int32_t { kFieldCopy = 0, kFieldPositionIds = 1, kFieldLinear = 2 };
 
-struct FieldDev {
-  int32_t kind;
+// One (field, destination shard) pair of a dispatch call, or one field of an inverse call:
+// everything a workgroup needs besides the segment table, in one 64-byte record.
+struct TileRec {
+  int64_t tile_first;       // first tile of this record in the launch
+  int64_t end_bytes;        // bytes of this destination shard (kFieldLinear: bytes to copy)
+  void* dst;                // destination shard (forward only)
+  uint64_t pad_scalar;      // padding scalar replicated to 8 bytes
+  int32_t e_begin, e_end;   // segments of this destination shard
   int32_t row_bytes;
   int32_t scalar_bytes;
+  int32_t kind;
+  uint32_t src_ptr_index;   // first of the field's S source pointers in the pointer table
+  uint32_t dst_ptr_index;   // first of the field's D*C destination pointers (inverse only)
   int32_t pad_;
-  uint64_t pad_scalar;      // replicated to fill 8 bytes (kFieldLinear: bytes to copy)
-  uint32_t src_ptr_index;   // first of S entries in DispatchDev::ptrs
-  uint32_t dst_ptr_index;   // first of D*C entries in DispatchDev::ptrs
 };
+static_assert(sizeof(TileRec) == 64, "TileRec layout");
 
-// Parameter block of one dispatch call, in device memory.
-//   tile_start[f*n_dst + q] = first tile of (field f, shard q); tile_start[n_fields*n_dst] = total
+// Parameter block of one call, in device memory: header, tile_start[n_recs+1] (tile_first of
+// every record, then the total), recs[n_recs], pointer table.
 struct DispatchDev {
-  int32_t n_fields;
-  int32_t n_dst;
-  int32_t n_src;
+  int32_t n_recs;
   int32_t pad_;
-  uint32_t fields_ofs;      // byte offsets from the start of the block
-  uint32_t tile_start_ofs;
+  uint32_t tile_start_ofs;  // byte offsets from the start of the block
+  uint32_t recs_ofs;
   uint32_t ptrs_ofs;
   uint32_t total_bytes;
 };
 
 struct CopyArgs {
   const DispatchDev* params;
-  const int64_t* shard_rows;       // [n_dst]
-  const int32_t* shard_seg_start;  // [n_dst+1]
-  const int64_t* seg_dst_row;
-  const int64_t* seg_src_row;
-  const int32_t* seg_src_shard;
-  const int32_t* seg_n_real;
-  const int32_t* seg_n_rows;
-  const int32_t* seg_pos0;
+  const SegRec* segs;
   int64_t n_tiles;
 };
 
 void launch_plan(const PlanDev& p, hipStream_t stream);
 void launch_copy(const CopyArgs& a, hipStream_t stream);
 // seg_real_prefix[e] = real rows of the segments before e (n_seg+1 entries)
-void launch_real_prefix(const int32_t* seg_n_real, int64_t* prefix, int n_seg, hipStream_t stream);
+void launch_real_prefix(const SegRec* segs, int64_t* prefix, int n_seg, hipStream_t stream);
 void launch_copy_inverse(const CopyArgs& a, const int64_t* seg_real_prefix,
                          const int32_t* seg_dst_shard, int n_seg, hipStream_t stream);
 

@@ -556,12 +556,14 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const PlanDev p) {
     int64_t n_real = (int64_t)p.lengths[i] - p0;
     n_real = n_real < 0 ? 0 : (n_real > mi ? mi : n_real);
     const int s = p.seq_shard[i];
-    p.seg_src_shard[e] = s;
-    p.seg_src_row[e] = p.seq_row[i] + p0;
-    p.seg_dst_row[e] = p.dst_row[i] + (int64_t)h * mi;
-    p.seg_n_real[e] = (int32_t)n_real;
-    p.seg_n_rows[e] = mi;
-    p.seg_pos0[e] = (int32_t)p0;
+    SegRec rec;
+    rec.dst_row = p.dst_row[i] + (int64_t)h * mi;
+    rec.src_row = p.seq_row[i] + p0;
+    rec.n_real = (int32_t)n_real;
+    rec.n_rows = mi;
+    rec.src_shard = s;
+    rec.pos0 = (int32_t)p0;
+    p.segs[e] = rec;
     p.seg_dst_shard[e] = r * C + c;
     if (n_real > 0)
       atomicAdd(reinterpret_cast<unsigned long long*>(&p.a2a[(size_t)s * n_dst + r * C + c]),
