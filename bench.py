@@ -97,9 +97,8 @@ def run_gpu(args, torch, B, synth):
     ws = torch.empty(B.plan_workspace_bytes(w.n_seqs, src_l, dst_l), dtype=torch.uint8, device="cuda")
 
     # sizes of the destination shards come from a first plan
-    plan = B.plan_build(lengths, w.n_seqs, src_l, dst_l, ws, stream=stream)
-    sm = B.plan_get_summary(plan)
-    B.plan_destroy(plan)
+    plan0 = B.plan_build(lengths, w.n_seqs, src_l, dst_l, ws, stream=stream)
+    sm = B.plan_get_summary(plan0)
     shard_rows = [int(r) for r in sm["shard_rows"]]
     fields = []
     for f in w.fields:
@@ -107,6 +106,9 @@ def run_gpu(args, torch, B, synth):
         fields.append(B.Field(f.scalar_bytes, f.width, f.pad_scalar, src[f.name], dsts))
     pos = [torch.empty((r,), dtype=torch.int32, device="cuda") for r in shard_rows]
     cu = torch.empty((sm["cu_seqlens_len"],), dtype=torch.int32, device="cuda")
+
+    scratch = torch.empty(B.dispatch_workspace_bytes(plan0, fields), dtype=torch.uint8, device="cuda")
+    B.plan_destroy(plan0)
 
     row_bytes = sum(f.row_bytes for f in w.fields)
     algo_bytes = (row_bytes * sm["total_real_rows"] + row_bytes * sm["total_dst_rows"]
@@ -117,7 +119,7 @@ def run_gpu(args, torch, B, synth):
         B.plan_get_summary(p)          # the consumer needs the shard sizes before it can dispatch
         if ev is not None:
             ev[0].record(stream)
-        B.dispatch(p, fields, position_ids=pos, cu_seqlens=cu, stream=stream)
+        B.dispatch(p, fields, position_ids=pos, cu_seqlens=cu, workspace=scratch, stream=stream)
         if ev is not None:
             ev[1].record(stream)
         return p

@@ -18,7 +18,8 @@
  * Conventions for every function:
  *   - returns an earl_status (int32); never throws, never aborts;
  *   - "device" pointers are HIP device pointers on the current device, "host" pointers are ordinary
- *     host memory; the caller owns every buffer it passes; the library allocates no device memory;
+ *     host memory; the caller owns every buffer it passes, scratch included; the library allocates
+ *     no device memory;
  *   - work is enqueued on the HIP stream passed as `void* hip_stream` (a hipStream_t; NULL = the
  *     default stream); device buffers must stay valid until that work has finished;
  *   - calls on the same plan must come from one thread at a time.
@@ -180,6 +181,16 @@ int32_t earl_plan_export_segments(earl_plan* plan, int32_t* src_shard, int64_t* 
                                   int32_t* n_rows, int32_t* pos0, int32_t* shard_seg_start);
 
 /*
+ * Bytes of device scratch one earl_dispatch call with these fields needs: the call's parameter
+ * block plus one 16-byte record per 4 KiB of destination (about 0.4 % of the bytes written).  The
+ * size depends on the plan's shard sizes, so this call waits for the plan like
+ * earl_plan_get_summary.  Only scalar_bytes and width of every field are read.
+ */
+int32_t earl_dispatch_workspace_bytes(earl_plan* plan, const earl_field* fields, int32_t n_fields,
+                                      int32_t with_position_ids, int32_t with_cu_seqlens,
+                                      size_t* out_bytes);
+
+/*
  * Materialises every destination shard of every field (asynchronously on the stream; the first call
  * on a plan waits for the plan as earl_plan_get_summary does).
  *   fields[n_fields]             0 <= n_fields <= EARL_MAX_FIELDS.
@@ -187,23 +198,27 @@ int32_t earl_plan_export_segments(earl_plan* plan, int32_t* src_shard, int64_t* 
  *                                shard_rows[q] entries), or NULL: logical position of every row,
  *                                padding rows included.
  *   cu_seqlens_dev               device int32[cu_seqlens_len] (16-byte aligned) or NULL.
+ *   dispatch_ws_dev / _bytes     device scratch, 256-byte aligned, at least
+ *                                earl_dispatch_workspace_bytes() bytes (EARL_CAPACITY otherwise);
+ *                                in use until the call's work has finished on the stream.
  * Every check (plan status, alignment, capacities) happens before anything is enqueued: a failed
- * call writes nothing.  All dispatches of one plan must be issued on the plan's stream or be ordered
- * after each other by the caller.
+ * call writes nothing.  Calls that share a scratch buffer must be ordered on one stream.
  */
 int32_t earl_dispatch(earl_plan* plan, const earl_field* fields, int32_t n_fields,
                       int32_t* const* position_ids_shard_ptrs, int32_t* cu_seqlens_dev,
-                      void* hip_stream);
+                      void* dispatch_ws_dev, size_t dispatch_ws_bytes, void* hip_stream);
 
 /*
  * The reverse direction (training layout back to the rollout layout, for the stages that run
  * between several models): every real row of every destination shard is copied back to the source
  * row it was read from.  Field descriptors as in earl_dispatch with the roles of the two pointer
- * arrays unchanged (dst_shard_ptrs is read, src_shard_ptrs is written; src pointers must be aligned
- * to scalar_bytes).  Rows of the source buffers that the plan does not read are left untouched.
+ * arrays unchanged (dst_shard_ptrs is read, src_shard_ptrs is written; both only need alignment to
+ * scalar_bytes).  Rows of the source buffers that the plan does not read are left untouched.
+ * The scratch buffer only holds the parameter block here: earl_dispatch_workspace_bytes() with the
+ * same fields is always enough.
  */
 int32_t earl_dispatch_inverse(earl_plan* plan, const earl_field* fields, int32_t n_fields,
-                              void* hip_stream);
+                              void* dispatch_ws_dev, size_t dispatch_ws_bytes, void* hip_stream);
 
 /* Frees the host object (device memory is the caller's). */
 int32_t earl_plan_destroy(earl_plan* plan);

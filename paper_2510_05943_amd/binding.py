@@ -21,7 +21,8 @@ EARL_OK, EARL_INVALID_ARG, EARL_SEQ_EXCEEDS_BUDGET, EARL_CAPACITY, EARL_HIP_ERRO
 EARL_MAX_FIELDS = 32
 
 EXPORTED = ("earl_plan_workspace_bytes", "earl_plan_build", "earl_plan_get_summary",
-            "earl_plan_export", "earl_plan_export_segments", "earl_dispatch",
+            "earl_plan_export", "earl_plan_export_segments", "earl_dispatch_workspace_bytes",
+            "earl_dispatch",
             "earl_dispatch_inverse", "earl_plan_destroy", "earl_status_string",
             "earl_last_error_message")
 
@@ -82,8 +83,10 @@ def load_library() -> C.CDLL:
     lib.earl_plan_get_summary.argtypes = [vp, C.POINTER(_Summary)]
     lib.earl_plan_export.argtypes = [vp] + [vp] * 10
     lib.earl_plan_export_segments.argtypes = [vp] + [vp] * 8
-    lib.earl_dispatch.argtypes = [vp, C.POINTER(_Field), i32, C.POINTER(vp), vp, vp]
-    lib.earl_dispatch_inverse.argtypes = [vp, C.POINTER(_Field), i32, vp]
+    lib.earl_dispatch_workspace_bytes.argtypes = [vp, C.POINTER(_Field), i32, i32, i32,
+                                                  C.POINTER(C.c_size_t)]
+    lib.earl_dispatch.argtypes = [vp, C.POINTER(_Field), i32, C.POINTER(vp), vp, vp, C.c_size_t, vp]
+    lib.earl_dispatch_inverse.argtypes = [vp, C.POINTER(_Field), i32, vp, C.c_size_t, vp]
     lib.earl_plan_destroy.argtypes = [vp]
     lib.earl_status_string.argtypes = [i32]
     lib.earl_status_string.restype = C.c_char_p
@@ -256,22 +259,39 @@ def _marshal_fields(fields: Sequence[Field]):
     return arr, n, keep
 
 
+def _nbytes(t) -> int:
+    return 0 if t is None else int(t.numel()) * int(t.element_size())
+
+
+def dispatch_workspace_bytes(plan: Plan, fields: Sequence[Field], with_position_ids: bool = True,
+                             with_cu_seqlens: bool = True) -> int:
+    """earl_dispatch_workspace_bytes: scratch one dispatch call with these fields needs."""
+    arr, n, keep = _marshal_fields(fields)
+    out = C.c_size_t(0)
+    _check(load_library().earl_dispatch_workspace_bytes(plan.handle, arr, n, int(with_position_ids),
+                                                        int(with_cu_seqlens), C.byref(out)))
+    return int(out.value)
+
+
 def dispatch(plan: Plan, fields: Sequence[Field], position_ids: Optional[Sequence] = None,
-             cu_seqlens=None, stream=None) -> None:
-    """earl_dispatch: materialise all destination shards (asynchronous on the stream)."""
+             cu_seqlens=None, workspace=None, stream=None) -> None:
+    """earl_dispatch: materialise all destination shards (asynchronous on the stream).
+    `workspace` is a device buffer of at least dispatch_workspace_bytes() bytes."""
     arr, n, keep = _marshal_fields(fields)
     pos = None
     if position_ids is not None:
         pos = (C.c_void_p * len(position_ids))(*[_ptr(t) for t in position_ids])
     _check(load_library().earl_dispatch(plan.handle, arr, n,
                                         C.cast(pos, C.POINTER(C.c_void_p)) if pos is not None else None,
-                                        _ptr(cu_seqlens), _stream_handle(stream)))
+                                        _ptr(cu_seqlens), _ptr(workspace), _nbytes(workspace),
+                                        _stream_handle(stream)))
 
 
-def dispatch_inverse(plan: Plan, fields: Sequence[Field], stream=None) -> None:
+def dispatch_inverse(plan: Plan, fields: Sequence[Field], workspace=None, stream=None) -> None:
     """earl_dispatch_inverse: copy every real row back to the rollout layout."""
     arr, n, keep = _marshal_fields(fields)
-    _check(load_library().earl_dispatch_inverse(plan.handle, arr, n, _stream_handle(stream)))
+    _check(load_library().earl_dispatch_inverse(plan.handle, arr, n, _ptr(workspace),
+                                                _nbytes(workspace), _stream_handle(stream)))
 
 
 def plan_destroy(plan: Plan) -> None:

@@ -55,7 +55,6 @@ struct Layout {
   size_t segs, seg_dst_shard;
   size_t shard_seg_start, seg_real_prefix;
   size_t sort_keys, lab_sum, lab_cnt;
-  size_t params_fwd, params_inv, params_bytes;
   size_t total;
 };
 
@@ -107,9 +106,6 @@ Layout make_layout(const Dims& d) {
   const size_t tab = (2 * (size_t)kPlanWaves + 1) * lmax;
   l.lab_sum = take(8 * tab);
   l.lab_cnt = take(4 * tab);
-  l.params_bytes = param_block_bytes(EARL_MAX_FIELDS + 2, d.S, (int)DC);
-  l.params_fwd = take(l.params_bytes);
-  l.params_inv = take(l.params_bytes);
   l.total = off;
   return l;
 }
@@ -218,12 +214,11 @@ const Tv* summary_ptr(const earl_plan* p, size_t off) {
 }
 
 // Copies a host-built parameter block into the workspace, ordered on the stream.
-int32_t upload_params(earl_plan* p, const std::vector<unsigned char>& block, size_t ws_off,
-                      hipStream_t stream) {
+int32_t upload_params(const std::vector<unsigned char>& block, void* dev_dst, hipStream_t stream) {
   if (block.size() > kStageBytes) {
     // too large for a staging slot: blocking copy
     HIP_TRY(hipStreamSynchronize(stream));
-    HIP_TRY(hipMemcpy(p->ws + ws_off, block.data(), block.size(), hipMemcpyHostToDevice));
+    HIP_TRY(hipMemcpy(dev_dst, block.data(), block.size(), hipMemcpyHostToDevice));
     return EARL_OK;
   }
   std::lock_guard<std::mutex> lock(g_stage_mu);
@@ -235,7 +230,7 @@ int32_t upload_params(earl_plan* p, const std::vector<unsigned char>& block, siz
   }
   if (s.in_flight) HIP_TRY(hipEventSynchronize(s.done));
   std::memcpy(s.host, block.data(), block.size());
-  HIP_TRY(hipMemcpyAsync(p->ws + ws_off, s.host, block.size(), hipMemcpyHostToDevice, stream));
+  HIP_TRY(hipMemcpyAsync(dev_dst, s.host, block.size(), hipMemcpyHostToDevice, stream));
   HIP_TRY(hipEventRecord(s.done, stream));
   s.in_flight = true;
   return EARL_OK;
@@ -302,9 +297,9 @@ int32_t check_field(const earl_plan* p, const earl_field& f, int idx, bool inver
   return EARL_OK;
 }
 
-CopyArgs copy_args(const earl_plan* p, size_t params_off, int64_t n_tiles) {
+CopyArgs copy_args(const earl_plan* p, const void* params_dev, int64_t n_tiles) {
   CopyArgs a{};
-  a.params = reinterpret_cast<const DispatchDev*>(p->ws + params_off);
+  a.params = static_cast<const DispatchDev*>(params_dev);
   a.segs = p->dev.segs;
   a.n_tiles = n_tiles;
   return a;
@@ -473,13 +468,62 @@ int32_t earl_plan_export_segments(earl_plan* p, int32_t* src_shard, int64_t* src
   return EARL_OK;
 }
 
-int32_t earl_dispatch(earl_plan* p, const earl_field* fields, int32_t n_fields,
-                      int32_t* const* position_ids_shard_ptrs, int32_t* cu_seqlens_dev,
-                      void* hip_stream) {
-  if (!p) return fail(EARL_INVALID_ARG, "null plan");
+}  // extern "C"
+
+namespace {
+
+// Tiles of one dispatch call: sum over (field, shard) of ceil(bytes / tile bytes).
+int64_t count_tiles(const earl_plan* p, const earl_field* fields, int32_t n_fields, bool with_pos,
+                    bool with_cu) {
+  const int n_dst = p->d.D * p->d.C;
+  const int64_t* shard_rows = summary_ptr<int64_t>(p, p->l.shard_rows);
+  int64_t tiles = 0;
+  for (int f = 0; f < n_fields + (with_pos ? 1 : 0); ++f) {
+    const int64_t w = f < n_fields ? (int64_t)fields[f].scalar_bytes * fields[f].width : 4;
+    for (int q = 0; q < n_dst; ++q) tiles += (shard_rows[q] * w + kTileBytes - 1) / kTileBytes;
+  }
+  if (with_cu) tiles += (4ll * p->hdr.cu_seqlens_len + kTileBytes - 1) / kTileBytes;
+  return tiles;
+}
+
+int32_t check_field_shapes(const earl_field* fields, int32_t n_fields) {
   if (n_fields < 0 || n_fields > EARL_MAX_FIELDS || (n_fields > 0 && !fields))
     return fail(EARL_INVALID_ARG, "n_fields outside [0, %d] or null fields", EARL_MAX_FIELDS);
-  int32_t st = ensure_summary(p);
+  for (int f = 0; f < n_fields; ++f) {
+    const int sb = fields[f].scalar_bytes;
+    if (sb != 1 && sb != 2 && sb != 4 && sb != 8)
+      return fail(EARL_INVALID_ARG, "field %d: scalar_bytes must be 1, 2, 4 or 8", f);
+    if (fields[f].width < 1 || (int64_t)fields[f].width * sb > EARL_MAX_ROW_BYTES)
+      return fail(EARL_INVALID_ARG, "field %d: row bytes outside [1, %d]", f, EARL_MAX_ROW_BYTES);
+  }
+  return EARL_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t earl_dispatch_workspace_bytes(earl_plan* p, const earl_field* fields, int32_t n_fields,
+                                      int32_t with_position_ids, int32_t with_cu_seqlens,
+                                      size_t* out_bytes) {
+  if (!p || !out_bytes) return fail(EARL_INVALID_ARG, "null argument");
+  int32_t st = check_field_shapes(fields, n_fields);
+  if (st != EARL_OK) return st;
+  st = ensure_summary(p);
+  if (st != EARL_OK) return st;
+  const int F = n_fields + (with_position_ids ? 1 : 0) + (with_cu_seqlens ? 1 : 0);
+  const int64_t tiles = count_tiles(p, fields, n_fields, with_position_ids != 0, with_cu_seqlens != 0);
+  *out_bytes = param_block_bytes(F, p->d.S, p->d.D * p->d.C) + kTileCodeBytes * (size_t)tiles;
+  return EARL_OK;
+}
+
+int32_t earl_dispatch(earl_plan* p, const earl_field* fields, int32_t n_fields,
+                      int32_t* const* position_ids_shard_ptrs, int32_t* cu_seqlens_dev,
+                      void* dispatch_ws_dev, size_t dispatch_ws_bytes, void* hip_stream) {
+  if (!p) return fail(EARL_INVALID_ARG, "null plan");
+  int32_t st = check_field_shapes(fields, n_fields);
+  if (st != EARL_OK) return st;
+  st = ensure_summary(p);
   if (st != EARL_OK) return st;
   const int n_dst = p->d.D * p->d.C, S = p->d.S;
   const int64_t* shard_rows = summary_ptr<int64_t>(p, p->l.shard_rows);
@@ -550,10 +594,17 @@ int32_t earl_dispatch(earl_plan* p, const earl_field* fields, int32_t n_fields,
   ts[(size_t)F * n_dst] = tiles;
   if (tiles > 0x7fffffffll) return fail(EARL_INVALID_ARG, "too many tiles for one launch");
   if (tiles == 0) return EARL_OK;
+  const size_t codes_off = b.bytes.size();
+  const size_t need = codes_off + kTileCodeBytes * (size_t)tiles;
+  if (!dispatch_ws_dev || reinterpret_cast<uintptr_t>(dispatch_ws_dev) % kAlign)
+    return fail(EARL_INVALID_ARG, "dispatch scratch is null or not %zu-byte aligned", kAlign);
+  if (dispatch_ws_bytes < need)
+    return fail(EARL_CAPACITY, "dispatch scratch has %zu bytes, %zu needed", dispatch_ws_bytes, need);
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  st = upload_params(p, b.bytes, p->l.params_fwd, stream);
+  st = upload_params(b.bytes, dispatch_ws_dev, stream);
   if (st != EARL_OK) return st;
-  launch_copy(copy_args(p, p->l.params_fwd, tiles), stream);
+  launch_copy(copy_args(p, dispatch_ws_dev, tiles),
+              static_cast<unsigned char*>(dispatch_ws_dev) + codes_off, stream);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess)
     return fail(EARL_HIP_ERROR, "re-layout kernel launch failed: %s", hipGetErrorString(e));
@@ -561,11 +612,11 @@ int32_t earl_dispatch(earl_plan* p, const earl_field* fields, int32_t n_fields,
 }
 
 int32_t earl_dispatch_inverse(earl_plan* p, const earl_field* fields, int32_t n_fields,
-                              void* hip_stream) {
+                              void* dispatch_ws_dev, size_t dispatch_ws_bytes, void* hip_stream) {
   if (!p) return fail(EARL_INVALID_ARG, "null plan");
-  if (n_fields < 0 || n_fields > EARL_MAX_FIELDS || (n_fields > 0 && !fields))
-    return fail(EARL_INVALID_ARG, "n_fields outside [0, %d] or null fields", EARL_MAX_FIELDS);
-  int32_t st = ensure_summary(p);
+  int32_t st = check_field_shapes(fields, n_fields);
+  if (st != EARL_OK) return st;
+  st = ensure_summary(p);
   if (st != EARL_OK) return st;
   const int n_dst = p->d.D * p->d.C, S = p->d.S;
   for (int f = 0; f < n_fields; ++f) {
@@ -575,10 +626,6 @@ int32_t earl_dispatch_inverse(earl_plan* p, const earl_field* fields, int32_t n_
   if (n_fields == 0 || p->hdr.total_real_rows == 0) return EARL_OK;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   int64_t* prefix = reinterpret_cast<int64_t*>(p->ws + p->l.seg_real_prefix);
-  if (!p->inverse_ready) {
-    launch_real_prefix(p->dev.segs, prefix, p->hdr.n_segments, stream);
-    p->inverse_ready = true;
-  }
   BlockBuilder b;
   b.init(n_fields, n_fields, S, n_dst);
   int64_t* ts = b.tile_start();
@@ -604,9 +651,18 @@ int32_t earl_dispatch_inverse(earl_plan* p, const earl_field* fields, int32_t n_
   }
   ts[n_fields] = tiles;
   if (tiles > 0x7fffffffll) return fail(EARL_INVALID_ARG, "too many tiles for one launch");
-  st = upload_params(p, b.bytes, p->l.params_inv, stream);
+  if (!dispatch_ws_dev || reinterpret_cast<uintptr_t>(dispatch_ws_dev) % kAlign)
+    return fail(EARL_INVALID_ARG, "dispatch scratch is null or not %zu-byte aligned", kAlign);
+  if (dispatch_ws_bytes < b.bytes.size())
+    return fail(EARL_CAPACITY, "dispatch scratch has %zu bytes, %zu needed", dispatch_ws_bytes,
+                b.bytes.size());
+  if (!p->inverse_ready) {
+    launch_real_prefix(p->dev.segs, prefix, p->hdr.n_segments, stream);
+    p->inverse_ready = true;
+  }
+  st = upload_params(b.bytes, dispatch_ws_dev, stream);
   if (st != EARL_OK) return st;
-  launch_copy_inverse(copy_args(p, p->l.params_inv, tiles), prefix, p->dev.seg_dst_shard,
+  launch_copy_inverse(copy_args(p, dispatch_ws_dev, tiles), prefix, p->dev.seg_dst_shard,
                       p->hdr.n_segments, stream);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess)

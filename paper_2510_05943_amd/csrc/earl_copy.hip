@@ -9,10 +9,12 @@
 //     acknowledgement) and the wavefronts in flight always cover one compact, advancing window
 //     of addresses.  Loops over large tiles, persistent grids and deeper unrolling all measured
 //     15-30 % slower.  So a workgroup owns exactly 4 KiB of one destination shard of one field;
-//   * with so little work per wavefront the kernel is instruction-bound unless the search for
-//     "which field, which shard, which segment" is almost free: wavefront 0 does it once per
-//     workgroup with lane-parallel probes (a ballot counts the hits, no divisions, all compares
-//     in bytes) and hands the result to the other wavefronts through LDS;
+//   * with so little work per wavefront, any search ("which field, which shard, which segment")
+//     in front of the load costs more than the copy itself.  A first kernel therefore decodes
+//     every tile ONCE, one tile per lane (64 decodes per wavefront instruction), into a 16-byte
+//     tile code: source pointer, destination pointer and what to do.  The copy kernel reads its
+//     code with one uniform load and, for a tile that lies inside the real part of one segment
+//     (nearly all bytes of a wide field), does nothing but load and store;
 //   * work is cut on the DESTINATION, every lane owns one whole 16-byte destination vector:
 //     stores are aligned global_store_dwordx4 and no two workgroups share a cache line;
 //   * a vector inside the real part of a segment is one (possibly unaligned)
@@ -79,24 +81,7 @@ __device__ __forceinline__ int last_le(const int64_t* table, int lo, int hi, int
 }
 
 // Last segment e in [lo, hi) whose first destination byte (dst_row * w) is <= byte; requires
-// that of segment lo to be.  Done by the 64 lanes together: every round each lane probes one of
-// 64 evenly spaced segments and a ballot narrows the range 64-fold.
-__device__ __forceinline__ int wave_find_segment(const SegRec* segs, int lo, int hi, int64_t byte,
-                                                 int64_t w, int lane) {
-  int len = hi - lo;
-  while (len > 1) {
-    const int stride = (len + kWave - 1) >> 6;
-    const int idx = lo + lane * stride;
-    const bool hit = idx < lo + len && segs[idx].dst_row * w <= byte;
-    const int cnt = __builtin_popcountll(__ballot(hit));   // >= 1
-    const int nlo = lo + (cnt - 1) * stride;
-    const int rest = lo + len - nlo;
-    len = rest < stride ? rest : stride;
-    lo = nlo;
-  }
-  return lo;
-}
-// The same by one lane.
+// that of segment lo to be.
 __device__ __forceinline__ int find_segment(const SegRec* segs, int lo, int hi, int64_t byte,
                                             int64_t w) {
   while (hi - lo > 1) {
@@ -114,20 +99,6 @@ struct SegCursor {
   int e;
 };
 
-// What wavefront 0 decodes for the whole workgroup.
-struct TileInfo {
-  u8* dst;
-  int64_t lo;                // first destination byte of the tile
-  int64_t end;               // bytes of the destination shard
-  uint64_t pad_scalar;
-  const void* const* src_ptrs;
-  SegCursor seg;             // segment holding byte lo
-  int32_t e_end;
-  int32_t row_bytes;
-  int32_t scalar_bytes;
-  int32_t kind;
-};
-
 __device__ __forceinline__ void load_segment(const SegRec* segs, const void* const* src_ptrs,
                                              int64_t w, int e, SegCursor& sc) {
   const SegRec r = segs[e];
@@ -139,6 +110,93 @@ __device__ __forceinline__ void load_segment(const SegRec* segs, const void* con
   sc.src = src_ptrs ? static_cast<const u8*>(src_ptrs[r.src_shard]) + r.src_row * w : nullptr;
 }
 
+// Tile codes.  `b` holds the destination pointer of the tile's first byte (16-byte aligned) with
+// the action in its low four bits; `a` depends on the action.
+enum TileAction : uint64_t {
+  kActCopy = 0,      // a = source pointer of the tile's first byte: 4 KiB straight copy
+  kActFill = 1,      // a = padding scalar replicated to 8 bytes: 4 KiB of padding
+  kActIota = 2,      // a = position id of the tile's first row: consecutive int32
+  kActGeneric = 3,   // a = record index << 32 | segment of the tile's first byte
+};
+struct TileCode {
+  uint64_t a, b;
+};
+
+struct ParamView {
+  const int64_t* tile_start;
+  const TileRec* recs;
+  const void* const* ptrs;
+  int n_recs;
+};
+__device__ __forceinline__ ParamView view_params(const DispatchDev* p) {
+  const u8* base = reinterpret_cast<const u8*>(p);
+  const DispatchDev hd = *p;
+  ParamView v;
+  v.tile_start = reinterpret_cast<const int64_t*>(base + hd.tile_start_ofs);
+  v.recs = reinterpret_cast<const TileRec*>(base + hd.recs_ofs);
+  v.ptrs = reinterpret_cast<const void* const*>(base + hd.ptrs_ofs);
+  v.n_recs = hd.n_recs;
+  return v;
+}
+
+// Pass 1: one lane per tile.
+__global__ __launch_bounds__(kCopyThreads) void tile_code_kernel(const CopyArgs a, TileCode* codes) {
+  const int64_t tile = (int64_t)blockIdx.x * kCopyThreads + threadIdx.x;
+  if (tile >= a.n_tiles) return;
+  const ParamView pv = view_params(a.params);
+  const int x = last_le(pv.tile_start, 0, pv.n_recs, tile);
+  const TileRec rec = pv.recs[x];
+  const int64_t lo = (tile - rec.tile_first) * (int64_t)kTileBytes;
+  const int64_t hi = lo + kTileBytes;
+  const uint64_t dst = reinterpret_cast<uint64_t>(static_cast<u8*>(rec.dst) + lo);
+  TileCode c;
+  c.a = (uint64_t)(uint32_t)x << 32;
+  c.b = dst | kActGeneric;
+  if (rec.kind == kFieldLinear) {
+    if (hi <= rec.end_bytes) {
+      c.a = reinterpret_cast<uint64_t>(static_cast<const u8*>(pv.ptrs[rec.src_ptr_index]) + lo);
+      c.b = dst | kActCopy;
+    }
+  } else {
+    const int64_t w = rec.row_bytes;
+    const int e0 = find_segment(a.segs, rec.e_begin, rec.e_end, lo, w);
+    const SegRec r = a.segs[e0];
+    const int64_t s_lo = r.dst_row * w;
+    const int64_t s_real_hi = (r.dst_row + r.n_real) * w;
+    const int64_t s_hi = (r.dst_row + r.n_rows) * w;
+    c.a |= (uint32_t)e0;
+    if (hi <= rec.end_bytes) {
+      if (rec.kind == kFieldPositionIds) {
+        if (hi <= s_hi) {
+          c.a = (uint64_t)(uint32_t)(r.pos0 + (int32_t)((lo - s_lo) >> 2));
+          c.b = dst | kActIota;
+        }
+      } else if (hi <= s_real_hi) {
+        c.a = reinterpret_cast<uint64_t>(
+            static_cast<const u8*>(pv.ptrs[rec.src_ptr_index + r.src_shard]) + r.src_row * w +
+            (lo - s_lo));
+        c.b = dst | kActCopy;
+      } else if (lo >= s_real_hi && hi <= s_hi) {
+        c.a = rec.pad_scalar;
+        c.b = dst | kActFill;
+      }
+    }
+  }
+  codes[tile] = c;
+}
+
+// What the generic path needs about its tile.
+struct TileInfo {
+  u8* dst;                   // destination shard
+  int64_t end;               // bytes of the destination shard
+  uint64_t pad_scalar;
+  const void* const* src_ptrs;
+  int32_t e_end;
+  int32_t row_bytes;
+  int32_t scalar_bytes;
+  int32_t kind;
+};
+
 // Moves a lane's cursor to the segment that holds destination byte o >= sc.lo.
 __device__ __forceinline__ void seek(const SegRec* segs, const TileInfo& t, int64_t o, SegCursor& sc) {
   if (o < sc.hi) return;
@@ -148,99 +206,40 @@ __device__ __forceinline__ void seek(const SegRec* segs, const TileInfo& t, int6
   load_segment(segs, t.src_ptrs, w, e, sc);
 }
 
-// One 16-byte destination vector that is not a plain copy or a plain fill: element by element.
-__device__ __noinline__ void slow_vector(const SegRec* segs, const TileInfo& t, int64_t o,
-                                         SegCursor sc) {
-  const int sb = t.scalar_bytes;
-  for (int64_t b = o; b < o + kVecBytes && b < t.end; b += sb) {
-    seek(segs, t, b, sc);
-    if (t.kind == kFieldPositionIds) {
-      store_scalar(t.dst + b, (uint64_t)(uint32_t)(sc.pos0 + (int32_t)((b - sc.lo) >> 2)), 4);
-    } else if (b < sc.real_hi) {
-      store_scalar(t.dst + b, load_scalar(sc.src + (b - sc.lo), sb), sb);
-    } else {
-      store_scalar(t.dst + b, t.pad_scalar, sb);
-    }
-  }
-}
-
-__global__ __launch_bounds__(kCopyThreads) void relayout_kernel(const CopyArgs a) {
-  __shared__ TileInfo s_tile;
-  const int lane = threadIdx.x & (kWave - 1);
-  const int64_t tile = blockIdx.x;
-
-  if (threadIdx.x < kWave) {
-    const u8* params = reinterpret_cast<const u8*>(a.params);
-    const DispatchDev hd = *a.params;
-    const int64_t* tile_start = reinterpret_cast<const int64_t*>(params + hd.tile_start_ofs);
-    const TileRec* recs = reinterpret_cast<const TileRec*>(params + hd.recs_ofs);
-    const void* const* ptrs = reinterpret_cast<const void* const*>(params + hd.ptrs_ofs);
-    // (field, shard) of this tile: last record whose first tile is <= tile
-    const int x = hd.n_recs <= 256 ? wave_count_le_256(tile_start, hd.n_recs, tile, lane) - 1
-                                   : last_le(tile_start, 0, hd.n_recs, tile);
-    const TileRec rec = recs[x];
-    TileInfo t;
-    t.dst = static_cast<u8*>(rec.dst);
-    t.lo = (tile - rec.tile_first) * (int64_t)kTileBytes;
-    t.end = rec.end_bytes;
-    t.pad_scalar = rec.pad_scalar;
-    t.src_ptrs = rec.kind == kFieldPositionIds ? nullptr : ptrs + rec.src_ptr_index;
-    t.e_end = rec.e_end;
-    t.row_bytes = rec.row_bytes;
-    t.scalar_bytes = rec.scalar_bytes;
-    t.kind = rec.kind;
-    if (rec.kind == kFieldLinear) {
-      t.seg = SegCursor{0, rec.end_bytes, rec.end_bytes, static_cast<const u8*>(t.src_ptrs[0]), 0, 0};
-    } else {
-      const int e0 = wave_find_segment(a.segs, rec.e_begin, rec.e_end, t.lo, rec.row_bytes, lane);
-      load_segment(a.segs, t.src_ptrs, rec.row_bytes, e0, t.seg);
-    }
-    if (lane == 0) s_tile = t;
-  }
-  __syncthreads();
-
-  const int64_t o = s_tile.lo + (int64_t)threadIdx.x * kVecBytes;   // this lane's vector
-  const int64_t end = s_tile.end;
-  if (o >= end) return;
-  u8* dst = s_tile.dst;
-  const int kind = s_tile.kind;
+// A tile that is not one plain copy / fill / iota: every lane places its own 16-byte vector.
+__device__ __noinline__ void generic_tile(const CopyArgs& a, const TileCode c) {
+  const ParamView pv = view_params(a.params);
+  const TileRec rec = pv.recs[(uint32_t)(c.a >> 32)];
+  const int64_t lo = ((int64_t)blockIdx.x - rec.tile_first) * (int64_t)kTileBytes;
+  const int64_t o = lo + (int64_t)threadIdx.x * kVecBytes;   // this lane's vector
+  if (o >= rec.end_bytes) return;
+  u8* dst = static_cast<u8*>(rec.dst);
   const int64_t o_end = o + kVecBytes;
 
-  if (kind == kFieldLinear) {
-    // a flat copy (cu_seqlens)
-    const u8* src = s_tile.seg.src;
-    if (o_end <= end) {
+  if (rec.kind == kFieldLinear) {
+    const u8* src = static_cast<const u8*>(pv.ptrs[rec.src_ptr_index]);
+    if (o_end <= rec.end_bytes) {
       store16(dst + o, load16(src + o));
     } else {
-      for (int64_t b = o; b < end; b += 4)
+      for (int64_t b = o; b < rec.end_bytes; b += 4)
         *reinterpret_cast<uint32_t*>(dst + b) = *reinterpret_cast<const uint32_t*>(src + b);
     }
     return;
   }
 
-  // fast paths against the segment decoded for the tile (uniform values from LDS)
-  const int64_t s_lo = s_tile.seg.lo, s_real_hi = s_tile.seg.real_hi, s_hi = s_tile.seg.hi;
-  if (kind == kFieldCopy) {
-    if (o_end <= s_real_hi) {
-      store16(dst + o, load16(s_tile.seg.src + (o - s_lo)));
-      return;
-    }
-    if (o >= s_real_hi && o_end <= s_hi) {
-      const uint64_t p = s_tile.pad_scalar;
-      store16(dst + o, u32x4{(uint32_t)p, (uint32_t)(p >> 32), (uint32_t)p, (uint32_t)(p >> 32)});
-      return;
-    }
-  } else if (o_end <= s_hi) {
-    const uint32_t p0 = (uint32_t)(s_tile.seg.pos0 + (int32_t)((o - s_lo) >> 2));
-    store16(dst + o, u32x4{p0, p0 + 1, p0 + 2, p0 + 3});
-    return;
-  }
-
-  // this lane's vector lies beyond the tile's first segment or straddles an edge
-  const TileInfo t = s_tile;
-  SegCursor sc = t.seg;
+  TileInfo t;
+  t.dst = dst;
+  t.end = rec.end_bytes;
+  t.pad_scalar = rec.pad_scalar;
+  t.src_ptrs = rec.kind == kFieldPositionIds ? nullptr : pv.ptrs + rec.src_ptr_index;
+  t.e_end = rec.e_end;
+  t.row_bytes = rec.row_bytes;
+  t.scalar_bytes = rec.scalar_bytes;
+  t.kind = rec.kind;
+  SegCursor sc;
+  load_segment(a.segs, t.src_ptrs, rec.row_bytes, (int)(uint32_t)c.a, sc);
   seek(a.segs, t, o, sc);
-  if (kind == kFieldCopy) {
+  if (rec.kind == kFieldCopy) {
     if (o_end <= sc.real_hi) {
       store16(dst + o, load16(sc.src + (o - sc.lo)));
       return;
@@ -255,7 +254,36 @@ __global__ __launch_bounds__(kCopyThreads) void relayout_kernel(const CopyArgs a
     store16(dst + o, u32x4{p0, p0 + 1, p0 + 2, p0 + 3});
     return;
   }
-  slow_vector(a.segs, t, o, sc);
+  // the vector straddles a segment edge, the real/padding edge or the end of the shard
+  const int sb = t.scalar_bytes;
+  for (int64_t b = o; b < o_end && b < t.end; b += sb) {
+    seek(a.segs, t, b, sc);
+    if (t.kind == kFieldPositionIds) {
+      store_scalar(dst + b, (uint64_t)(uint32_t)(sc.pos0 + (int32_t)((b - sc.lo) >> 2)), 4);
+    } else if (b < sc.real_hi) {
+      store_scalar(dst + b, load_scalar(sc.src + (b - sc.lo), sb), sb);
+    } else {
+      store_scalar(dst + b, t.pad_scalar, sb);
+    }
+  }
+}
+
+// Pass 2: one workgroup per 4 KiB tile, one 16-byte vector per lane.
+__global__ __launch_bounds__(kCopyThreads) void relayout_kernel(const CopyArgs a,
+                                                                const TileCode* __restrict__ codes) {
+  const TileCode c = codes[blockIdx.x];
+  const uint64_t act = c.b & 15u;
+  u8* dst = reinterpret_cast<u8*>(c.b & ~(uint64_t)15) + threadIdx.x * kVecBytes;
+  if (act == kActCopy) {
+    store16(dst, load16(reinterpret_cast<const u8*>(c.a) + threadIdx.x * kVecBytes));
+  } else if (act == kActFill) {
+    store16(dst, u32x4{(uint32_t)c.a, (uint32_t)(c.a >> 32), (uint32_t)c.a, (uint32_t)(c.a >> 32)});
+  } else if (act == kActIota) {
+    const uint32_t p0 = (uint32_t)c.a + threadIdx.x * 4;
+    store16(dst, u32x4{p0, p0 + 1, p0 + 2, p0 + 3});
+  } else {
+    generic_tile(a, c);
+  }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -386,9 +414,13 @@ __global__ __launch_bounds__(kCopyThreads) void inverse_kernel(const CopyArgs a,
 
 }  // namespace
 
-void launch_copy(const CopyArgs& a, hipStream_t stream) {
+void launch_copy(const CopyArgs& a, void* tile_codes, hipStream_t stream) {
   if (a.n_tiles <= 0) return;
-  hipLaunchKernelGGL(relayout_kernel, dim3((unsigned)a.n_tiles), dim3(kCopyThreads), 0, stream, a);
+  TileCode* codes = static_cast<TileCode*>(tile_codes);
+  const unsigned g1 = (unsigned)((a.n_tiles + kCopyThreads - 1) / kCopyThreads);
+  hipLaunchKernelGGL(tile_code_kernel, dim3(g1), dim3(kCopyThreads), 0, stream, a, codes);
+  hipLaunchKernelGGL(relayout_kernel, dim3((unsigned)a.n_tiles), dim3(kCopyThreads), 0, stream, a,
+                     codes);
 }
 
 void launch_real_prefix(const SegRec* segs, int64_t* prefix, int n_seg, hipStream_t stream) {

@@ -86,11 +86,14 @@ def run_dispatch(w: synth.Workload, plan, fields: Sequence[synth.FieldSpec],
         bfields.append(B.Field(f.scalar_bytes, f.width, f.pad_scalar, srcs, inner[f.name]))
     pos_pairs = [guarded(int(shard_rows[q]) * 4) for q in range(n_dst)] if want_position_ids else None
     cu_pair = guarded(sm["cu_seqlens_len"] * 4) if want_cu else None
+    ws_whole, ws = guarded(B.dispatch_workspace_bytes(plan, bfields, want_position_ids, want_cu))
     B.dispatch(plan, bfields,
                position_ids=[p[1] for p in pos_pairs] if pos_pairs else None,
-               cu_seqlens=cu_pair[1] if cu_pair else None, stream=stream)
+               cu_seqlens=cu_pair[1] if cu_pair else None, workspace=ws, stream=stream)
     torch.cuda.synchronize()
-    out = {"fields": {}, "dev": inner, "src_dev": {f.name: s for f, s in zip(fields, keep)}}
+    assert guards_intact(ws_whole), "write outside the dispatch scratch"
+    out = {"fields": {}, "dev": inner, "src_dev": {f.name: s for f, s in zip(fields, keep)},
+           "workspace": ws}
     for f in fields:
         assert all(guards_intact(x) for x in wholes[f.name]), f"{f.name}: write outside its shard"
         out["fields"][f.name] = [

@@ -195,7 +195,7 @@ def test_small_batches(H, case):
     back = {f.name: [torch.full_like(t, 0x5A) for t in out["src_dev"][f.name]] for f in w.fields}
     bfields = [H.B.Field(f.scalar_bytes, f.width, f.pad_scalar, back[f.name], out["dev"][f.name])
                for f in w.fields]
-    H.B.dispatch_inverse(plan, bfields)
+    H.B.dispatch_inverse(plan, bfields, workspace=out["workspace"])
     torch.cuda.synchronize()
     for f in w.fields:
         want = [np.full_like(b, 0x5A) for b in shards[f.name]]
@@ -278,6 +278,7 @@ def test_dispatch_with_empty_ranks_and_no_fields(H):
     out = H.run_dispatch(w, plan, w.fields, src_host=shards)
     assert_dispatch_equal(w, oplan, out, shards, w.fields)
     H.B.dispatch(plan, [], position_ids=None, cu_seqlens=None)     # nothing to do is not an error
+    assert H.B.dispatch_workspace_bytes(plan, [], False, False) < 4096
     H.B.plan_destroy(plan)
 
 
@@ -323,9 +324,11 @@ def test_errors(H):
     rows = [int(x) for x in sm["shard_rows"]]
     good = [torch.full((r * 4 + 64,), 0xCD, dtype=torch.uint8, device="cuda") for r in rows]
 
-    def attempt(dsts, sb=4, width=1, srcs_=None):
+    scratch = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
+
+    def attempt(dsts, sb=4, width=1, srcs_=None, ws=scratch):
         with pytest.raises(B.EarlError) as e:
-            B.dispatch(plan, [B.Field(sb, width, 0, srcs_ or srcs, dsts)])
+            B.dispatch(plan, [B.Field(sb, width, 0, srcs_ or srcs, dsts)], workspace=ws)
         torch.cuda.synchronize()
         for t in good:
             assert bool((t == 0xCD).all().item())
@@ -339,6 +342,10 @@ def test_errors(H):
     assert attempt([t[:r * 4] for t, r in zip(good, rows)],
                    srcs_=[s[:-1] for s in srcs]) == B.EARL_CAPACITY       # source too short
     assert attempt([None] + [t[:r * 4] for t, r in zip(good[1:], rows[1:])]) == B.EARL_INVALID_ARG
+    fit = [t[:r * 4] for t, r in zip(good, rows)]
+    assert attempt(fit, ws=None) == B.EARL_INVALID_ARG                   # no scratch
+    assert attempt(fit, ws=scratch[:64]) == B.EARL_CAPACITY              # scratch too small
+    assert attempt(fit, ws=scratch[8:]) == B.EARL_INVALID_ARG            # scratch misaligned
     # and the same plan still works afterwards
     out = H.run_dispatch(w, plan, w.fields, src_host=shards)
     assert_dispatch_equal(w, oracle_plan(w), out, shards, w.fields)
