@@ -18,6 +18,7 @@ namespace earl {
 namespace {
 
 constexpr int T = kPlanThreads;
+constexpr int kLdsA2a = 2048;   // (source shard, destination shard) pairs counted in LDS
 
 // ---------------------------------------------------------------------------------------
 // wavefront primitives
@@ -38,18 +39,6 @@ constexpr int kDppRowMirror = 0x140;
 constexpr int kDppRowBcast15 = 0x142;
 constexpr int kDppRowBcast31 = 0x143;
 constexpr int kDppRowShr = 0x110;       // + n
-
-// Minimum of x over the 64 lanes (result valid in every lane: read back from lane 63).
-__device__ __forceinline__ uint32_t wave_min_u32(uint32_t x) {
-  uint32_t y;
-  y = dpp_u32<kDppQuadXor1, 0xf>(x, x); x = y < x ? y : x;
-  y = dpp_u32<kDppQuadXor2, 0xf>(x, x); x = y < x ? y : x;
-  y = dpp_u32<kDppRowHalfMirror, 0xf>(x, x); x = y < x ? y : x;
-  y = dpp_u32<kDppRowMirror, 0xf>(x, x); x = y < x ? y : x;
-  y = dpp_u32<kDppRowBcast15, 0xa>(x, x); x = y < x ? y : x;
-  y = dpp_u32<kDppRowBcast31, 0xc>(x, x); x = y < x ? y : x;
-  return (uint32_t)__builtin_amdgcn_readlane((int)x, 63);
-}
 
 // Inclusive prefix sum over the 64 lanes: Hillis-Steele inside each row of 16 lanes with
 // row_shr, then the row totals are carried across rows with row_bcast.
@@ -220,13 +209,89 @@ __device__ void bitonic_sort(uint64_t* keys, int n) {
 // Longest-first list scheduling in wavefront 0.
 //
 // keys[] holds the sequences sorted by (padded length descending, index ascending); the low
-// word is the index, the high word is 0x7fffffff - padded length.  Each lane owns the loads of
-// a block of consecutive ranks, so a lower lane always means lower ranks and ties resolve to
-// the lowest rank by taking the first lane that holds the minimum.  Loads are compared as
-// 32-bit distances from a running uniform base (the greedy rule keeps max - min load within one
-// padded length, which is < 2^31), so the arg-min is six v_min_u32 DPP steps.
+// word is the index, the high word is 0x7fffffff - padded length.  The chain of N arg-mins is
+// serial by definition, so everything is about the latency of one step.  The greedy rule keeps
+// max - min load within one padded length, so loads are kept as 32-bit distances from the
+// current minimum (re-based every step) and the arg-min is a short v_min_u32 DPP butterfly.
 // ---------------------------------------------------------------------------------------
-__device__ void lpt_wave0(const PlanDev& p, const uint64_t* keys, int64_t* lds_load) {
+
+// Minimum over the first 2^kSteps lanes (kSteps <= 4) or over all 64 lanes (kSteps == 6).
+template <int kCtrl>
+__device__ __forceinline__ uint32_t dpp_min_all_rows(uint32_t x) {
+  // every source lane of these controls exists, so bound_ctrl never takes effect; written this
+  // way the compiler folds the move into one v_min_u32_dpp
+  const uint32_t y = (uint32_t)__builtin_amdgcn_mov_dpp((int)x, kCtrl, 0xf, 0xf, true);
+  return y < x ? y : x;
+}
+template <int kSteps>
+__device__ __forceinline__ uint32_t wave_min_low(uint32_t x) {
+  uint32_t y;
+  if (kSteps >= 1) x = dpp_min_all_rows<kDppQuadXor1>(x);
+  if (kSteps >= 2) x = dpp_min_all_rows<kDppQuadXor2>(x);
+  if (kSteps >= 3) x = dpp_min_all_rows<kDppRowHalfMirror>(x);
+  if (kSteps >= 4) x = dpp_min_all_rows<kDppRowMirror>(x);
+  if (kSteps >= 5) {
+    y = dpp_u32<kDppRowBcast15, 0xa>(x, x); x = y < x ? y : x;
+    y = dpp_u32<kDppRowBcast31, 0xc>(x, x); x = y < x ? y : x;
+  }
+  return (uint32_t)__builtin_amdgcn_readlane((int)x, kSteps >= 5 ? 63 : 0);
+}
+
+// D <= 64, one rank per lane, loads small enough that (load << 6 | lane) fits 32 bits for the
+// whole run: the lane number rides in the low six bits of the compared word, so one reduction
+// yields the minimum load AND the lowest rank that has it (the lane bits make all words
+// distinct, and equal loads order by lane).  Lanes >= D hold 0xffffffff and never win.
+template <int kSteps>
+__device__ void lpt_packed(const PlanDev& p, const uint64_t* keys) {
+  const int lane = lane_id();
+  const int N = p.N;
+  uint32_t word = lane < p.D ? (uint32_t)lane : 0xffffffffu;   // load << 6 | lane
+  for (int start = 0; start < N; start += kWave) {
+    const int i = start + lane;
+    const uint64_t key = i < N ? keys[i] : ~0ull;
+    const uint32_t lp6 = (uint32_t)(0x7fffffff - (int32_t)(key >> 32)) << 6;
+    const int32_t idx = (int32_t)(key & 0xffffffffu);
+    int my_rank = 0;
+    const int cnt = min(kWave, N - start);
+    for (int s = 0; s < cnt; ++s) {
+      const uint32_t lp_s = (uint32_t)__builtin_amdgcn_readlane((int)lp6, s);
+      const int wl = (int)(wave_min_low<kSteps>(word) & 63u);
+      word += lane == wl ? lp_s : 0u;
+      my_rank = lane == s ? wl : my_rank;
+    }
+    if (i < N) p.rank[idx] = my_rank;
+  }
+}
+
+// D <= 64, one rank per lane, any padded length: minimum first, then the first lane that has it.
+__device__ void lpt_one_per_lane(const PlanDev& p, const uint64_t* keys) {
+  const int lane = lane_id();
+  const int N = p.N;
+  const bool valid = lane < p.D;
+  uint32_t rel = valid ? 0u : 0xffffffffu;   // load - min load
+  for (int start = 0; start < N; start += kWave) {
+    const int i = start + lane;
+    const uint64_t key = i < N ? keys[i] : ~0ull;
+    const uint32_t lp = (uint32_t)(0x7fffffff - (int32_t)(key >> 32));
+    const int32_t idx = (int32_t)(key & 0xffffffffu);
+    int my_rank = 0;
+    const int cnt = min(kWave, N - start);
+    for (int s = 0; s < cnt; ++s) {
+      const uint32_t lp_s = (uint32_t)__builtin_amdgcn_readlane((int)lp, s);
+      const uint32_t mn = wave_min_low<6>(rel);
+      const int wl = __builtin_ctzll(__ballot(rel == mn));
+      const uint32_t next = rel - mn + (lane == wl ? lp_s : 0u);
+      rel = valid ? next : rel;
+      my_rank = lane == s ? wl : my_rank;
+    }
+    if (i < N) p.rank[idx] = my_rank;
+  }
+}
+
+// Any D <= 1024: each lane owns the loads (in LDS) of a block of consecutive ranks, so a lower
+// lane always means lower ranks and ties resolve to the lowest rank by taking the first lane
+// that holds the minimum.
+__device__ void lpt_blocks(const PlanDev& p, const uint64_t* keys, int64_t* lds_load) {
   const int lane = lane_id();
   const int D = p.D, N = p.N;
   const int kper = (D + kWave - 1) / kWave;
@@ -248,32 +313,43 @@ __device__ void lpt_wave0(const PlanDev& p, const uint64_t* keys, int64_t* lds_l
     for (int s = 0; s < cnt; ++s) {
       const int32_t lp_s = __builtin_amdgcn_readlane(lp, s);
       const uint32_t rel = owner ? (uint32_t)(best - base) : 0xffffffffu;
-      const uint32_t mn = wave_min_u32(rel);
-      const uint64_t at_min = __ballot(rel == mn);
-      const int wl = __builtin_ctzll(at_min);
+      const uint32_t mn = wave_min_low<6>(rel);
+      const int wl = __builtin_ctzll(__ballot(rel == mn));
       const int r = __builtin_amdgcn_readlane(best_r, wl);
       base += mn;
       if (lane == wl) {
-        if (kper == 1) {
-          best += lp_s;
-        } else {
-          lds_load[r] += lp_s;
-          best = lds_load[r_lo];
-          best_r = r_lo;
-          for (int q = r_lo + 1; q < r_hi; ++q) {
-            const int64_t v = lds_load[q];
-            if (v < best) { best = v; best_r = q; }
-          }
+        lds_load[r] += lp_s;
+        best = lds_load[r_lo];
+        best_r = r_lo;
+        for (int q = r_lo + 1; q < r_hi; ++q) {
+          const int64_t v = lds_load[q];
+          if (v < best) { best = v; best_r = q; }
         }
       }
       if (lane == s) my_rank = r;
     }
     if (i < N) p.rank[idx] = my_rank;
   }
-  if (kper == 1) {
-    if (owner) p.rank_load[lane] = best;
+}
+
+__device__ void lpt_wave0(const PlanDev& p, const uint64_t* keys, int64_t* lds_load) {
+  const int D = p.D;
+  const int64_t max_lp = 0x7fffffffll - (int64_t)(keys[0] >> 32);   // keys are sorted
+  if (D > kWave) {
+    lpt_blocks(p, keys, lds_load);
+  } else if (((int64_t)p.N * max_lp / D + max_lp) >= (1 << 26)) {
+    // some load could reach 2^26: the packed word would overflow
+    lpt_one_per_lane(p, keys);
+  } else if (D <= 2) {
+    lpt_packed<1>(p, keys);
+  } else if (D <= 4) {
+    lpt_packed<2>(p, keys);
+  } else if (D <= 8) {
+    lpt_packed<3>(p, keys);
+  } else if (D <= 16) {
+    lpt_packed<4>(p, keys);
   } else {
-    for (int r = r_lo; r < r_hi; ++r) p.rank_load[r] = lds_load[r];
+    lpt_packed<6>(p, keys);
   }
 }
 
@@ -299,6 +375,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const PlanDev p) {
   __shared__ int64_t lds_load[kMaxDp];
   __shared__ BlockScratch bs;
   __shared__ int s_invalid, s_exceeds, s_bad;
+  __shared__ unsigned long long s_a2a[kLdsA2a];
 
   const int tid = threadIdx.x;
   const int N = p.N, G = p.G, R = p.R, S = p.S, D = p.D, C = p.C, K = p.K, P = p.P;
@@ -308,7 +385,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const PlanDev p) {
 
   // ---- phase 0: clear accumulators --------------------------------------------------------
   if (tid == 0) { s_invalid = 0; s_exceeds = 0; s_bad = -1; }
-  for (int64_t x = tid; x < (int64_t)S * n_dst; x += T) p.a2a[x] = 0;
+  if (S * n_dst > kLdsA2a)
+    for (int64_t x = tid; x < (int64_t)S * n_dst; x += T) p.a2a[x] = 0;
   for (int x = tid; x < S; x += T) p.src_rows_needed[x] = 0;
   for (int x = tid; x < n_dst; x += T) p.shard_rows[x] = 0;
   for (int x = tid; x < D; x += T) { p.n_seq[x] = 0; p.n_mb[x] = 0; p.rank_load[x] = 0; }
@@ -426,7 +504,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const PlanDev p) {
       for (int c = 0; c < C; ++c) p.shard_rows[(size_t)tid * C + c] = rank_rows[tid];
     }
     if (tid == 0) p.rank_seq_base[D] = N;
-    const int64_t ld = tid < D ? p.rank_load[tid] : 0;
+    const int64_t ld = tid < D ? rank_rows[tid] * C : 0;   // padded tokens = C * rows per SP rank
+    if (tid < D) p.rank_load[tid] = ld;
     load_max = block_reduce_max(tid < D ? ld : INT64_MIN, bs);
     load_min = block_reduce_min(tid < D ? ld : INT64_MAX, bs);
   }
@@ -540,34 +619,51 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const PlanDev p) {
   // One segment per (sequence, chunk): m rows contiguous in both layouts.  SP rank c holds chunk
   // c and, with zigzag, chunk 2C-1-c right after it.
   const int64_t n_seg = (int64_t)N * K;
-  for (int64_t t = tid; t < n_seg; t += T) {
-    const int pos = (int)(t / K);
-    const int rem = (int)(t - (int64_t)pos * K);
-    const int c = rem / halves;
-    const int h = rem - c * halves;
+  const int n_pairs = S * n_dst;
+  const bool lds_counts = n_pairs <= kLdsA2a;   // count in LDS, flush once
+  if (lds_counts) {
+    for (int x = tid; x < n_pairs; x += T) s_a2a[x] = 0;
+    __syncthreads();
+  }
+  for (int pos = tid; pos < N; pos += T) {
     const int i = p.seq_ids[pos];
     const int r = p.rank[i];
     const int base = p.rank_seq_base[r];
     const int n = rank_cnt[r];
-    const int64_t e = (int64_t)halves * ((int64_t)C * base + (int64_t)c * n + (pos - base)) + h;
     const int32_t mi = p.m[i];
-    const int kappa = h == 0 ? c : 2 * C - 1 - c;
-    const int64_t p0 = (int64_t)kappa * mi;
-    int64_t n_real = (int64_t)p.lengths[i] - p0;
-    n_real = n_real < 0 ? 0 : (n_real > mi ? mi : n_real);
+    const int64_t len = p.lengths[i];
     const int s = p.seq_shard[i];
-    SegRec rec;
-    rec.dst_row = p.dst_row[i] + (int64_t)h * mi;
-    rec.src_row = p.seq_row[i] + p0;
-    rec.n_real = (int32_t)n_real;
-    rec.n_rows = mi;
-    rec.src_shard = s;
-    rec.pos0 = (int32_t)p0;
-    p.segs[e] = rec;
-    p.seg_dst_shard[e] = r * C + c;
-    if (n_real > 0)
-      atomicAdd(reinterpret_cast<unsigned long long*>(&p.a2a[(size_t)s * n_dst + r * C + c]),
-                (unsigned long long)n_real);
+    const int64_t src_row = p.seq_row[i];
+    const int64_t dst_row = p.dst_row[i];
+    for (int c = 0; c < C; ++c) {
+      const int64_t e0 = (int64_t)halves * ((int64_t)C * base + (int64_t)c * n + (pos - base));
+      int64_t real_rows = 0;
+      for (int h = 0; h < halves; ++h) {
+        const int kappa = h == 0 ? c : 2 * C - 1 - c;
+        const int64_t p0 = (int64_t)kappa * mi;
+        int64_t n_real = len - p0;
+        n_real = n_real < 0 ? 0 : (n_real > mi ? mi : n_real);
+        SegRec rec;
+        rec.dst_row = dst_row + (int64_t)h * mi;
+        rec.src_row = src_row + p0;
+        rec.n_real = (int32_t)n_real;
+        rec.n_rows = mi;
+        rec.src_shard = s;
+        rec.pos0 = (int32_t)p0;
+        p.segs[e0 + h] = rec;
+        p.seg_dst_shard[e0 + h] = r * C + c;
+        real_rows += n_real;
+      }
+      if (real_rows > 0) {
+        const size_t x = (size_t)s * n_dst + r * C + c;
+        if (lds_counts) atomicAdd(&s_a2a[x], (unsigned long long)real_rows);
+        else atomicAdd(reinterpret_cast<unsigned long long*>(&p.a2a[x]), (unsigned long long)real_rows);
+      }
+    }
+  }
+  if (lds_counts) {
+    __syncthreads();
+    for (int x = tid; x < n_pairs; x += T) p.a2a[x] = (int64_t)s_a2a[x];
   }
   for (int q = tid; q <= n_dst; q += T) {
     int64_t v = n_seg;

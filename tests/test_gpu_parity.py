@@ -247,6 +247,8 @@ def test_explicit_source_rows_with_gaps(H):
     ("one_sequence_many_ranks", dict(L=[77], dp=7, sp=4, zigzag=1, pad=8, B=1024)),
     ("all_length_one", dict(L=[1] * 300, dp=3, sp=2, zigzag=1, B=8)),
     ("fewer_sequences_than_ranks", dict(L=[5, 9, 2], dp=5, sp=2, zigzag=1, B=100)),
+    ("dp_40", dict(L=[(i * 7919) % 601 + 1 for i in range(777)], dp=40, sp=2, zigzag=1, B=100000)),
+    ("many_shard_pairs", dict(L=[(i * 13) % 70 + 1 for i in range(900)], G=64, dp=48, sp=1, B=100000)),
     ("dp_100", dict(L=list(range(1, 1301)), dp=100, sp=1, B=100000)),
     ("dp_1024", dict(L=[(i * 7919) % 997 + 1 for i in range(3000)], dp=1024, sp=1, B=100000)),
     ("groups_300", dict(L=[(i * 31) % 50 + 1 for i in range(2500)], G=300, dp=4, sp=2, B=1 << 20)),
