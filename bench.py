@@ -35,7 +35,8 @@ HBM_PEAK_GBPS = 8000.0
 # (scaled by a plain copy kernel of known size, see profiles/), keyed by the sha256 of the kernel
 # source the counters were taken on.  A changed kernel reports null until re-measured.
 MEASURED_TRAFFIC = {
-    # "<sha256 of csrc/earl_copy.hip>": {"heavy": bytes_per_launch, "longctx": ...},
+    "4293ad2168db80bd7d67ed2293eded4fddc87ca2349673d36023a10148eb6e1d":
+        {"heavy": 52051818764, "longctx": 46735745497},
 }
 
 WORKLOAD_NOTES = {
@@ -57,36 +58,38 @@ def kernel_source_hash() -> str:
         return hashlib.sha256(f.read()).hexdigest()
 
 
-def stage_workload(w, torch, B):
-    """Uploads every source shard buffer; the wide bf16 field is gathered from its pool on the
-    device (same bytes as the host generator: pool[index])."""
-    signed = {1: np.uint8, 2: np.int16, 4: np.int32, 8: np.int64}
+class HipEvents:
+    """hipEvent_t handles through ctypes (the HIP runtime is already loaded by torch)."""
 
-    def dev(a):
-        a = np.ascontiguousarray(a)
-        return torch.from_numpy(a.view(signed[a.dtype.itemsize])).cuda()
+    def __init__(self):
+        import ctypes
+        self.c = ctypes
+        self.lib = ctypes.CDLL("libamdhip64.so")
+        self.lib.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.lib.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.lib.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p,
+                                                 ctypes.c_void_p]
 
-    src = {}
-    for f in w.fields:
-        groups = []
-        for g in range(w.n_groups):
-            if f.kind == "hidden":
-                pool = dev(w.hidden_pool(f.width))
-                idx = torch.from_numpy(w.hidden_rows_index(g)).cuda()
-                groups.append(pool.index_select(0, idx))
-                del idx
-            else:
-                groups.append(dev(w.group_buffer(f, g)))
-        # replicas are separate buffers holding the same bytes
-        src[f.name] = [groups[s // w.replication] if s % w.replication == 0
-                       else groups[s // w.replication].clone() for s in range(w.n_shards)]
-    return src
+    def create(self) -> int:
+        ev = self.c.c_void_p()
+        if self.lib.hipEventCreate(self.c.byref(ev)) != 0:
+            raise RuntimeError("hipEventCreate failed")
+        return ev.value
+
+    def elapsed_ms(self, a: int, b: int) -> float:
+        ms = self.c.c_float()
+        if self.lib.hipEventElapsedTime(self.c.byref(ms), a, b) != 0:
+            raise RuntimeError("hipEventElapsedTime failed")
+        return float(ms.value)
+
+    def destroy(self, ev: int) -> None:
+        self.lib.hipEventDestroy(ev)
 
 
 def run_gpu(args, torch, B, synth):
     w = synth.make_workload(args.workload, seed=args.seed)
     t0 = time.time()
-    src = stage_workload(w, torch, B)
+    src = {f.name: w.device_shard_buffers(f, torch) for f in w.fields}
     torch.cuda.synchronize()
     stage_s = time.time() - t0
 
@@ -114,23 +117,34 @@ def run_gpu(args, torch, B, synth):
     algo_bytes = (row_bytes * sm["total_real_rows"] + row_bytes * sm["total_dst_rows"]
                   + 4 * sm["total_dst_rows"])
 
+    hip = HipEvents()
+
     def step(ev=None):
         p = B.plan_build(lengths, w.n_seqs, src_l, dst_l, ws, stream=stream)
         B.plan_get_summary(p)          # the consumer needs the shard sizes before it can dispatch
         if ev is not None:
-            ev[0].record(stream)
+            B.plan_set_dispatch_events(p, ev[0], ev[1])
         B.dispatch(p, fields, position_ids=pos, cu_seqlens=cu, workspace=scratch, stream=stream)
-        if ev is not None:
-            ev[1].record(stream)
         return p
+
+    if args.reference_copy:
+        # a plain copy of known size on the same stream: the yardstick for the HBM counters
+        n = 4 << 30
+        a = torch.empty(n, dtype=torch.uint8, device="cuda")
+        b = torch.empty(n, dtype=torch.uint8, device="cuda")
+        a.view(torch.int32).fill_(1)
+        for _ in range(3):
+            b.view(torch.int32).copy_(a.view(torch.int32))
+        torch.cuda.synchronize()
+        del a, b
 
     plans = [step() for _ in range(args.warmup)]
     torch.cuda.synchronize()
     for p in plans:
         B.plan_destroy(p)
 
-    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-              for _ in range(args.steps)]
+    # HIP events recorded by the library on the dispatch stream, right around the re-layout kernel
+    events = [(hip.create(), hip.create()) for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     plans = [step(events[k]) for k in range(args.steps)]
@@ -140,7 +154,10 @@ def run_gpu(args, torch, B, synth):
         B.plan_destroy(p)
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    kern_ms = [a.elapsed_time(b) for a, b in events]
+    kern_ms = [hip.elapsed_ms(a, b) for a, b in events]
+    for a, b in events:
+        hip.destroy(a)
+        hip.destroy(b)
     kern_avg_ms = float(np.mean(kern_ms))
     achieved = algo_bytes / (kern_avg_ms * 1e-3) / 1e9
     traffic = MEASURED_TRAFFIC.get(kernel_source_hash(), {}).get(args.workload)
@@ -150,27 +167,37 @@ def run_gpu(args, torch, B, synth):
 
 
 def run_cpu_baseline(args, synth):
-    """The oracle as it stands (single thread: Python loops + numpy slice copies), on a reduced
-    sequence count of the same workload; forward path only (plan, all fields, all shards,
-    position ids)."""
+    """The oracle as it stands (single thread: Python loops + numpy slice copies) on a bounded
+    sample of the workload: a reduced sequence count with the same length distribution, fields
+    and layouts, forward path only (plan, all fields, all shards, position ids), repeated until
+    about ten seconds of CPU time have been spent."""
     from oracle import earl_oracle as O
-    scale = {"tiny": 1.0, "mid": 1.0, "agentic": 1.0, "heavy": 1.0 / 16, "longctx": 1.0 / 16}[args.workload]
+    scale = {"tiny": 1.0, "mid": 1.0, "agentic": 1.0, "heavy": 1.0 / 8, "longctx": 1.0 / 8}[args.workload]
     w = synth.make_workload(args.workload, seed=args.seed, scale=scale)
     host = {f.name: [w.group_buffer(f, s // w.replication) for s in range(w.n_shards)]
             for f in w.fields}
+    passes = 0
     t0 = time.perf_counter()
-    plan = O.build_plan(w.lengths, n_groups=w.n_groups, replication=w.replication,
-                        seq_group=w.seq_group, dp=w.dp, sp=w.sp, zigzag=w.zigzag,
-                        pad_multiple=w.pad_multiple, mb_token_budget=w.mb_token_budget)
-    for q in range(w.dp * w.sp):
-        O.position_ids_shard(plan, q)
-        for f in w.fields:
-            O.dispatch_field_shard(plan, q, host[f.name], f.np_dtype, f.width, f.pad_scalar)
-    dt = time.perf_counter() - t0
-    return {"value": w.total_tokens / dt, "unit": "tokens/s", "cores": 1, "kind": "oracle",
-            "sample": f"{w.n_seqs} of the workload's sequences ({w.total_tokens} tokens), all fields, "
-                      f"all {w.dp * w.sp} destination shards, plan + dispatch, {dt:.2f} s of one core "
-                      f"(host has {os.cpu_count()} logical cpus)"}
+    while True:
+        plan = O.build_plan(w.lengths, n_groups=w.n_groups, replication=w.replication,
+                            seq_group=w.seq_group, dp=w.dp, sp=w.sp, zigzag=w.zigzag,
+                            pad_multiple=w.pad_multiple, mb_token_budget=w.mb_token_budget)
+        for q in range(w.dp * w.sp):
+            O.position_ids_shard(plan, q)
+            for f in w.fields:
+                O.dispatch_field_shard(plan, q, host[f.name], f.np_dtype, f.width, f.pad_scalar)
+        passes += 1
+        dt = time.perf_counter() - t0
+        if dt >= 10.0 or passes >= 200:
+            break
+    row_bytes = sum(f.row_bytes for f in w.fields)
+    algo = row_bytes * (plan.total_real_rows + plan.total_dst_rows) + 4 * plan.total_dst_rows
+    return {"value": passes * w.total_tokens / dt, "unit": "tokens/s", "cores": 1, "kind": "oracle",
+            "GBps": passes * algo / dt / 1e9,
+            "sample": f"{w.n_seqs} sequences drawn like the workload ({w.total_tokens} tokens, "
+                      f"{algo / 1e9:.2f} GB moved per pass), all fields, all {w.dp * w.sp} destination "
+                      f"shards, plan + dispatch, {passes} passes in {dt:.1f} s on one core "
+                      f"(host reports {os.cpu_count()} logical cpus)"}
 
 
 def main() -> int:
@@ -181,6 +208,8 @@ def main() -> int:
     ap.add_argument("--workload", default="heavy", choices=list(WORKLOAD_NOTES))
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--reference-copy", action="store_true",
+                    help="also run three plain 4 GiB device copies (for scaling profiler counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU's share of the re-layout (all destination shards in one "

@@ -209,6 +209,14 @@ int32_t earl_dispatch(earl_plan* plan, const earl_field* fields, int32_t n_field
                       void* dispatch_ws_dev, size_t dispatch_ws_bytes, void* hip_stream);
 
 /*
+ * Measurement hook: the following earl_dispatch calls on this plan record `event_before` on the
+ * stream right before the re-layout kernel and `event_after` right after it (both hipEvent_t created
+ * by the caller with timing enabled; NULL, NULL switches the hook off).  The interval is the
+ * duration of the copy kernel alone, without the tile-code pass and the parameter upload.
+ */
+int32_t earl_plan_set_dispatch_events(earl_plan* plan, void* event_before, void* event_after);
+
+/*
  * The reverse direction (training layout back to the rollout layout, for the stages that run
  * between several models): every real row of every destination shard is copied back to the source
  * row it was read from.  Field descriptors as in earl_dispatch with the roles of the two pointer

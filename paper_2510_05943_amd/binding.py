@@ -23,7 +23,7 @@ EARL_MAX_FIELDS = 32
 EXPORTED = ("earl_plan_workspace_bytes", "earl_plan_build", "earl_plan_get_summary",
             "earl_plan_export", "earl_plan_export_segments", "earl_dispatch_workspace_bytes",
             "earl_dispatch",
-            "earl_dispatch_inverse", "earl_plan_destroy", "earl_status_string",
+            "earl_dispatch_inverse", "earl_plan_set_dispatch_events", "earl_plan_destroy", "earl_status_string",
             "earl_last_error_message")
 
 
@@ -87,6 +87,7 @@ def load_library() -> C.CDLL:
                                                   C.POINTER(C.c_size_t)]
     lib.earl_dispatch.argtypes = [vp, C.POINTER(_Field), i32, C.POINTER(vp), vp, vp, C.c_size_t, vp]
     lib.earl_dispatch_inverse.argtypes = [vp, C.POINTER(_Field), i32, vp, C.c_size_t, vp]
+    lib.earl_plan_set_dispatch_events.argtypes = [vp, vp, vp]
     lib.earl_plan_destroy.argtypes = [vp]
     lib.earl_status_string.argtypes = [i32]
     lib.earl_status_string.restype = C.c_char_p
@@ -292,6 +293,11 @@ def dispatch_inverse(plan: Plan, fields: Sequence[Field], workspace=None, stream
     arr, n, keep = _marshal_fields(fields)
     _check(load_library().earl_dispatch_inverse(plan.handle, arr, n, _ptr(workspace),
                                                 _nbytes(workspace), _stream_handle(stream)))
+
+
+def plan_set_dispatch_events(plan: Plan, event_before: Optional[int], event_after: Optional[int]) -> None:
+    """earl_plan_set_dispatch_events: raw hipEvent_t handles (ints) or None, None."""
+    _check(load_library().earl_plan_set_dispatch_events(plan.handle, event_before, event_after))
 
 
 def plan_destroy(plan: Plan) -> None:

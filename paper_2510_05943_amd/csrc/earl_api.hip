@@ -170,6 +170,8 @@ struct earl_plan {
   bool summary_ready;
   int32_t status;
   bool inverse_ready;
+  void* ev_before;
+  void* ev_after;
   std::vector<int32_t> seg_starts;      // first segment of every destination shard (+ total)
   std::vector<unsigned char> summary;   // host copy of the workspace's summary block
   PlanHeader hdr;
@@ -343,6 +345,8 @@ int32_t earl_plan_build(const int32_t* lengths_dev, int32_t n_seqs, const earl_s
   p->summary_ready = false;
   p->status = EARL_OK;
   p->inverse_ready = false;
+  p->ev_before = nullptr;
+  p->ev_after = nullptr;
 
   PlanDev& v = p->dev;
   unsigned char* w = p->ws;
@@ -603,8 +607,12 @@ int32_t earl_dispatch(earl_plan* p, const earl_field* fields, int32_t n_fields,
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   st = upload_params(b.bytes, dispatch_ws_dev, stream);
   if (st != EARL_OK) return st;
-  launch_copy(copy_args(p, dispatch_ws_dev, tiles),
-              static_cast<unsigned char*>(dispatch_ws_dev) + codes_off, stream);
+  const CopyArgs ca = copy_args(p, dispatch_ws_dev, tiles);
+  void* codes = static_cast<unsigned char*>(dispatch_ws_dev) + codes_off;
+  launch_tile_codes(ca, codes, stream);
+  if (p->ev_before) HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(p->ev_before), stream));
+  launch_copy(ca, codes, stream);
+  if (p->ev_after) HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(p->ev_after), stream));
   hipError_t e = hipGetLastError();
   if (e != hipSuccess)
     return fail(EARL_HIP_ERROR, "re-layout kernel launch failed: %s", hipGetErrorString(e));
@@ -667,6 +675,15 @@ int32_t earl_dispatch_inverse(earl_plan* p, const earl_field* fields, int32_t n_
   hipError_t e = hipGetLastError();
   if (e != hipSuccess)
     return fail(EARL_HIP_ERROR, "inverse kernel launch failed: %s", hipGetErrorString(e));
+  return EARL_OK;
+}
+
+int32_t earl_plan_set_dispatch_events(earl_plan* p, void* event_before, void* event_after) {
+  if (!p) return fail(EARL_INVALID_ARG, "null plan");
+  if ((event_before == nullptr) != (event_after == nullptr))
+    return fail(EARL_INVALID_ARG, "pass two events or two NULLs");
+  p->ev_before = event_before;
+  p->ev_after = event_after;
   return EARL_OK;
 }
 

@@ -414,13 +414,17 @@ __global__ __launch_bounds__(kCopyThreads) void inverse_kernel(const CopyArgs a,
 
 }  // namespace
 
-void launch_copy(const CopyArgs& a, void* tile_codes, hipStream_t stream) {
+void launch_tile_codes(const CopyArgs& a, void* tile_codes, hipStream_t stream) {
   if (a.n_tiles <= 0) return;
-  TileCode* codes = static_cast<TileCode*>(tile_codes);
-  const unsigned g1 = (unsigned)((a.n_tiles + kCopyThreads - 1) / kCopyThreads);
-  hipLaunchKernelGGL(tile_code_kernel, dim3(g1), dim3(kCopyThreads), 0, stream, a, codes);
+  const unsigned grid = (unsigned)((a.n_tiles + kCopyThreads - 1) / kCopyThreads);
+  hipLaunchKernelGGL(tile_code_kernel, dim3(grid), dim3(kCopyThreads), 0, stream, a,
+                     static_cast<TileCode*>(tile_codes));
+}
+
+void launch_copy(const CopyArgs& a, const void* tile_codes, hipStream_t stream) {
+  if (a.n_tiles <= 0) return;
   hipLaunchKernelGGL(relayout_kernel, dim3((unsigned)a.n_tiles), dim3(kCopyThreads), 0, stream, a,
-                     codes);
+                     static_cast<const TileCode*>(tile_codes));
 }
 
 void launch_real_prefix(const SegRec* segs, int64_t* prefix, int n_seg, hipStream_t stream) {

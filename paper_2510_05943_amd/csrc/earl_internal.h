@@ -139,7 +139,8 @@ struct CopyArgs {
 void launch_plan(const PlanDev& p, hipStream_t stream);
 // tile_codes: 16 bytes of scratch per tile
 constexpr size_t kTileCodeBytes = 16;
-void launch_copy(const CopyArgs& a, void* tile_codes, hipStream_t stream);
+void launch_tile_codes(const CopyArgs& a, void* tile_codes, hipStream_t stream);
+void launch_copy(const CopyArgs& a, const void* tile_codes, hipStream_t stream);
 // seg_real_prefix[e] = real rows of the segments before e (n_seg+1 entries)
 void launch_real_prefix(const SegRec* segs, int64_t* prefix, int n_seg, hipStream_t stream);
 void launch_copy_inverse(const CopyArgs& a, const int64_t* seg_real_prefix,

@@ -178,6 +178,33 @@ class Workload:
         return out
 
 
+    def device_shard_buffers(self, field: FieldSpec, torch) -> list:
+        """The S shard buffers of `field` as device tensors (input staging only).
+
+        Narrow fields are drawn on the host and uploaded.  The wide bf16 field is materialised on
+        the device as pool[index] (torch.index_select), which yields exactly the bytes
+        group_buffer() returns, without drawing tens of gigabytes on the host.  Replicas of a
+        group are separate buffers holding the same bytes.
+        """
+        signed = {1: np.uint8, 2: np.int16, 4: np.int32, 8: np.int64}
+
+        def dev(a):
+            a = np.ascontiguousarray(a)
+            return torch.from_numpy(a.view(signed[a.dtype.itemsize])).cuda()
+
+        groups = []
+        for g in range(self.n_groups):
+            if field.kind == "hidden":
+                pool = dev(self.hidden_pool(field.width))
+                idx = torch.from_numpy(self.hidden_rows_index(g)).cuda()
+                groups.append(pool.index_select(0, idx))
+                del idx, pool
+            else:
+                groups.append(dev(self.group_buffer(field, g)))
+        return [groups[s // self.replication] if s % self.replication == 0
+                else groups[s // self.replication].clone() for s in range(self.n_shards)]
+
+
 CONFIG_NAMES = ("tiny", "mid", "agentic", "heavy", "longctx")
 
 
