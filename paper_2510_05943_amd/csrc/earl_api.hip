@@ -596,7 +596,7 @@ int32_t earl_dispatch(earl_plan* p, const earl_field* fields, int32_t n_fields,
     pi += S + n_dst;
   }
   ts[(size_t)F * n_dst] = tiles;
-  if (tiles > 0x7fffffffll) return fail(EARL_INVALID_ARG, "too many tiles for one launch");
+  if (tiles * kSubTiles > 0x7fffffffll) return fail(EARL_INVALID_ARG, "too many tiles for one launch");
   if (tiles == 0) return EARL_OK;
   const size_t codes_off = b.bytes.size();
   const size_t need = codes_off + kTileCodeBytes * (size_t)tiles;

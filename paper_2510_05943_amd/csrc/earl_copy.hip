@@ -8,13 +8,14 @@
 //     the wavefront then ends: stores are fire-and-forget (nothing waits for their
 //     acknowledgement) and the wavefronts in flight always cover one compact, advancing window
 //     of addresses.  Loops over large tiles, persistent grids and deeper unrolling all measured
-//     15-30 % slower.  So a workgroup owns exactly 4 KiB of one destination shard of one field;
+//     15-30 % slower, and one-wavefront workgroups beat larger ones.  So a workgroup is one
+//     wavefront and owns exactly 1 KiB of one destination shard of one field;
 //   * with so little work per wavefront, any search ("which field, which shard, which segment")
 //     in front of the load costs more than the copy itself.  A first kernel therefore decodes
 //     every tile ONCE, one tile per lane (64 decodes per wavefront instruction), into a 16-byte
-//     tile code: source pointer, destination pointer and what to do.  The copy kernel reads its
-//     code with one uniform load and, for a tile that lies inside the real part of one segment
-//     (nearly all bytes of a wide field), does nothing but load and store;
+//     tile code per 4 KiB of destination: source pointer, destination pointer and what to do.
+//     The copy kernel reads its code with one uniform load and, for a tile that lies inside the
+//     real part of one segment (nearly all bytes of a wide field), does nothing but load and store;
 //   * work is cut on the DESTINATION, every lane owns one whole 16-byte destination vector:
 //     stores are aligned global_store_dwordx4 and no two workgroups share a cache line;
 //   * a vector inside the real part of a segment is one (possibly unaligned)
@@ -140,8 +141,8 @@ __device__ __forceinline__ ParamView view_params(const DispatchDev* p) {
 }
 
 // Pass 1: one lane per tile.
-__global__ __launch_bounds__(kCopyThreads) void tile_code_kernel(const CopyArgs a, TileCode* codes) {
-  const int64_t tile = (int64_t)blockIdx.x * kCopyThreads + threadIdx.x;
+__global__ __launch_bounds__(kCodeThreads) void tile_code_kernel(const CopyArgs a, TileCode* codes) {
+  const int64_t tile = (int64_t)blockIdx.x * kCodeThreads + threadIdx.x;
   if (tile >= a.n_tiles) return;
   const ParamView pv = view_params(a.params);
   const int x = last_le(pv.tile_start, 0, pv.n_recs, tile);
@@ -210,8 +211,8 @@ __device__ __forceinline__ void seek(const SegRec* segs, const TileInfo& t, int6
 __device__ __noinline__ void generic_tile(const CopyArgs& a, const TileCode c) {
   const ParamView pv = view_params(a.params);
   const TileRec rec = pv.recs[(uint32_t)(c.a >> 32)];
-  const int64_t lo = ((int64_t)blockIdx.x - rec.tile_first) * (int64_t)kTileBytes;
-  const int64_t o = lo + (int64_t)threadIdx.x * kVecBytes;   // this lane's vector
+  const int64_t lo = ((int64_t)(blockIdx.x / kSubTiles) - rec.tile_first) * (int64_t)kTileBytes;
+  const int64_t o = lo + (int64_t)((blockIdx.x % kSubTiles) * kCopyThreads + threadIdx.x) * kVecBytes;
   if (o >= rec.end_bytes) return;
   u8* dst = static_cast<u8*>(rec.dst);
   const int64_t o_end = o + kVecBytes;
@@ -268,18 +269,19 @@ __device__ __noinline__ void generic_tile(const CopyArgs& a, const TileCode c) {
   }
 }
 
-// Pass 2: one workgroup per 4 KiB tile, one 16-byte vector per lane.
+// Pass 2: kSubTiles one-wavefront workgroups per 4 KiB tile, one 16-byte vector per lane.
 __global__ __launch_bounds__(kCopyThreads) void relayout_kernel(const CopyArgs a,
                                                                 const TileCode* __restrict__ codes) {
-  const TileCode c = codes[blockIdx.x];
+  const TileCode c = codes[blockIdx.x / kSubTiles];
   const uint64_t act = c.b & 15u;
-  u8* dst = reinterpret_cast<u8*>(c.b & ~(uint64_t)15) + threadIdx.x * kVecBytes;
+  const uint32_t v = (blockIdx.x % kSubTiles) * kCopyThreads + threadIdx.x;   // vector in the tile
+  u8* dst = reinterpret_cast<u8*>(c.b & ~(uint64_t)15) + v * kVecBytes;
   if (act == kActCopy) {
-    store16(dst, load16(reinterpret_cast<const u8*>(c.a) + threadIdx.x * kVecBytes));
+    store16(dst, load16(reinterpret_cast<const u8*>(c.a) + v * kVecBytes));
   } else if (act == kActFill) {
     store16(dst, u32x4{(uint32_t)c.a, (uint32_t)(c.a >> 32), (uint32_t)c.a, (uint32_t)(c.a >> 32)});
   } else if (act == kActIota) {
-    const uint32_t p0 = (uint32_t)c.a + threadIdx.x * 4;
+    const uint32_t p0 = (uint32_t)c.a + v * 4;
     store16(dst, u32x4{p0, p0 + 1, p0 + 2, p0 + 3});
   } else {
     generic_tile(a, c);
@@ -331,7 +333,7 @@ struct InvInfo {
   int32_t scalar_bytes;
 };
 
-__global__ __launch_bounds__(kCopyThreads) void inverse_kernel(const CopyArgs a,
+__global__ __launch_bounds__(kInverseThreads) void inverse_kernel(const CopyArgs a,
                                                                const int64_t* seg_real_prefix,
                                                                const int32_t* seg_dst_shard,
                                                                int n_seg) {
@@ -416,15 +418,15 @@ __global__ __launch_bounds__(kCopyThreads) void inverse_kernel(const CopyArgs a,
 
 void launch_tile_codes(const CopyArgs& a, void* tile_codes, hipStream_t stream) {
   if (a.n_tiles <= 0) return;
-  const unsigned grid = (unsigned)((a.n_tiles + kCopyThreads - 1) / kCopyThreads);
-  hipLaunchKernelGGL(tile_code_kernel, dim3(grid), dim3(kCopyThreads), 0, stream, a,
+  const unsigned grid = (unsigned)((a.n_tiles + kCodeThreads - 1) / kCodeThreads);
+  hipLaunchKernelGGL(tile_code_kernel, dim3(grid), dim3(kCodeThreads), 0, stream, a,
                      static_cast<TileCode*>(tile_codes));
 }
 
 void launch_copy(const CopyArgs& a, const void* tile_codes, hipStream_t stream) {
   if (a.n_tiles <= 0) return;
-  hipLaunchKernelGGL(relayout_kernel, dim3((unsigned)a.n_tiles), dim3(kCopyThreads), 0, stream, a,
-                     static_cast<const TileCode*>(tile_codes));
+  hipLaunchKernelGGL(relayout_kernel, dim3((unsigned)(a.n_tiles * kSubTiles)), dim3(kCopyThreads), 0,
+                     stream, a, static_cast<const TileCode*>(tile_codes));
 }
 
 void launch_real_prefix(const SegRec* segs, int64_t* prefix, int n_seg, hipStream_t stream) {
@@ -434,7 +436,7 @@ void launch_real_prefix(const SegRec* segs, int64_t* prefix, int n_seg, hipStrea
 void launch_copy_inverse(const CopyArgs& a, const int64_t* seg_real_prefix,
                          const int32_t* seg_dst_shard, int n_seg, hipStream_t stream) {
   if (a.n_tiles <= 0) return;
-  hipLaunchKernelGGL(inverse_kernel, dim3((unsigned)a.n_tiles), dim3(kCopyThreads), 0, stream, a,
+  hipLaunchKernelGGL(inverse_kernel, dim3((unsigned)a.n_tiles), dim3(kInverseThreads), 0, stream, a,
                      seg_real_prefix, seg_dst_shard, n_seg);
 }
 

@@ -19,9 +19,12 @@ constexpr int kLdsLabels = 256;
 // Sort keys kept in LDS up to this many (power of two); more go to the workspace.
 constexpr int kLdsSortKeys = 8192;
 
-constexpr int kCopyThreads = 256;    // re-layout kernel workgroup (4 wavefronts, one tile each)
 constexpr int kVecBytes = 16;        // one global_load/store_dwordx4 per lane
-constexpr int kTileBytes = kCopyThreads * kVecBytes;  // destination bytes per workgroup
+constexpr int kTileBytes = 4096;     // destination bytes described by one tile code
+constexpr int kCopyThreads = 64;     // re-layout workgroup: one wavefront, 1 KiB of a tile
+constexpr int kSubTiles = kTileBytes / (kCopyThreads * kVecBytes);   // workgroups per tile
+constexpr int kCodeThreads = 256;    // tile-code kernel workgroup (one tile per lane)
+constexpr int kInverseThreads = kTileBytes / kVecBytes;   // inverse kernel: one tile per workgroup
 
 // First bytes of the workspace; copied to the host together with the arrays that follow it.
 struct PlanHeader {
