@@ -151,7 +151,8 @@ class DstLayout:
 @dataclasses.dataclass
 class Field:
     """One field: per-shard device buffers in both layouts.  Buffers are tensors (or objects
-    with data_ptr()/numel()/element_size()); None marks a shard without a buffer."""
+    with data_ptr()/numel()/element_size()); None marks a shard without a buffer.  The C
+    descriptor is built at the first call and kept: do not change a Field after using it."""
     scalar_bytes: int
     width: int
     pad_scalar: int
@@ -243,20 +244,31 @@ def plan_export_segments(plan: Plan) -> Dict[str, np.ndarray]:
     return bufs
 
 
+def _marshal_field(f: Field):
+    """C descriptor of one field; built once per Field object and kept with it."""
+    cached = getattr(f, "_c", None)
+    if cached is not None:
+        return cached
+    src = (C.c_void_p * len(f.src_shards))(*[_ptr(t) for t in f.src_shards])
+    dst = (C.c_void_p * len(f.dst_shards))(*[_ptr(t) for t in f.dst_shards])
+    cap = (C.c_int64 * len(f.dst_shards))(*[f._rows(t) for t in f.dst_shards])
+    scap = (C.c_int64 * len(f.src_shards))(*[f._rows(t) for t in f.src_shards])
+    desc = _Field(f.scalar_bytes, f.width, f.pad_scalar & 0xFFFFFFFFFFFFFFFF,
+                  C.cast(src, C.POINTER(C.c_void_p)), C.cast(dst, C.POINTER(C.c_void_p)),
+                  C.cast(cap, C.POINTER(C.c_int64)),
+                  C.cast(scap, C.POINTER(C.c_int64)) if f.check_src_capacity else None)
+    f._c = (desc, (src, dst, cap, scap))
+    return f._c
+
+
 def _marshal_fields(fields: Sequence[Field]):
     n = len(fields)
     arr = (_Field * max(n, 1))()
     keep = []
     for k, f in enumerate(fields):
-        src = (C.c_void_p * len(f.src_shards))(*[_ptr(t) for t in f.src_shards])
-        dst = (C.c_void_p * len(f.dst_shards))(*[_ptr(t) for t in f.dst_shards])
-        cap = (C.c_int64 * len(f.dst_shards))(*[f._rows(t) for t in f.dst_shards])
-        scap = (C.c_int64 * len(f.src_shards))(*[f._rows(t) for t in f.src_shards])
-        keep += [src, dst, cap, scap]
-        arr[k] = _Field(f.scalar_bytes, f.width, f.pad_scalar & 0xFFFFFFFFFFFFFFFF,
-                        C.cast(src, C.POINTER(C.c_void_p)), C.cast(dst, C.POINTER(C.c_void_p)),
-                        C.cast(cap, C.POINTER(C.c_int64)),
-                        C.cast(scap, C.POINTER(C.c_int64)) if f.check_src_capacity else None)
+        desc, owned = _marshal_field(f)
+        arr[k] = desc
+        keep.append(owned)
     return arr, n, keep
 
 

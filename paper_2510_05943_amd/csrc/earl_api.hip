@@ -224,12 +224,17 @@ int32_t upload_params(const std::vector<unsigned char>& block, void* dev_dst, hi
     return EARL_OK;
   }
   std::lock_guard<std::mutex> lock(g_stage_mu);
+  if (!g_stage[0].host) {
+    // first use: one pinned allocation for all slots
+    void* base = nullptr;
+    HIP_TRY(hipHostMalloc(&base, kStageBytes * kStageSlots, hipHostMallocDefault));
+    for (int k = 0; k < kStageSlots; ++k) {
+      HIP_TRY(hipEventCreateWithFlags(&g_stage[k].done, hipEventDisableTiming));
+      g_stage[k].host = static_cast<unsigned char*>(base) + (size_t)k * kStageBytes;
+    }
+  }
   StageSlot& s = g_stage[g_stage_next];
   g_stage_next = (g_stage_next + 1) % kStageSlots;
-  if (!s.host) {
-    HIP_TRY(hipHostMalloc(&s.host, kStageBytes, hipHostMallocDefault));
-    HIP_TRY(hipEventCreateWithFlags(&s.done, hipEventDisableTiming));
-  }
   if (s.in_flight) HIP_TRY(hipEventSynchronize(s.done));
   std::memcpy(s.host, block.data(), block.size());
   HIP_TRY(hipMemcpyAsync(dev_dst, s.host, block.size(), hipMemcpyHostToDevice, stream));
