@@ -32,14 +32,17 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef u32x4 u32x4_u __attribute__((aligned(1)));
 typedef unsigned char u8;
 
+// All field buffers are global (HBM) memory: say so, or pointers rebuilt from integers compile to
+// FLAT instead of GLOBAL loads and stores.
+#define EARL_GLOBAL __attribute__((address_space(1)))
 __device__ __forceinline__ u32x4 load16(const u8* p) {
-  return __builtin_nontemporal_load(reinterpret_cast<const u32x4_u*>(p));
+  return __builtin_nontemporal_load((const EARL_GLOBAL u32x4_u*)p);
 }
 __device__ __forceinline__ void store16(u8* p, u32x4 v) {
-  __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(p));
+  __builtin_nontemporal_store(v, (EARL_GLOBAL u32x4*)p);
 }
 __device__ __forceinline__ void store16_any(u8* p, u32x4 v) {
-  __builtin_nontemporal_store(v, reinterpret_cast<u32x4_u*>(p));
+  __builtin_nontemporal_store(v, (EARL_GLOBAL u32x4_u*)p);
 }
 
 __device__ __forceinline__ uint64_t load_scalar(const u8* p, int sb) {

@@ -187,7 +187,11 @@ __device__ void label_scan(int N, int n_labels, LabF lab, ValF val, OutF out, in
 // ---------------------------------------------------------------------------------------
 // Bitonic sort of n (power of two) unique 64-bit keys, ascending.
 // ---------------------------------------------------------------------------------------
-__device__ void bitonic_sort(uint64_t* keys, int n) {
+// Stages whose partner distance j is at most 64 only touch aligned blocks of 128 keys, and the
+// 64 compare-exchanges of a block all belong to one wavefront (thread t handles block t / 64), so
+// those stages need no workgroup barrier, only program order inside the wavefront.
+template <class KeyPtr, bool kLds>
+__device__ void bitonic_sort_impl(KeyPtr keys, int n) {
   for (int k = 2; k <= n; k <<= 1) {
     for (int j = k >> 1; j > 0; j >>= 1) {
       for (int t = threadIdx.x; t < (n >> 1); t += T) {
@@ -200,8 +204,24 @@ __device__ void bitonic_sort(uint64_t* keys, int n) {
           keys[x] = a;
         }
       }
-      __syncthreads();
+      if (!kLds || j > kWave || (j == 1 && k > kWave)) {
+        __syncthreads();   // the next stage crosses wavefront blocks
+      } else {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      }
     }
+  }
+  __syncthreads();
+}
+
+__device__ void bitonic_sort(uint64_t* keys, int n, bool keys_in_lds) {
+  if (keys_in_lds) {
+    typedef __attribute__((address_space(3))) uint64_t* LdsKeys;
+    bitonic_sort_impl<LdsKeys, true>((LdsKeys)keys, n);
+  } else {
+    bitonic_sort_impl<uint64_t*, false>(keys, n);
   }
 }
 
@@ -237,12 +257,55 @@ __device__ __forceinline__ uint32_t wave_min_low(uint32_t x) {
   return (uint32_t)__builtin_amdgcn_readlane((int)x, kSteps >= 5 ? 63 : 0);
 }
 
-// D <= 64, one rank per lane, loads small enough that (load << 6 | lane) fits 32 bits for the
-// whole run: the lane number rides in the low six bits of the compared word, so one reduction
+// D <= 16, one rank per lane, loads small enough that (load << 6 | lane) fits 32 bits for the
+// whole run: the lane number rides in the low six bits of the compared word, so one butterfly
 // yields the minimum load AND the lowest rank that has it (the lane bits make all words
 // distinct, and equal loads order by lane).  Lanes >= D hold 0xffffffff and never win.
+// After the butterfly every lane of the group holds the winning word, so the whole step stays
+// in the vector ALU (no scalar round trip): compare the low bits with the own lane number, add
+// the padded length if they match, and note the step in a 64-bit "won" mask.  After 64 steps
+// the masks are turned into ranks.  Items past N have length 0 and come last, so running full
+// blocks of 64 steps changes nothing.
 template <int kSteps>
 __device__ void lpt_packed(const PlanDev& p, const uint64_t* keys) {
+  static_assert(kSteps <= 4, "the butterfly must stay inside one row of 16 lanes");
+  const int lane = lane_id();
+  const int N = p.N, D = p.D;
+  const bool valid = lane < D;
+  uint32_t word = valid ? (uint32_t)lane : 0xffffffffu;   // load << 6 | lane
+  for (int start = 0; start < N; start += kWave) {
+    const int i = start + lane;
+    const uint64_t key = i < N ? keys[i] : ~0ull;
+    const uint32_t lp6 = i < N ? (uint32_t)(0x7fffffff - (int32_t)(key >> 32)) << 6 : 0u;
+    const int32_t idx = (int32_t)(key & 0xffffffffu);
+    uint32_t won_lo = 0, won_hi = 0;
+#pragma unroll
+    for (int s = 0; s < kWave; ++s) {
+      const uint32_t lp_s = (uint32_t)__builtin_amdgcn_readlane((int)lp6, s);
+      uint32_t mn = word;
+      if (kSteps >= 1) mn = dpp_min_all_rows<kDppQuadXor1>(mn);
+      if (kSteps >= 2) mn = dpp_min_all_rows<kDppQuadXor2>(mn);
+      if (kSteps >= 3) mn = dpp_min_all_rows<kDppRowHalfMirror>(mn);
+      if (kSteps >= 4) mn = dpp_min_all_rows<kDppRowMirror>(mn);
+      const bool win = valid && (mn & 63u) == (uint32_t)lane;
+      word += win ? lp_s : 0u;
+      if (s < 32) won_lo |= win ? (1u << s) : 0u;
+      else won_hi |= win ? (1u << (s - 32)) : 0u;
+    }
+    int my_rank = 0;
+    for (int r = 0; r < D; ++r) {
+      const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)won_lo, r);
+      const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)won_hi, r);
+      const uint64_t steps = ((uint64_t)hi << 32) | lo;
+      if ((steps >> lane) & 1ull) my_rank = r;
+    }
+    if (i < N) p.rank[idx] = my_rank;
+  }
+}
+
+// 16 < D <= 64 with small loads: the same packed word, reduced over all 64 lanes and read back
+// through a scalar register.
+__device__ void lpt_packed_wave(const PlanDev& p, const uint64_t* keys) {
   const int lane = lane_id();
   const int N = p.N;
   uint32_t word = lane < p.D ? (uint32_t)lane : 0xffffffffu;   // load << 6 | lane
@@ -255,7 +318,7 @@ __device__ void lpt_packed(const PlanDev& p, const uint64_t* keys) {
     const int cnt = min(kWave, N - start);
     for (int s = 0; s < cnt; ++s) {
       const uint32_t lp_s = (uint32_t)__builtin_amdgcn_readlane((int)lp6, s);
-      const int wl = (int)(wave_min_low<kSteps>(word) & 63u);
+      const int wl = (int)(wave_min_low<6>(word) & 63u);
       word += lane == wl ? lp_s : 0u;
       my_rank = lane == s ? wl : my_rank;
     }
@@ -349,7 +412,7 @@ __device__ void lpt_wave0(const PlanDev& p, const uint64_t* keys, int64_t* lds_l
   } else if (D <= 16) {
     lpt_packed<4>(p, keys);
   } else {
-    lpt_packed<6>(p, keys);
+    lpt_packed_wave(p, keys);
   }
 }
 
@@ -454,13 +517,23 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const PlanDev p) {
       tab_sum, tab_cnt);
   {
     const int32_t* group_cnt = tab_cnt + 2 * (size_t)kPlanWaves * G;
+    const bool lds_max = S <= kLdsA2a;   // rows needed per shard: maximum taken in LDS
+    if (lds_max) {
+      for (int x = tid; x < S; x += T) s_a2a[x] = 0;
+      __syncthreads();
+    }
     for (int i = tid; i < N; i += T) {
       const int g = p.seq_group[i];
-      const int64_t t = ((int64_t)p.slot[i] * R) / group_cnt[g];
+      const int64_t t = R == 1 ? 0 : ((int64_t)p.slot[i] * R) / group_cnt[g];
       const int s = g * R + (int)t;
       p.seq_shard[i] = s;
-      atomicMax(reinterpret_cast<unsigned long long*>(&p.src_rows_needed[s]),
-                (unsigned long long)(p.seq_row[i] + p.lengths[i]));
+      const unsigned long long need = (unsigned long long)(p.seq_row[i] + p.lengths[i]);
+      if (lds_max) atomicMax(&s_a2a[s], need);
+      else atomicMax(reinterpret_cast<unsigned long long*>(&p.src_rows_needed[s]), need);
+    }
+    if (lds_max) {
+      __syncthreads();
+      for (int x = tid; x < S; x += T) p.src_rows_needed[x] = (int64_t)s_a2a[x];
     }
   }
   __syncthreads();
@@ -476,7 +549,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const PlanDev p) {
     keys[i] = key;
   }
   __syncthreads();
-  bitonic_sort(keys, p.n_pow2);
+  bitonic_sort(keys, p.n_pow2, p.n_pow2 <= kLdsSortKeys);
   if (wave_id() == 0) lpt_wave0(p, keys, lds_load);
   __syncthreads();
 
