@@ -116,6 +116,13 @@ def run_gpu(args, torch, B, synth):
     row_bytes = sum(f.row_bytes for f in w.fields)
     algo_bytes = (row_bytes * sm["total_real_rows"] + row_bytes * sm["total_dst_rows"]
                   + 4 * sm["total_dst_rows"])
+    if args.inverse:
+        # training layout -> rollout layout: every real row read once and written once
+        algo_bytes = 2 * row_bytes * sm["total_real_rows"]
+        p1 = B.plan_build(lengths, w.n_seqs, src_l, dst_l, ws, stream=stream)
+        B.dispatch(p1, fields, position_ids=pos, cu_seqlens=cu, workspace=scratch, stream=stream)
+        torch.cuda.synchronize()        # the destination shards now hold a real training layout
+        B.plan_destroy(p1)
 
     hip = HipEvents()
 
@@ -124,7 +131,10 @@ def run_gpu(args, torch, B, synth):
         B.plan_get_summary(p)          # the consumer needs the shard sizes before it can dispatch
         if ev is not None:
             B.plan_set_dispatch_events(p, ev[0], ev[1])
-        B.dispatch(p, fields, position_ids=pos, cu_seqlens=cu, workspace=scratch, stream=stream)
+        if args.inverse:
+            B.dispatch_inverse(p, fields, workspace=scratch, stream=stream)
+        else:
+            B.dispatch(p, fields, position_ids=pos, cu_seqlens=cu, workspace=scratch, stream=stream)
         return p
 
     if args.reference_copy:
@@ -160,7 +170,7 @@ def run_gpu(args, torch, B, synth):
         hip.destroy(b)
     kern_avg_ms = float(np.mean(kern_ms))
     achieved = algo_bytes / (kern_avg_ms * 1e-3) / 1e9
-    traffic = MEASURED_TRAFFIC.get(kernel_source_hash(), {}).get(args.workload)
+    traffic = None if args.inverse else MEASURED_TRAFFIC.get(kernel_source_hash(), {}).get(args.workload)
     return dict(w=w, sm=sm, ms_per_step=ms_per_step, kern_avg_ms=kern_avg_ms,
                 kern_min_ms=float(np.min(kern_ms)), achieved=achieved, algo_bytes=algo_bytes,
                 traffic=traffic, stage_s=stage_s, row_bytes=row_bytes)
@@ -208,6 +218,8 @@ def main() -> int:
     ap.add_argument("--workload", default="heavy", choices=list(WORKLOAD_NOTES))
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--inverse", action="store_true",
+                    help="time the reverse direction (earl_dispatch_inverse) instead of earl_dispatch")
     ap.add_argument("--reference-copy", action="store_true",
                     help="also run three plain 4 GiB device copies (for scaling profiler counters)")
     args = ap.parse_args()
@@ -244,11 +256,13 @@ def main() -> int:
                    "seed": args.seed, "n_seqs": w.n_seqs, "real_tokens": sm["total_real_rows"],
                    "dst_rows": sm["total_dst_rows"], "bytes_per_token_row": r["row_bytes"],
                    "dst_shards": w.dp * w.sp, "src_shards": w.n_shards,
-                   "step": "earl_plan_build + earl_plan_get_summary + earl_dispatch"},
+                   "step": "earl_plan_build + earl_plan_get_summary + " +
+                           ("earl_dispatch_inverse" if args.inverse else "earl_dispatch")},
         "whole_path_GBps": r["algo_bytes"] / (r["ms_per_step"] * 1e-3) / 1e9,
         "roofline": {"bound": "hbm", "achieved": r["achieved"], "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": r["achieved"] / HBM_PEAK_GBPS, "traffic": r["traffic"],
-                     "kernel": "relayout_kernel", "algorithmic_bytes_per_launch": r["algo_bytes"],
+                     "kernel": "inverse_kernel" if args.inverse else "relayout_kernel",
+                     "algorithmic_bytes_per_launch": r["algo_bytes"],
                      "kernel_ms_avg": r["kern_avg_ms"], "kernel_ms_min": r["kern_min_ms"]},
         "input_staging_s": r["stage_s"],
     }

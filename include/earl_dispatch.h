@@ -209,8 +209,8 @@ int32_t earl_dispatch(earl_plan* plan, const earl_field* fields, int32_t n_field
                       void* dispatch_ws_dev, size_t dispatch_ws_bytes, void* hip_stream);
 
 /*
- * Measurement hook: the following earl_dispatch calls on this plan record `event_before` on the
- * stream right before the re-layout kernel and `event_after` right after it (both hipEvent_t created
+ * Measurement hook: the following earl_dispatch / earl_dispatch_inverse calls on this plan record
+ * `event_before` on the stream right before the re-layout kernel and `event_after` right after it (both hipEvent_t created
  * by the caller with timing enabled; NULL, NULL switches the hook off).  The interval is the
  * duration of the copy kernel alone, without the tile-code pass and the parameter upload.
  */

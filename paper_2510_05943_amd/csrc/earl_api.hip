@@ -663,12 +663,13 @@ int32_t earl_dispatch_inverse(earl_plan* p, const earl_field* fields, int32_t n_
     tiles += (r.end_bytes + kTileBytes - 1) / kTileBytes;
   }
   ts[n_fields] = tiles;
-  if (tiles > 0x7fffffffll) return fail(EARL_INVALID_ARG, "too many tiles for one launch");
+  if (tiles * kSubTiles > 0x7fffffffll) return fail(EARL_INVALID_ARG, "too many tiles for one launch");
+  const size_t codes_off = b.bytes.size();
+  const size_t need = codes_off + kTileCodeBytes * (size_t)tiles;
   if (!dispatch_ws_dev || reinterpret_cast<uintptr_t>(dispatch_ws_dev) % kAlign)
     return fail(EARL_INVALID_ARG, "dispatch scratch is null or not %zu-byte aligned", kAlign);
-  if (dispatch_ws_bytes < b.bytes.size())
-    return fail(EARL_CAPACITY, "dispatch scratch has %zu bytes, %zu needed", dispatch_ws_bytes,
-                b.bytes.size());
+  if (dispatch_ws_bytes < need)
+    return fail(EARL_CAPACITY, "dispatch scratch has %zu bytes, %zu needed", dispatch_ws_bytes, need);
   if (!p->inverse_ready) {
     launch_real_prefix(p->dev.segs, prefix, p->hdr.n_segments, stream);
     p->inverse_ready = true;
@@ -676,7 +677,9 @@ int32_t earl_dispatch_inverse(earl_plan* p, const earl_field* fields, int32_t n_
   st = upload_params(b.bytes, dispatch_ws_dev, stream);
   if (st != EARL_OK) return st;
   launch_copy_inverse(copy_args(p, dispatch_ws_dev, tiles), prefix, p->dev.seg_dst_shard,
-                      p->hdr.n_segments, stream);
+                      p->hdr.n_segments, static_cast<unsigned char*>(dispatch_ws_dev) + codes_off,
+                      static_cast<hipEvent_t>(p->ev_before), static_cast<hipEvent_t>(p->ev_after),
+                      stream);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess)
     return fail(EARL_HIP_ERROR, "inverse kernel launch failed: %s", hipGetErrorString(e));

@@ -62,19 +62,6 @@ __device__ __forceinline__ void store_scalar(u8* p, uint64_t v, int sb) {
   }
 }
 
-// Number of entries of the ascending table t[0..n) that are <= v, n <= 256, counted by the
-// wavefront: lane l looks at entries 4l..4l+3.
-__device__ __forceinline__ int wave_count_le_256(const int64_t* t, int n, int64_t v, int lane) {
-  int c = 0;
-#pragma unroll
-  for (int k = 0; k < 4; ++k) {
-    const int idx = 4 * lane + k;
-    if (idx < n && t[idx] <= v) ++c;
-  }
-  return __builtin_popcountll(__ballot(c >= 1)) + __builtin_popcountll(__ballot(c >= 2)) +
-         __builtin_popcountll(__ballot(c >= 3)) + __builtin_popcountll(__ballot(c >= 4));
-}
-
 // Last record x in [lo, hi) of `table` with table[x] <= v, one lane on its own.
 __device__ __forceinline__ int last_le(const int64_t* table, int lo, int hi, int64_t v) {
   while (hi - lo > 1) {
@@ -211,7 +198,7 @@ __device__ __forceinline__ void seek(const SegRec* segs, const TileInfo& t, int6
 }
 
 // A tile that is not one plain copy / fill / iota: every lane places its own 16-byte vector.
-__device__ __noinline__ void generic_tile(const CopyArgs& a, const TileCode c) {
+__device__ __noinline__ void generic_tile(const CopyArgs a, const TileCode c) {
   const ParamView pv = view_params(a.params);
   const TileRec rec = pv.recs[(uint32_t)(c.a >> 32)];
   const int64_t lo = ((int64_t)(blockIdx.x / kSubTiles) - rec.tile_first) * (int64_t)kTileBytes;
@@ -298,7 +285,8 @@ __global__ __launch_bounds__(kCopyThreads) void relayout_kernel(const CopyArgs a
 // precede segment e, so a tile of the stream finds its segments by search and the host only
 // needs the total row count to size the grid.  Reads (destination shards) and writes (source
 // shards) are both contiguous inside a segment; vectors that would cross a segment edge are
-// moved scalar by scalar.  Same one-load-one-store-per-lane shape as the forward kernel.
+// moved scalar by scalar.  Same two passes and the same one-load-one-store-per-lane shape as
+// the forward direction; the stores may be unaligned (rollout rows start anywhere).
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kPlanThreads) void real_prefix_kernel(const SegRec* segs,
                                                                     int64_t* prefix, int n_seg) {
@@ -326,83 +314,78 @@ __global__ __launch_bounds__(kPlanThreads) void real_prefix_kernel(const SegRec*
   if (tid == kPlanThreads - 1) prefix[n_seg] = acc;
 }
 
-struct InvInfo {
-  int64_t lo;        // first stream byte of the tile
-  int64_t total;     // bytes of the real-row stream of this field
-  const void* const* src_ptrs;
-  const void* const* dst_ptrs;
-  int32_t e0;
-  int32_t row_bytes;
-  int32_t scalar_bytes;
+// Last segment of [lo, hi) whose stream prefix (in bytes) is <= byte; empty segments share a
+// prefix with their successor, and taking the last one skips them.
+__device__ __forceinline__ int find_stream_segment(const int64_t* prefix, int lo, int hi,
+                                                   int64_t byte, int64_t w) {
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (prefix[mid] * w <= byte) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+struct InverseArgs {
+  CopyArgs c;
+  const int64_t* seg_real_prefix;   // [n_seg+1]
+  const int32_t* seg_dst_shard;     // [n_seg]
+  int32_t n_seg;
 };
 
-__global__ __launch_bounds__(kInverseThreads) void inverse_kernel(const CopyArgs a,
-                                                               const int64_t* seg_real_prefix,
-                                                               const int32_t* seg_dst_shard,
-                                                               int n_seg) {
-  __shared__ InvInfo s_inv;
-  const int lane = threadIdx.x & (kWave - 1);
-  const int64_t tile = blockIdx.x;
-  if (threadIdx.x < kWave) {
-    const u8* params = reinterpret_cast<const u8*>(a.params);
-    const DispatchDev hd = *a.params;
-    const int64_t* tile_start = reinterpret_cast<const int64_t*>(params + hd.tile_start_ofs);
-    const TileRec* recs = reinterpret_cast<const TileRec*>(params + hd.recs_ofs);
-    const void* const* ptrs = reinterpret_cast<const void* const*>(params + hd.ptrs_ofs);
-    // one record per field here (at most EARL_MAX_FIELDS of them)
-    const int f = wave_count_le_256(tile_start, hd.n_recs, tile, lane) - 1;
-    const TileRec rec = recs[f];
-    InvInfo t;
-    t.lo = (tile - rec.tile_first) * (int64_t)kTileBytes;
-    t.total = rec.end_bytes;
-    t.src_ptrs = ptrs + rec.src_ptr_index;
-    t.dst_ptrs = ptrs + rec.dst_ptr_index;
-    t.row_bytes = rec.row_bytes;
-    t.scalar_bytes = rec.scalar_bytes;
-    // last segment whose prefix (in bytes) is <= lo: 64-ary search by the wavefront; empty
-    // segments share a prefix with their successor, and taking the last one skips them
-    int lo = 0, len = n_seg;
-    const int64_t w = rec.row_bytes;
-    while (len > 1) {
-      const int stride = (len + kWave - 1) >> 6;
-      const int idx = lo + lane * stride;
-      const bool hit = idx < lo + len && seg_real_prefix[idx] * w <= t.lo;
-      const int cnt = __builtin_popcountll(__ballot(hit));
-      const int nlo = lo + (cnt - 1) * stride;
-      const int rest = lo + len - nlo;
-      len = rest < stride ? rest : stride;
-      lo = nlo;
-    }
-    t.e0 = lo;
-    if (lane == 0) s_inv = t;
+// Inverse tile codes: a = training-layout pointer of the tile's first byte (0 = generic tile,
+// then b = field << 32 | first segment), b = rollout-layout pointer (any alignment).
+__global__ __launch_bounds__(kCodeThreads) void inverse_code_kernel(const InverseArgs a,
+                                                                   TileCode* codes) {
+  const int64_t tile = (int64_t)blockIdx.x * kCodeThreads + threadIdx.x;
+  if (tile >= a.c.n_tiles) return;
+  const ParamView pv = view_params(a.c.params);
+  const int f = last_le(pv.tile_start, 0, pv.n_recs, tile);   // one record per field
+  const TileRec rec = pv.recs[f];
+  const int64_t w = rec.row_bytes;
+  const int64_t lo = (tile - rec.tile_first) * (int64_t)kTileBytes;
+  const int e = find_stream_segment(a.seg_real_prefix, 0, a.n_seg, lo, w);
+  const SegRec r = a.c.segs[e];
+  const int64_t s_lo = a.seg_real_prefix[e] * w;
+  TileCode c;
+  c.a = 0;
+  c.b = (uint64_t)(uint32_t)f << 32 | (uint32_t)e;
+  if (lo + kTileBytes <= s_lo + (int64_t)r.n_real * w) {
+    c.a = reinterpret_cast<uint64_t>(
+        static_cast<const u8*>(pv.ptrs[rec.dst_ptr_index + a.seg_dst_shard[e]]) + r.dst_row * w +
+        (lo - s_lo));
+    c.b = reinterpret_cast<uint64_t>(
+        static_cast<const u8*>(pv.ptrs[rec.src_ptr_index + r.src_shard]) + r.src_row * w +
+        (lo - s_lo));
   }
-  __syncthreads();
+  codes[tile] = c;
+}
 
-  const InvInfo t = s_inv;
-  const int64_t w = t.row_bytes;
-  const int sb = t.scalar_bytes;
-  const int64_t o = t.lo + (int64_t)threadIdx.x * kVecBytes;
-  if (o >= t.total) return;
+__device__ __noinline__ void generic_inverse_tile(const InverseArgs a, const TileCode c) {
+  const ParamView pv = view_params(a.c.params);
+  const TileRec rec = pv.recs[(uint32_t)(c.b >> 32)];
+  const int64_t w = rec.row_bytes;
+  const int sb = rec.scalar_bytes;
+  const int64_t total = rec.end_bytes;   // bytes of the real-row stream of this field
+  const int64_t lo = ((int64_t)(blockIdx.x / kSubTiles) - rec.tile_first) * (int64_t)kTileBytes;
+  const int64_t o = lo + (int64_t)((blockIdx.x % kSubTiles) * kCopyThreads + threadIdx.x) * kVecBytes;
+  if (o >= total) return;
+  const void* const* src_ptrs = pv.ptrs + rec.src_ptr_index;
+  const void* const* dst_ptrs = pv.ptrs + rec.dst_ptr_index;
 
-  int e = t.e0;
+  int e = (int)(uint32_t)c.b;
   int64_t s_lo = 0, s_hi = 0;     // stream byte range of the cached segment
   const u8* from = nullptr;       // training-layout byte of stream byte s_lo
   u8* to = nullptr;               // rollout-layout byte of stream byte s_lo
   auto load_seg = [&]() {
-    const SegRec r = a.segs[e];
-    s_lo = seg_real_prefix[e] * w;
+    const SegRec r = a.c.segs[e];
+    s_lo = a.seg_real_prefix[e] * w;
     s_hi = s_lo + (int64_t)r.n_real * w;
-    from = static_cast<const u8*>(t.dst_ptrs[seg_dst_shard[e]]) + r.dst_row * w;
-    to = static_cast<u8*>(const_cast<void*>(t.src_ptrs[r.src_shard])) + r.src_row * w;
+    from = static_cast<const u8*>(dst_ptrs[a.seg_dst_shard[e]]) + r.dst_row * w;
+    to = static_cast<u8*>(const_cast<void*>(src_ptrs[r.src_shard])) + r.src_row * w;
   };
   auto seek_stream = [&](int64_t b) {
     if (b < s_hi) return;
-    int lo = e, hi = n_seg;       // last segment with prefix * w <= b
-    while (hi - lo > 1) {
-      const int mid = (lo + hi) >> 1;
-      if (seg_real_prefix[mid] * w <= b) lo = mid; else hi = mid;
-    }
-    e = lo;
+    e = find_stream_segment(a.seg_real_prefix, e, a.n_seg, b, w);
     load_seg();
   };
   load_seg();
@@ -410,10 +393,22 @@ __global__ __launch_bounds__(kInverseThreads) void inverse_kernel(const CopyArgs
   if (o + kVecBytes <= s_hi) {
     store16_any(to + (o - s_lo), load16(from + (o - s_lo)));
   } else {
-    for (int64_t b = o; b < o + kVecBytes && b < t.total; b += sb) {
+    for (int64_t b = o; b < o + kVecBytes && b < total; b += sb) {
       seek_stream(b);
       store_scalar(to + (b - s_lo), load_scalar(from + (b - s_lo), sb), sb);
     }
+  }
+}
+
+__global__ __launch_bounds__(kCopyThreads) void inverse_kernel(const InverseArgs a,
+                                                               const TileCode* __restrict__ codes) {
+  const TileCode c = codes[blockIdx.x / kSubTiles];
+  if (c.a != 0) {
+    const uint32_t v = (blockIdx.x % kSubTiles) * kCopyThreads + threadIdx.x;
+    store16_any(reinterpret_cast<u8*>(c.b) + v * kVecBytes,
+                load16(reinterpret_cast<const u8*>(c.a) + v * kVecBytes));
+  } else {
+    generic_inverse_tile(a, c);
   }
 }
 
@@ -437,10 +432,17 @@ void launch_real_prefix(const SegRec* segs, int64_t* prefix, int n_seg, hipStrea
 }
 
 void launch_copy_inverse(const CopyArgs& a, const int64_t* seg_real_prefix,
-                         const int32_t* seg_dst_shard, int n_seg, hipStream_t stream) {
+                         const int32_t* seg_dst_shard, int n_seg, void* tile_codes,
+                         hipEvent_t before, hipEvent_t after, hipStream_t stream) {
   if (a.n_tiles <= 0) return;
-  hipLaunchKernelGGL(inverse_kernel, dim3((unsigned)a.n_tiles), dim3(kInverseThreads), 0, stream, a,
-                     seg_real_prefix, seg_dst_shard, n_seg);
+  InverseArgs ia{a, seg_real_prefix, seg_dst_shard, n_seg};
+  TileCode* codes = static_cast<TileCode*>(tile_codes);
+  const unsigned g1 = (unsigned)((a.n_tiles + kCodeThreads - 1) / kCodeThreads);
+  hipLaunchKernelGGL(inverse_code_kernel, dim3(g1), dim3(kCodeThreads), 0, stream, ia, codes);
+  if (before) (void)hipEventRecord(before, stream);
+  hipLaunchKernelGGL(inverse_kernel, dim3((unsigned)(a.n_tiles * kSubTiles)), dim3(kCopyThreads), 0,
+                     stream, ia, codes);
+  if (after) (void)hipEventRecord(after, stream);
 }
 
 }  // namespace earl

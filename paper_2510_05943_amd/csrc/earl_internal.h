@@ -147,6 +147,7 @@ void launch_copy(const CopyArgs& a, const void* tile_codes, hipStream_t stream);
 // seg_real_prefix[e] = real rows of the segments before e (n_seg+1 entries)
 void launch_real_prefix(const SegRec* segs, int64_t* prefix, int n_seg, hipStream_t stream);
 void launch_copy_inverse(const CopyArgs& a, const int64_t* seg_real_prefix,
-                         const int32_t* seg_dst_shard, int n_seg, hipStream_t stream);
+                         const int32_t* seg_dst_shard, int n_seg, void* tile_codes,
+                         hipEvent_t before, hipEvent_t after, hipStream_t stream);
 
 }  // namespace earl

@@ -97,4 +97,16 @@ def test_full_size_parity(name):
         want = O.dispatch_field_shard(oplan, q, lazy, wide.np_dtype, wide.width, wide.pad_scalar)
         got = dsts[wide.name][q].cpu().numpy().view(wide.np_dtype).reshape(-1, wide.width)
         assert np.array_equal(got, want), (wide.name, q)
+
+    # reverse direction at full size: every source row is read by the plan here (no replicas),
+    # so the round trip must give back the source buffers bit for bit
+    back = {f.name: [torch.full_like(t, 0x5A) for t in src[f.name]] for f in w.fields}
+    inv_fields = [B.Field(f.scalar_bytes, f.width, f.pad_scalar, back[f.name], dsts[f.name])
+                  for f in w.fields]
+    B.dispatch_inverse(plan, inv_fields, workspace=scratch)
+    torch.cuda.synchronize()
+    for f in w.fields:
+        for s in range(w.n_shards):
+            assert torch.equal(back[f.name][s], src[f.name][s]), (f.name, s)
+    print(f"[{name}] inverse: round trip restores all source shards", flush=True)
     B.plan_destroy(plan)
