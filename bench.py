@@ -95,7 +95,7 @@ def run_gpu(args, torch, B, synth):
 
     stream = torch.cuda.current_stream()
     src_l = B.SrcLayout(w.n_groups, w.replication)
-    dst_l = B.DstLayout(w.dp, w.sp, w.zigzag, w.pad_multiple, w.mb_token_budget)
+    dst_l = B.DstLayout(w.dp, w.sp, w.zigzag, w.pad_multiple, w.mb_token_budget, args.balance_policy)
     lengths = torch.from_numpy(w.lengths.astype(np.int32)).cuda()
     ws = torch.empty(B.plan_workspace_bytes(w.n_seqs, src_l, dst_l), dtype=torch.uint8, device="cuda")
 
@@ -170,10 +170,85 @@ def run_gpu(args, torch, B, synth):
         hip.destroy(b)
     kern_avg_ms = float(np.mean(kern_ms))
     achieved = algo_bytes / (kern_avg_ms * 1e-3) / 1e9
-    traffic = None if args.inverse else MEASURED_TRAFFIC.get(kernel_source_hash(), {}).get(args.workload)
+    traffic = None if (args.inverse or args.balance_policy) else MEASURED_TRAFFIC.get(kernel_source_hash(), {}).get(args.workload)
     return dict(w=w, sm=sm, ms_per_step=ms_per_step, kern_avg_ms=kern_avg_ms,
                 kern_min_ms=float(np.min(kern_ms)), achieved=achieved, algo_bytes=algo_bytes,
                 traffic=traffic, stage_s=stage_s, row_bytes=row_bytes)
+
+
+def run_gpu_two_pass(args, torch, B, synth):
+    """The single-controller pattern the paper argues against (Section 1: all intermediate data is
+    aggregated in one place before it is redistributed), done with the same library on one GPU:
+    pass 1 gathers every field into one canonical buffer (plan with dp = sp = 1), pass 2 scatters
+    it from there into the training layout.  Same result as the direct dispatch, twice the bytes."""
+    w = synth.make_workload(args.workload, seed=args.seed)
+    t0 = time.time()
+    src = {f.name: w.device_shard_buffers(f, torch) for f in w.fields}
+    torch.cuda.synchronize()
+    stage_s = time.time() - t0
+    stream = torch.cuda.current_stream()
+    lengths = torch.from_numpy(w.lengths.astype(np.int32)).cuda()
+    lay_a = (B.SrcLayout(w.n_groups, w.replication), B.DstLayout(1, 1, 0, 1, 1 << 40))
+    lay_b = (B.SrcLayout(1, 1), B.DstLayout(w.dp, w.sp, w.zigzag, w.pad_multiple, w.mb_token_budget,
+                                            args.balance_policy))
+    ws_a = torch.empty(B.plan_workspace_bytes(w.n_seqs, *lay_a), dtype=torch.uint8, device="cuda")
+    ws_b = torch.empty(B.plan_workspace_bytes(w.n_seqs, *lay_b), dtype=torch.uint8, device="cuda")
+    pa = B.plan_build(lengths, w.n_seqs, *lay_a, ws_a, stream=stream)
+    pb = B.plan_build(lengths, w.n_seqs, *lay_b, ws_b, stream=stream)
+    sm_a, sm = B.plan_get_summary(pa), B.plan_get_summary(pb)
+    total = int(sm_a["shard_rows"][0])
+    shard_rows = [int(r) for r in sm["shard_rows"]]
+    fields_a, fields_b = [], []
+    for f in w.fields:
+        canon = torch.empty((total * f.row_bytes,), dtype=torch.uint8, device="cuda")
+        dsts = [torch.empty((r * f.row_bytes,), dtype=torch.uint8, device="cuda") for r in shard_rows]
+        fields_a.append(B.Field(f.scalar_bytes, f.width, f.pad_scalar, src[f.name], [canon]))
+        fields_b.append(B.Field(f.scalar_bytes, f.width, f.pad_scalar, [canon], dsts))
+    pos = [torch.empty((r,), dtype=torch.int32, device="cuda") for r in shard_rows]
+    cu = torch.empty((sm["cu_seqlens_len"],), dtype=torch.int32, device="cuda")
+    scr_a = torch.empty(B.dispatch_workspace_bytes(pa, fields_a, False, False), dtype=torch.uint8, device="cuda")
+    scr_b = torch.empty(B.dispatch_workspace_bytes(pb, fields_b), dtype=torch.uint8, device="cuda")
+    B.plan_destroy(pa)
+    B.plan_destroy(pb)
+    row_bytes = sum(f.row_bytes for f in w.fields)
+    algo_bytes = (2 * row_bytes * total
+                  + row_bytes * (sm["total_real_rows"] + sm["total_dst_rows"]) + 4 * sm["total_dst_rows"])
+    hip = HipEvents()
+
+    def step(ev=None):
+        a = B.plan_build(lengths, w.n_seqs, *lay_a, ws_a, stream=stream)
+        B.plan_get_summary(a)
+        if ev is not None:
+            B.plan_set_dispatch_events(a, ev[0], ev[1])
+        B.dispatch(a, fields_a, workspace=scr_a, stream=stream)
+        b = B.plan_build(lengths, w.n_seqs, *lay_b, ws_b, stream=stream)
+        B.plan_get_summary(b)
+        if ev is not None:
+            B.plan_set_dispatch_events(b, ev[2], ev[3])
+        B.dispatch(b, fields_b, position_ids=pos, cu_seqlens=cu, workspace=scr_b, stream=stream)
+        return [a, b]
+
+    plans = [p for _ in range(args.warmup) for p in step()]
+    torch.cuda.synchronize()
+    for p in plans:
+        B.plan_destroy(p)
+    events = [tuple(hip.create() for _ in range(4)) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    plans = [p for k in range(args.steps) for p in step(events[k])]
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for p in plans:
+        B.plan_destroy(p)
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    kern_ms = [hip.elapsed_ms(e[0], e[1]) + hip.elapsed_ms(e[2], e[3]) for e in events]
+    for e in events:
+        for x in e:
+            hip.destroy(x)
+    kern_avg_ms = float(np.mean(kern_ms))
+    return dict(w=w, sm=sm, ms_per_step=ms_per_step, kern_avg_ms=kern_avg_ms,
+                kern_min_ms=float(np.min(kern_ms)), achieved=algo_bytes / (kern_avg_ms * 1e-3) / 1e9,
+                algo_bytes=algo_bytes, traffic=None, stage_s=stage_s, row_bytes=row_bytes)
 
 
 def run_cpu_baseline(args, synth):
@@ -218,6 +293,10 @@ def main() -> int:
     ap.add_argument("--workload", default="heavy", choices=list(WORKLOAD_NOTES))
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--two-pass", action="store_true",
+                    help="gather into one canonical buffer, then scatter (single-controller pattern)")
+    ap.add_argument("--balance-policy", type=int, default=0, choices=[0, 1],
+                    help="0 longest-first list scheduling (default), 1 sorted snake deal")
     ap.add_argument("--inverse", action="store_true",
                     help="time the reverse direction (earl_dispatch_inverse) instead of earl_dispatch")
     ap.add_argument("--reference-copy", action="store_true",
@@ -237,7 +316,7 @@ def main() -> int:
     B.load_library()
     torch.cuda.set_device(0)
 
-    r = run_gpu(args, torch, B, synth)
+    r = run_gpu_two_pass(args, torch, B, synth) if args.two_pass else run_gpu(args, torch, B, synth)
     w, sm = r["w"], r["sm"]
     line = {
         "metric": "re-layout throughput: tokens/s and achieved HBM GB/s (% of peak) at 1 GPU",
@@ -256,12 +335,15 @@ def main() -> int:
                    "seed": args.seed, "n_seqs": w.n_seqs, "real_tokens": sm["total_real_rows"],
                    "dst_rows": sm["total_dst_rows"], "bytes_per_token_row": r["row_bytes"],
                    "dst_shards": w.dp * w.sp, "src_shards": w.n_shards,
-                   "step": "earl_plan_build + earl_plan_get_summary + " +
+                   "balance_policy": args.balance_policy,
+                   "step": ("two passes (gather to one buffer, scatter from it), each " if args.two_pass
+                            else "") + "earl_plan_build + earl_plan_get_summary + " +
                            ("earl_dispatch_inverse" if args.inverse else "earl_dispatch")},
         "whole_path_GBps": r["algo_bytes"] / (r["ms_per_step"] * 1e-3) / 1e9,
         "roofline": {"bound": "hbm", "achieved": r["achieved"], "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": r["achieved"] / HBM_PEAK_GBPS, "traffic": r["traffic"],
-                     "kernel": "inverse_kernel" if args.inverse else "relayout_kernel",
+                     "kernel": ("inverse_kernel" if args.inverse else
+                                "relayout_kernel (both passes)" if args.two_pass else "relayout_kernel"),
                      "algorithmic_bytes_per_launch": r["algo_bytes"],
                      "kernel_ms_avg": r["kern_avg_ms"], "kernel_ms_min": r["kern_min_ms"]},
         "input_staging_s": r["stage_s"],

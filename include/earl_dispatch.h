@@ -78,7 +78,10 @@ typedef struct {
  *   zigzag            1: a sequence is cut into 2*sp chunks and SP rank c holds chunks c and
  *                     2*sp-1-c (equal causal-attention work); 0: sp contiguous chunks.
  *   pad_multiple      every chunk is padded to a multiple of this many rows (>= 1).
- *   balance_policy    0 = longest-first list scheduling on padded lengths (the only policy).
+ *   balance_policy    0 = longest-first list scheduling on padded lengths (ties: lower index, lower
+ *                     rank); 1 = sorted snake deal: longest first in rounds of dp, left to right in
+ *                     even rounds and right to left in odd ones (no serial chain; equal sequence
+ *                     counts per rank, loads within one padded length of each other).
  *   mb_token_budget   a micro-batch holds whole sequences whose padded lengths sum to at most this.
  */
 typedef struct {

@@ -137,6 +137,23 @@ def lpt_ranks(Lp, D: int):
     return np.array(rank, np.int32), np.array(load, np.int64)
 
 
+def snake_ranks(Lp, D: int):
+    """Alternative balancing without a serial chain (balance_policy 1): visit sequences longest
+    first (equal lengths: lower index first) and deal them to the ranks in rounds of D, left to
+    right in even rounds and right to left in odd rounds, so that the rank that got the longest
+    sequence of one round gets the shortest of the next."""
+    N = len(Lp)
+    order = sorted(range(N), key=lambda i: (-int(Lp[i]), i))
+    load = [0] * D
+    rank = [0] * N
+    for j, i in enumerate(order):
+        t, k = divmod(j, D)
+        r = k if t % 2 == 0 else D - 1 - k
+        rank[i] = r
+        load[r] += int(Lp[i])
+    return np.array(rank, np.int32), np.array(load, np.int64)
+
+
 # ----------------------------------------------------------------------------------------
 # Packing order, micro-batches, destination offsets
 # ----------------------------------------------------------------------------------------
@@ -255,7 +272,8 @@ class Plan:
 
 
 def build_plan(L, *, n_groups: int, replication: int = 1, seq_group=None, seq_row=None,
-               dp: int, sp: int, zigzag: int, pad_multiple: int, mb_token_budget: int) -> Plan:
+               dp: int, sp: int, zigzag: int, pad_multiple: int, mb_token_budget: int,
+               balance_policy: int = 0) -> Plan:
     """The dispatch plan: for every sequence, where it is read and where each part is written.
 
     This is the "parallelism- and layout-aware" decision of Section 2 made explicit.  The
@@ -278,7 +296,9 @@ def build_plan(L, *, n_groups: int, replication: int = 1, seq_group=None, seq_ro
     K, m, Lp, loc = padded_geometry(L, C, zigzag, P)
     if any(int(x) > B for x in Lp):
         raise OracleError(SEQ_EXCEEDS_BUDGET, "a padded sequence is longer than the budget")
-    rank, load = lpt_ranks(Lp, D)
+    if balance_policy not in (0, 1):
+        raise OracleError(INVALID_ARG, "unknown balance_policy")
+    rank, load = lpt_ranks(Lp, D) if balance_policy == 0 else snake_ranks(Lp, D)
     pk = pack_ranks(rank, Lp, loc, D, B)
 
     shard_rows = np.repeat(pk["rank_rows"], C).astype(np.int64)

@@ -64,6 +64,7 @@ struct PlanDev {
   const int64_t* seq_row_in;     // may be null
   int32_t N, G, R, S, D, C, K, halves, P;
   int32_t n_pow2;                // N rounded up to a power of two (sort size)
+  int32_t policy;                // 0 longest-first list scheduling, 1 sorted snake deal
   int64_t B;
   // summary block (contiguous, copied to the host in one piece)
   PlanHeader* hdr;

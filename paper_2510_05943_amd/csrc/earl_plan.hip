@@ -538,7 +538,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const PlanDev p) {
   }
   __syncthreads();
 
-  // ---- phase 3: sort by (padded length desc, index asc), then list scheduling --------------
+  // ---- phase 3: sort by (padded length desc, index asc), then rank assignment --------------
   uint64_t* keys = p.n_pow2 <= kLdsSortKeys ? reinterpret_cast<uint64_t*>(lds_union) : p.sort_keys;
   for (int i = tid; i < p.n_pow2; i += T) {
     uint64_t key = ~0ull;
@@ -550,7 +550,15 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const PlanDev p) {
   }
   __syncthreads();
   bitonic_sort(keys, p.n_pow2, p.n_pow2 <= kLdsSortKeys);
-  if (wave_id() == 0) lpt_wave0(p, keys, lds_load);
+  if (p.policy == 1) {
+    // sorted snake deal: rounds of D, left to right in even rounds, right to left in odd ones
+    for (int j = tid; j < N; j += T) {
+      const int round = j / D, k = j - round * D;
+      p.rank[(int32_t)(keys[j] & 0xffffffffu)] = (round & 1) ? D - 1 - k : k;
+    }
+  } else if (wave_id() == 0) {
+    lpt_wave0(p, keys, lds_load);
+  }
   __syncthreads();
 
   // ---- phase 4: packing order, destination offsets, micro-batches --------------------------

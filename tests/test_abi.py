@@ -51,6 +51,7 @@ def test_workspace_bytes_validation_and_growth():
         (64, src, B.DstLayout(dp=1, pad_multiple=0)),
         (64, src, B.DstLayout(dp=1, mb_token_budget=0)),
         (64, src, B.DstLayout(dp=1, balance_policy=7)),
+        (64, src, B.DstLayout(dp=1, balance_policy=-1)),
     ]
     for n, s, d in bad:
         with pytest.raises(B.EarlError) as e:

@@ -25,10 +25,11 @@ def H():
     return gpu_harness
 
 
-def oracle_plan(w, seq_row=None):
+def oracle_plan(w, seq_row=None, balance_policy=0):
     return O.build_plan(w.lengths, n_groups=w.n_groups, replication=w.replication,
                         seq_group=w.seq_group, seq_row=seq_row, dp=w.dp, sp=w.sp, zigzag=w.zigzag,
-                        pad_multiple=w.pad_multiple, mb_token_budget=w.mb_token_budget)
+                        pad_multiple=w.pad_multiple, mb_token_budget=w.mb_token_budget,
+                        balance_policy=balance_policy)
 
 
 PLAN_KEYS = ("rank", "slot", "mb", "dst_row", "seq_shard", "seq_row", "seq_ids", "mb_seq_start",
@@ -269,6 +270,49 @@ def test_plan_edge_cases(H, desc, kw):
     plan = H.build_plan(w)
     assert_plan_equal(H.plan_result(plan), oracle_plan(w))
     H.B.plan_destroy(plan)
+
+
+@pytest.mark.parametrize("name,scale", [("tiny", 1.0), ("mid", 1.0), ("agentic", 1.0), ("heavy", 1.0),
+                                        ("longctx", 1.0), ("mid", 0.02)])
+def test_snake_deal_policy(H, name, scale):
+    w = synth.make_workload(name, seed=5, scale=scale)
+    plan = H.build_plan(w, balance_policy=1)
+    oplan = oracle_plan(w, balance_policy=1)
+    assert_plan_equal(H.plan_result(plan), oplan)
+    if name in ("tiny", "mid") and scale == 1.0:
+        _, shards = H.host_sources(w, w.fields)
+        out = H.run_dispatch(w, plan, w.fields, src_host=shards)
+        assert_dispatch_equal(w, oplan, out, shards, w.fields)
+    H.B.plan_destroy(plan)
+
+
+def test_two_pass_gather_then_scatter_equals_direct_dispatch(H):
+    """Gathering everything into one canonical buffer and scattering it from there (the
+    single-controller pattern) gives the same training layout as the direct dispatch."""
+    import torch
+    B = H.B
+    w = synth.make_workload("mid", seed=6, scale=0.25)
+    _, shards = H.host_sources(w, w.fields)
+    direct_plan = H.build_plan(w)
+    direct = H.run_dispatch(w, direct_plan, w.fields, src_host=shards)
+    gather_w = synth.custom_workload(w.lengths, n_groups=w.n_groups, replication=w.replication,
+                                     seq_group=w.seq_group, dp=1, sp=1, fields=w.fields)
+    gather_plan = H.build_plan(gather_w)
+    one = H.run_dispatch(gather_w, gather_plan, w.fields, src_host=shards, want_position_ids=False,
+                         want_cu=False)
+    scatter_w = synth.custom_workload(w.lengths, n_groups=1, dp=w.dp, sp=w.sp, zigzag=w.zigzag,
+                                      pad_multiple=w.pad_multiple, mb_token_budget=w.mb_token_budget,
+                                      fields=w.fields)
+    scatter_plan = H.build_plan(scatter_w)
+    canon = {f.name: [one["fields"][f.name][0]] for f in w.fields}
+    two = H.run_dispatch(scatter_w, scatter_plan, w.fields, src_host=canon)
+    for f in w.fields:
+        for a, b in zip(two["fields"][f.name], direct["fields"][f.name]):
+            assert np.array_equal(a, b), f.name
+    for a, b in zip(two["position_ids"], direct["position_ids"]):
+        assert np.array_equal(a, b)
+    for p in (direct_plan, gather_plan, scatter_plan):
+        B.plan_destroy(p)
 
 
 def test_dispatch_with_empty_ranks_and_no_fields(H):

@@ -132,6 +132,47 @@ def test_lpt_equal_lengths_is_round_robin():
         assert len(set(load.tolist())) == 1
 
 
+def test_snake_hand_worked_and_bounds():
+    g = gold("snake_three_ranks.json")
+    rank, load = O.snake_ranks(g["Lp"], g["D"])
+    assert rank.tolist() == g["rank"] and load.tolist() == g["load"]
+    rng = np.random.default_rng(8)
+    for trial in range(200):
+        D = int(rng.integers(1, 9))
+        N = int(rng.integers(1, 60))
+        Lp = rng.integers(1, 1000, size=N)
+        rank, load = O.snake_ranks(Lp, D)
+        counts = np.bincount(rank, minlength=D)
+        assert counts.max() - counts.min() <= 1          # a deal: equal counts up to one
+        assert load.tolist() == [int(Lp[rank == d].sum()) for d in range(D)]
+        if N >= D:
+            assert load.max() - load.min() <= Lp.max()   # round ranges telescope
+    # equal lengths: boustrophedon over the index
+    rank, _ = O.snake_ranks([5] * 8, 3)
+    assert rank.tolist() == [0, 1, 2, 2, 1, 0, 0, 1]
+
+
+def test_two_pass_gather_then_scatter_equals_direct_dispatch():
+    """The single-controller pattern of Section 1 (everything gathered in one place, then
+    redistributed) must produce the same training layout as the direct dispatch."""
+    w = synth.make_workload("mid", seed=4, scale=0.0625)
+    direct = plan_of(w)
+    gather = O.build_plan(w.lengths, n_groups=w.n_groups, replication=w.replication,
+                          seq_group=w.seq_group, dp=1, sp=1, zigzag=0, pad_multiple=1,
+                          mb_token_budget=1 << 40)
+    scatter = O.build_plan(w.lengths, n_groups=1, dp=w.dp, sp=w.sp, zigzag=w.zigzag,
+                           pad_multiple=w.pad_multiple, mb_token_budget=w.mb_token_budget)
+    for f in w.fields:
+        _, bufs = shard_bufs(w, f)
+        one = O.dispatch_field(gather, bufs, f.np_dtype, f.width, f.pad_scalar)
+        assert len(one) == 1 and one[0].shape[0] == w.total_tokens
+        two = O.dispatch_field(scatter, one, f.np_dtype, f.width, f.pad_scalar)
+        want = O.dispatch_field(direct, bufs, f.np_dtype, f.width, f.pad_scalar)
+        assert all(np.array_equal(a, b) for a, b in zip(two, want))
+    assert O.algorithmic_bytes(gather, [4], False) + O.algorithmic_bytes(scatter, [4], False) \
+        > 1.9 * O.algorithmic_bytes(direct, [4], False)
+
+
 def test_lpt_fewer_sequences_than_ranks():
     plan = O.build_plan([5, 9, 2], n_groups=1, dp=5, sp=2, zigzag=1, pad_multiple=1,
                         mb_token_budget=100)
