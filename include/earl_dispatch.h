@@ -98,6 +98,12 @@ typedef struct {
  *   dst_shard_ptrs[D*C] destination shards (16-byte aligned; NULL allowed for a shard of 0 rows).
  *   dst_capacity_rows   rows each destination buffer can hold; EARL_CAPACITY if fewer than needed.
  *   src_capacity_rows   rows each source buffer holds, or NULL to skip the check.
+ *   per_sequence        0: the source holds one row per token (the normal case).  1: the source holds
+ *                       ONE row per sequence (row k of a group's buffer = its k-th sequence in index
+ *                       order, whatever seq_row says) and the dispatch broadcasts it to every real
+ *                       token of the sequence while it copies (e.g. a sequence-level advantage or
+ *                       reward, Section 4 of the paper); padding rows get pad_scalar.  Needs
+ *                       scalar_bytes * width in {1, 2, 4, 8}; not accepted by earl_dispatch_inverse.
  * Source and destination buffers must not overlap.
  */
 typedef struct {
@@ -108,6 +114,7 @@ typedef struct {
   void* const* dst_shard_ptrs;
   const int64_t* dst_capacity_rows;
   const int64_t* src_capacity_rows;
+  int32_t per_sequence;
 } earl_field;
 
 typedef struct earl_plan earl_plan; /* host object owned by the library */
@@ -126,6 +133,7 @@ typedef struct {
   int64_t rank_load_min, rank_load_max;  /* padded tokens on the least / most loaded DP rank */
   const int64_t* shard_rows;       /* [D*C] rows of every destination shard                  */
   const int64_t* src_rows_needed;  /* [S]   rows every source shard buffer must hold         */
+  const int64_t* src_seqs_needed;  /* [S]   the same for per_sequence fields (rows = sequences) */
   const int32_t* n_seq;            /* [D]   sequences per DP rank                            */
   const int32_t* n_mb;             /* [D]   micro-batches per DP rank                        */
   const int64_t* rank_load;        /* [D]   padded tokens per DP rank                        */

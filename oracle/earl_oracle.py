@@ -57,8 +57,9 @@ def source_layout(L, n_groups: int, replication: int, seq_group=None, seq_row=No
     the k-th of the n_g members of a group is read from replica t = floor(k*R/n_g), i.e.
     shard buffer g*R + t.
 
-    Returns (seq_group, seq_shard, seq_row, group_rows) where group_rows[g] is the number of
-    rows the packed buffers of group g hold (sum of its members' L).
+    Returns (seq_group, seq_shard, seq_row, group_rows, seq_k) where group_rows[g] is the number
+    of rows the packed buffers of group g hold (sum of its members' L) and seq_k[i] says that
+    sequence i is the k-th member of its group (the row of a per-sequence field).
     """
     L = [int(x) for x in L]
     N = len(L)
@@ -72,6 +73,7 @@ def source_layout(L, n_groups: int, replication: int, seq_group=None, seq_row=No
         raise OracleError(INVALID_ARG, "seq_group out of range")
     members = [[i for i in range(N) if seq_group[i] == g] for g in range(G)]
     seq_shard = [0] * N
+    seq_k = [0] * N
     packed_row = [0] * N
     group_rows = [0] * G
     for g in range(G):
@@ -79,6 +81,7 @@ def source_layout(L, n_groups: int, replication: int, seq_group=None, seq_row=No
         acc = 0
         for k, i in enumerate(members[g]):
             seq_shard[i] = g * R + (k * R) // n_g
+            seq_k[i] = k
             packed_row[i] = acc
             acc += L[i]
         group_rows[g] = acc
@@ -89,7 +92,7 @@ def source_layout(L, n_groups: int, replication: int, seq_group=None, seq_row=No
         if any(x < 0 for x in seq_row):
             raise OracleError(INVALID_ARG, "negative seq_row")
     return (np.array(seq_group, np.int32), np.array(seq_shard, np.int32),
-            np.array(seq_row, np.int64), np.array(group_rows, np.int64))
+            np.array(seq_row, np.int64), np.array(group_rows, np.int64), np.array(seq_k, np.int32))
 
 
 # ----------------------------------------------------------------------------------------
@@ -237,6 +240,7 @@ class Plan:
     seq_group: np.ndarray
     seq_shard: np.ndarray
     seq_row: np.ndarray
+    seq_k: np.ndarray
     group_rows: np.ndarray
     rank: np.ndarray
     rank_load: np.ndarray
@@ -291,7 +295,8 @@ def build_plan(L, *, n_groups: int, replication: int = 1, seq_group=None, seq_ro
         raise OracleError(INVALID_ARG, "N, dp, sp, pad_multiple, budget must be >= 1")
     if any(int(x) < 1 for x in L):
         raise OracleError(INVALID_ARG, "every length must be >= 1")
-    grp, seq_shard, srow, group_rows = source_layout(L, n_groups, replication, seq_group, seq_row)
+    grp, seq_shard, srow, group_rows, seq_k = source_layout(L, n_groups, replication, seq_group,
+                                                            seq_row)
     S = int(n_groups) * int(replication)
     K, m, Lp, loc = padded_geometry(L, C, zigzag, P)
     if any(int(x) > B for x in Lp):
@@ -350,7 +355,7 @@ def build_plan(L, *, n_groups: int, replication: int = 1, seq_group=None, seq_ro
             shard_seg_start.append(len(seg["seq"]))
 
     return Plan(N=N, S=S, D=D, C=C, K=K, P=P, B=B, L=np.asarray(L, np.int64), m=m, Lp=Lp, loc=loc,
-                seq_group=grp, seq_shard=seq_shard, seq_row=srow, group_rows=group_rows,
+                seq_group=grp, seq_shard=seq_shard, seq_row=srow, seq_k=seq_k, group_rows=group_rows,
                 rank=rank, rank_load=load, slot=pk["slot"], mb=pk["mb"], dst_row=pk["dst_row"],
                 n_seq=pk["n_seq"], n_mb=pk["n_mb"], shard_rows=shard_rows, seq_ids=seq_ids,
                 mb_seq_start=mb_seq_start, mb_row_start=mb_row_start, cu_seqlens=cu_seqlens,
@@ -377,13 +382,17 @@ def pad_row(scalar_dtype, width: int, pad_scalar: int) -> np.ndarray:
 
 
 def dispatch_field_shard(plan: Plan, q: int, src_bufs: Sequence, scalar_dtype, width: int,
-                         pad_scalar: int) -> np.ndarray:
+                         pad_scalar: int, per_sequence: bool = False) -> np.ndarray:
     """Destination shard q of one field, in the training layout.
 
     src_bufs[s] is shard buffer s as an array of shape (rows, width) (anything that supports
     row slicing).  For sequence i on DP rank r = q // C and each chunk kappa held by SP rank
     c = q % C, logical position p = kappa*m + j lands on row dst_row[i] + h*m + j; it receives
     source row seq_row[i] + p of buffer seq_shard[i] when p < L[i], else the padding row.
+
+    per_sequence: the source buffers hold ONE row per sequence (row seq_k[i] of buffer
+    seq_shard[i]), e.g. a sequence-level advantage or reward (Section 4 names them as the next
+    tensors to dispatch); every real position of the sequence receives that row.
     """
     C, K = plan.C, plan.K
     r, c = divmod(q, C)
@@ -402,15 +411,18 @@ def dispatch_field_shard(plan: Plan, q: int, src_bufs: Sequence, scalar_dtype, w
             n_real = min(max(Li - p0, 0), mi)
             d0 = int(plan.dst_row[i]) + h * mi
             s0 = int(plan.seq_row[i]) + p0
-            out[d0:d0 + n_real] = src[s0:s0 + n_real]
+            if per_sequence:
+                out[d0:d0 + n_real] = src[int(plan.seq_k[i])]
+            else:
+                out[d0:d0 + n_real] = src[s0:s0 + n_real]
             out[d0 + n_real:d0 + mi] = pad
     return out
 
 
 def dispatch_field(plan: Plan, src_bufs: Sequence, scalar_dtype, width: int,
-                   pad_scalar: int) -> List[np.ndarray]:
+                   pad_scalar: int, per_sequence: bool = False) -> List[np.ndarray]:
     """All D*C destination shards of one field."""
-    return [dispatch_field_shard(plan, q, src_bufs, scalar_dtype, width, pad_scalar)
+    return [dispatch_field_shard(plan, q, src_bufs, scalar_dtype, width, pad_scalar, per_sequence)
             for q in range(plan.D * plan.C)]
 
 

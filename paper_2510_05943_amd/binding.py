@@ -48,7 +48,8 @@ class _Field(C.Structure):
     _fields_ = [("scalar_bytes", C.c_int32), ("width", C.c_int32), ("pad_scalar", C.c_uint64),
                 ("src_shard_ptrs", C.POINTER(C.c_void_p)), ("dst_shard_ptrs", C.POINTER(C.c_void_p)),
                 ("dst_capacity_rows", C.POINTER(C.c_int64)),
-                ("src_capacity_rows", C.POINTER(C.c_int64))]
+                ("src_capacity_rows", C.POINTER(C.c_int64)),
+                ("per_sequence", C.c_int32)]
 
 
 class _Summary(C.Structure):
@@ -58,6 +59,7 @@ class _Summary(C.Structure):
                 ("total_real_rows", C.c_int64), ("total_dst_rows", C.c_int64),
                 ("rank_load_min", C.c_int64), ("rank_load_max", C.c_int64),
                 ("shard_rows", C.POINTER(C.c_int64)), ("src_rows_needed", C.POINTER(C.c_int64)),
+                ("src_seqs_needed", C.POINTER(C.c_int64)),
                 ("n_seq", C.POINTER(C.c_int32)), ("n_mb", C.POINTER(C.c_int32)),
                 ("rank_load", C.POINTER(C.c_int64)), ("a2a_counts", C.POINTER(C.c_int64))]
 
@@ -159,6 +161,7 @@ class Field:
     src_shards: Sequence
     dst_shards: Sequence
     check_src_capacity: bool = True
+    per_sequence: bool = False     # source holds one row per sequence, broadcast to its tokens
 
     def _rows(self, t) -> int:
         row_bytes = self.scalar_bytes * self.width
@@ -207,6 +210,7 @@ def plan_get_summary(plan: Plan) -> Dict:
             "rank_load_min", "rank_load_max")}
     out["shard_rows"] = np.ctypeslib.as_array(s.shard_rows, (n_dst,)).copy()
     out["src_rows_needed"] = np.ctypeslib.as_array(s.src_rows_needed, (n_src,)).copy()
+    out["src_seqs_needed"] = np.ctypeslib.as_array(s.src_seqs_needed, (n_src,)).copy()
     out["n_seq"] = np.ctypeslib.as_array(s.n_seq, (dp,)).copy()
     out["n_mb"] = np.ctypeslib.as_array(s.n_mb, (dp,)).copy()
     out["rank_load"] = np.ctypeslib.as_array(s.rank_load, (dp,)).copy()
@@ -256,7 +260,8 @@ def _marshal_field(f: Field):
     desc = _Field(f.scalar_bytes, f.width, f.pad_scalar & 0xFFFFFFFFFFFFFFFF,
                   C.cast(src, C.POINTER(C.c_void_p)), C.cast(dst, C.POINTER(C.c_void_p)),
                   C.cast(cap, C.POINTER(C.c_int64)),
-                  C.cast(scap, C.POINTER(C.c_int64)) if f.check_src_capacity else None)
+                  C.cast(scap, C.POINTER(C.c_int64)) if f.check_src_capacity else None,
+                  1 if f.per_sequence else 0)
     f._c = (desc, (src, dst, cap, scap))
     return f._c
 

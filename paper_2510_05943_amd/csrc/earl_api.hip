@@ -48,11 +48,11 @@ size_t param_block_bytes(int n_fields, int n_src, int n_dst) {
 
 // Byte offsets of every array inside the workspace.
 struct Layout {
-  size_t hdr, shard_rows, src_rows_needed, n_seq, n_mb, rank_load, a2a, summary_end;
-  size_t seq_group, seq_shard, seq_row, m, rank, slot, mb, dst_row;
+  size_t hdr, shard_rows, src_rows_needed, src_seqs_needed, n_seq, n_mb, rank_load, a2a, summary_end;
+  size_t seq_group, seq_shard, seq_k, seq_row, m, rank, slot, mb, dst_row;
   size_t seq_ids, next_start, mb_tmp, mb_seq_start, mb_row_start, cu_seqlens;
   size_t rank_seq_base, rank_mbt_base, rank_cu_base;
-  size_t segs, seg_dst_shard;
+  size_t segs, seg_dst_shard, seg_src_seq;
   size_t shard_seg_start, seg_real_prefix;
   size_t sort_keys, lab_sum, lab_cnt;
   size_t total;
@@ -75,6 +75,7 @@ Layout make_layout(const Dims& d) {
   l.hdr = take(sizeof(PlanHeader));
   l.shard_rows = take(8 * DC);
   l.src_rows_needed = take(8 * S);
+  l.src_seqs_needed = take(8 * S);
   l.n_seq = take(4 * D);
   l.n_mb = take(4 * D);
   l.rank_load = take(8 * D);
@@ -82,6 +83,7 @@ Layout make_layout(const Dims& d) {
   l.summary_end = off;
   l.seq_group = take(4 * N);
   l.seq_shard = take(4 * N);
+  l.seq_k = take(4 * N);
   l.seq_row = take(8 * N);
   l.m = take(4 * N);
   l.rank = take(4 * N);
@@ -99,6 +101,7 @@ Layout make_layout(const Dims& d) {
   l.rank_cu_base = take(4 * (D + 1));
   l.segs = take(sizeof(SegRec) * NK);
   l.seg_dst_shard = take(4 * NK);
+  l.seg_src_seq = take(4 * NK);
   l.shard_seg_start = take(4 * (DC + 1));
   l.seg_real_prefix = take(8 * (NK + 1));
   l.sort_keys = take(8 * (size_t)d.n_pow2);
@@ -283,7 +286,16 @@ int32_t check_field(const earl_plan* p, const earl_field& f, int idx, bool inver
   if (!f.src_shard_ptrs || !f.dst_shard_ptrs || !f.dst_capacity_rows)
     return fail(EARL_INVALID_ARG, "field %d: null pointer array", idx);
   const int64_t* shard_rows = summary_ptr<int64_t>(p, p->l.shard_rows);
-  const int64_t* need = summary_ptr<int64_t>(p, p->l.src_rows_needed);
+  if (f.per_sequence != 0 && f.per_sequence != 1)
+    return fail(EARL_INVALID_ARG, "field %d: per_sequence must be 0 or 1", idx);
+  if (f.per_sequence) {
+    const int64_t w = (int64_t)sb * f.width;
+    if (inverse) return fail(EARL_INVALID_ARG, "field %d: a per-sequence field has no inverse", idx);
+    if (w != 1 && w != 2 && w != 4 && w != 8)
+      return fail(EARL_INVALID_ARG, "field %d: a per-sequence field needs 1, 2, 4 or 8 row bytes", idx);
+  }
+  const int64_t* need = summary_ptr<int64_t>(p, f.per_sequence ? p->l.src_seqs_needed
+                                                               : p->l.src_rows_needed);
   const int n_dst = p->d.D * p->d.C;
   for (int q = 0; q < n_dst; ++q) {
     if (shard_rows[q] == 0) continue;
@@ -310,6 +322,7 @@ CopyArgs copy_args(const earl_plan* p, const void* params_dev, int64_t n_tiles) 
   CopyArgs a{};
   a.params = static_cast<const DispatchDev*>(params_dev);
   a.segs = p->dev.segs;
+  a.seg_src_seq = p->dev.seg_src_seq;
   a.n_tiles = n_tiles;
   return a;
 }
@@ -365,12 +378,14 @@ int32_t earl_plan_build(const int32_t* lengths_dev, int32_t n_seqs, const earl_s
   v.hdr = reinterpret_cast<PlanHeader*>(w + l.hdr);
   v.shard_rows = reinterpret_cast<int64_t*>(w + l.shard_rows);
   v.src_rows_needed = reinterpret_cast<int64_t*>(w + l.src_rows_needed);
+  v.src_seqs_needed = reinterpret_cast<int64_t*>(w + l.src_seqs_needed);
   v.n_seq = reinterpret_cast<int32_t*>(w + l.n_seq);
   v.n_mb = reinterpret_cast<int32_t*>(w + l.n_mb);
   v.rank_load = reinterpret_cast<int64_t*>(w + l.rank_load);
   v.a2a = reinterpret_cast<int64_t*>(w + l.a2a);
   v.seq_group = reinterpret_cast<int32_t*>(w + l.seq_group);
   v.seq_shard = reinterpret_cast<int32_t*>(w + l.seq_shard);
+  v.seq_k = reinterpret_cast<int32_t*>(w + l.seq_k);
   v.seq_row = reinterpret_cast<int64_t*>(w + l.seq_row);
   v.m = reinterpret_cast<int32_t*>(w + l.m);
   v.rank = reinterpret_cast<int32_t*>(w + l.rank);
@@ -388,6 +403,7 @@ int32_t earl_plan_build(const int32_t* lengths_dev, int32_t n_seqs, const earl_s
   v.rank_cu_base = reinterpret_cast<int32_t*>(w + l.rank_cu_base);
   v.segs = reinterpret_cast<SegRec*>(w + l.segs);
   v.seg_dst_shard = reinterpret_cast<int32_t*>(w + l.seg_dst_shard);
+  v.seg_src_seq = reinterpret_cast<int32_t*>(w + l.seg_src_seq);
   v.shard_seg_start = reinterpret_cast<int32_t*>(w + l.shard_seg_start);
   v.sort_keys = reinterpret_cast<uint64_t*>(w + l.sort_keys);
   v.lab_sum = reinterpret_cast<int64_t*>(w + l.lab_sum);
@@ -422,6 +438,7 @@ int32_t earl_plan_get_summary(earl_plan* p, earl_plan_summary* out) {
   out->rank_load_max = p->hdr.rank_load_max;
   out->shard_rows = summary_ptr<int64_t>(p, p->l.shard_rows);
   out->src_rows_needed = summary_ptr<int64_t>(p, p->l.src_rows_needed);
+  out->src_seqs_needed = summary_ptr<int64_t>(p, p->l.src_seqs_needed);
   out->n_seq = summary_ptr<int32_t>(p, p->l.n_seq);
   out->n_mb = summary_ptr<int32_t>(p, p->l.n_mb);
   out->rank_load = summary_ptr<int64_t>(p, p->l.rank_load);
@@ -573,6 +590,7 @@ int32_t earl_dispatch(earl_plan* p, const earl_field* fields, int32_t n_fields,
       proto.scalar_bytes = uf.scalar_bytes;
       proto.row_bytes = uf.scalar_bytes * uf.width;
       proto.pad_scalar = replicate_scalar(uf.pad_scalar, uf.scalar_bytes);
+      proto.per_sequence = uf.per_sequence;
       for (int s = 0; s < S; ++s) ptrs[pi + s] = uf.src_shard_ptrs[s];
       for (int q = 0; q < n_dst; ++q) ptrs[pi + S + q] = uf.dst_shard_ptrs[q];
     } else if (position_ids_shard_ptrs && f == n_fields) {

@@ -90,15 +90,26 @@ struct SegCursor {
   int e;
 };
 
-__device__ __forceinline__ void load_segment(const SegRec* segs, const void* const* src_ptrs,
-                                             int64_t w, int e, SegCursor& sc) {
+// seg_src_seq != null: a per-sequence field, whose source row is the sequence's row.
+__device__ __forceinline__ void load_segment(const SegRec* segs, const int32_t* seg_src_seq,
+                                             const void* const* src_ptrs, int64_t w, int e,
+                                             SegCursor& sc) {
   const SegRec r = segs[e];
   sc.e = e;
   sc.lo = r.dst_row * w;
   sc.real_hi = (r.dst_row + r.n_real) * w;
   sc.hi = (r.dst_row + r.n_rows) * w;
   sc.pos0 = r.pos0;
-  sc.src = src_ptrs ? static_cast<const u8*>(src_ptrs[r.src_shard]) + r.src_row * w : nullptr;
+  const int64_t src_row = seg_src_seq ? (int64_t)seg_src_seq[e] : r.src_row;
+  sc.src = src_ptrs ? static_cast<const u8*>(src_ptrs[r.src_shard]) + src_row * w : nullptr;
+}
+
+// 8 bytes holding copies of the low w bytes of v (w in {1, 2, 4, 8}).
+__device__ __forceinline__ uint64_t splat_scalar(uint64_t v, int w) {
+  if (w >= 8) return v;
+  v &= (1ull << (8 * w)) - 1ull;
+  for (int b = w; b < 8; b *= 2) v |= v << (8 * b);
+  return v;
 }
 
 // Tile codes.  `b` holds the destination pointer of the tile's first byte (16-byte aligned) with
@@ -163,10 +174,15 @@ __global__ __launch_bounds__(kCodeThreads) void tile_code_kernel(const CopyArgs 
           c.b = dst | kActIota;
         }
       } else if (hi <= s_real_hi) {
-        c.a = reinterpret_cast<uint64_t>(
-            static_cast<const u8*>(pv.ptrs[rec.src_ptr_index + r.src_shard]) + r.src_row * w +
-            (lo - s_lo));
-        c.b = dst | kActCopy;
+        const u8* shard = static_cast<const u8*>(pv.ptrs[rec.src_ptr_index + r.src_shard]);
+        if (rec.per_sequence) {
+          // the whole tile repeats the sequence's value
+          c.a = splat_scalar(load_scalar(shard + (int64_t)a.seg_src_seq[e0] * w, (int)w), (int)w);
+          c.b = dst | kActFill;
+        } else {
+          c.a = reinterpret_cast<uint64_t>(shard + r.src_row * w + (lo - s_lo));
+          c.b = dst | kActCopy;
+        }
       } else if (lo >= s_real_hi && hi <= s_hi) {
         c.a = rec.pad_scalar;
         c.b = dst | kActFill;
@@ -182,6 +198,7 @@ struct TileInfo {
   int64_t end;               // bytes of the destination shard
   uint64_t pad_scalar;
   const void* const* src_ptrs;
+  const int32_t* seg_src_seq;   // non-null for a per-sequence field
   int32_t e_end;
   int32_t row_bytes;
   int32_t scalar_bytes;
@@ -194,7 +211,7 @@ __device__ __forceinline__ void seek(const SegRec* segs, const TileInfo& t, int6
   const int64_t w = t.row_bytes;
   int e = sc.e + 1;
   if (e + 1 < t.e_end && segs[e + 1].dst_row * w <= o) e = find_segment(segs, e + 1, t.e_end, o, w);
-  load_segment(segs, t.src_ptrs, w, e, sc);
+  load_segment(segs, t.seg_src_seq, t.src_ptrs, w, e, sc);
 }
 
 // A tile that is not one plain copy / fill / iota: every lane places its own 16-byte vector.
@@ -223,16 +240,22 @@ __device__ __noinline__ void generic_tile(const CopyArgs a, const TileCode c) {
   t.end = rec.end_bytes;
   t.pad_scalar = rec.pad_scalar;
   t.src_ptrs = rec.kind == kFieldPositionIds ? nullptr : pv.ptrs + rec.src_ptr_index;
+  t.seg_src_seq = rec.per_sequence ? a.seg_src_seq : nullptr;
   t.e_end = rec.e_end;
   t.row_bytes = rec.row_bytes;
   t.scalar_bytes = rec.scalar_bytes;
   t.kind = rec.kind;
   SegCursor sc;
-  load_segment(a.segs, t.src_ptrs, rec.row_bytes, (int)(uint32_t)c.a, sc);
+  load_segment(a.segs, t.seg_src_seq, t.src_ptrs, rec.row_bytes, (int)(uint32_t)c.a, sc);
   seek(a.segs, t, o, sc);
   if (rec.kind == kFieldCopy) {
     if (o_end <= sc.real_hi) {
-      store16(dst + o, load16(sc.src + (o - sc.lo)));
+      if (t.seg_src_seq) {
+        const uint64_t v = splat_scalar(load_scalar(sc.src, rec.row_bytes), rec.row_bytes);
+        store16(dst + o, u32x4{(uint32_t)v, (uint32_t)(v >> 32), (uint32_t)v, (uint32_t)(v >> 32)});
+      } else {
+        store16(dst + o, load16(sc.src + (o - sc.lo)));
+      }
       return;
     }
     if (o >= sc.real_hi && o_end <= sc.hi) {
@@ -252,7 +275,9 @@ __device__ __noinline__ void generic_tile(const CopyArgs a, const TileCode c) {
     if (t.kind == kFieldPositionIds) {
       store_scalar(dst + b, (uint64_t)(uint32_t)(sc.pos0 + (int32_t)((b - sc.lo) >> 2)), 4);
     } else if (b < sc.real_hi) {
-      store_scalar(dst + b, load_scalar(sc.src + (b - sc.lo), sb), sb);
+      // a per-sequence row is at most 8 bytes: byte (b - lo) mod w of it
+      const int64_t off = t.seg_src_seq ? (b - sc.lo) % t.row_bytes : (b - sc.lo);
+      store_scalar(dst + b, load_scalar(sc.src + off, sb), sb);
     } else {
       store_scalar(dst + b, t.pad_scalar, sb);
     }

@@ -70,6 +70,7 @@ struct PlanDev {
   PlanHeader* hdr;
   int64_t* shard_rows;           // [D*C]
   int64_t* src_rows_needed;      // [S]
+  int64_t* src_seqs_needed;      // [S]
   int32_t* n_seq;                // [D]
   int32_t* n_mb;                 // [D]
   int64_t* rank_load;            // [D]
@@ -77,6 +78,7 @@ struct PlanDev {
   // per sequence
   int32_t* seq_group;            // [N]
   int32_t* seq_shard;            // [N]
+  int32_t* seq_k;                // [N] index of the sequence among its group's members
   int64_t* seq_row;              // [N]
   int32_t* m;                    // [N] chunk length
   int32_t* rank;                 // [N]
@@ -96,6 +98,7 @@ struct PlanDev {
   // segment table, ordered by (destination shard, destination row)
   SegRec* segs;                  // [N*K]
   int32_t* seg_dst_shard;        // [N*K]
+  int32_t* seg_src_seq;          // [N*K] seq_k of the segment's sequence
   int32_t* shard_seg_start;      // [D*C+1]
   // scratch
   uint64_t* sort_keys;           // [n_pow2]; reused as int64 row offsets in packed order
@@ -119,7 +122,7 @@ struct TileRec {
   int32_t kind;
   uint32_t src_ptr_index;   // first of the field's S source pointers in the pointer table
   uint32_t dst_ptr_index;   // first of the field's D*C destination pointers (inverse only)
-  int32_t pad_;
+  int32_t per_sequence;     // source holds one row per sequence, broadcast to its tokens
 };
 static_assert(sizeof(TileRec) == 64, "TileRec layout");
 
@@ -137,6 +140,7 @@ struct DispatchDev {
 struct CopyArgs {
   const DispatchDev* params;
   const SegRec* segs;
+  const int32_t* seg_src_seq;
   int64_t n_tiles;
 };
 

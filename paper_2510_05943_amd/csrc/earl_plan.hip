@@ -450,7 +450,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const PlanDev p) {
   if (tid == 0) { s_invalid = 0; s_exceeds = 0; s_bad = -1; }
   if (S * n_dst > kLdsA2a)
     for (int64_t x = tid; x < (int64_t)S * n_dst; x += T) p.a2a[x] = 0;
-  for (int x = tid; x < S; x += T) p.src_rows_needed[x] = 0;
+  for (int x = tid; x < S; x += T) { p.src_rows_needed[x] = 0; p.src_seqs_needed[x] = 0; }
   for (int x = tid; x < n_dst; x += T) p.shard_rows[x] = 0;
   for (int x = tid; x < D; x += T) { p.n_seq[x] = 0; p.n_mb[x] = 0; p.rank_load[x] = 0; }
   __syncthreads();
@@ -511,29 +511,39 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const PlanDev p) {
   label_scan(
       N, G, [&](int i) { return p.seq_group[i]; }, [&](int i) { return (int64_t)p.lengths[i]; },
       [&](int i, int32_t k, int64_t row) {
-        p.slot[i] = k;
+        p.seq_k[i] = k;
         p.seq_row[i] = p.seq_row_in ? p.seq_row_in[i] : row;
       },
       tab_sum, tab_cnt);
   {
     const int32_t* group_cnt = tab_cnt + 2 * (size_t)kPlanWaves * G;
-    const bool lds_max = S <= kLdsA2a;   // rows needed per shard: maximum taken in LDS
+    const bool lds_max = 2 * S <= kLdsA2a;   // rows needed per shard: maxima taken in LDS
     if (lds_max) {
-      for (int x = tid; x < S; x += T) s_a2a[x] = 0;
+      for (int x = tid; x < 2 * S; x += T) s_a2a[x] = 0;
       __syncthreads();
     }
     for (int i = tid; i < N; i += T) {
       const int g = p.seq_group[i];
-      const int64_t t = R == 1 ? 0 : ((int64_t)p.slot[i] * R) / group_cnt[g];
+      const int k = p.seq_k[i];
+      const int64_t t = R == 1 ? 0 : ((int64_t)k * R) / group_cnt[g];
       const int s = g * R + (int)t;
       p.seq_shard[i] = s;
       const unsigned long long need = (unsigned long long)(p.seq_row[i] + p.lengths[i]);
-      if (lds_max) atomicMax(&s_a2a[s], need);
-      else atomicMax(reinterpret_cast<unsigned long long*>(&p.src_rows_needed[s]), need);
+      const unsigned long long need_seqs = (unsigned long long)k + 1ull;
+      if (lds_max) {
+        atomicMax(&s_a2a[s], need);
+        atomicMax(&s_a2a[S + s], need_seqs);
+      } else {
+        atomicMax(reinterpret_cast<unsigned long long*>(&p.src_rows_needed[s]), need);
+        atomicMax(reinterpret_cast<unsigned long long*>(&p.src_seqs_needed[s]), need_seqs);
+      }
     }
     if (lds_max) {
       __syncthreads();
-      for (int x = tid; x < S; x += T) p.src_rows_needed[x] = (int64_t)s_a2a[x];
+      for (int x = tid; x < S; x += T) {
+        p.src_rows_needed[x] = (int64_t)s_a2a[x];
+        p.src_seqs_needed[x] = (int64_t)s_a2a[S + x];
+      }
     }
   }
   __syncthreads();
@@ -716,6 +726,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const PlanDev p) {
     const int s = p.seq_shard[i];
     const int64_t src_row = p.seq_row[i];
     const int64_t dst_row = p.dst_row[i];
+    const int32_t k_in_group = p.seq_k[i];
     for (int c = 0; c < C; ++c) {
       const int64_t e0 = (int64_t)halves * ((int64_t)C * base + (int64_t)c * n + (pos - base));
       int64_t real_rows = 0;
@@ -733,6 +744,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const PlanDev p) {
         rec.pos0 = (int32_t)p0;
         p.segs[e0 + h] = rec;
         p.seg_dst_shard[e0 + h] = r * C + c;
+        p.seg_src_seq[e0 + h] = k_in_group;
         real_rows += n_real;
       }
       if (real_rows > 0) {

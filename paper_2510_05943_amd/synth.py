@@ -33,6 +33,7 @@ class FieldSpec:
     width: int
     pad_scalar: int          # low `scalar_bytes` bytes are the fill pattern for padding rows
     kind: str                # which generator draws it (see Workload.group_buffer)
+    per_sequence: bool = False   # the source holds one row per sequence instead of one per token
 
     @property
     def row_bytes(self) -> int:
@@ -168,6 +169,9 @@ class Workload:
             out = np.repeat(per_seq, lens).view(np.uint32)
         elif field.kind == "hidden":
             out = self._hidden_pool(field.width)[self.hidden_rows_index(g)]
+        elif field.kind == "seq_value":
+            rows = len(members)
+            out = rng.integers(0, 256, size=(rows, field.row_bytes), dtype=np.uint8).view(field.np_dtype)
         elif field.kind == "bytes":
             out = rng.integers(0, 256, size=(rows, field.row_bytes),
                                dtype=np.uint8).view(field.np_dtype)
@@ -290,6 +294,11 @@ def custom_workload(lengths: Sequence[int], *, n_groups: int = 1, replication: i
                     replication=replication, seq_group=np.asarray(seq_group, dtype=np.int32),
                     dp=dp, sp=sp, zigzag=zigzag, pad_multiple=pad_multiple,
                     mb_token_budget=mb_token_budget, fields=tuple(fields))
+
+
+def per_sequence_field(name: str, scalar_bytes: int, width: int = 1, pad_scalar: int = 0) -> FieldSpec:
+    """One random row per SEQUENCE (a sequence-level reward or advantage), to be broadcast."""
+    return FieldSpec(name, scalar_bytes, width, pad_scalar, "seq_value", per_sequence=True)
 
 
 def bytes_field(name: str, scalar_bytes: int, width: int, pad_scalar: int = 0) -> FieldSpec:

@@ -84,7 +84,8 @@ def run_dispatch(w: synth.Workload, plan, fields: Sequence[synth.FieldSpec],
         pairs = [guarded(int(shard_rows[q]) * f.row_bytes) for q in range(n_dst)]
         wholes[f.name] = [p[0] for p in pairs]
         inner[f.name] = [p[1] for p in pairs]
-        bfields.append(B.Field(f.scalar_bytes, f.width, f.pad_scalar, srcs, inner[f.name]))
+        bfields.append(B.Field(f.scalar_bytes, f.width, f.pad_scalar, srcs, inner[f.name],
+                               per_sequence=f.per_sequence))
     pos_pairs = [guarded(int(shard_rows[q]) * 4) for q in range(n_dst)] if want_position_ids else None
     cu_pair = guarded(sm["cu_seqlens_len"] * 4) if want_cu else None
     ws_whole, ws = guarded(B.dispatch_workspace_bytes(plan, bfields, want_position_ids, want_cu))

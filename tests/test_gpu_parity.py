@@ -69,7 +69,7 @@ def assert_dispatch_equal(w, plan, out, shards_host, fields):
     for f in fields:
         for q in range(plan.D * plan.C):
             want = O.dispatch_field_shard(plan, q, shards_host[f.name], f.np_dtype, f.width,
-                                          f.pad_scalar)
+                                          f.pad_scalar, per_sequence=f.per_sequence)
             got = out["fields"][f.name][q]
             assert got.shape == want.shape, (f.name, q)
             assert np.array_equal(got, want), (f.name, q)
@@ -284,6 +284,45 @@ def test_snake_deal_policy(H, name, scale):
         out = H.run_dispatch(w, plan, w.fields, src_host=shards)
         assert_dispatch_equal(w, oplan, out, shards, w.fields)
     H.B.plan_destroy(plan)
+
+
+SEQ_FIELDS = (synth.per_sequence_field("adv_f32", 4, 1, 0x7FC00000), synth.per_sequence_field("flag_u8", 1),
+              synth.per_sequence_field("pair_u16", 2, 2, 0xBEEF), synth.per_sequence_field("ret_f64", 8, 1, 5),
+              synth.per_sequence_field("half", 2, 1, 0x3C00), synth.F_ID)
+
+
+@pytest.mark.parametrize("case", small_cases()[::3] + [dict(L=np.random.default_rng(9).integers(1, 3000, size=300),
+                                                           G=4, R=2, D=4, C=2, z=1, P=8, B=1 << 20, grp=None,
+                                                           seed=99)],
+                         ids=lambda c: f"case{c['seed']}")
+def test_per_sequence_fields_are_broadcast(H, case):
+    w = synth.custom_workload(case["L"], n_groups=case["G"], replication=case["R"],
+                              seq_group=case["grp"], dp=case["D"], sp=case["C"], zigzag=case["z"],
+                              pad_multiple=case["P"], mb_token_budget=case["B"], fields=SEQ_FIELDS,
+                              seed=case["seed"])
+    oplan = oracle_plan(w)
+    plan = H.build_plan(w)
+    res = H.plan_result(plan)
+    assert_plan_equal(res, oplan)
+    need = np.zeros(oplan.S, np.int64)
+    for i in range(oplan.N):
+        need[oplan.seq_shard[i]] = max(need[oplan.seq_shard[i]], int(oplan.seq_k[i]) + 1)
+    assert np.array_equal(res["src_seqs_needed"], need)
+    _, shards = H.host_sources(w, w.fields)
+    out = H.run_dispatch(w, plan, w.fields, src_host=shards)
+    assert_dispatch_equal(w, oplan, out, shards, w.fields)
+    # not invertible, and only scalar-sized rows
+    B = H.B
+    f = SEQ_FIELDS[0]
+    bf = B.Field(4, 1, 0, out["src_dev"][f.name], out["dev"][f.name], per_sequence=True)
+    with pytest.raises(B.EarlError) as e:
+        B.dispatch_inverse(plan, [bf], workspace=out["workspace"])
+    assert e.value.status == B.EARL_INVALID_ARG
+    with pytest.raises(B.EarlError) as e:
+        B.dispatch(plan, [B.Field(4, 4, 0, out["src_dev"][f.name], out["dev"][f.name], per_sequence=True)],
+                   workspace=out["workspace"])
+    assert e.value.status == B.EARL_INVALID_ARG
+    B.plan_destroy(plan)
 
 
 def test_two_pass_gather_then_scatter_equals_direct_dispatch(H):

@@ -100,7 +100,8 @@ def test_next_fit_hand_worked():
 
 def test_replica_choice_hand_worked():
     g = gold("replica_choice.json")
-    _, seq_shard, seq_row, _ = O.source_layout([3] * g["N"], g["G"], g["R"])
+    _, seq_shard, seq_row, _, seq_k = O.source_layout([3] * g["N"], g["G"], g["R"])
+    assert seq_k.tolist() == [0, 1, 2, 3, 4, 0, 1, 2, 3, 4]
     assert seq_shard.tolist() == g["seq_shard"]
     assert seq_row.tolist() == [0, 3, 6, 9, 12, 0, 3, 6, 9, 12]
 
@@ -150,6 +151,27 @@ def test_snake_hand_worked_and_bounds():
     # equal lengths: boustrophedon over the index
     rank, _ = O.snake_ranks([5] * 8, 3)
     assert rank.tolist() == [0, 1, 2, 2, 1, 0, 0, 1]
+
+
+def test_per_sequence_field_equals_the_repeated_per_token_field():
+    """Broadcasting one row per sequence must equal dispatching the field after numpy.repeat has
+    expanded it to one row per token."""
+    for case in small_cases()[:12]:
+        f = synth.per_sequence_field("adv", 4)
+        w = synth.custom_workload(case["L"], n_groups=case["G"], replication=case["R"],
+                                  seq_group=case["grp"], dp=case["D"], sp=case["C"], zigzag=case["z"],
+                                  pad_multiple=case["P"], mb_token_budget=case["B"], fields=(f,),
+                                  seed=case["seed"])
+        plan = plan_of(w)
+        per_seq = [w.group_buffer(f, s // w.replication) for s in range(w.n_shards)]
+        per_tok = []
+        for s in range(w.n_shards):
+            members = w.group_members(s // w.replication)
+            assert per_seq[s].shape[0] == len(members)
+            per_tok.append(np.repeat(per_seq[s], w.lengths[members], axis=0))
+        a = O.dispatch_field(plan, per_seq, f.np_dtype, 1, 0x7F, per_sequence=True)
+        b = O.dispatch_field(plan, per_tok, f.np_dtype, 1, 0x7F)
+        assert all(np.array_equal(x, y) for x, y in zip(a, b))
 
 
 def test_two_pass_gather_then_scatter_equals_direct_dispatch():
@@ -216,7 +238,8 @@ def test_source_offsets_are_per_group_cumsum():
     rng = np.random.default_rng(3)
     L = rng.integers(1, 30, size=40)
     grp = rng.integers(0, 5, size=40)
-    _, seq_shard, seq_row, group_rows = O.source_layout(L, 5, 1, seq_group=grp)
+    _, seq_shard, seq_row, group_rows, seq_k = O.source_layout(L, 5, 1, seq_group=grp)
+    assert seq_k.tolist() == [int((grp[:i] == grp[i]).sum()) for i in range(40)]
     assert seq_row.tolist() == checkers.packed_source_rows(L, grp, 5).tolist()
     assert seq_shard.tolist() == grp.tolist()
     assert group_rows.tolist() == [int(L[grp == g].sum()) for g in range(5)]
@@ -440,8 +463,8 @@ def _mut_replica_always_zero(monkeypatch):
     real = O.source_layout
 
     def bad(L, G, R, seq_group=None, seq_row=None):
-        grp, shard, row, rows = real(L, G, R, seq_group, seq_row)
-        return grp, (grp * R).astype(np.int32), row, rows
+        grp, shard, row, rows, k = real(L, G, R, seq_group, seq_row)
+        return grp, (grp * R).astype(np.int32), row, rows, k
     monkeypatch.setattr(O, "source_layout", bad)
 
 
