@@ -35,8 +35,8 @@ HBM_PEAK_GBPS = 8000.0
 # (scaled by a plain copy kernel of known size, see profiles/), keyed by the sha256 of the kernel
 # source the counters were taken on.  A changed kernel reports null until re-measured.
 MEASURED_TRAFFIC = {
-    "4293ad2168db80bd7d67ed2293eded4fddc87ca2349673d36023a10148eb6e1d":
-        {"heavy": 52051818764, "longctx": 46735745497},
+    "45fa313c73000d39a750ccc84af1e6031a3a32e912875e3fcd91080a203f8b78":
+        {"heavy": 52861018135, "longctx": 47490414836},
 }
 
 WORKLOAD_NOTES = {

@@ -146,7 +146,13 @@ __global__ __launch_bounds__(kCodeThreads) void tile_code_kernel(const CopyArgs 
   const int64_t tile = (int64_t)blockIdx.x * kCodeThreads + threadIdx.x;
   if (tile >= a.n_tiles) return;
   const ParamView pv = view_params(a.params);
-  const int x = last_le(pv.tile_start, 0, pv.n_recs, tile);
+  // The 64 tiles of a wavefront are consecutive, so most of them share the record, and often the
+  // segment, of the first one: search once for the first lane (uniform values, scalar loads),
+  // then every lane only checks whether the answer holds for its own tile.
+  const int64_t tile0 = ((int64_t)__builtin_amdgcn_readfirstlane((int)(tile >> 32)) << 32) |
+                        (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)tile);
+  const int x0 = last_le(pv.tile_start, 0, pv.n_recs, tile0);
+  const int x = tile < pv.tile_start[x0 + 1] ? x0 : last_le(pv.tile_start, x0, pv.n_recs, tile);
   const TileRec rec = pv.recs[x];
   const int64_t lo = (tile - rec.tile_first) * (int64_t)kTileBytes;
   const int64_t hi = lo + kTileBytes;
@@ -161,7 +167,19 @@ __global__ __launch_bounds__(kCodeThreads) void tile_code_kernel(const CopyArgs 
     }
   } else {
     const int64_t w = rec.row_bytes;
-    const int e0 = find_segment(a.segs, rec.e_begin, rec.e_end, lo, w);
+    // the first lane's segment (meaningful for the lanes that share its record)
+    const TileRec rec0 = pv.recs[x0];
+    int e_guess = rec0.e_begin;
+    if (rec0.kind != kFieldLinear)
+      e_guess = find_segment(a.segs, rec0.e_begin, rec0.e_end,
+                             (tile0 - rec0.tile_first) * (int64_t)kTileBytes, rec0.row_bytes);
+    int e0;
+    if (x == x0) {
+      const SegRec g = a.segs[e_guess];
+      e0 = lo < (g.dst_row + g.n_rows) * w ? e_guess : find_segment(a.segs, e_guess, rec.e_end, lo, w);
+    } else {
+      e0 = find_segment(a.segs, rec.e_begin, rec.e_end, lo, w);
+    }
     const SegRec r = a.segs[e0];
     const int64_t s_lo = r.dst_row * w;
     const int64_t s_real_hi = (r.dst_row + r.n_real) * w;
