@@ -110,3 +110,46 @@ def test_full_size_parity(name):
             assert torch.equal(back[f.name][s], src[f.name][s]), (f.name, s)
     print(f"[{name}] inverse: round trip restores all source shards", flush=True)
     B.plan_destroy(plan)
+
+
+def test_buffers_beyond_4_gib():
+    """One source buffer and one destination shard of more than 4 GiB each: every byte offset
+    inside a buffer has to be computed in 64 bits."""
+    import torch
+    import gpu_harness as H
+    B = H.B
+    wide = synth.FieldSpec("hidden_bf16", 2, 1024, 0, "hidden")
+    lengths = [36000 + 997 * (i % 7) for i in range(64)]            # 2.49 M rows of 2 KiB = 5.1 GB
+    w = synth.custom_workload(lengths, n_groups=1, dp=1, sp=1, zigzag=0, pad_multiple=8,
+                              mb_token_budget=1 << 30, fields=(synth.F_ID, wide), seed=3)
+    oplan = O.build_plan(w.lengths, n_groups=1, dp=1, sp=1, zigzag=0, pad_multiple=8,
+                         mb_token_budget=1 << 30)
+    src = {f.name: w.device_shard_buffers(f, torch) for f in w.fields}
+    assert src[wide.name][0].numel() * 2 > (4 << 30)
+    plan = H.build_plan(w)
+    sm = B.plan_get_summary(plan)
+    rows = [int(r) for r in sm["shard_rows"]]
+    assert rows == oplan.shard_rows.tolist() and rows[0] * wide.row_bytes > (4 << 30)
+    dsts = {f.name: [torch.full((r * f.row_bytes,), 0xCD, dtype=torch.uint8, device="cuda") for r in rows]
+            for f in w.fields}
+    fields = [B.Field(f.scalar_bytes, f.width, f.pad_scalar, src[f.name], dsts[f.name]) for f in w.fields]
+    scratch = torch.empty(B.dispatch_workspace_bytes(plan, fields, False, False), dtype=torch.uint8,
+                          device="cuda")
+    B.dispatch(plan, fields, workspace=scratch)
+    torch.cuda.synchronize()
+    for q in range(len(rows)):
+        shard, row = O.source_row_map_shard(oplan, q)
+        got = dsts[wide.name][q].view(torch.int16).reshape(-1, wide.width)
+        want = torch.full_like(got, 0)
+        sel = torch.from_numpy(np.nonzero(shard == 0)[0]).cuda()
+        want[sel] = src[wide.name][0].index_select(0, torch.from_numpy(row[shard == 0]).cuda())
+        assert torch.equal(got, want), q
+        del want
+    # and back: the 5 GB source buffer is restored bit for bit
+    back = {f.name: [torch.full_like(t, 0x5A) for t in src[f.name]] for f in w.fields}
+    inv = [B.Field(f.scalar_bytes, f.width, f.pad_scalar, back[f.name], dsts[f.name]) for f in w.fields]
+    B.dispatch_inverse(plan, inv, workspace=scratch)
+    torch.cuda.synchronize()
+    for f in w.fields:
+        assert torch.equal(back[f.name][0], src[f.name][0]), f.name
+    B.plan_destroy(plan)
