@@ -287,8 +287,11 @@ __device__ void lpt_packed(const PlanDev& p, const uint64_t* keys) {
       if (kSteps >= 2) mn = dpp_min_all_rows<kDppQuadXor2>(mn);
       if (kSteps >= 3) mn = dpp_min_all_rows<kDppRowHalfMirror>(mn);
       if (kSteps >= 4) mn = dpp_min_all_rows<kDppRowMirror>(mn);
-      const bool win = valid && (mn & 63u) == (uint32_t)lane;
-      word += win ? lp_s : 0u;
+      // the winner is the lane whose own word is the minimum (all words are distinct); its
+      // updated word is prepared beside the reduction, so the chain is butterfly, compare, select
+      const uint32_t grown = word + lp_s;
+      const bool win = valid && mn == word;
+      word = win ? grown : word;
       if (s < 32) won_lo |= win ? (1u << s) : 0u;
       else won_hi |= win ? (1u << (s - 32)) : 0u;
     }

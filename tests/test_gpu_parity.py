@@ -354,6 +354,38 @@ def test_two_pass_gather_then_scatter_equals_direct_dispatch(H):
         B.plan_destroy(p)
 
 
+def test_random_plans_sweep(H):
+    """Plan-only parity on many random layouts: every size class of the rank-assignment code
+    (1, 2, 4, 8, 16, 64 and more ranks), tight budgets with many micro-batches, replicated and
+    scattered source groups, both balancing policies."""
+    rng = np.random.default_rng(2024)
+    for t in range(160):
+        D = int(rng.choice([1, 2, 3, 4, 5, 8, 9, 16, 17, 33, 64, 65, 130]))
+        C = int(rng.choice([1, 1, 2, 3, 4, 8]))
+        z = int(rng.integers(0, 2))
+        P = int(rng.choice([1, 1, 4, 64]))
+        G = int(rng.choice([1, 2, 5, 8]))
+        R = int(rng.choice([1, 1, 2, 4]))
+        N = int(rng.integers(1, 700))
+        hi = int(rng.choice([8, 300, 5000]))
+        L = rng.integers(1, hi + 1, size=N)
+        K = 2 * C if (z and C > 1) else C
+        worst = K * P * (-(-(-(-int(L.max()) // K)) // P))
+        B = int(worst * rng.choice([1, 1, 2, 7, 1000]))
+        policy = int(rng.integers(0, 2))
+        w = synth.custom_workload(L, n_groups=G, replication=R, dp=D, sp=C, zigzag=z,
+                                  pad_multiple=P, mb_token_budget=B, seed=t)
+        if t % 3 == 0:
+            w.seq_group = rng.integers(0, G, size=N).astype(np.int32)
+        plan = H.build_plan(w, balance_policy=policy)
+        try:
+            assert_plan_equal(H.plan_result(plan), oracle_plan(w, balance_policy=policy))
+        except AssertionError as err:
+            raise AssertionError(f"case {t}: N={N} D={D} C={C} z={z} P={P} G={G} R={R} B={B} "
+                                 f"policy={policy}: {err}")
+        H.B.plan_destroy(plan)
+
+
 def test_dispatch_with_empty_ranks_and_no_fields(H):
     w = synth.custom_workload([5, 9, 2], dp=5, sp=2, zigzag=1, mb_token_budget=100,
                               fields=(synth.F_ID, synth.F_MASK))
