@@ -103,7 +103,8 @@ typedef struct {
  *                       order, whatever seq_row says) and the dispatch broadcasts it to every real
  *                       token of the sequence while it copies (e.g. a sequence-level advantage or
  *                       reward, Section 4 of the paper); padding rows get pad_scalar.  Needs
- *                       scalar_bytes * width in {1, 2, 4, 8}; not accepted by earl_dispatch_inverse.
+ *                       scalar_bytes * width in {1, 2, 4, 8} and source buffers aligned to that;
+ *                       not accepted by earl_dispatch_inverse.
  * Source and destination buffers must not overlap.
  */
 typedef struct {

@@ -309,7 +309,8 @@ int32_t check_field(const earl_plan* p, const earl_field& f, int idx, bool inver
   for (int s = 0; s < p->d.S; ++s) {
     if (need[s] == 0) continue;
     if (!f.src_shard_ptrs[s]) return fail(EARL_INVALID_ARG, "field %d: source %d is null", idx, s);
-    if (reinterpret_cast<uintptr_t>(f.src_shard_ptrs[s]) % sb)
+    // a per-sequence row is fetched as one scalar of row_bytes
+    if (reinterpret_cast<uintptr_t>(f.src_shard_ptrs[s]) % (f.per_sequence ? sb * f.width : sb))
       return fail(EARL_INVALID_ARG, "field %d: source %d is misaligned", idx, s);
     if (f.src_capacity_rows && f.src_capacity_rows[s] < need[s])
       return fail(EARL_CAPACITY, "field %d: source %d holds %lld rows, %lld needed", idx, s,
