@@ -35,8 +35,8 @@ HBM_PEAK_GBPS = 8000.0
 # (scaled by a plain copy kernel of known size, see profiles/), keyed by the sha256 of the kernel
 # source the counters were taken on.  A changed kernel reports null until re-measured.
 MEASURED_TRAFFIC = {
-    "45fa313c73000d39a750ccc84af1e6031a3a32e912875e3fcd91080a203f8b78":
-        {"heavy": 52861018135, "longctx": 47490414836},
+    "4c9f58824f9b885dff07364d978ee7283653c05d64b7209bf08b839421f0e5fc":
+        {"heavy": 52873342253, "longctx": 47518264371},
 }
 
 WORKLOAD_NOTES = {

@@ -501,7 +501,17 @@ int32_t earl_plan_export_segments(earl_plan* p, int32_t* src_shard, int64_t* src
 
 namespace {
 
-// Tiles of one dispatch call: sum over (field, shard) of ceil(bytes / tile bytes).
+// Bytes per tile code: fields with rows under 16 bytes are cut into 1 KiB tiles (with several
+// hundred rows per tile most tiles then lie inside one segment and are plain copies), all others
+// into 4 KiB tiles (16 KiB tiles for wide rows measured slower: more bytes in edge tiles).
+inline int tile_shift_of(int64_t row_bytes, int kind) {
+  return kind != kFieldLinear && row_bytes < kVecBytes ? kFineTileShift : kTileShift;
+}
+inline int64_t tile_bytes_of(int64_t row_bytes, int kind) {
+  return (int64_t)1 << tile_shift_of(row_bytes, kind);
+}
+
+// Tile codes of one dispatch call: sum over (field, shard) of ceil(bytes / tile bytes).
 int64_t count_tiles(const earl_plan* p, const earl_field* fields, int32_t n_fields, bool with_pos,
                     bool with_cu) {
   const int n_dst = p->d.D * p->d.C;
@@ -509,7 +519,8 @@ int64_t count_tiles(const earl_plan* p, const earl_field* fields, int32_t n_fiel
   int64_t tiles = 0;
   for (int f = 0; f < n_fields + (with_pos ? 1 : 0); ++f) {
     const int64_t w = f < n_fields ? (int64_t)fields[f].scalar_bytes * fields[f].width : 4;
-    for (int q = 0; q < n_dst; ++q) tiles += (shard_rows[q] * w + kTileBytes - 1) / kTileBytes;
+    const int64_t tb = tile_bytes_of(w, kFieldCopy);
+    for (int q = 0; q < n_dst; ++q) tiles += (shard_rows[q] * w + tb - 1) / tb;
   }
   if (with_cu) tiles += (4ll * p->hdr.cu_seqlens_len + kTileBytes - 1) / kTileBytes;
   return tiles;
@@ -541,7 +552,13 @@ int32_t earl_dispatch_workspace_bytes(earl_plan* p, const earl_field* fields, in
   st = ensure_summary(p);
   if (st != EARL_OK) return st;
   const int F = n_fields + (with_position_ids ? 1 : 0) + (with_cu_seqlens ? 1 : 0);
-  const int64_t tiles = count_tiles(p, fields, n_fields, with_position_ids != 0, with_cu_seqlens != 0);
+  int64_t tiles = count_tiles(p, fields, n_fields, with_position_ids != 0, with_cu_seqlens != 0);
+  // the same scratch must do for earl_dispatch_inverse with these fields
+  int64_t inverse_tiles = 0;
+  for (int f = 0; f < n_fields; ++f)
+    inverse_tiles += (p->hdr.total_real_rows * (int64_t)fields[f].scalar_bytes * fields[f].width +
+                      kTileBytes - 1) / kTileBytes;
+  if (inverse_tiles > tiles) tiles = inverse_tiles;
   *out_bytes = param_block_bytes(F, p->d.S, p->d.D * p->d.C) + kTileCodeBytes * (size_t)tiles;
   return EARL_OK;
 }
@@ -579,10 +596,12 @@ int32_t earl_dispatch(earl_plan* p, const earl_field* fields, int32_t n_fields,
   int64_t* ts = b.tile_start();
   TileRec* recs = b.recs();
   const void** ptrs = b.ptrs();
+  // pointer tables and one prototype record per field
+  std::vector<TileRec> protos((size_t)F);
   uint32_t pi = 0;
-  int64_t tiles = 0;
   for (int f = 0; f < F; ++f) {
-    TileRec proto{};
+    TileRec& proto = protos[f];
+    proto = TileRec{};
     proto.src_ptr_index = pi;
     proto.dst_ptr_index = pi + S;
     if (f < n_fields) {
@@ -591,7 +610,7 @@ int32_t earl_dispatch(earl_plan* p, const earl_field* fields, int32_t n_fields,
       proto.scalar_bytes = uf.scalar_bytes;
       proto.row_bytes = uf.scalar_bytes * uf.width;
       proto.pad_scalar = replicate_scalar(uf.pad_scalar, uf.scalar_bytes);
-      proto.per_sequence = uf.per_sequence;
+      proto.per_sequence = (int16_t)uf.per_sequence;
       for (int s = 0; s < S; ++s) ptrs[pi + s] = uf.src_shard_ptrs[s];
       for (int q = 0; q < n_dst; ++q) ptrs[pi + S + q] = uf.dst_shard_ptrs[q];
     } else if (position_ids_shard_ptrs && f == n_fields) {
@@ -606,23 +625,36 @@ int32_t earl_dispatch(earl_plan* p, const earl_field* fields, int32_t n_fields,
       ptrs[pi] = p->dev.cu_seqlens;
       ptrs[pi + S] = cu_seqlens_dev;
     }
-    for (int q = 0; q < n_dst; ++q) {
-      TileRec& r = recs[(size_t)f * n_dst + q];
-      r = proto;
-      r.tile_first = tiles;
-      r.dst = const_cast<void*>(ptrs[pi + S + q]);
-      r.e_begin = p->seg_starts[q];
-      r.e_end = p->seg_starts[q + 1];
-      r.end_bytes = proto.kind == kFieldLinear
-                        ? (q == 0 ? 4ll * p->hdr.cu_seqlens_len : 0)
-                        : shard_rows[q] * (int64_t)proto.row_bytes;
-      ts[(size_t)f * n_dst + q] = tiles;
-      tiles += (r.end_bytes + kTileBytes - 1) / kTileBytes;
-    }
+    proto.tile_shift = (int16_t)tile_shift_of(proto.row_bytes, proto.kind);
     pi += S + n_dst;
   }
-  ts[(size_t)F * n_dst] = tiles;
-  if (tiles * kSubTiles > 0x7fffffffll) return fail(EARL_INVALID_ARG, "too many tiles for one launch");
+  // records in launch order: the fields with 1 KiB tiles first
+  int64_t tiles = 0, fine = 0;
+  size_t n_rec = 0;
+  for (int pass = 0; pass < 2; ++pass) {
+    for (int f = 0; f < F; ++f) {
+      const TileRec& proto = protos[f];
+      if ((proto.tile_shift == kFineTileShift) != (pass == 0)) continue;
+      const int64_t tb = (int64_t)1 << proto.tile_shift;
+      for (int q = 0; q < n_dst; ++q) {
+        TileRec& r = recs[n_rec];
+        r = proto;
+        r.tile_first = tiles;
+        r.dst = const_cast<void*>(ptrs[proto.dst_ptr_index + q]);
+        r.e_begin = p->seg_starts[q];
+        r.e_end = p->seg_starts[q + 1];
+        r.end_bytes = proto.kind == kFieldLinear
+                          ? (q == 0 ? 4ll * p->hdr.cu_seqlens_len : 0)
+                          : shard_rows[q] * (int64_t)proto.row_bytes;
+        ts[n_rec++] = tiles;
+        tiles += (r.end_bytes + tb - 1) / tb;
+      }
+    }
+    if (pass == 0) fine = tiles;
+  }
+  ts[n_rec] = tiles;
+  if (fine + (tiles - fine) * kSubTiles > 0x7fffffffll)
+    return fail(EARL_INVALID_ARG, "too many tiles for one launch");
   if (tiles == 0) return EARL_OK;
   const size_t codes_off = b.bytes.size();
   const size_t need = codes_off + kTileCodeBytes * (size_t)tiles;
@@ -633,7 +665,8 @@ int32_t earl_dispatch(earl_plan* p, const earl_field* fields, int32_t n_fields,
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   st = upload_params(b.bytes, dispatch_ws_dev, stream);
   if (st != EARL_OK) return st;
-  const CopyArgs ca = copy_args(p, dispatch_ws_dev, tiles);
+  CopyArgs ca = copy_args(p, dispatch_ws_dev, tiles);
+  ca.n_fine_tiles = fine;
   void* codes = static_cast<unsigned char*>(dispatch_ws_dev) + codes_off;
   launch_tile_codes(ca, codes, stream);
   if (p->ev_before) HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(p->ev_before), stream));
@@ -675,6 +708,7 @@ int32_t earl_dispatch_inverse(earl_plan* p, const earl_field* fields, int32_t n_
     r.row_bytes = uf.scalar_bytes * uf.width;
     r.src_ptr_index = pi;
     r.dst_ptr_index = pi + S;
+    r.tile_shift = kTileShift;
     for (int s = 0; s < S; ++s) ptrs[pi + s] = uf.src_shard_ptrs[s];
     for (int q = 0; q < n_dst; ++q) ptrs[pi + S + q] = uf.dst_shard_ptrs[q];
     pi += S + n_dst;

@@ -154,8 +154,8 @@ __global__ __launch_bounds__(kCodeThreads) void tile_code_kernel(const CopyArgs 
   const int x0 = last_le(pv.tile_start, 0, pv.n_recs, tile0);
   const int x = tile < pv.tile_start[x0 + 1] ? x0 : last_le(pv.tile_start, x0, pv.n_recs, tile);
   const TileRec rec = pv.recs[x];
-  const int64_t lo = (tile - rec.tile_first) * (int64_t)kTileBytes;
-  const int64_t hi = lo + kTileBytes;
+  const int64_t lo = (tile - rec.tile_first) << rec.tile_shift;
+  const int64_t hi = lo + ((int64_t)1 << rec.tile_shift);
   const uint64_t dst = reinterpret_cast<uint64_t>(static_cast<u8*>(rec.dst) + lo);
   TileCode c;
   c.a = (uint64_t)(uint32_t)x << 32;
@@ -172,7 +172,7 @@ __global__ __launch_bounds__(kCodeThreads) void tile_code_kernel(const CopyArgs 
     int e_guess = rec0.e_begin;
     if (rec0.kind != kFieldLinear)
       e_guess = find_segment(a.segs, rec0.e_begin, rec0.e_end,
-                             (tile0 - rec0.tile_first) * (int64_t)kTileBytes, rec0.row_bytes);
+                             (tile0 - rec0.tile_first) << rec0.tile_shift, rec0.row_bytes);
     int e0;
     if (x == x0) {
       const SegRec g = a.segs[e_guess];
@@ -233,11 +233,13 @@ __device__ __forceinline__ void seek(const SegRec* segs, const TileInfo& t, int6
 }
 
 // A tile that is not one plain copy / fill / iota: every lane places its own 16-byte vector.
-__device__ __noinline__ void generic_tile(const CopyArgs a, const TileCode c, const uint32_t bid) {
+// `tile` is the tile's code index, `vec0` the first 16-byte vector of the tile this workgroup owns.
+__device__ __noinline__ void generic_tile(const CopyArgs a, const TileCode c, const int64_t tile,
+                                          const uint32_t vec0) {
   const ParamView pv = view_params(a.params);
   const TileRec rec = pv.recs[(uint32_t)(c.a >> 32)];
-  const int64_t lo = ((int64_t)(bid / kSubTiles) - rec.tile_first) * (int64_t)kTileBytes;
-  const int64_t o = lo + (int64_t)((bid % kSubTiles) * kCopyThreads + threadIdx.x) * kVecBytes;
+  const int64_t lo = (tile - rec.tile_first) << rec.tile_shift;
+  const int64_t o = lo + (int64_t)(vec0 + threadIdx.x) * kVecBytes;   // this lane's vector
   if (o >= rec.end_bytes) return;
   u8* dst = static_cast<u8*>(rec.dst);
   const int64_t o_end = o + kVecBytes;
@@ -302,15 +304,22 @@ __device__ __noinline__ void generic_tile(const CopyArgs a, const TileCode c, co
   }
 }
 
-// Pass 2: kSubTiles one-wavefront workgroups per 4 KiB tile, one 16-byte vector per lane.
+// Pass 2: one-wavefront workgroups, one 16-byte vector per lane: one workgroup per 1 KiB tile
+// code (the first n_fine_tiles codes), kSubTiles workgroups per 4 KiB tile code (the rest).
 __global__ __launch_bounds__(kCopyThreads) void relayout_kernel(const CopyArgs a,
                                                                 const TileCode* __restrict__ codes) {
   // consecutive workgroups go to different XCDs; grouping a tile's workgroups on one XCD
   // measured 5-12 % slower, so the hardware order is kept
-  const uint32_t bid = blockIdx.x;
-  const TileCode c = codes[bid / kSubTiles];
+  int64_t tile = blockIdx.x;
+  uint32_t vec0 = 0;
+  if (tile >= a.n_fine_tiles) {
+    const int64_t rest = tile - a.n_fine_tiles;
+    tile = a.n_fine_tiles + rest / kSubTiles;
+    vec0 = (uint32_t)(rest % kSubTiles) * kCopyThreads;
+  }
+  const TileCode c = codes[tile];
   const uint64_t act = c.b & 15u;
-  const uint32_t v = (bid % kSubTiles) * kCopyThreads + threadIdx.x;   // vector in the tile
+  const uint32_t v = vec0 + threadIdx.x;   // vector in the tile
   u8* dst = reinterpret_cast<u8*>(c.b & ~(uint64_t)15) + v * kVecBytes;
   if (act == kActCopy) {
     store16(dst, load16(reinterpret_cast<const u8*>(c.a) + v * kVecBytes));
@@ -320,7 +329,7 @@ __global__ __launch_bounds__(kCopyThreads) void relayout_kernel(const CopyArgs a
     const uint32_t p0 = (uint32_t)c.a + v * 4;
     store16(dst, u32x4{p0, p0 + 1, p0 + 2, p0 + 3});
   } else {
-    generic_tile(a, c, bid);
+    generic_tile(a, c, tile, vec0);
   }
 }
 
@@ -469,8 +478,9 @@ void launch_tile_codes(const CopyArgs& a, void* tile_codes, hipStream_t stream) 
 
 void launch_copy(const CopyArgs& a, const void* tile_codes, hipStream_t stream) {
   if (a.n_tiles <= 0) return;
-  hipLaunchKernelGGL(relayout_kernel, dim3((unsigned)(a.n_tiles * kSubTiles)), dim3(kCopyThreads), 0,
-                     stream, a, static_cast<const TileCode*>(tile_codes));
+  const int64_t grid = a.n_fine_tiles + (a.n_tiles - a.n_fine_tiles) * kSubTiles;
+  hipLaunchKernelGGL(relayout_kernel, dim3((unsigned)grid), dim3(kCopyThreads), 0, stream, a,
+                     static_cast<const TileCode*>(tile_codes));
 }
 
 void launch_real_prefix(const SegRec* segs, int64_t* prefix, int n_seg, hipStream_t stream) {

@@ -20,9 +20,11 @@ constexpr int kLdsLabels = 256;
 constexpr int kLdsSortKeys = 8192;
 
 constexpr int kVecBytes = 16;        // one global_load/store_dwordx4 per lane
+constexpr int kTileShift = 12;       // log2 of kTileBytes
 constexpr int kTileBytes = 4096;     // destination bytes described by one tile code
+constexpr int kFineTileShift = 10;   // fields with rows under 16 bytes: 1 KiB per tile code
 constexpr int kCopyThreads = 64;     // re-layout workgroup: one wavefront, 1 KiB of a tile
-constexpr int kSubTiles = kTileBytes / (kCopyThreads * kVecBytes);   // workgroups per tile
+constexpr int kSubTiles = kTileBytes / (kCopyThreads * kVecBytes);   // workgroups per 4 KiB tile
 constexpr int kCodeThreads = 256;    // tile-code kernel workgroup (one tile per lane)
 constexpr int kInverseThreads = kTileBytes / kVecBytes;   // inverse kernel: one tile per workgroup
 
@@ -122,7 +124,8 @@ struct TileRec {
   int32_t kind;
   uint32_t src_ptr_index;   // first of the field's S source pointers in the pointer table
   uint32_t dst_ptr_index;   // first of the field's D*C destination pointers (inverse only)
-  int32_t per_sequence;     // source holds one row per sequence, broadcast to its tokens
+  int16_t per_sequence;     // source holds one row per sequence, broadcast to its tokens
+  int16_t tile_shift;       // log2 of the bytes one tile code of this record describes
 };
 static_assert(sizeof(TileRec) == 64, "TileRec layout");
 
@@ -141,7 +144,10 @@ struct CopyArgs {
   const DispatchDev* params;
   const SegRec* segs;
   const int32_t* seg_src_seq;
-  int64_t n_tiles;
+  int64_t n_tiles;       // tile codes in the launch
+  // Forward direction: the first n_fine_tiles codes describe 1 KiB each (one workgroup per code),
+  // the others 4 KiB (kSubTiles workgroups per code).
+  int64_t n_fine_tiles;
 };
 
 void launch_plan(const PlanDev& p, hipStream_t stream);
