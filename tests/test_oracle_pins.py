@@ -388,6 +388,26 @@ def test_byte_accounting_is_linear_in_tokens():
     assert sizes[0] == 13 * int(base.sum()) * 2 + 4 * int(base.sum())
 
 
+def test_batch_volume_matches_the_papers_table():
+    """Table 1 of the paper prints the batch volume for six context lengths.  The rows that
+    leave the source workers (all-to-all counts), times the bytes per token, must give those
+    sizes exactly: every real token counted once, whatever the replication of the sources and
+    the padding of the destination."""
+    g = gold("table1_batch_size.json")
+    n, bpt = g["n_seqs"], g["bytes_per_token"]
+    for ctx, mib in zip(g["context_length"], g["estimated_size_MiB"]):
+        lengths = np.full((n,), ctx, dtype=np.int64)
+        for n_groups, repl, sp, pad in ((8, 1, 1, 1), (2, 4, 4, 64), (1, 8, 3, 7)):
+            plan = O.build_plan(lengths, n_groups=n_groups, replication=repl, dp=4, sp=sp, zigzag=1,
+                                pad_multiple=pad, mb_token_budget=1 << 40)
+            sent = int(plan.a2a_counts.sum()) * bpt
+            assert sent == mib * (1 << 20)
+            assert plan.total_real_rows * bpt == mib * (1 << 20)
+            # the bytes one dispatch moves: that volume read once, and the padded layout written
+            assert O.algorithmic_bytes(plan, [bpt], with_position_ids=False) == \
+                sent + plan.total_dst_rows * bpt
+
+
 def test_plan_ignores_field_contents_and_is_deterministic():
     w = synth.make_workload("mid", seed=2, scale=0.125)
     a, b = plan_of(w), plan_of(w)
