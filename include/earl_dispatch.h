@@ -41,7 +41,8 @@ typedef enum {
                                   reported by earl_plan_get_summary / earl_dispatch)              */
   EARL_SEQ_EXCEEDS_BUDGET = 2, /* some padded sequence is longer than mb_token_budget            */
   EARL_CAPACITY = 3,           /* workspace or a destination/source buffer is too small          */
-  EARL_HIP_ERROR = 4           /* a HIP runtime call failed; see earl_last_error_message()       */
+  EARL_HIP_ERROR = 4,          /* a HIP runtime call failed; see earl_last_error_message()       */
+  EARL_NO_FEASIBLE_CONFIG = 5  /* earl_selector.h: every configuration failed in this range      */
 } earl_status;
 
 /* Limits (EARL_INVALID_ARG beyond them). */

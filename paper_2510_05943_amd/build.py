@@ -10,7 +10,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libearl_dispatch.so")
-SOURCES = ("earl_api.hip", "earl_plan.hip", "earl_copy.hip")
+SOURCES = ("earl_api.hip", "earl_plan.hip", "earl_copy.hip", "earl_selector.cpp")
 
 
 def hipcc() -> str:

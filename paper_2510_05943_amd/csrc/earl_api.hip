@@ -762,6 +762,7 @@ const char* earl_status_string(int32_t status) {
     case EARL_SEQ_EXCEEDS_BUDGET: return "a padded sequence exceeds the micro-batch token budget";
     case EARL_CAPACITY: return "a buffer is too small";
     case EARL_HIP_ERROR: return "HIP runtime error";
+    case EARL_NO_FEASIBLE_CONFIG: return "no feasible configuration for this context length";
     default: return "unknown status";
   }
 }
