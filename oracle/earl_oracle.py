@@ -122,12 +122,15 @@ def padded_geometry(L, C: int, zigzag: int, P: int):
 # ----------------------------------------------------------------------------------------
 # Rank assignment
 # ----------------------------------------------------------------------------------------
-def lpt_ranks(Lp, D: int):
+def lpt_ranks(Lp, D: int, quadratic: bool = False):
     """Length-balanced assignment of sequences to the D data-parallel ranks.
 
     Longest-processing-time list scheduling (Graham 1969): visit sequences by padded length,
     longest first (equal lengths: lower index first); give each to the rank whose load is
-    smallest so far (equal loads: lower rank); its load grows by the padded length.
+    smallest so far (equal loads: lower rank); its load grows by the sequence's cost.  The cost
+    is the padded length (balance_policy 0: equal token counts) or its square (balance_policy
+    2: equal causal-attention work, which grows with the square of the length).  Returns the
+    ranks and the per-rank sums of the cost.
     """
     N = len(Lp)
     order = sorted(range(N), key=lambda i: (-int(Lp[i]), i))
@@ -136,8 +139,8 @@ def lpt_ranks(Lp, D: int):
     for i in order:
         r = min(range(D), key=lambda d: (load[d], d))
         rank[i] = r
-        load[r] += int(Lp[i])
-    return np.array(rank, np.int32), np.array(load, np.int64)
+        load[r] += int(Lp[i]) ** 2 if quadratic else int(Lp[i])
+    return np.array(rank, np.int32), np.array(load, dtype=object if quadratic else np.int64)
 
 
 def snake_ranks(Lp, D: int):
@@ -160,7 +163,7 @@ def snake_ranks(Lp, D: int):
 # ----------------------------------------------------------------------------------------
 # Packing order, micro-batches, destination offsets
 # ----------------------------------------------------------------------------------------
-def pack_ranks(rank, Lp, loc, D: int, B: int):
+def pack_ranks(rank, Lp, loc, D: int, B: int, equal_mb: bool = False):
     """Order inside a rank, micro-batch of every sequence, destination row offsets.
 
     Inside a rank sequences keep ascending original index.  Micro-batches are cut next-fit
@@ -169,6 +172,9 @@ def pack_ranks(rank, Lp, loc, D: int, B: int):
     of whole sequences on the DP rank, before the split over SP ranks).  Rows of a rank's
     shards are consecutive over all its sequences, so micro-batches are consecutive row
     ranges; dst_row[i] is the sum of loc over the sequences packed before i in its rank.
+    With equal_mb every rank reports as many micro-batches as the rank that has most: the
+    missing ones are appended empty (no sequence, no row), so that all data-parallel ranks run
+    the same number of steps.
     """
     N = len(rank)
     slot = [0] * N
@@ -193,11 +199,16 @@ def pack_ranks(rank, Lp, loc, D: int, B: int):
         seq_ids[r].append(i)
         cur[r] += int(Lp[i])
         rows[r] += int(loc[i])
+    most = max(len(mb_seq_start[r]) for r in range(D))
     for r in range(D):
         n_seq[r] = len(seq_ids[r])
         n_mb[r] = len(mb_seq_start[r])
         mb_seq_start[r].append(n_seq[r])
         mb_row_start[r].append(rows[r])
+        while equal_mb and n_mb[r] < most:
+            n_mb[r] += 1
+            mb_seq_start[r].append(n_seq[r])
+            mb_row_start[r].append(rows[r])
     return dict(slot=np.array(slot, np.int32), mb=np.array(mb, np.int32),
                 dst_row=np.array(dst_row, np.int64), n_seq=np.array(n_seq, np.int32),
                 n_mb=np.array(n_mb, np.int32), rank_rows=np.array(rows, np.int64),
@@ -277,7 +288,7 @@ class Plan:
 
 def build_plan(L, *, n_groups: int, replication: int = 1, seq_group=None, seq_row=None,
                dp: int, sp: int, zigzag: int, pad_multiple: int, mb_token_budget: int,
-               balance_policy: int = 0) -> Plan:
+               balance_policy: int = 0, equal_mb: int = 0) -> Plan:
     """The dispatch plan: for every sequence, where it is read and where each part is written.
 
     This is the "parallelism- and layout-aware" decision of Section 2 made explicit.  The
@@ -301,10 +312,16 @@ def build_plan(L, *, n_groups: int, replication: int = 1, seq_group=None, seq_ro
     K, m, Lp, loc = padded_geometry(L, C, zigzag, P)
     if any(int(x) > B for x in Lp):
         raise OracleError(SEQ_EXCEEDS_BUDGET, "a padded sequence is longer than the budget")
-    if balance_policy not in (0, 1):
-        raise OracleError(INVALID_ARG, "unknown balance_policy")
-    rank, load = lpt_ranks(Lp, D) if balance_policy == 0 else snake_ranks(Lp, D)
-    pk = pack_ranks(rank, Lp, loc, D, B)
+    if balance_policy not in (0, 1, 2) or equal_mb not in (0, 1):
+        raise OracleError(INVALID_ARG, "unknown balance_policy or equal_mb")
+    if balance_policy == 1:
+        rank, _ = snake_ranks(Lp, D)
+    else:
+        rank, _ = lpt_ranks(Lp, D, quadratic=(balance_policy == 2))
+    # reported load of a rank: its padded tokens, whatever cost the policy balanced
+    load = np.zeros((D,), np.int64)
+    np.add.at(load, rank, np.asarray(Lp, np.int64))
+    pk = pack_ranks(rank, Lp, loc, D, B, equal_mb=bool(equal_mb))
 
     shard_rows = np.repeat(pk["rank_rows"], C).astype(np.int64)
 

@@ -13,7 +13,9 @@
 //   * with so little work per wavefront, any search ("which field, which shard, which segment")
 //     in front of the load costs more than the copy itself.  A first kernel therefore decodes
 //     every tile ONCE, one tile per lane (64 decodes per wavefront instruction), into a 16-byte
-//     tile code per 4 KiB of destination: source pointer, destination pointer and what to do.
+//     tile code per 4 KiB of destination (1 KiB for fields whose rows are shorter than a
+//     vector, so that a tile seldom crosses a segment edge): source pointer, destination pointer
+//     and what to do.
 //     The copy kernel reads its code with one uniform load and, for a tile that lies inside the
 //     real part of one segment (nearly all bytes of a wide field), does nothing but load and store;
 //   * work is cut on the DESTINATION, every lane owns one whole 16-byte destination vector:
@@ -115,8 +117,8 @@ __device__ __forceinline__ uint64_t splat_scalar(uint64_t v, int w) {
 // Tile codes.  `b` holds the destination pointer of the tile's first byte (16-byte aligned) with
 // the action in its low four bits; `a` depends on the action.
 enum TileAction : uint64_t {
-  kActCopy = 0,      // a = source pointer of the tile's first byte: 4 KiB straight copy
-  kActFill = 1,      // a = padding scalar replicated to 8 bytes: 4 KiB of padding
+  kActCopy = 0,      // a = source pointer of the tile's first byte: the tile is a straight copy
+  kActFill = 1,      // a = scalar replicated to 8 bytes: the whole tile repeats it
   kActIota = 2,      // a = position id of the tile's first row: consecutive int32
   kActGeneric = 3,   // a = record index << 32 | segment of the tile's first byte
 };

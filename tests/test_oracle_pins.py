@@ -98,6 +98,28 @@ def test_next_fit_hand_worked():
     assert plan.cu_seqlens.tolist() == g["cu_seqlens"]
 
 
+def test_quadratic_lpt_hand_worked():
+    g = gold("lpt_quadratic_two_ranks.json")
+    rank, load = O.lpt_ranks(g["Lp"], g["D"])
+    assert rank.tolist() == g["rank_linear"] and load.tolist() == g["load_linear"]
+    rank, load = O.lpt_ranks(g["Lp"], g["D"], quadratic=True)
+    assert rank.tolist() == g["rank_quadratic"] and load.tolist() == g["load_quadratic"]
+    plan = O.build_plan(g["Lp"], n_groups=1, dp=g["D"], sp=1, zigzag=0, pad_multiple=1,
+                        mb_token_budget=1 << 20, balance_policy=2)
+    assert plan.rank.tolist() == g["rank_quadratic"]
+    assert plan.rank_load.tolist() == g["token_load_quadratic"]   # reported in tokens
+
+
+def test_equal_mb_hand_worked():
+    g = gold("equal_mb_two_ranks.json")
+    for key, flag in (("plain", 0), ("equal", 1)):
+        plan = O.build_plan(g["L"], n_groups=1, dp=g["D"], sp=1, zigzag=0, pad_multiple=1,
+                            mb_token_budget=g["B"], equal_mb=flag)
+        assert plan.rank.tolist() == g["rank"] and plan.mb.tolist() == g["mb"]
+        for name, want in g[key].items():
+            assert getattr(plan, name).tolist() == want, (key, name)
+
+
 def test_replica_choice_hand_worked():
     g = gold("replica_choice.json")
     _, seq_shard, seq_row, _, seq_k = O.source_layout([3] * g["N"], g["G"], g["R"])
@@ -123,6 +145,58 @@ def test_lpt_against_brute_force_optimum():
         if N >= D:
             assert load.max() - load.min() <= max(Lp)
         assert load.max() <= sum(Lp) / D + (1 - 1 / D) * max(Lp) + 1e-9
+
+
+def test_quadratic_lpt_against_brute_force_optimum():
+    """The same list-scheduling guarantees, on the squared lengths."""
+    rng = np.random.default_rng(6)
+    for trial in range(60):
+        D = int(rng.integers(2, 4))
+        N = int(rng.integers(1, 9))
+        Lp = rng.integers(1, 40, size=N).tolist()
+        cost = [x * x for x in Lp]
+        rank, load = O.lpt_ranks(Lp, D, quadratic=True)
+        best = min(max(sum(cost[i] for i in range(N) if a[i] == d) for d in range(D))
+                   for a in itertools.product(range(D), repeat=N))
+        assert max(load) * 3 * D <= (4 * D - 1) * best, (Lp, D)
+        assert load.tolist() == [sum(cost[i] for i in range(N) if rank[i] == d) for d in range(D)]
+        if N >= D:
+            assert max(load) - min(load) <= max(cost)
+    # equal lengths: both costs give the round-robin deal
+    assert O.lpt_ranks([9] * 12, 4, quadratic=True)[0].tolist() == [i % 4 for i in range(12)]
+    # squares are exact beyond 2^53 (no floating point on the way)
+    big = [(1 << 21) - k for k in range(6)]
+    _, load = O.lpt_ranks(big, 2, quadratic=True)
+    assert sum(load) == sum(x * x for x in big)
+
+
+def test_equal_mb_only_appends_empty_micro_batches():
+    rng = np.random.default_rng(7)
+    for trial in range(40):
+        N, D, C = int(rng.integers(1, 40)), int(rng.integers(1, 7)), int(rng.integers(1, 4))
+        L = rng.integers(1, 300, size=N)
+        kw = dict(n_groups=1, dp=D, sp=C, zigzag=int(rng.integers(0, 2)), pad_multiple=1,
+                  mb_token_budget=int(rng.integers(700, 1500)),
+                  balance_policy=int(rng.integers(0, 3)))
+        a, b = O.build_plan(L, **kw), O.build_plan(L, equal_mb=1, **kw)
+        for name in ("rank", "slot", "mb", "dst_row", "seq_ids", "shard_rows", "n_seq",
+                     "seg_dst_row", "seg_src_row", "seg_n_real", "a2a_counts"):
+            assert np.array_equal(getattr(a, name), getattr(b, name)), name
+        most = int(a.n_mb.max())
+        assert b.n_mb.tolist() == [most] * D
+        pa = pb = ca = cb = 0
+        for r in range(D):
+            na, extra = int(a.n_mb[r]), most - int(a.n_mb[r])
+            assert b.mb_seq_start[pb:pb + na + 1].tolist() == a.mb_seq_start[pa:pa + na + 1].tolist()
+            assert b.mb_row_start[pb:pb + na + 1].tolist() == a.mb_row_start[pa:pa + na + 1].tolist()
+            assert b.mb_seq_start[pb + na + 1:pb + most + 1].tolist() == [int(a.n_seq[r])] * extra
+            assert b.mb_row_start[pb + na + 1:pb + most + 1].tolist() == \
+                [int(a.shard_rows[r * C])] * extra
+            la = int(a.n_seq[r]) + na
+            assert b.cu_seqlens[cb:cb + la].tolist() == a.cu_seqlens[ca:ca + la].tolist()
+            assert b.cu_seqlens[cb + la:cb + la + extra].tolist() == [0] * extra
+            pa, pb, ca, cb = pa + na + 1, pb + most + 1, ca + la, cb + la + extra
+        assert pb == len(b.mb_seq_start) and cb == len(b.cu_seqlens)
 
 
 def test_lpt_equal_lengths_is_round_robin():
@@ -437,7 +511,7 @@ def _mut_zigzag_not_mirrored(monkeypatch):
 
 
 def _mut_lpt_tie_to_higher_rank(monkeypatch):
-    def bad(Lp, D):
+    def bad(Lp, D, quadratic=False):
         order = sorted(range(len(Lp)), key=lambda i: (-int(Lp[i]), i))
         load, rank = [0] * D, [0] * len(Lp)
         for i in order:
@@ -449,7 +523,7 @@ def _mut_lpt_tie_to_higher_rank(monkeypatch):
 
 
 def _mut_lpt_shortest_first(monkeypatch):
-    def bad(Lp, D):
+    def bad(Lp, D, quadratic=False):
         order = sorted(range(len(Lp)), key=lambda i: (int(Lp[i]), i))
         load, rank = [0] * D, [0] * len(Lp)
         for i in order:
@@ -467,7 +541,8 @@ def _mut_pad_ignores_multiple(monkeypatch):
 
 def _mut_budget_strict(monkeypatch):
     real = O.pack_ranks
-    monkeypatch.setattr(O, "pack_ranks", lambda rank, Lp, loc, D, B: real(rank, Lp, loc, D, B - 1))
+    monkeypatch.setattr(O, "pack_ranks",
+                        lambda rank, Lp, loc, D, B, **kw: real(rank, Lp, loc, D, B - 1, **kw))
 
 
 def _mut_positions_restart_per_chunk(monkeypatch):
@@ -488,7 +563,27 @@ def _mut_replica_always_zero(monkeypatch):
     monkeypatch.setattr(O, "source_layout", bad)
 
 
-MUTANTS = [_mut_zigzag_not_mirrored, _mut_lpt_tie_to_higher_rank, _mut_lpt_shortest_first,
+def _mut_quadratic_cost_is_linear(monkeypatch):
+    real = O.lpt_ranks
+    monkeypatch.setattr(O, "lpt_ranks", lambda Lp, D, quadratic=False: real(Lp, D))
+
+
+def _mut_equal_mb_pads_to_most_plus_one(monkeypatch):
+    real = O.pack_ranks
+
+    def bad(rank, Lp, loc, D, B, equal_mb=False):
+        pk = real(rank, Lp, loc, D, B, equal_mb=equal_mb)
+        if equal_mb:
+            for r in range(D):
+                pk["n_mb"][r] += 1
+                pk["mb_seq_start"][r].append(pk["mb_seq_start"][r][-1])
+                pk["mb_row_start"][r].append(pk["mb_row_start"][r][-1])
+        return pk
+    monkeypatch.setattr(O, "pack_ranks", bad)
+
+
+MUTANTS = [_mut_quadratic_cost_is_linear, _mut_equal_mb_pads_to_most_plus_one,
+           _mut_zigzag_not_mirrored, _mut_lpt_tie_to_higher_rank, _mut_lpt_shortest_first,
            _mut_pad_ignores_multiple, _mut_budget_strict, _mut_positions_restart_per_chunk,
            _mut_replica_always_zero]
 
@@ -500,6 +595,8 @@ def _run_fixture_pins():
     test_zigzag_hand_worked_pad64()
     test_next_fit_hand_worked()
     test_replica_choice_hand_worked()
+    test_quadratic_lpt_hand_worked()
+    test_equal_mb_hand_worked()
     test_lpt_against_brute_force_optimum()
     test_lpt_equal_lengths_is_round_robin()
     for case in small_cases():
