@@ -295,8 +295,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--two-pass", action="store_true",
                     help="gather into one canonical buffer, then scatter (single-controller pattern)")
-    ap.add_argument("--balance-policy", type=int, default=0, choices=[0, 1],
-                    help="0 longest-first list scheduling (default), 1 sorted snake deal")
+    ap.add_argument("--balance-policy", type=int, default=0, choices=[0, 1, 2],
+                    help="0 longest-first list scheduling (default), 1 sorted snake deal, "
+                         "2 list scheduling on squared padded lengths")
     ap.add_argument("--inverse", action="store_true",
                     help="time the reverse direction (earl_dispatch_inverse) instead of earl_dispatch")
     ap.add_argument("--reference-copy", action="store_true",

@@ -82,11 +82,20 @@ typedef struct {
  *   balance_policy    0 = longest-first list scheduling on padded lengths (ties: lower index, lower
  *                     rank); 1 = sorted snake deal: longest first in rounds of dp, left to right in
  *                     even rounds and right to left in odd ones (no serial chain; equal sequence
- *                     counts per rank, loads within one padded length of each other).
+ *                     counts per rank, loads within one padded length of each other);
+ *                     2 = as 0, but a rank's load grows by the SQUARE of the padded length (equal
+ *                     causal-attention work instead of equal token counts); padded lengths must
+ *                     not exceed 2^21 then (EARL_INVALID_ARG, reported like a bad length).
+ *                     rank_load in the summary is in padded tokens under every policy.
+ *   equal_mb          1: every DP rank reports n_mb_max micro-batches; ranks that need fewer get
+ *                     empty ones appended (no sequence, no row; their entries in mb_seq_start /
+ *                     mb_row_start repeat the rank's totals, their cu_seqlens array is the single
+ *                     entry 0), so that all ranks run the same number of steps.  Needs
+ *                     dp * (n_seqs + 1) <= 2^27.  0: each rank reports what next-fit produced.
  *   mb_token_budget   a micro-batch holds whole sequences whose padded lengths sum to at most this.
  */
 typedef struct {
-  int32_t dp, sp, zigzag, pad_multiple, balance_policy;
+  int32_t dp, sp, zigzag, pad_multiple, balance_policy, equal_mb;
   int64_t mb_token_budget;
 } earl_dst_layout;
 

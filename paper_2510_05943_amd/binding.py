@@ -41,7 +41,7 @@ class _SrcLayout(C.Structure):
 class _DstLayout(C.Structure):
     _fields_ = [("dp", C.c_int32), ("sp", C.c_int32), ("zigzag", C.c_int32),
                 ("pad_multiple", C.c_int32), ("balance_policy", C.c_int32),
-                ("mb_token_budget", C.c_int64)]
+                ("equal_mb", C.c_int32), ("mb_token_budget", C.c_int64)]
 
 
 class _Field(C.Structure):
@@ -144,10 +144,11 @@ class DstLayout:
     pad_multiple: int = 1
     mb_token_budget: int = 1 << 40
     balance_policy: int = 0
+    equal_mb: int = 0
 
     def c(self) -> _DstLayout:
         return _DstLayout(self.dp, self.sp, self.zigzag, self.pad_multiple, self.balance_policy,
-                          self.mb_token_budget)
+                          self.equal_mb, self.mb_token_budget)
 
 
 @dataclasses.dataclass

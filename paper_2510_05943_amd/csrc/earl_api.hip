@@ -59,7 +59,7 @@ struct Layout {
 };
 
 struct Dims {
-  int32_t N, G, R, S, D, C, K, halves, P, zigzag, n_pow2, policy;
+  int32_t N, G, R, S, D, C, K, halves, P, zigzag, n_pow2, policy, equal_mb;
   int64_t B, n_seg;
 };
 
@@ -93,9 +93,12 @@ Layout make_layout(const Dims& d) {
   l.seq_ids = take(4 * N);
   l.next_start = take(4 * N);
   l.mb_tmp = take(4 * (N + D));
-  l.mb_seq_start = take(4 * (N + D));
-  l.mb_row_start = take(8 * (N + D));
-  l.cu_seqlens = take(4 * 2 * N);
+  // micro-batch tables: sum over ranks of (n_mb + 1) entries, cu_seqlens: N + sum of n_mb; a
+  // rank has at most as many micro-batches as sequences, with equal_mb at most N each
+  const size_t mb_entries = d.equal_mb ? D * (N + 1) : N + D;
+  l.mb_seq_start = take(4 * mb_entries);
+  l.mb_row_start = take(8 * mb_entries);
+  l.cu_seqlens = take(4 * (N + mb_entries));
   l.rank_seq_base = take(4 * (D + 1));
   l.rank_mbt_base = take(4 * (D + 1));
   l.rank_cu_base = take(4 * (D + 1));
@@ -126,8 +129,12 @@ int32_t check_layouts(int32_t n_seqs, const earl_src_layout* src, const earl_dst
   if (dst->sp < 1 || dst->sp > EARL_MAX_SP) return fail(EARL_INVALID_ARG, "sp out of range");
   if (dst->zigzag != 0 && dst->zigzag != 1) return fail(EARL_INVALID_ARG, "zigzag must be 0 or 1");
   if (dst->pad_multiple < 1) return fail(EARL_INVALID_ARG, "pad_multiple must be >= 1");
-  if (dst->balance_policy != 0 && dst->balance_policy != 1)
+  if (dst->balance_policy < 0 || dst->balance_policy > 2)
     return fail(EARL_INVALID_ARG, "unknown balance_policy");
+  if (dst->equal_mb != 0 && dst->equal_mb != 1)
+    return fail(EARL_INVALID_ARG, "equal_mb must be 0 or 1");
+  if (dst->equal_mb && (int64_t)dst->dp * ((int64_t)n_seqs + 1) > (int64_t)1 << 27)
+    return fail(EARL_INVALID_ARG, "equal_mb: dp * (n_seqs + 1) exceeds 2^27");
   if (dst->mb_token_budget < 1) return fail(EARL_INVALID_ARG, "mb_token_budget must be >= 1");
   Dims d{};
   d.N = n_seqs;
@@ -142,6 +149,7 @@ int32_t check_layouts(int32_t n_seqs, const earl_src_layout* src, const earl_dst
   d.P = dst->pad_multiple;
   d.B = dst->mb_token_budget;
   d.policy = dst->balance_policy;
+  d.equal_mb = dst->equal_mb;
   d.n_seg = (int64_t)d.N * d.K;
   if (d.n_seg > (int64_t)1 << 27) return fail(EARL_INVALID_ARG, "n_seqs * chunks exceeds 2^27");
   if ((int64_t)d.S * d.D * d.C > (int64_t)1 << 24)
@@ -375,7 +383,7 @@ int32_t earl_plan_build(const int32_t* lengths_dev, int32_t n_seqs, const earl_s
   v.seq_group_in = src->seq_group;
   v.seq_row_in = src->seq_row;
   v.N = d.N; v.G = d.G; v.R = d.R; v.S = d.S; v.D = d.D; v.C = d.C; v.K = d.K;
-  v.halves = d.halves; v.P = d.P; v.n_pow2 = d.n_pow2; v.B = d.B; v.policy = d.policy;
+  v.halves = d.halves; v.P = d.P; v.n_pow2 = d.n_pow2; v.B = d.B; v.policy = d.policy; v.equal_mb = d.equal_mb;
   v.hdr = reinterpret_cast<PlanHeader*>(w + l.hdr);
   v.shard_rows = reinterpret_cast<int64_t*>(w + l.shard_rows);
   v.src_rows_needed = reinterpret_cast<int64_t*>(w + l.src_rows_needed);

@@ -15,6 +15,7 @@ constexpr int kMaxDp = 1024;         // one DP rank per plan thread
 
 // Labels (source groups, DP ranks) whose per-wave scan tables fit the workgroup's LDS; larger
 // label counts use the same code on tables in the workspace.
+constexpr int kMaxQuadraticLp = 1 << 21;   // largest padded length under balance_policy 2
 constexpr int kLdsLabels = 256;
 // Sort keys kept in LDS up to this many (power of two); more go to the workspace.
 constexpr int kLdsSortKeys = 8192;
@@ -66,7 +67,9 @@ struct PlanDev {
   const int64_t* seq_row_in;     // may be null
   int32_t N, G, R, S, D, C, K, halves, P;
   int32_t n_pow2;                // N rounded up to a power of two (sort size)
-  int32_t policy;                // 0 longest-first list scheduling, 1 sorted snake deal
+  int32_t policy;                // 0 longest-first list scheduling, 1 sorted snake deal,
+                                 // 2 list scheduling on squared padded lengths
+  int32_t equal_mb;              // 1: every rank reports the largest micro-batch count
   int64_t B;
   // summary block (contiguous, copied to the host in one piece)
   PlanHeader* hdr;

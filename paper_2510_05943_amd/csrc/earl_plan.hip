@@ -356,7 +356,10 @@ __device__ void lpt_one_per_lane(const PlanDev& p, const uint64_t* keys) {
 
 // Any D <= 1024: each lane owns the loads (in LDS) of a block of consecutive ranks, so a lower
 // lane always means lower ranks and ties resolve to the lowest rank by taking the first lane
-// that holds the minimum.
+// that holds the minimum.  kQuadratic: a rank's load grows by the square of the padded length
+// (padded lengths up to 2^21, so a load stays below 2^62); the distance of a load from the
+// smallest one then needs 64 bits and is reduced in two 32-bit rounds, high words first.
+template <bool kQuadratic>
 __device__ void lpt_blocks(const PlanDev& p, const uint64_t* keys, int64_t* lds_load) {
   const int lane = lane_id();
   const int D = p.D, N = p.N;
@@ -378,13 +381,25 @@ __device__ void lpt_blocks(const PlanDev& p, const uint64_t* keys, int64_t* lds_
     const int cnt = min(kWave, N - start);
     for (int s = 0; s < cnt; ++s) {
       const int32_t lp_s = __builtin_amdgcn_readlane(lp, s);
-      const uint32_t rel = owner ? (uint32_t)(best - base) : 0xffffffffu;
-      const uint32_t mn = wave_min_low<6>(rel);
-      const int wl = __builtin_ctzll(__ballot(rel == mn));
+      int wl;
+      int64_t mn;
+      if (kQuadratic) {
+        const uint64_t rel = owner ? (uint64_t)(best - base) : ~0ull;
+        const uint32_t hi = (uint32_t)(rel >> 32), lo = (uint32_t)rel;
+        const uint32_t hi_mn = wave_min_low<6>(hi);
+        const uint32_t lo_mn = wave_min_low<6>(hi == hi_mn ? lo : 0xffffffffu);
+        wl = __builtin_ctzll(__ballot(hi == hi_mn && lo == lo_mn));
+        mn = (int64_t)(((uint64_t)hi_mn << 32) | lo_mn);
+      } else {
+        const uint32_t rel = owner ? (uint32_t)(best - base) : 0xffffffffu;
+        const uint32_t rel_mn = wave_min_low<6>(rel);
+        wl = __builtin_ctzll(__ballot(rel == rel_mn));
+        mn = rel_mn;
+      }
       const int r = __builtin_amdgcn_readlane(best_r, wl);
       base += mn;
       if (lane == wl) {
-        lds_load[r] += lp_s;
+        lds_load[r] += kQuadratic ? (int64_t)lp_s * lp_s : (int64_t)lp_s;
         best = lds_load[r_lo];
         best_r = r_lo;
         for (int q = r_lo + 1; q < r_hi; ++q) {
@@ -401,8 +416,10 @@ __device__ void lpt_blocks(const PlanDev& p, const uint64_t* keys, int64_t* lds_
 __device__ void lpt_wave0(const PlanDev& p, const uint64_t* keys, int64_t* lds_load) {
   const int D = p.D;
   const int64_t max_lp = 0x7fffffffll - (int64_t)(keys[0] >> 32);   // keys are sorted
-  if (D > kWave) {
-    lpt_blocks(p, keys, lds_load);
+  if (p.policy == 2) {
+    lpt_blocks<true>(p, keys, lds_load);
+  } else if (D > kWave) {
+    lpt_blocks<false>(p, keys, lds_load);
   } else if (((int64_t)p.N * max_lp / D + max_lp) >= (1 << 26)) {
     // some load could reach 2^26: the packed word would overflow
     lpt_one_per_lane(p, keys);
@@ -473,6 +490,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const PlanDev p) {
     int64_t m = (int64_t)P * ((per + P - 1) / P);
     const bool exceeds = m * K > lp_cap;
     if (exceeds) m = 1;
+    if (p.policy == 2 && m * K > kMaxQuadraticLp) invalid = true;   // squared loads must fit
     p.seq_group[i] = (int32_t)g;
     p.m[i] = (int32_t)m;
     real_rows += L;
@@ -646,7 +664,10 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const PlanDev p) {
   int n_mb_max = 0;
   int64_t mb_table_len = 0, cu_len = 0;
   {
-    const int32_t nm = tid < D ? p.n_mb[tid] : 0;
+    const int32_t nm_own = tid < D ? p.n_mb[tid] : 0;
+    n_mb_max = (int)block_reduce_max(nm_own, bs);
+    // equal_mb: every rank gets the micro-batch count of the rank that has most
+    const int32_t nm = p.equal_mb && tid < D ? n_mb_max : nm_own;
     const int32_t ns = tid < D ? rank_cnt[tid] : 0;
     const int64_t ex1 = block_excl_scan(tid < D ? nm + 1 : 0, bs, &mb_table_len);
     const int64_t ex2 = block_excl_scan(tid < D ? nm + ns : 0, bs, &cu_len);
@@ -658,7 +679,6 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const PlanDev p) {
       p.rank_mbt_base[D] = (int32_t)mb_table_len;
       p.rank_cu_base[D] = (int32_t)cu_len;
     }
-    n_mb_max = (int)block_reduce_max(nm, bs);
   }
   __syncthreads();
   // compact the per-rank micro-batch tables
@@ -677,6 +697,19 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const PlanDev p) {
       p.mb_seq_start[o] = s;
       p.mb_row_start[o] = s < n ? row_packed[p.rank_seq_base[r] + s] : rank_rows[r];
     }
+  }
+  if (p.equal_mb) {
+    // the appended micro-batches are empty: they start at the rank's last sequence and last row
+    for (int x = tid; x < (int)mb_table_len; x += T) {
+      const int r = x / (n_mb_max + 1);
+      const int b = x - r * (n_mb_max + 1);
+      if (b > p.n_mb[r]) {
+        p.mb_seq_start[x] = rank_cnt[r];
+        p.mb_row_start[x] = rank_rows[r];
+      }
+    }
+    __syncthreads();
+    for (int r = tid; r < D; r += T) p.n_mb[r] = n_mb_max;
   }
   __syncthreads();
   // micro-batch of every sequence; cu_seqlens (local rows, restarting in every micro-batch)

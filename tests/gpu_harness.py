@@ -33,7 +33,8 @@ def guards_intact(whole: torch.Tensor) -> bool:
     return bool((whole[:CANARY] == POISON).all().item() and (whole[-CANARY:] == POISON).all().item())
 
 
-def layouts_of(w: synth.Workload, explicit_groups: bool, seq_row=None, balance_policy: int = 0):
+def layouts_of(w: synth.Workload, explicit_groups: bool, seq_row=None, balance_policy: int = 0,
+               equal_mb: int = 0):
     contiguous = (np.arange(w.n_seqs, dtype=np.int64) * w.n_groups) // max(w.n_seqs, 1)
     keep = []
     grp = None
@@ -45,13 +46,14 @@ def layouts_of(w: synth.Workload, explicit_groups: bool, seq_row=None, balance_p
         row = to_dev(np.asarray(seq_row, np.int64))
         keep.append(row)
     src = B.SrcLayout(w.n_groups, w.replication, grp, row)
-    dst = B.DstLayout(w.dp, w.sp, w.zigzag, w.pad_multiple, w.mb_token_budget, balance_policy)
+    dst = B.DstLayout(w.dp, w.sp, w.zigzag, w.pad_multiple, w.mb_token_budget, balance_policy,
+                      equal_mb)
     return src, dst, keep
 
 
 def build_plan(w: synth.Workload, explicit_groups: bool = False, seq_row=None, stream=None,
-               balance_policy: int = 0):
-    src, dst, keep = layouts_of(w, explicit_groups, seq_row, balance_policy)
+               balance_policy: int = 0, equal_mb: int = 0):
+    src, dst, keep = layouts_of(w, explicit_groups, seq_row, balance_policy, equal_mb)
     lengths = to_dev(w.lengths.astype(np.int32))
     ws = torch.empty(B.plan_workspace_bytes(w.n_seqs, src, dst), dtype=torch.uint8, device="cuda")
     plan = B.plan_build(lengths, w.n_seqs, src, dst, ws, stream=stream)

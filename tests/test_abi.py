@@ -50,7 +50,9 @@ def test_workspace_bytes_validation_and_growth():
         (64, src, B.DstLayout(dp=1, zigzag=2)),
         (64, src, B.DstLayout(dp=1, pad_multiple=0)),
         (64, src, B.DstLayout(dp=1, mb_token_budget=0)),
-        (64, src, B.DstLayout(dp=1, balance_policy=7)),
+        (64, src, B.DstLayout(dp=1, balance_policy=3)),
+        (64, src, B.DstLayout(dp=1, equal_mb=2)),
+        ((1 << 20), src, B.DstLayout(dp=1024, equal_mb=1)),
         (64, src, B.DstLayout(dp=1, balance_policy=-1)),
     ]
     for n, s, d in bad:

@@ -25,11 +25,11 @@ def H():
     return gpu_harness
 
 
-def oracle_plan(w, seq_row=None, balance_policy=0):
+def oracle_plan(w, seq_row=None, balance_policy=0, equal_mb=0):
     return O.build_plan(w.lengths, n_groups=w.n_groups, replication=w.replication,
                         seq_group=w.seq_group, seq_row=seq_row, dp=w.dp, sp=w.sp, zigzag=w.zigzag,
                         pad_multiple=w.pad_multiple, mb_token_budget=w.mb_token_budget,
-                        balance_policy=balance_policy)
+                        balance_policy=balance_policy, equal_mb=equal_mb)
 
 
 PLAN_KEYS = ("rank", "slot", "mb", "dst_row", "seq_shard", "seq_row", "seq_ids", "mb_seq_start",
@@ -286,6 +286,59 @@ def test_snake_deal_policy(H, name, scale):
     H.B.plan_destroy(plan)
 
 
+@pytest.mark.parametrize("name,scale", [("tiny", 1.0), ("mid", 1.0), ("agentic", 1.0), ("heavy", 1.0),
+                                        ("longctx", 1.0), ("mid", 0.02)])
+def test_quadratic_cost_policy_and_equal_micro_batch_counts(H, name, scale):
+    """balance_policy 2 (list scheduling on squared padded lengths) with equal_mb: plan parity on
+    every workload, dispatch parity (fields, position ids, cu_seqlens with the empty
+    micro-batches) on the two small ones."""
+    w = synth.make_workload(name, seed=6, scale=scale)
+    plan = H.build_plan(w, balance_policy=2, equal_mb=1)
+    oplan = oracle_plan(w, balance_policy=2, equal_mb=1)
+    res = H.plan_result(plan)
+    assert_plan_equal(res, oplan)
+    assert res["n_mb"].tolist() == [res["n_mb_max"]] * w.dp
+    if name in ("tiny", "mid") and scale == 1.0:
+        _, shards = H.host_sources(w, w.fields)
+        out = H.run_dispatch(w, plan, w.fields, src_host=shards)
+        assert_dispatch_equal(w, oplan, out, shards, w.fields)
+    H.B.plan_destroy(plan)
+
+
+def test_equal_micro_batch_counts_with_tight_budget_and_empty_ranks(H):
+    """Many micro-batches on some ranks, none on others (fewer sequences than ranks)."""
+    rng = np.random.default_rng(31)
+    for D, N, hi, budget in ((4, 200, 900, 1000), (7, 3, 50, 50), (64, 40, 300, 300),
+                             (130, 500, 64, 64), (2, 1, 5, 5)):
+        L = rng.integers(1, hi + 1, size=N)
+        w = synth.custom_workload(L, dp=D, sp=2, zigzag=1, mb_token_budget=budget + 3,
+                                  fields=(synth.F_ID,), seed=D)
+        for policy in (0, 1, 2):
+            plan = H.build_plan(w, balance_policy=policy, equal_mb=1)
+            oplan = oracle_plan(w, balance_policy=policy, equal_mb=1)
+            assert_plan_equal(H.plan_result(plan), oplan)
+            if policy == 0:
+                _, shards = H.host_sources(w, w.fields)
+                out = H.run_dispatch(w, plan, w.fields, src_host=shards)
+                assert_dispatch_equal(w, oplan, out, shards, w.fields)
+            H.B.plan_destroy(plan)
+
+
+def test_quadratic_policy_rejects_padded_lengths_beyond_its_limit(H):
+    w = synth.custom_workload([10, (1 << 21) + 1, 7], dp=2, sp=1, mb_token_budget=1 << 40)
+    plan = H.build_plan(w, balance_policy=2)
+    with pytest.raises(H.B.EarlError) as e:
+        H.B.plan_get_summary(plan)
+    assert e.value.status == H.B.EARL_INVALID_ARG
+    H.B.plan_destroy(plan)
+    # the limit itself is fine, and the squares are added exactly
+    w = synth.custom_workload([1 << 21, (1 << 21) - 1, (1 << 21) - 2, 5, 1 << 20], dp=2, sp=1,
+                              mb_token_budget=1 << 40)
+    plan = H.build_plan(w, balance_policy=2)
+    assert_plan_equal(H.plan_result(plan), oracle_plan(w, balance_policy=2))
+    H.B.plan_destroy(plan)
+
+
 SEQ_FIELDS = (synth.per_sequence_field("adv_f32", 4, 1, 0x7FC00000), synth.per_sequence_field("flag_u8", 1),
               synth.per_sequence_field("pair_u16", 2, 2, 0xBEEF), synth.per_sequence_field("ret_f64", 8, 1, 5),
               synth.per_sequence_field("half", 2, 1, 0x3C00), synth.F_ID)
@@ -357,7 +410,7 @@ def test_two_pass_gather_then_scatter_equals_direct_dispatch(H):
 def test_random_plans_sweep(H):
     """Plan-only parity on many random layouts: every size class of the rank-assignment code
     (1, 2, 4, 8, 16, 64 and more ranks), tight budgets with many micro-batches, replicated and
-    scattered source groups, both balancing policies."""
+    scattered source groups, all balancing policies, equal micro-batch counts on and off."""
     rng = np.random.default_rng(2024)
     for t in range(160):
         D = int(rng.choice([1, 2, 3, 4, 5, 8, 9, 16, 17, 33, 64, 65, 130]))
@@ -373,16 +426,20 @@ def test_random_plans_sweep(H):
         worst = K * P * (-(-(-(-int(L.max()) // K)) // P))
         B = int(worst * rng.choice([1, 1, 2, 7, 1000]))
         policy = int(rng.integers(0, 2))
+        if t % 4 == 1:
+            policy = 2
+        equal_mb = int(t % 5 < 2)
         w = synth.custom_workload(L, n_groups=G, replication=R, dp=D, sp=C, zigzag=z,
                                   pad_multiple=P, mb_token_budget=B, seed=t)
         if t % 3 == 0:
             w.seq_group = rng.integers(0, G, size=N).astype(np.int32)
-        plan = H.build_plan(w, balance_policy=policy)
+        plan = H.build_plan(w, balance_policy=policy, equal_mb=equal_mb)
         try:
-            assert_plan_equal(H.plan_result(plan), oracle_plan(w, balance_policy=policy))
+            assert_plan_equal(H.plan_result(plan),
+                              oracle_plan(w, balance_policy=policy, equal_mb=equal_mb))
         except AssertionError as err:
             raise AssertionError(f"case {t}: N={N} D={D} C={C} z={z} P={P} G={G} R={R} B={B} "
-                                 f"policy={policy}: {err}")
+                                 f"policy={policy} equal_mb={equal_mb}: {err}")
         H.B.plan_destroy(plan)
 
 
