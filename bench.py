@@ -163,6 +163,24 @@ def run_gpu(args, torch, B, synth):
     for p in plans:
         B.plan_destroy(p)
 
+    # the two halves on their own (outside the timed region): plan = build + summary (ends with
+    # the library's own stream synchronisation), dispatch = enqueue + stream synchronisation
+    plan_ms, dispatch_ms = [], []
+    for _ in range(10):
+        ta = time.perf_counter()
+        p = B.plan_build(lengths, w.n_seqs, src_l, dst_l, ws, stream=stream)
+        B.plan_get_summary(p)
+        tb = time.perf_counter()
+        if args.inverse:
+            B.dispatch_inverse(p, fields, workspace=scratch, stream=stream)
+        else:
+            B.dispatch(p, fields, position_ids=pos, cu_seqlens=cu, workspace=scratch, stream=stream)
+        torch.cuda.synchronize()
+        tc = time.perf_counter()
+        B.plan_destroy(p)
+        plan_ms.append((tb - ta) * 1e3)
+        dispatch_ms.append((tc - tb) * 1e3)
+
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     kern_ms = [hip.elapsed_ms(a, b) for a, b in events]
     for a, b in events:
@@ -173,7 +191,8 @@ def run_gpu(args, torch, B, synth):
     traffic = None if (args.inverse or args.balance_policy) else MEASURED_TRAFFIC.get(kernel_source_hash(), {}).get(args.workload)
     return dict(w=w, sm=sm, ms_per_step=ms_per_step, kern_avg_ms=kern_avg_ms,
                 kern_min_ms=float(np.min(kern_ms)), achieved=achieved, algo_bytes=algo_bytes,
-                traffic=traffic, stage_s=stage_s, row_bytes=row_bytes)
+                traffic=traffic, stage_s=stage_s, row_bytes=row_bytes,
+                plan_ms=float(np.median(plan_ms)), dispatch_ms=float(np.median(dispatch_ms)))
 
 
 def run_gpu_two_pass(args, torch, B, synth):
@@ -349,6 +368,10 @@ def main() -> int:
                      "kernel_ms_avg": r["kern_avg_ms"], "kernel_ms_min": r["kern_min_ms"]},
         "input_staging_s": r["stage_s"],
     }
+    if "plan_ms" in r:
+        # the two calls on their own, each ending with a stream synchronisation (medians of 10)
+        line["plan_ms"] = r["plan_ms"]
+        line["dispatch_ms"] = r["dispatch_ms"]
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = run_cpu_baseline(args, synth)
     print(json.dumps(line))

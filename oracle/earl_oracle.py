@@ -443,6 +443,30 @@ def dispatch_field(plan: Plan, src_bufs: Sequence, scalar_dtype, width: int,
             for q in range(plan.D * plan.C)]
 
 
+def nonzero_counts(plan: Plan, src_bufs: Sequence, width: int = 1) -> np.ndarray:
+    """A consumer of the dispatched field computed on the way: counts[q][b] = how many scalars
+    of the REAL rows of destination shard q that lie in micro-batch b of its data-parallel rank
+    are non-zero, as int64[D*C][max n_mb] (zero where a rank has fewer micro-batches).  For a
+    0/1 response mask this is the number of loss tokens every (shard, micro-batch) holds, the
+    denominator of a token-mean loss.  Padding rows never count, whatever the padding scalar.
+    """
+    C, K, D = plan.C, plan.K, plan.D
+    most = int(plan.n_mb.max()) if D else 0
+    out = np.zeros((D * C, most), np.int64)
+    for i in range(plan.N):
+        r = int(plan.rank[i])
+        mi, Li = int(plan.m[i]), int(plan.L[i])
+        src = src_bufs[int(plan.seq_shard[i])]
+        for kappa in range(K):
+            c, _ = chunk_to_sp(kappa, C, K)
+            p0 = kappa * mi
+            n_real = min(max(Li - p0, 0), mi)
+            s0 = int(plan.seq_row[i]) + p0
+            rows = np.asarray(src[s0:s0 + n_real]).reshape(n_real, width)
+            out[r * C + c, int(plan.mb[i])] += int(np.count_nonzero(rows))
+    return out
+
+
 def position_ids_shard(plan: Plan, q: int) -> np.ndarray:
     """Position ids of destination shard q: the logical position p of every row, padding rows
     included (they keep counting past L)."""

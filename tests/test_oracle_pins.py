@@ -248,6 +248,61 @@ def test_per_sequence_field_equals_the_repeated_per_token_field():
         assert all(np.array_equal(x, y) for x, y in zip(a, b))
 
 
+def test_nonzero_counts_against_the_dispatched_field():
+    """Two other routes to the same numbers: a plain count on the zero-padded dispatched shard,
+    micro-batch by micro-batch; and the sum over everything equals the non-zeros of the source
+    (every real token lands on exactly one shard and micro-batch)."""
+    rng = np.random.default_rng(11)
+    for trial in range(25):
+        N, D, C = int(rng.integers(1, 30)), int(rng.integers(1, 5)), int(rng.integers(1, 4))
+        L = rng.integers(1, 200, size=N)
+        G, R = int(rng.integers(1, 4)), int(rng.integers(1, 3))
+        plan = O.build_plan(L, n_groups=G, replication=R, dp=D, sp=C, zigzag=int(rng.integers(0, 2)),
+                            pad_multiple=int(rng.choice([1, 8])),
+                            mb_token_budget=int(rng.integers(700, 2000)),
+                            equal_mb=int(rng.integers(0, 2)))
+        width = int(rng.choice([1, 1, 3]))
+        # one buffer per group, identical over its replicas; sequences packed in index order
+        grp = (np.arange(N) * G) // N
+        bufs = []
+        for g in range(G):
+            rows = int(L[grp == g].sum())
+            buf = (rng.random((rows, width)) < 0.6).astype(np.uint8) * rng.integers(1, 255)
+            bufs.extend([buf.astype(np.uint8)] * R)
+        got = O.nonzero_counts(plan, bufs, width)
+        assert got.shape == (D * C, int(plan.n_mb.max()))
+        total = 0
+        tbl = 0
+        for r in range(D):
+            nmb = int(plan.n_mb[r])
+            starts = plan.mb_row_start[tbl:tbl + nmb + 1]
+            tbl += nmb + 1
+            for c in range(C):
+                q = r * C + c
+                # padded with zeros, the padding rows add nothing to a plain count of the shard
+                out = O.dispatch_field_shard(plan, q, bufs, np.uint8, width, 0)
+                for b in range(nmb):
+                    lo, hi = int(starts[b]), int(starts[b + 1])
+                    want = int(np.count_nonzero(out[lo:hi]))
+                    assert got[q, b] == want, (trial, q, b)
+                    total += want
+                assert not got[q, nmb:].any()
+        assert total == int(got.sum()) == sum(int(np.count_nonzero(bufs[g * R])) for g in range(G))
+
+
+def test_nonzero_counts_hand_worked():
+    # one rank, two SP ranks (contiguous halves), B=8: sequences of 4 and 4 fill micro-batch 0,
+    # the sequence of 6 is micro-batch 1.  mask rows: seq0 = 1,1,0,1  seq1 = 0,0,0,1  seq2 = 1,0,1,1,1,0
+    L = [4, 4, 6]
+    mask = np.array([1, 1, 0, 1, 0, 0, 0, 1, 1, 0, 1, 1, 1, 0], np.uint8).reshape(-1, 1)
+    plan = O.build_plan(L, n_groups=1, dp=1, sp=2, zigzag=0, pad_multiple=1, mb_token_budget=8)
+    assert plan.mb.tolist() == [0, 0, 1]
+    # SP rank 0 holds the first halves: (1,1),(0,0) | (1,0,1); SP rank 1 the second: (0,1),(0,1) | (1,1,0)
+    assert O.nonzero_counts(plan, [mask]).tolist() == [[2, 2], [2, 2]]
+    mask[4] = 7   # any non-zero value counts once
+    assert O.nonzero_counts(plan, [mask]).tolist() == [[3, 2], [2, 2]]
+
+
 def test_two_pass_gather_then_scatter_equals_direct_dispatch():
     """The single-controller pattern of Section 1 (everything gathered in one place, then
     redistributed) must produce the same training layout as the direct dispatch."""
