@@ -35,8 +35,8 @@ HBM_PEAK_GBPS = 8000.0
 # (scaled by a plain copy kernel of known size, see profiles/), keyed by the sha256 of the kernel
 # source the counters were taken on.  A changed kernel reports null until re-measured.
 MEASURED_TRAFFIC = {
-    "4c9f58824f9b885dff07364d978ee7283653c05d64b7209bf08b839421f0e5fc":
-        {"heavy": 52873342253, "longctx": 47518264371},
+    "0b43c721a42f886d55572768a5bbb7e5ae03b0045d30223b332e4b24f7ebe6c9":
+        {"heavy": 52881578938, "longctx": 47518071260},
 }
 
 WORKLOAD_NOTES = {

@@ -115,6 +115,15 @@ typedef struct {
  *                       reward, Section 4 of the paper); padding rows get pad_scalar.  Needs
  *                       scalar_bytes * width in {1, 2, 4, 8} and source buffers aligned to that;
  *                       not accepted by earl_dispatch_inverse.
+ *   nonzero_counts      NULL, or device int64[D*C][n_mb_max] (8-byte aligned): while the field is
+ *                       copied, entry [q][b] receives the number of non-zero scalars among the REAL
+ *                       rows of destination shard q that lie in micro-batch b of its DP rank
+ *                       (entries of micro-batches a rank does not have become 0; padding rows never
+ *                       count).  For a 0/1 loss mask this is the token count every (shard,
+ *                       micro-batch) normalises its loss by.  Needs a per-token field with
+ *                       scalar_bytes * width < 16; not accepted by earl_dispatch_inverse.  The
+ *                       array is cleared and filled on the stream by earl_dispatch.
+ *   nonzero_counts_capacity  entries the array holds; EARL_CAPACITY if fewer than D*C*n_mb_max.
  * Source and destination buffers must not overlap.
  */
 typedef struct {
@@ -126,6 +135,8 @@ typedef struct {
   const int64_t* dst_capacity_rows;
   const int64_t* src_capacity_rows;
   int32_t per_sequence;
+  int64_t* nonzero_counts;
+  int64_t nonzero_counts_capacity;
 } earl_field;
 
 typedef struct earl_plan earl_plan; /* host object owned by the library */
@@ -206,7 +217,8 @@ int32_t earl_plan_export_segments(earl_plan* plan, int32_t* src_shard, int64_t* 
  * Bytes of device scratch one earl_dispatch call with these fields needs: the call's parameter
  * block plus one 16-byte record per 4 KiB of destination (about 0.4 % of the bytes written).  The
  * size depends on the plan's shard sizes, so this call waits for the plan like
- * earl_plan_get_summary.  Only scalar_bytes and width of every field are read.
+ * earl_plan_get_summary.  Only scalar_bytes, width and nonzero_counts (null or not) of every field
+ * are read.
  */
 int32_t earl_dispatch_workspace_bytes(earl_plan* plan, const earl_field* fields, int32_t n_fields,
                                       int32_t with_position_ids, int32_t with_cu_seqlens,

@@ -49,7 +49,8 @@ class _Field(C.Structure):
                 ("src_shard_ptrs", C.POINTER(C.c_void_p)), ("dst_shard_ptrs", C.POINTER(C.c_void_p)),
                 ("dst_capacity_rows", C.POINTER(C.c_int64)),
                 ("src_capacity_rows", C.POINTER(C.c_int64)),
-                ("per_sequence", C.c_int32)]
+                ("per_sequence", C.c_int32), ("nonzero_counts", C.c_void_p),
+                ("nonzero_counts_capacity", C.c_int64)]
 
 
 class _Summary(C.Structure):
@@ -163,6 +164,7 @@ class Field:
     dst_shards: Sequence
     check_src_capacity: bool = True
     per_sequence: bool = False     # source holds one row per sequence, broadcast to its tokens
+    nonzero_counts: object = None  # int64 tensor [D*C * n_mb_max]: non-zero scalars per micro-batch
 
     def _rows(self, t) -> int:
         row_bytes = self.scalar_bytes * self.width
@@ -262,7 +264,8 @@ def _marshal_field(f: Field):
                   C.cast(src, C.POINTER(C.c_void_p)), C.cast(dst, C.POINTER(C.c_void_p)),
                   C.cast(cap, C.POINTER(C.c_int64)),
                   C.cast(scap, C.POINTER(C.c_int64)) if f.check_src_capacity else None,
-                  1 if f.per_sequence else 0)
+                  1 if f.per_sequence else 0, _ptr(f.nonzero_counts),
+                  0 if f.nonzero_counts is None else int(f.nonzero_counts.numel()))
     f._c = (desc, (src, dst, cap, scap))
     return f._c
 

@@ -42,7 +42,8 @@ size_t param_block_bytes(int n_fields, int n_src, int n_dst) {
   size_t b = align_up(sizeof(DispatchDev));
   b += align_up(sizeof(int64_t) * (n_recs + 1));
   b += align_up(sizeof(TileRec) * n_recs);
-  b += align_up(sizeof(void*) * (size_t)n_fields * ((size_t)n_src + n_dst));
+  // per field: S source pointers, D*C destination pointers, D*C counter rows
+  b += align_up(sizeof(void*) * (size_t)n_fields * ((size_t)n_src + 2 * (size_t)n_dst));
   return b;
 }
 
@@ -52,7 +53,7 @@ struct Layout {
   size_t seq_group, seq_shard, seq_k, seq_row, m, rank, slot, mb, dst_row;
   size_t seq_ids, next_start, mb_tmp, mb_seq_start, mb_row_start, cu_seqlens;
   size_t rank_seq_base, rank_mbt_base, rank_cu_base;
-  size_t segs, seg_dst_shard, seg_src_seq;
+  size_t segs, seg_dst_shard, seg_src_seq, seg_mb;
   size_t shard_seg_start, seg_real_prefix;
   size_t sort_keys, lab_sum, lab_cnt;
   size_t total;
@@ -105,6 +106,7 @@ Layout make_layout(const Dims& d) {
   l.segs = take(sizeof(SegRec) * NK);
   l.seg_dst_shard = take(4 * NK);
   l.seg_src_seq = take(4 * NK);
+  l.seg_mb = take(4 * NK);
   l.shard_seg_start = take(4 * (DC + 1));
   l.seg_real_prefix = take(8 * (NK + 1));
   l.sort_keys = take(8 * (size_t)d.n_pow2);
@@ -270,7 +272,7 @@ struct BlockBuilder {
     hd.recs_ofs = (uint32_t)off;
     off += align_up(sizeof(TileRec) * (size_t)n_recs);
     hd.ptrs_ofs = (uint32_t)off;
-    off += align_up(sizeof(void*) * (size_t)n_fields * ((size_t)n_src + n_dst));
+    off += align_up(sizeof(void*) * (size_t)n_fields * ((size_t)n_src + 2 * (size_t)n_dst));
     hd.total_bytes = (uint32_t)off;
     bytes.assign(off, 0);
     std::memcpy(bytes.data(), &hd, sizeof(hd));
@@ -302,6 +304,18 @@ int32_t check_field(const earl_plan* p, const earl_field& f, int idx, bool inver
     if (w != 1 && w != 2 && w != 4 && w != 8)
       return fail(EARL_INVALID_ARG, "field %d: a per-sequence field needs 1, 2, 4 or 8 row bytes", idx);
   }
+  if (f.nonzero_counts) {
+    if (inverse) return fail(EARL_INVALID_ARG, "field %d: nonzero_counts has no inverse", idx);
+    if (f.per_sequence || (int64_t)sb * f.width >= kVecBytes)
+      return fail(EARL_INVALID_ARG,
+                  "field %d: nonzero_counts needs a per-token field with rows under 16 bytes", idx);
+    if (reinterpret_cast<uintptr_t>(f.nonzero_counts) % 8)
+      return fail(EARL_INVALID_ARG, "field %d: nonzero_counts is misaligned", idx);
+    const int64_t entries = (int64_t)p->d.D * p->d.C * p->hdr.n_mb_max;
+    if (f.nonzero_counts_capacity < entries)
+      return fail(EARL_CAPACITY, "field %d: nonzero_counts holds %lld entries, %lld needed", idx,
+                  (long long)f.nonzero_counts_capacity, (long long)entries);
+  }
   const int64_t* need = summary_ptr<int64_t>(p, f.per_sequence ? p->l.src_seqs_needed
                                                                : p->l.src_rows_needed);
   const int n_dst = p->d.D * p->d.C;
@@ -332,6 +346,7 @@ CopyArgs copy_args(const earl_plan* p, const void* params_dev, int64_t n_tiles) 
   a.params = static_cast<const DispatchDev*>(params_dev);
   a.segs = p->dev.segs;
   a.seg_src_seq = p->dev.seg_src_seq;
+  a.seg_mb = p->dev.seg_mb;
   a.n_tiles = n_tiles;
   return a;
 }
@@ -413,6 +428,7 @@ int32_t earl_plan_build(const int32_t* lengths_dev, int32_t n_seqs, const earl_s
   v.segs = reinterpret_cast<SegRec*>(w + l.segs);
   v.seg_dst_shard = reinterpret_cast<int32_t*>(w + l.seg_dst_shard);
   v.seg_src_seq = reinterpret_cast<int32_t*>(w + l.seg_src_seq);
+  v.seg_mb = reinterpret_cast<int32_t*>(w + l.seg_mb);
   v.shard_seg_start = reinterpret_cast<int32_t*>(w + l.shard_seg_start);
   v.sort_keys = reinterpret_cast<uint64_t*>(w + l.sort_keys);
   v.lab_sum = reinterpret_cast<int64_t*>(w + l.lab_sum);
@@ -567,7 +583,9 @@ int32_t earl_dispatch_workspace_bytes(earl_plan* p, const earl_field* fields, in
     inverse_tiles += (p->hdr.total_real_rows * (int64_t)fields[f].scalar_bytes * fields[f].width +
                       kTileBytes - 1) / kTileBytes;
   if (inverse_tiles > tiles) tiles = inverse_tiles;
-  *out_bytes = param_block_bytes(F, p->d.S, p->d.D * p->d.C) + kTileCodeBytes * (size_t)tiles;
+  // one word per tile code on top (only the 1 KiB codes of counting fields use theirs)
+  *out_bytes = param_block_bytes(F, p->d.S, p->d.D * p->d.C) +
+               (kTileCodeBytes + sizeof(uint64_t)) * (size_t)tiles;
   return EARL_OK;
 }
 
@@ -606,6 +624,9 @@ int32_t earl_dispatch(earl_plan* p, const earl_field* fields, int32_t n_fields,
   const void** ptrs = b.ptrs();
   // pointer tables and one prototype record per field
   std::vector<TileRec> protos((size_t)F);
+  std::vector<uint32_t> counter_slot((size_t)F, kNoCounters);   // first counter row pointer
+  const int64_t n_mb_max = p->hdr.n_mb_max;
+  bool counting = false;
   uint32_t pi = 0;
   for (int f = 0; f < F; ++f) {
     TileRec& proto = protos[f];
@@ -621,6 +642,11 @@ int32_t earl_dispatch(earl_plan* p, const earl_field* fields, int32_t n_fields,
       proto.per_sequence = (int16_t)uf.per_sequence;
       for (int s = 0; s < S; ++s) ptrs[pi + s] = uf.src_shard_ptrs[s];
       for (int q = 0; q < n_dst; ++q) ptrs[pi + S + q] = uf.dst_shard_ptrs[q];
+      if (uf.nonzero_counts) {
+        counting = true;
+        counter_slot[f] = pi + S + n_dst;
+        for (int q = 0; q < n_dst; ++q) ptrs[pi + S + n_dst + q] = uf.nonzero_counts + q * n_mb_max;
+      }
     } else if (position_ids_shard_ptrs && f == n_fields) {
       proto.kind = kFieldPositionIds;
       proto.scalar_bytes = 4;
@@ -634,7 +660,7 @@ int32_t earl_dispatch(earl_plan* p, const earl_field* fields, int32_t n_fields,
       ptrs[pi + S] = cu_seqlens_dev;
     }
     proto.tile_shift = (int16_t)tile_shift_of(proto.row_bytes, proto.kind);
-    pi += S + n_dst;
+    pi += S + 2 * n_dst;
   }
   // records in launch order: the fields with 1 KiB tiles first
   int64_t tiles = 0, fine = 0;
@@ -649,6 +675,7 @@ int32_t earl_dispatch(earl_plan* p, const earl_field* fields, int32_t n_fields,
         r = proto;
         r.tile_first = tiles;
         r.dst = const_cast<void*>(ptrs[proto.dst_ptr_index + q]);
+        r.dst_ptr_index = counter_slot[f] == kNoCounters ? kNoCounters : counter_slot[f] + q;
         r.e_begin = p->seg_starts[q];
         r.e_end = p->seg_starts[q + 1];
         r.end_bytes = proto.kind == kFieldLinear
@@ -665,7 +692,8 @@ int32_t earl_dispatch(earl_plan* p, const earl_field* fields, int32_t n_fields,
     return fail(EARL_INVALID_ARG, "too many tiles for one launch");
   if (tiles == 0) return EARL_OK;
   const size_t codes_off = b.bytes.size();
-  const size_t need = codes_off + kTileCodeBytes * (size_t)tiles;
+  const size_t counter_words_off = codes_off + kTileCodeBytes * (size_t)tiles;
+  const size_t need = counter_words_off + (counting ? sizeof(uint64_t) * (size_t)fine : 0);
   if (!dispatch_ws_dev || reinterpret_cast<uintptr_t>(dispatch_ws_dev) % kAlign)
     return fail(EARL_INVALID_ARG, "dispatch scratch is null or not %zu-byte aligned", kAlign);
   if (dispatch_ws_bytes < need)
@@ -675,6 +703,13 @@ int32_t earl_dispatch(earl_plan* p, const earl_field* fields, int32_t n_fields,
   if (st != EARL_OK) return st;
   CopyArgs ca = copy_args(p, dispatch_ws_dev, tiles);
   ca.n_fine_tiles = fine;
+  if (counting) {
+    ca.tile_counter = reinterpret_cast<uint64_t*>(static_cast<unsigned char*>(dispatch_ws_dev) +
+                                                  counter_words_off);
+    for (int f = 0; f < n_fields; ++f)
+      if (fields[f].nonzero_counts)
+        launch_zero_counters(fields[f].nonzero_counts, n_mb_max * n_dst, stream);
+  }
   void* codes = static_cast<unsigned char*>(dispatch_ws_dev) + codes_off;
   launch_tile_codes(ca, codes, stream);
   if (p->ev_before) HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(p->ev_before), stream));

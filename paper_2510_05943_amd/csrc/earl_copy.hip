@@ -114,6 +114,28 @@ __device__ __forceinline__ uint64_t splat_scalar(uint64_t v, int w) {
   return v;
 }
 
+// Non-zero scalars (of 1 << sb_log2 bytes) among the 16 bytes of v.
+__device__ __forceinline__ int count_nonzero16(u32x4 v, int sb_log2) {
+  int n = 0;
+  if (sb_log2 == 3) {
+    n = ((v.x | v.y) != 0) + ((v.z | v.w) != 0);
+  } else if (sb_log2 == 2) {
+    n = (v.x != 0) + (v.y != 0) + (v.z != 0) + (v.w != 0);
+  } else {
+    // per scalar: the top bit of (low bits + all-ones-below-top) | value is set iff it is non-zero
+    const uint32_t low = sb_log2 == 1 ? 0x7fff7fffu : 0x7f7f7f7fu;
+    for (int k = 0; k < 4; ++k) {
+      const uint32_t x = v[k];
+      n += __builtin_popcount((((x & low) + low) | x) & ~low);
+    }
+  }
+  return n;
+}
+
+__device__ __forceinline__ void add_to_counter(int64_t* counter, int n) {
+  if (n) atomicAdd(reinterpret_cast<unsigned long long*>(counter), (unsigned long long)n);
+}
+
 // Tile codes.  `b` holds the destination pointer of the tile's first byte (16-byte aligned) with
 // the action in its low four bits; `a` depends on the action.
 enum TileAction : uint64_t {
@@ -121,6 +143,8 @@ enum TileAction : uint64_t {
   kActFill = 1,      // a = scalar replicated to 8 bytes: the whole tile repeats it
   kActIota = 2,      // a = position id of the tile's first row: consecutive int32
   kActGeneric = 3,   // a = record index << 32 | segment of the tile's first byte
+  kActCopyCount = 4, // as kActCopy for a 1 KiB tile of a counting field: tile_counter[tile] says
+                     // which counter receives the tile's number of non-zero scalars
 };
 struct TileCode {
   uint64_t a, b;
@@ -202,6 +226,13 @@ __global__ __launch_bounds__(kCodeThreads) void tile_code_kernel(const CopyArgs 
         } else {
           c.a = reinterpret_cast<uint64_t>(shard + r.src_row * w + (lo - s_lo));
           c.b = dst | kActCopy;
+          if (rec.dst_ptr_index != kNoCounters) {
+            // a counting field (always 1 KiB tiles): the whole tile belongs to one micro-batch
+            int64_t* row = static_cast<int64_t*>(const_cast<void*>(pv.ptrs[rec.dst_ptr_index]));
+            a.tile_counter[tile] = reinterpret_cast<uint64_t>(row + a.seg_mb[e0]) |
+                                   (uint64_t)(31 - __builtin_clz(rec.scalar_bytes));
+            c.b = dst | kActCopyCount;
+          }
         }
       } else if (lo >= s_real_hi && hi <= s_hi) {
         c.a = rec.pad_scalar;
@@ -219,6 +250,7 @@ struct TileInfo {
   uint64_t pad_scalar;
   const void* const* src_ptrs;
   const int32_t* seg_src_seq;   // non-null for a per-sequence field
+  int64_t* counters;            // non-null for a counting field: this shard's counter row
   int32_t e_end;
   int32_t row_bytes;
   int32_t scalar_bytes;
@@ -236,7 +268,7 @@ __device__ __forceinline__ void seek(const SegRec* segs, const TileInfo& t, int6
 
 // A tile that is not one plain copy / fill / iota: every lane places its own 16-byte vector.
 // `tile` is the tile's code index, `vec0` the first 16-byte vector of the tile this workgroup owns.
-__device__ __noinline__ void generic_tile(const CopyArgs a, const TileCode c, const int64_t tile,
+__device__ __forceinline__ void generic_tile(const CopyArgs a, const TileCode c, const int64_t tile,
                                           const uint32_t vec0) {
   const ParamView pv = view_params(a.params);
   const TileRec rec = pv.recs[(uint32_t)(c.a >> 32)];
@@ -263,6 +295,9 @@ __device__ __noinline__ void generic_tile(const CopyArgs a, const TileCode c, co
   t.pad_scalar = rec.pad_scalar;
   t.src_ptrs = rec.kind == kFieldPositionIds ? nullptr : pv.ptrs + rec.src_ptr_index;
   t.seg_src_seq = rec.per_sequence ? a.seg_src_seq : nullptr;
+  t.counters = rec.kind == kFieldCopy && rec.dst_ptr_index != kNoCounters
+                   ? static_cast<int64_t*>(const_cast<void*>(pv.ptrs[rec.dst_ptr_index]))
+                   : nullptr;
   t.e_end = rec.e_end;
   t.row_bytes = rec.row_bytes;
   t.scalar_bytes = rec.scalar_bytes;
@@ -276,7 +311,11 @@ __device__ __noinline__ void generic_tile(const CopyArgs a, const TileCode c, co
         const uint64_t v = splat_scalar(load_scalar(sc.src, rec.row_bytes), rec.row_bytes);
         store16(dst + o, u32x4{(uint32_t)v, (uint32_t)(v >> 32), (uint32_t)v, (uint32_t)(v >> 32)});
       } else {
-        store16(dst + o, load16(sc.src + (o - sc.lo)));
+        const u32x4 v = load16(sc.src + (o - sc.lo));
+        store16(dst + o, v);
+        if (t.counters)
+          add_to_counter(t.counters + a.seg_mb[sc.e],
+                         count_nonzero16(v, 31 - __builtin_clz(rec.scalar_bytes)));
       }
       return;
     }
@@ -299,11 +338,31 @@ __device__ __noinline__ void generic_tile(const CopyArgs a, const TileCode c, co
     } else if (b < sc.real_hi) {
       // a per-sequence row is at most 8 bytes: byte (b - lo) mod w of it
       const int64_t off = t.seg_src_seq ? (b - sc.lo) % t.row_bytes : (b - sc.lo);
-      store_scalar(dst + b, load_scalar(sc.src + off, sb), sb);
+      const uint64_t v = load_scalar(sc.src + off, sb);
+      store_scalar(dst + b, v, sb);
+      if (t.counters) add_to_counter(t.counters + a.seg_mb[sc.e], v != 0);
     } else {
       store_scalar(dst + b, t.pad_scalar, sb);
     }
   }
+}
+
+// A plain-copy tile (1 KiB, one workgroup) of a counting field: copy, count the non-zero scalars
+// of the whole tile with a wavefront reduction, one atomic add.
+__device__ __forceinline__ void counting_copy_tile(const CopyArgs a, const TileCode c, const int64_t tile) {
+  const uint64_t word = a.tile_counter[tile];
+  const uint32_t lane = threadIdx.x;
+  const u32x4 v = load16(reinterpret_cast<const u8*>(c.a) + lane * kVecBytes);
+  store16(reinterpret_cast<u8*>(c.b & ~(uint64_t)15) + lane * kVecBytes, v);
+  int n = count_nonzero16(v, (int)(word & 7u));
+  for (int d = kCopyThreads / 2; d > 0; d >>= 1) n += __shfl_xor(n, d);
+  if (lane == 0) add_to_counter(reinterpret_cast<int64_t*>(word & ~(uint64_t)7), n);
+}
+
+__device__ __noinline__ void rare_tile(const CopyArgs a, const TileCode c, const int64_t tile,
+                                       const uint32_t vec0) {
+  if ((c.b & 15u) == kActCopyCount) counting_copy_tile(a, c, tile);
+  else generic_tile(a, c, tile, vec0);
 }
 
 // Pass 2: one-wavefront workgroups, one 16-byte vector per lane: one workgroup per 1 KiB tile
@@ -323,16 +382,24 @@ __global__ __launch_bounds__(kCopyThreads) void relayout_kernel(const CopyArgs a
   const uint64_t act = c.b & 15u;
   const uint32_t v = vec0 + threadIdx.x;   // vector in the tile
   u8* dst = reinterpret_cast<u8*>(c.b & ~(uint64_t)15) + v * kVecBytes;
-  if (act == kActCopy) {
+  // the plain copy first and on its own: nearly every workgroup of a wide field takes it
+  if (__builtin_expect(act == kActCopy, 1)) {
     store16(dst, load16(reinterpret_cast<const u8*>(c.a) + v * kVecBytes));
-  } else if (act == kActFill) {
+    return;
+  }
+  if (act == kActFill) {
     store16(dst, u32x4{(uint32_t)c.a, (uint32_t)(c.a >> 32), (uint32_t)c.a, (uint32_t)(c.a >> 32)});
   } else if (act == kActIota) {
     const uint32_t p0 = (uint32_t)c.a + v * 4;
     store16(dst, u32x4{p0, p0 + 1, p0 + 2, p0 + 3});
   } else {
-    generic_tile(a, c, tile, vec0);
+    rare_tile(a, c, tile, vec0);
   }
+}
+
+__global__ void zero_i64_kernel(int64_t* p, int64_t n) {
+  const int64_t x = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (x < n) p[x] = 0;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -483,6 +550,12 @@ void launch_copy(const CopyArgs& a, const void* tile_codes, hipStream_t stream) 
   const int64_t grid = a.n_fine_tiles + (a.n_tiles - a.n_fine_tiles) * kSubTiles;
   hipLaunchKernelGGL(relayout_kernel, dim3((unsigned)grid), dim3(kCopyThreads), 0, stream, a,
                      static_cast<const TileCode*>(tile_codes));
+}
+
+void launch_zero_counters(int64_t* counters, int64_t n, hipStream_t stream) {
+  if (n <= 0) return;
+  hipLaunchKernelGGL(zero_i64_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream,
+                     counters, n);
 }
 
 void launch_real_prefix(const SegRec* segs, int64_t* prefix, int n_seg, hipStream_t stream) {

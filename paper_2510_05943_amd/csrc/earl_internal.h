@@ -104,6 +104,7 @@ struct PlanDev {
   SegRec* segs;                  // [N*K]
   int32_t* seg_dst_shard;        // [N*K]
   int32_t* seg_src_seq;          // [N*K] seq_k of the segment's sequence
+  int32_t* seg_mb;               // [N*K] micro-batch (within its rank) of the segment's sequence
   int32_t* shard_seg_start;      // [D*C+1]
   // scratch
   uint64_t* sort_keys;           // [n_pow2]; reused as int64 row offsets in packed order
@@ -116,6 +117,8 @@ enum FieldKind : int32_t { kFieldCopy = 0, kFieldPositionIds = 1, kFieldLinear =
 
 // One (field, destination shard) pair of a dispatch call, or one field of an inverse call:
 // everything a workgroup needs besides the segment table, in one 64-byte record.
+constexpr uint32_t kNoCounters = 0xffffffffu;
+
 struct TileRec {
   int64_t tile_first;       // first tile of this record in the launch
   int64_t end_bytes;        // bytes of this destination shard (kFieldLinear: bytes to copy)
@@ -126,7 +129,8 @@ struct TileRec {
   int32_t scalar_bytes;
   int32_t kind;
   uint32_t src_ptr_index;   // first of the field's S source pointers in the pointer table
-  uint32_t dst_ptr_index;   // first of the field's D*C destination pointers (inverse only)
+  uint32_t dst_ptr_index;   // inverse: first of the field's D*C destination pointers; forward:
+                            // pointer-table slot of this shard's counter row, or kNoCounters
   int16_t per_sequence;     // source holds one row per sequence, broadcast to its tokens
   int16_t tile_shift;       // log2 of the bytes one tile code of this record describes
 };
@@ -151,6 +155,10 @@ struct CopyArgs {
   // Forward direction: the first n_fine_tiles codes describe 1 KiB each (one workgroup per code),
   // the others 4 KiB (kSubTiles workgroups per code).
   int64_t n_fine_tiles;
+  // Non-zero counting (forward, fields that ask for it): micro-batch of every segment, and one
+  // word per 1 KiB tile code: the counter a plain-copy tile adds to | log2(scalar bytes).
+  const int32_t* seg_mb;
+  uint64_t* tile_counter;
 };
 
 void launch_plan(const PlanDev& p, hipStream_t stream);
@@ -159,6 +167,7 @@ constexpr size_t kTileCodeBytes = 16;
 void launch_tile_codes(const CopyArgs& a, void* tile_codes, hipStream_t stream);
 void launch_copy(const CopyArgs& a, const void* tile_codes, hipStream_t stream);
 // seg_real_prefix[e] = real rows of the segments before e (n_seg+1 entries)
+void launch_zero_counters(int64_t* counters, int64_t n, hipStream_t stream);
 void launch_real_prefix(const SegRec* segs, int64_t* prefix, int n_seg, hipStream_t stream);
 void launch_copy_inverse(const CopyArgs& a, const int64_t* seg_real_prefix,
                          const int32_t* seg_dst_shard, int n_seg, void* tile_codes,

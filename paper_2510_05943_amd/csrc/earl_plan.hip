@@ -752,12 +752,14 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const PlanDev p) {
     for (int x = tid; x < n_pairs; x += T) s_a2a[x] = 0;
     __syncthreads();
   }
+  __syncthreads();   // mb[] of every sequence is complete
   for (int pos = tid; pos < N; pos += T) {
     const int i = p.seq_ids[pos];
     const int r = p.rank[i];
     const int base = p.rank_seq_base[r];
     const int n = rank_cnt[r];
     const int32_t mi = p.m[i];
+    const int32_t mb_i = p.mb[i];
     const int64_t len = p.lengths[i];
     const int s = p.seq_shard[i];
     const int64_t src_row = p.seq_row[i];
@@ -781,6 +783,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const PlanDev p) {
         p.segs[e0 + h] = rec;
         p.seg_dst_shard[e0 + h] = r * C + c;
         p.seg_src_seq[e0 + h] = k_in_group;
+        p.seg_mb[e0 + h] = mb_i;
         real_rows += n_real;
       }
       if (real_rows > 0) {

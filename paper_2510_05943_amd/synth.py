@@ -175,6 +175,13 @@ class Workload:
         elif field.kind == "bytes":
             out = rng.integers(0, 256, size=(rows, field.row_bytes),
                                dtype=np.uint8).view(field.np_dtype)
+        elif field.kind == "sparse":
+            # random scalars, about half of them zero, some with a single non-zero byte
+            out = rng.integers(0, 256, size=(rows, field.row_bytes), dtype=np.uint8)
+            keep_byte = rng.random((rows, field.row_bytes)) < 0.5
+            out = np.where(keep_byte, out, 0).astype(np.uint8).view(field.np_dtype)
+            out = np.where(rng.random((rows, field.width)) < 0.5, out.reshape(rows, field.width), 0)
+            out = out.astype(field.np_dtype)
         else:
             raise ValueError(field.kind)
         out = np.ascontiguousarray(out.reshape(rows, field.width))
@@ -299,6 +306,11 @@ def custom_workload(lengths: Sequence[int], *, n_groups: int = 1, replication: i
 def per_sequence_field(name: str, scalar_bytes: int, width: int = 1, pad_scalar: int = 0) -> FieldSpec:
     """One random row per SEQUENCE (a sequence-level reward or advantage), to be broadcast."""
     return FieldSpec(name, scalar_bytes, width, pad_scalar, "seq_value", per_sequence=True)
+
+
+def sparse_field(name: str, scalar_bytes: int, width: int = 1, pad_scalar: int = 0) -> FieldSpec:
+    """Random scalars of which about half are zero (what a non-zero count can be tested on)."""
+    return FieldSpec(name, scalar_bytes, width, pad_scalar, "sparse")
 
 
 def bytes_field(name: str, scalar_bytes: int, width: int, pad_scalar: int = 0) -> FieldSpec:

@@ -71,12 +71,15 @@ def plan_result(plan) -> Dict:
 def run_dispatch(w: synth.Workload, plan, fields: Sequence[synth.FieldSpec],
                  src_host: Optional[Dict[str, List[np.ndarray]]] = None,
                  src_dev: Optional[Dict[str, List[torch.Tensor]]] = None,
-                 want_position_ids: bool = True, want_cu: bool = True, stream=None) -> Dict:
-    """Runs earl_dispatch for `fields`.  src_host[name][s] / src_dev[name][s] = shard buffer s."""
+                 want_position_ids: bool = True, want_cu: bool = True, stream=None,
+                 count_nonzero: Sequence[str] = ()) -> Dict:
+    """Runs earl_dispatch for `fields`.  src_host[name][s] / src_dev[name][s] = shard buffer s.
+    Fields named in count_nonzero also get a (poisoned, guarded) non-zero counter array."""
     sm = B.plan_get_summary(plan)
     n_dst = sm["n_dst_shards"]
     shard_rows = sm["shard_rows"]
     bfields, wholes, inner, keep = [], {}, {}, []
+    counters = {}
     for f in fields:
         if src_dev is not None and f.name in src_dev:
             srcs = src_dev[f.name]
@@ -86,8 +89,12 @@ def run_dispatch(w: synth.Workload, plan, fields: Sequence[synth.FieldSpec],
         pairs = [guarded(int(shard_rows[q]) * f.row_bytes) for q in range(n_dst)]
         wholes[f.name] = [p[0] for p in pairs]
         inner[f.name] = [p[1] for p in pairs]
+        cnt = None
+        if f.name in count_nonzero:
+            counters[f.name] = guarded(8 * n_dst * sm["n_mb_max"])
+            cnt = counters[f.name][1].view(torch.int64)
         bfields.append(B.Field(f.scalar_bytes, f.width, f.pad_scalar, srcs, inner[f.name],
-                               per_sequence=f.per_sequence))
+                               per_sequence=f.per_sequence, nonzero_counts=cnt))
     pos_pairs = [guarded(int(shard_rows[q]) * 4) for q in range(n_dst)] if want_position_ids else None
     cu_pair = guarded(sm["cu_seqlens_len"] * 4) if want_cu else None
     ws_whole, ws = guarded(B.dispatch_workspace_bytes(plan, bfields, want_position_ids, want_cu))
@@ -102,6 +109,12 @@ def run_dispatch(w: synth.Workload, plan, fields: Sequence[synth.FieldSpec],
         assert all(guards_intact(x) for x in wholes[f.name]), f"{f.name}: write outside its shard"
         out["fields"][f.name] = [
             t.cpu().numpy().view(f.np_dtype).reshape(-1, f.width) for t in inner[f.name]]
+    if counters:
+        out["nonzero_counts"] = {}
+        for name, (whole, inside) in counters.items():
+            assert guards_intact(whole), f"{name}: write outside its counters"
+            out["nonzero_counts"][name] = inside.view(torch.int64).cpu().numpy().reshape(
+                n_dst, sm["n_mb_max"])
     if pos_pairs:
         assert all(guards_intact(p[0]) for p in pos_pairs)
         out["position_ids"] = [p[1].cpu().numpy().view(np.int32) for p in pos_pairs]

@@ -339,6 +339,74 @@ def test_quadratic_policy_rejects_padded_lengths_beyond_its_limit(H):
     H.B.plan_destroy(plan)
 
 
+COUNT_FIELDS = (synth.F_MASK, synth.sparse_field("s_u8x3", 1, 3, 0xAB), synth.sparse_field("s_u16", 2, 1, 0xFFFF),
+                synth.sparse_field("s_u16x5", 2, 5, 1), synth.sparse_field("s_u32", 4, 1, 7),
+                synth.sparse_field("s_u32x3", 4, 3, 0), synth.sparse_field("s_u64", 8, 1, 9), synth.F_ID)
+
+
+@pytest.mark.parametrize("case", small_cases()[1::3] + [
+    dict(L=np.random.default_rng(19).integers(1, 3000, size=400), G=4, R=2, D=4, C=2, z=1, P=8,
+         B=9000, grp=None, seed=98),
+    dict(L=np.random.default_rng(20).integers(1, 40, size=900), G=1, R=1, D=3, C=1, z=0, P=1,
+         B=64, grp=None, seed=97)], ids=lambda c: f"case{c['seed']}")
+def test_nonzero_counts_per_micro_batch(H, case):
+    """The counting consumer: every scalar size, widths that do not divide 16, non-zero padding
+    scalars (which must not count), many small micro-batches, equal_mb on and off."""
+    w = synth.custom_workload(case["L"], n_groups=case["G"], replication=case["R"],
+                              seq_group=case["grp"], dp=case["D"], sp=case["C"], zigzag=case["z"],
+                              pad_multiple=case["P"], mb_token_budget=case["B"], fields=COUNT_FIELDS,
+                              seed=case["seed"])
+    for equal_mb in (0, 1):
+        oplan = oracle_plan(w, equal_mb=equal_mb)
+        plan = H.build_plan(w, equal_mb=equal_mb)
+        _, shards = H.host_sources(w, w.fields)
+        names = [f.name for f in COUNT_FIELDS[:-1]]
+        out = H.run_dispatch(w, plan, w.fields, src_host=shards, count_nonzero=names)
+        assert_dispatch_equal(w, oplan, out, shards, w.fields)
+        for f in COUNT_FIELDS[:-1]:
+            want = O.nonzero_counts(oplan, shards[f.name], f.width)
+            assert np.array_equal(out["nonzero_counts"][f.name], want), f.name
+        H.B.plan_destroy(plan)
+
+
+def test_nonzero_counts_on_the_mid_workload_and_argument_checks(H):
+    import torch
+    w = synth.make_workload("mid", seed=3)
+    plan, oplan = H.build_plan(w), oracle_plan(w)
+    _, shards = H.host_sources(w, w.fields)
+    out = H.run_dispatch(w, plan, w.fields, src_host=shards, count_nonzero=["loss_mask"])
+    want = O.nonzero_counts(oplan, shards["loss_mask"])
+    assert np.array_equal(out["nonzero_counts"]["loss_mask"], want)
+    assert int(want.sum()) == sum(int(np.count_nonzero(a)) for a in shards["loss_mask"][::w.replication])
+    # a second call into the same array starts from zero again
+    sm = H.B.plan_get_summary(plan)
+    n_dst = sm["n_dst_shards"]
+    mask = [f for f in w.fields if f.name == "loss_mask"][0]
+    cnt = torch.full((n_dst * sm["n_mb_max"],), 123, dtype=torch.int64, device="cuda")
+    dsts = [torch.empty((int(r),), dtype=torch.uint8, device="cuda") for r in sm["shard_rows"]]
+    fld = H.B.Field(1, 1, 0, out["src_dev"]["loss_mask"], dsts, nonzero_counts=cnt)
+    ws = torch.empty(H.B.dispatch_workspace_bytes(plan, [fld], False, False), dtype=torch.uint8, device="cuda")
+    for _ in range(2):
+        H.B.dispatch(plan, [fld], workspace=ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(cnt.cpu().numpy().reshape(n_dst, -1), want)
+    # too small an array, a wide field, a per-sequence field, the inverse
+    small = H.B.Field(1, 1, 0, out["src_dev"]["loss_mask"], dsts, nonzero_counts=cnt[:-1])
+    with pytest.raises(H.B.EarlError) as e:
+        H.B.dispatch(plan, [small], workspace=ws)
+    assert e.value.status == H.B.EARL_CAPACITY
+    wide_dst = [torch.empty((int(r) * 16,), dtype=torch.uint8, device="cuda") for r in sm["shard_rows"]]
+    wide_src = [torch.zeros((int(r) * 16,), dtype=torch.uint8, device="cuda") for r in sm["src_rows_needed"]]
+    wide = H.B.Field(4, 4, 0, wide_src, wide_dst, nonzero_counts=cnt)
+    with pytest.raises(H.B.EarlError) as e:
+        H.B.dispatch(plan, [wide], workspace=torch.empty(1 << 24, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == H.B.EARL_INVALID_ARG
+    with pytest.raises(H.B.EarlError) as e:
+        H.B.dispatch_inverse(plan, [fld], workspace=ws)
+    assert e.value.status == H.B.EARL_INVALID_ARG
+    H.B.plan_destroy(plan)
+
+
 SEQ_FIELDS = (synth.per_sequence_field("adv_f32", 4, 1, 0x7FC00000), synth.per_sequence_field("flag_u8", 1),
               synth.per_sequence_field("pair_u16", 2, 2, 0xBEEF), synth.per_sequence_field("ret_f64", 8, 1, 5),
               synth.per_sequence_field("half", 2, 1, 0x3C00), synth.F_ID)
