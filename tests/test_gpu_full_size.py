@@ -153,3 +153,27 @@ def test_buffers_beyond_4_gib():
     for f in w.fields:
         assert torch.equal(back[f.name][0], src[f.name][0]), f.name
     B.plan_destroy(plan)
+
+
+def test_plan_and_dispatch_at_the_maximum_sequence_count():
+    """N = 2^20 sequences (the library's limit), short lengths, many micro-batches per rank: the
+    plan against the oracle array by array, then one 4-byte field, position ids and cu_seqlens
+    against the oracle's dispatch."""
+    import torch
+    import gpu_harness as H
+    import test_gpu_parity as T
+    n = 1 << 20
+    lengths = np.random.default_rng(77).integers(1, 17, size=n)
+    w = synth.custom_workload(lengths, n_groups=8, dp=8, sp=1, zigzag=0, pad_multiple=1,
+                              mb_token_budget=4096, fields=(synth.F_ID,), seed=77)
+    print("[max N] oracle plan", flush=True)
+    oplan = T.oracle_plan(w)
+    print("[max N] GPU plan", flush=True)
+    plan = H.build_plan(w)
+    T.assert_plan_equal(H.plan_result(plan), oplan)
+    print("[max N] dispatch", flush=True)
+    _, shards = H.host_sources(w, w.fields)
+    out = H.run_dispatch(w, plan, w.fields, src_host=shards)
+    T.assert_dispatch_equal(w, oplan, out, shards, w.fields)
+    H.B.plan_destroy(plan)
+    torch.cuda.synchronize()
