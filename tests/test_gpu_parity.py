@@ -207,6 +207,58 @@ def test_small_batches(H, case):
     H.B.plan_destroy(plan)
 
 
+def _dispatch_and_inverse_equal_oracle(H, w):
+    import torch
+    oplan = oracle_plan(w)
+    plan = H.build_plan(w)
+    assert_plan_equal(H.plan_result(plan), oplan)
+    _, shards = H.host_sources(w, w.fields)
+    out = H.run_dispatch(w, plan, w.fields, src_host=shards)
+    assert_dispatch_equal(w, oplan, out, shards, w.fields)
+    back = {f.name: [torch.full_like(t, 0x5A) for t in out["src_dev"][f.name]] for f in w.fields}
+    bfields = [H.B.Field(f.scalar_bytes, f.width, f.pad_scalar, back[f.name], out["dev"][f.name])
+               for f in w.fields]
+    H.B.dispatch_inverse(plan, bfields, workspace=out["workspace"])
+    torch.cuda.synchronize()
+    for f in w.fields:
+        want = [np.full_like(b, 0x5A) for b in shards[f.name]]
+        O.inverse_field(oplan, out["fields"][f.name], want)
+        for s in range(w.n_shards):
+            got = back[f.name][s].cpu().numpy().view(f.np_dtype).reshape(-1, f.width)
+            assert np.array_equal(got, want[s]), (f.name, s)
+    H.B.plan_destroy(plan)
+
+
+def test_field_shape_limits(H):
+    """The widest row the library accepts (1 MiB), a row one scalar short of it (so rows are not
+    a multiple of 16 bytes and every vector load is unaligned), and the largest number of
+    fields in one call, each forward and back."""
+    max_row = 1 << 20
+    lengths = [3, 1, 5, 2, 4, 1, 2]
+    for fields in ((synth.bytes_field("row_1MiB", 8, max_row // 8, 0x0123456789ABCDEF),),
+                   (synth.bytes_field("row_1MiB_minus_2", 2, max_row // 2 - 1, 0xA5C3),
+                    synth.bytes_field("row_1MiB_minus_1", 1, max_row - 1, 0x5A))):
+        w = synth.custom_workload(lengths, n_groups=2, dp=2, sp=2, zigzag=1, pad_multiple=2,
+                                  mb_token_budget=1 << 20, fields=fields, seed=41)
+        _dispatch_and_inverse_equal_oracle(H, w)
+    many = tuple(synth.bytes_field(f"f{k}", (1, 2, 4, 8)[k % 4], 1 + (k * 5) % 7, 0x1F2E3D4C5B6A7988 >> k)
+                 for k in range(32))
+    rng = np.random.default_rng(43)
+    w = synth.custom_workload(rng.integers(1, 400, size=150), n_groups=3, replication=2, dp=3, sp=2,
+                              zigzag=1, pad_multiple=4, mb_token_budget=4000, fields=many, seed=43)
+    _dispatch_and_inverse_equal_oracle(H, w)
+    # one field more is refused before anything is enqueued
+    plan = H.build_plan(w)
+    sm = H.B.plan_get_summary(plan)
+    import torch
+    buf = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda")
+    f33 = [H.B.Field(1, 1, 0, [buf] * w.n_shards, [buf] * sm["n_dst_shards"]) for _ in range(33)]
+    with pytest.raises(H.B.EarlError) as e:
+        H.B.dispatch(plan, f33, workspace=torch.empty(1 << 22, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == H.B.EARL_INVALID_ARG
+    H.B.plan_destroy(plan)
+
+
 def test_explicit_source_rows_with_gaps(H):
     rng = np.random.default_rng(21)
     L = rng.integers(1, 300, size=37)
