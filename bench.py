@@ -35,8 +35,8 @@ HBM_PEAK_GBPS = 8000.0
 # (scaled by a plain copy kernel of known size, see profiles/), keyed by the sha256 of the kernel
 # source the counters were taken on.  A changed kernel reports null until re-measured.
 MEASURED_TRAFFIC = {
-    "0b43c721a42f886d55572768a5bbb7e5ae03b0045d30223b332e4b24f7ebe6c9":
-        {"heavy": 52881578938, "longctx": 47518071260},
+    "1d51f287c7201848908587edf3ba8ee762b919abc43e5da44b723a9cfd7bd790":
+        {"heavy": 52881570038, "longctx": 47518054128},
 }
 
 WORKLOAD_NOTES = {

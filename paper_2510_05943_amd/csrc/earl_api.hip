@@ -579,9 +579,11 @@ int32_t earl_dispatch_workspace_bytes(earl_plan* p, const earl_field* fields, in
   int64_t tiles = count_tiles(p, fields, n_fields, with_position_ids != 0, with_cu_seqlens != 0);
   // the same scratch must do for earl_dispatch_inverse with these fields
   int64_t inverse_tiles = 0;
-  for (int f = 0; f < n_fields; ++f)
-    inverse_tiles += (p->hdr.total_real_rows * (int64_t)fields[f].scalar_bytes * fields[f].width +
-                      kTileBytes - 1) / kTileBytes;
+  for (int f = 0; f < n_fields; ++f) {
+    const int64_t w = (int64_t)fields[f].scalar_bytes * fields[f].width;
+    const int64_t tb = tile_bytes_of(w, kFieldCopy);
+    inverse_tiles += (p->hdr.total_real_rows * w + tb - 1) / tb;
+  }
   if (inverse_tiles > tiles) tiles = inverse_tiles;
   // one word per tile code on top (only the 1 KiB codes of counting fields use theirs)
   *out_bytes = param_block_bytes(F, p->d.S, p->d.D * p->d.C) +
@@ -741,27 +743,35 @@ int32_t earl_dispatch_inverse(earl_plan* p, const earl_field* fields, int32_t n_
   int64_t* ts = b.tile_start();
   TileRec* recs = b.recs();
   const void** ptrs = b.ptrs();
-  uint32_t pi = 0;
-  int64_t tiles = 0;
-  for (int f = 0; f < n_fields; ++f) {
-    const earl_field& uf = fields[f];
-    TileRec& r = recs[f];
-    r.kind = kFieldCopy;
-    r.scalar_bytes = uf.scalar_bytes;
-    r.row_bytes = uf.scalar_bytes * uf.width;
-    r.src_ptr_index = pi;
-    r.dst_ptr_index = pi + S;
-    r.tile_shift = kTileShift;
-    for (int s = 0; s < S; ++s) ptrs[pi + s] = uf.src_shard_ptrs[s];
-    for (int q = 0; q < n_dst; ++q) ptrs[pi + S + q] = uf.dst_shard_ptrs[q];
-    pi += S + n_dst;
-    r.tile_first = tiles;
-    r.end_bytes = p->hdr.total_real_rows * (int64_t)r.row_bytes;
-    ts[f] = tiles;
-    tiles += (r.end_bytes + kTileBytes - 1) / kTileBytes;
+  // one record per field, the fields with 1 KiB tiles first (as in the forward direction)
+  int64_t tiles = 0, fine = 0;
+  int n_rec = 0;
+  for (int pass = 0; pass < 2; ++pass) {
+    for (int f = 0; f < n_fields; ++f) {
+      const earl_field& uf = fields[f];
+      const int64_t w = (int64_t)uf.scalar_bytes * uf.width;
+      const int shift = tile_shift_of(w, kFieldCopy);
+      if ((shift == kFineTileShift) != (pass == 0)) continue;
+      const uint32_t pi = (uint32_t)f * (uint32_t)(S + n_dst);
+      TileRec& r = recs[n_rec];
+      r.kind = kFieldCopy;
+      r.scalar_bytes = uf.scalar_bytes;
+      r.row_bytes = (int32_t)w;
+      r.src_ptr_index = pi;
+      r.dst_ptr_index = pi + S;
+      r.tile_shift = (int16_t)shift;
+      for (int s = 0; s < S; ++s) ptrs[pi + s] = uf.src_shard_ptrs[s];
+      for (int q = 0; q < n_dst; ++q) ptrs[pi + S + q] = uf.dst_shard_ptrs[q];
+      r.tile_first = tiles;
+      r.end_bytes = p->hdr.total_real_rows * w;
+      ts[n_rec++] = tiles;
+      tiles += (r.end_bytes + ((int64_t)1 << shift) - 1) >> shift;
+    }
+    if (pass == 0) fine = tiles;
   }
   ts[n_fields] = tiles;
-  if (tiles * kSubTiles > 0x7fffffffll) return fail(EARL_INVALID_ARG, "too many tiles for one launch");
+  if (fine + (tiles - fine) * kSubTiles > 0x7fffffffll)
+    return fail(EARL_INVALID_ARG, "too many tiles for one launch");
   const size_t codes_off = b.bytes.size();
   const size_t need = codes_off + kTileCodeBytes * (size_t)tiles;
   if (!dispatch_ws_dev || reinterpret_cast<uintptr_t>(dispatch_ws_dev) % kAlign)
@@ -774,7 +784,9 @@ int32_t earl_dispatch_inverse(earl_plan* p, const earl_field* fields, int32_t n_
   }
   st = upload_params(b.bytes, dispatch_ws_dev, stream);
   if (st != EARL_OK) return st;
-  launch_copy_inverse(copy_args(p, dispatch_ws_dev, tiles), prefix, p->dev.seg_dst_shard,
+  CopyArgs ca = copy_args(p, dispatch_ws_dev, tiles);
+  ca.n_fine_tiles = fine;
+  launch_copy_inverse(ca, prefix, p->dev.seg_dst_shard,
                       p->hdr.n_segments, static_cast<unsigned char*>(dispatch_ws_dev) + codes_off,
                       static_cast<hipEvent_t>(p->ev_before), static_cast<hipEvent_t>(p->ev_after),
                       stream);

@@ -457,7 +457,7 @@ struct InverseArgs {
 };
 
 // Inverse tile codes: a = training-layout pointer of the tile's first byte (0 = generic tile,
-// then b = field << 32 | first segment), b = rollout-layout pointer (any alignment).
+// then b = record << 32 | first segment), b = rollout-layout pointer (any alignment).
 __global__ __launch_bounds__(kCodeThreads) void inverse_code_kernel(const InverseArgs a,
                                                                    TileCode* codes) {
   const int64_t tile = (int64_t)blockIdx.x * kCodeThreads + threadIdx.x;
@@ -466,14 +466,15 @@ __global__ __launch_bounds__(kCodeThreads) void inverse_code_kernel(const Invers
   const int f = last_le(pv.tile_start, 0, pv.n_recs, tile);   // one record per field
   const TileRec rec = pv.recs[f];
   const int64_t w = rec.row_bytes;
-  const int64_t lo = (tile - rec.tile_first) * (int64_t)kTileBytes;
+  const int64_t lo = (tile - rec.tile_first) << rec.tile_shift;
+  const int64_t tile_bytes = (int64_t)1 << rec.tile_shift;
   const int e = find_stream_segment(a.seg_real_prefix, 0, a.n_seg, lo, w);
   const SegRec r = a.c.segs[e];
   const int64_t s_lo = a.seg_real_prefix[e] * w;
   TileCode c;
   c.a = 0;
   c.b = (uint64_t)(uint32_t)f << 32 | (uint32_t)e;
-  if (lo + kTileBytes <= s_lo + (int64_t)r.n_real * w) {
+  if (lo + tile_bytes <= s_lo + (int64_t)r.n_real * w) {
     c.a = reinterpret_cast<uint64_t>(
         static_cast<const u8*>(pv.ptrs[rec.dst_ptr_index + a.seg_dst_shard[e]]) + r.dst_row * w +
         (lo - s_lo));
@@ -484,14 +485,15 @@ __global__ __launch_bounds__(kCodeThreads) void inverse_code_kernel(const Invers
   codes[tile] = c;
 }
 
-__device__ __noinline__ void generic_inverse_tile(const InverseArgs a, const TileCode c) {
+__device__ __noinline__ void generic_inverse_tile(const InverseArgs a, const TileCode c,
+                                                  const int64_t tile, const uint32_t vec0) {
   const ParamView pv = view_params(a.c.params);
   const TileRec rec = pv.recs[(uint32_t)(c.b >> 32)];
   const int64_t w = rec.row_bytes;
   const int sb = rec.scalar_bytes;
   const int64_t total = rec.end_bytes;   // bytes of the real-row stream of this field
-  const int64_t lo = ((int64_t)(blockIdx.x / kSubTiles) - rec.tile_first) * (int64_t)kTileBytes;
-  const int64_t o = lo + (int64_t)((blockIdx.x % kSubTiles) * kCopyThreads + threadIdx.x) * kVecBytes;
+  const int64_t lo = (tile - rec.tile_first) << rec.tile_shift;
+  const int64_t o = lo + (int64_t)(vec0 + threadIdx.x) * kVecBytes;
   if (o >= total) return;
   const void* const* src_ptrs = pv.ptrs + rec.src_ptr_index;
   const void* const* dst_ptrs = pv.ptrs + rec.dst_ptr_index;
@@ -526,13 +528,21 @@ __device__ __noinline__ void generic_inverse_tile(const InverseArgs a, const Til
 
 __global__ __launch_bounds__(kCopyThreads) void inverse_kernel(const InverseArgs a,
                                                                const TileCode* __restrict__ codes) {
-  const TileCode c = codes[blockIdx.x / kSubTiles];
+  // as in the forward kernel: one workgroup per 1 KiB tile code, kSubTiles per 4 KiB tile code
+  int64_t tile = blockIdx.x;
+  uint32_t vec0 = 0;
+  if (tile >= a.c.n_fine_tiles) {
+    const int64_t rest = tile - a.c.n_fine_tiles;
+    tile = a.c.n_fine_tiles + rest / kSubTiles;
+    vec0 = (uint32_t)(rest % kSubTiles) * kCopyThreads;
+  }
+  const TileCode c = codes[tile];
   if (c.a != 0) {
-    const uint32_t v = (blockIdx.x % kSubTiles) * kCopyThreads + threadIdx.x;
+    const uint32_t v = vec0 + threadIdx.x;
     store16_any(reinterpret_cast<u8*>(c.b) + v * kVecBytes,
                 load16(reinterpret_cast<const u8*>(c.a) + v * kVecBytes));
   } else {
-    generic_inverse_tile(a, c);
+    generic_inverse_tile(a, c, tile, vec0);
   }
 }
 
@@ -571,8 +581,8 @@ void launch_copy_inverse(const CopyArgs& a, const int64_t* seg_real_prefix,
   const unsigned g1 = (unsigned)((a.n_tiles + kCodeThreads - 1) / kCodeThreads);
   hipLaunchKernelGGL(inverse_code_kernel, dim3(g1), dim3(kCodeThreads), 0, stream, ia, codes);
   if (before) (void)hipEventRecord(before, stream);
-  hipLaunchKernelGGL(inverse_kernel, dim3((unsigned)(a.n_tiles * kSubTiles)), dim3(kCopyThreads), 0,
-                     stream, ia, codes);
+  const int64_t grid = a.n_fine_tiles + (a.n_tiles - a.n_fine_tiles) * kSubTiles;
+  hipLaunchKernelGGL(inverse_kernel, dim3((unsigned)grid), dim3(kCopyThreads), 0, stream, ia, codes);
   if (after) (void)hipEventRecord(after, stream);
 }
 

@@ -27,7 +27,6 @@ constexpr int kFineTileShift = 10;   // fields with rows under 16 bytes: 1 KiB p
 constexpr int kCopyThreads = 64;     // re-layout workgroup: one wavefront, 1 KiB of a tile
 constexpr int kSubTiles = kTileBytes / (kCopyThreads * kVecBytes);   // workgroups per 4 KiB tile
 constexpr int kCodeThreads = 256;    // tile-code kernel workgroup (one tile per lane)
-constexpr int kInverseThreads = kTileBytes / kVecBytes;   // inverse kernel: one tile per workgroup
 
 // First bytes of the workspace; copied to the host together with the arrays that follow it.
 struct PlanHeader {
