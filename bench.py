@@ -35,8 +35,8 @@ HBM_PEAK_GBPS = 8000.0
 # (scaled by a plain copy kernel of known size, see profiles/), keyed by the sha256 of the kernel
 # source the counters were taken on.  A changed kernel reports null until re-measured.
 MEASURED_TRAFFIC = {
-    "1d51f287c7201848908587edf3ba8ee762b919abc43e5da44b723a9cfd7bd790":
-        {"heavy": 52881570038, "longctx": 47518054128},
+    "4635cc1248983b6472b828437d81edc05907d6b2026330643045dfe87899dfd6":
+        {"heavy": 52941840535, "longctx": 47530506600},
 }
 
 WORKLOAD_NOTES = {
