@@ -35,8 +35,8 @@ HBM_PEAK_GBPS = 8000.0
 # (scaled by a plain copy kernel of known size, see profiles/), keyed by the sha256 of the kernel
 # source the counters were taken on.  A changed kernel reports null until re-measured.
 MEASURED_TRAFFIC = {
-    "4635cc1248983b6472b828437d81edc05907d6b2026330643045dfe87899dfd6":
-        {"heavy": 52941840535, "longctx": 47530506600},
+    "91c52b53fb47cf45432f9a629ee29bd9dd07f890b185fa421c52c338b433b24c":
+        {"heavy": 52969780375, "longctx": 47532744110},
 }
 
 WORKLOAD_NOTES = {
