@@ -35,8 +35,8 @@ HBM_PEAK_GBPS = 8000.0
 # (scaled by a plain copy kernel of known size, see profiles/), keyed by the sha256 of the kernel
 # source the counters were taken on.  A changed kernel reports null until re-measured.
 MEASURED_TRAFFIC = {
-    "91c52b53fb47cf45432f9a629ee29bd9dd07f890b185fa421c52c338b433b24c":
-        {"heavy": 52969780375, "longctx": 47532744110},
+    "41bd168a1413dc3a49faefb5ac22eb5797a7c061cf004da48e0ec2363645f699":
+        {"heavy": 52969750638, "longctx": 47532742366},
 }
 
 WORKLOAD_NOTES = {

@@ -174,80 +174,131 @@ __device__ __forceinline__ ParamView view_params(const DispatchDev* p) {
   return v;
 }
 
-// Pass 1: one lane per tile.
-__global__ __launch_bounds__(kCodeThreads) void tile_code_kernel(const CopyArgs a, TileCode* codes) {
-  const int64_t tile = (int64_t)blockIdx.x * kCodeThreads + threadIdx.x;
-  if (tile >= a.n_tiles) return;
-  const ParamView pv = view_params(a.params);
-  // The 64 tiles of a wavefront are consecutive, so most of them share the record, and often the
-  // segment, of the first one: search once for the first lane (uniform values, scalar loads),
-  // then every lane only checks whether the answer holds for its own tile.
-  const int64_t tile0 = ((int64_t)__builtin_amdgcn_readfirstlane((int)(tile >> 32)) << 32) |
-                        (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)tile);
-  const int x0 = last_le(pv.tile_start, 0, pv.n_recs, tile0);
-  const int x = tile < pv.tile_start[x0 + 1] ? x0 : last_le(pv.tile_start, x0, pv.n_recs, tile);
-  const TileRec rec = pv.recs[x];
+// Pass 1: every lane writes the codes of kTilesPerLane consecutive tiles.
+//
+// The searches (which record, which segment) are chains of dependent loads, a few microseconds
+// per wavefront whatever the number of tiles it covers, so the kernel's time is that latency times
+// the number of wavefront rounds.  Two things shorten it: the 64 lanes of a wavefront cover
+// consecutive tiles, so the search is done once for the first lane with uniform values (scalar
+// loads) and every lane only checks whether the answer holds for its own first tile; and a lane
+// carries record and segment from one of its tiles to the next, searching again only when the
+// next tile has left them.
+struct TileCursor {
+  int x;            // record of the current tile
+  TileRec rec;
+  int64_t x_end;    // first tile of the next record
+  int e;            // segment holding the tile's first byte (copy and position-id records)
+  SegRec seg;
+};
+
+__device__ __forceinline__ void cursor_set_record(const ParamView& pv, TileCursor& cur, int x) {
+  cur.x = x;
+  cur.rec = pv.recs[x];
+  cur.x_end = pv.tile_start[x + 1];
+}
+
+__device__ __forceinline__ TileCode code_of_tile(const CopyArgs& a, const ParamView& pv,
+                                                 const TileCursor& cur, int64_t tile) {
+  const TileRec& rec = cur.rec;
   const int64_t lo = (tile - rec.tile_first) << rec.tile_shift;
   const int64_t hi = lo + ((int64_t)1 << rec.tile_shift);
   const uint64_t dst = reinterpret_cast<uint64_t>(static_cast<u8*>(rec.dst) + lo);
   TileCode c;
-  c.a = (uint64_t)(uint32_t)x << 32;
+  c.a = (uint64_t)(uint32_t)cur.x << 32;
   c.b = dst | kActGeneric;
   if (rec.kind == kFieldLinear) {
     if (hi <= rec.end_bytes) {
       c.a = reinterpret_cast<uint64_t>(static_cast<const u8*>(pv.ptrs[rec.src_ptr_index]) + lo);
       c.b = dst | kActCopy;
     }
-  } else {
-    const int64_t w = rec.row_bytes;
-    // the first lane's segment (meaningful for the lanes that share its record)
-    const TileRec rec0 = pv.recs[x0];
-    int e_guess = rec0.e_begin;
-    if (rec0.kind != kFieldLinear)
-      e_guess = find_segment(a.segs, rec0.e_begin, rec0.e_end,
-                             (tile0 - rec0.tile_first) << rec0.tile_shift, rec0.row_bytes);
-    int e0;
-    if (x == x0) {
-      const SegRec g = a.segs[e_guess];
-      e0 = lo < (g.dst_row + g.n_rows) * w ? e_guess : find_segment(a.segs, e_guess, rec.e_end, lo, w);
-    } else {
-      e0 = find_segment(a.segs, rec.e_begin, rec.e_end, lo, w);
+    return c;
+  }
+  const int64_t w = rec.row_bytes;
+  const SegRec& r = cur.seg;
+  const int64_t s_lo = r.dst_row * w;
+  const int64_t s_real_hi = (r.dst_row + r.n_real) * w;
+  const int64_t s_hi = (r.dst_row + r.n_rows) * w;
+  c.a |= (uint32_t)cur.e;
+  if (hi > rec.end_bytes) return c;
+  if (rec.kind == kFieldPositionIds) {
+    if (hi <= s_hi) {
+      c.a = (uint64_t)(uint32_t)(r.pos0 + (int32_t)((lo - s_lo) >> 2));
+      c.b = dst | kActIota;
     }
-    const SegRec r = a.segs[e0];
-    const int64_t s_lo = r.dst_row * w;
-    const int64_t s_real_hi = (r.dst_row + r.n_real) * w;
-    const int64_t s_hi = (r.dst_row + r.n_rows) * w;
-    c.a |= (uint32_t)e0;
-    if (hi <= rec.end_bytes) {
-      if (rec.kind == kFieldPositionIds) {
-        if (hi <= s_hi) {
-          c.a = (uint64_t)(uint32_t)(r.pos0 + (int32_t)((lo - s_lo) >> 2));
-          c.b = dst | kActIota;
-        }
-      } else if (hi <= s_real_hi) {
-        const u8* shard = static_cast<const u8*>(pv.ptrs[rec.src_ptr_index + r.src_shard]);
-        if (rec.per_sequence) {
-          // the whole tile repeats the sequence's value
-          c.a = splat_scalar(load_scalar(shard + (int64_t)a.seg_src_seq[e0] * w, (int)w), (int)w);
-          c.b = dst | kActFill;
-        } else {
-          c.a = reinterpret_cast<uint64_t>(shard + r.src_row * w + (lo - s_lo));
-          c.b = dst | kActCopy;
-          if (rec.dst_ptr_index != kNoCounters) {
-            // a counting field (always 1 KiB tiles): the whole tile belongs to one micro-batch
-            int64_t* row = static_cast<int64_t*>(const_cast<void*>(pv.ptrs[rec.dst_ptr_index]));
-            a.tile_counter[tile] = reinterpret_cast<uint64_t>(row + a.seg_mb[e0]) |
-                                   (uint64_t)(31 - __builtin_clz(rec.scalar_bytes));
-            c.b = dst | kActCopyCount;
-          }
-        }
-      } else if (lo >= s_real_hi && hi <= s_hi) {
-        c.a = rec.pad_scalar;
-        c.b = dst | kActFill;
+  } else if (hi <= s_real_hi) {
+    const u8* shard = static_cast<const u8*>(pv.ptrs[rec.src_ptr_index + r.src_shard]);
+    if (rec.per_sequence) {
+      // the whole tile repeats the sequence's value
+      c.a = splat_scalar(load_scalar(shard + (int64_t)a.seg_src_seq[cur.e] * w, (int)w), (int)w);
+      c.b = dst | kActFill;
+    } else {
+      c.a = reinterpret_cast<uint64_t>(shard + r.src_row * w + (lo - s_lo));
+      c.b = dst | kActCopy;
+      if (rec.dst_ptr_index != kNoCounters) {
+        // a counting field (always 1 KiB tiles): the whole tile belongs to one micro-batch
+        int64_t* row = static_cast<int64_t*>(const_cast<void*>(pv.ptrs[rec.dst_ptr_index]));
+        a.tile_counter[tile] = reinterpret_cast<uint64_t>(row + a.seg_mb[cur.e]) |
+                               (uint64_t)(31 - __builtin_clz(rec.scalar_bytes));
+        c.b = dst | kActCopyCount;
       }
     }
+  } else if (lo >= s_real_hi && hi <= s_hi) {
+    c.a = rec.pad_scalar;
+    c.b = dst | kActFill;
   }
-  codes[tile] = c;
+  return c;
+}
+
+__global__ __launch_bounds__(kCodeThreads) void tile_code_kernel(const CopyArgs a, TileCode* codes) {
+  const int64_t first = ((int64_t)blockIdx.x * kCodeThreads + threadIdx.x) * kTilesPerLane;
+  if (first >= a.n_tiles) return;
+  const ParamView pv = view_params(a.params);
+  // the wavefront's first tile: uniform, searched with scalar loads
+  const int64_t tile0 = ((int64_t)__builtin_amdgcn_readfirstlane((int)(first >> 32)) << 32) |
+                        (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)first);
+  const int x0 = last_le(pv.tile_start, 0, pv.n_recs, tile0);
+  const TileRec rec0 = pv.recs[x0];
+  int e_guess = rec0.e_begin;
+  if (rec0.kind != kFieldLinear)
+    e_guess = find_segment(a.segs, rec0.e_begin, rec0.e_end,
+                           (tile0 - rec0.tile_first) << rec0.tile_shift, rec0.row_bytes);
+
+  TileCursor cur;
+  cursor_set_record(pv, cur, first < pv.tile_start[x0 + 1] ? x0
+                                                             : last_le(pv.tile_start, x0, pv.n_recs, first));
+  cur.e = cur.rec.e_begin;
+  if (cur.rec.kind != kFieldLinear) {
+    const int64_t w = cur.rec.row_bytes;
+    const int64_t lo = (first - cur.rec.tile_first) << cur.rec.tile_shift;
+    if (cur.x == x0) {
+      const SegRec g = a.segs[e_guess];
+      cur.e = lo < (g.dst_row + g.n_rows) * w ? e_guess
+                                               : find_segment(a.segs, e_guess, cur.rec.e_end, lo, w);
+    } else {
+      cur.e = find_segment(a.segs, cur.rec.e_begin, cur.rec.e_end, lo, w);
+    }
+    cur.seg = a.segs[cur.e];
+  }
+  const int64_t last = first + kTilesPerLane < a.n_tiles ? first + kTilesPerLane : a.n_tiles;
+  for (int64_t tile = first; tile < last; ++tile) {
+    if (tile != first) {
+      if (tile >= cur.x_end) {
+        // next record (records without tiles are skipped by the search)
+        cursor_set_record(pv, cur, last_le(pv.tile_start, cur.x, pv.n_recs, tile));
+        cur.e = cur.rec.e_begin;
+        if (cur.rec.kind != kFieldLinear) cur.seg = a.segs[cur.e];
+      }
+      if (cur.rec.kind != kFieldLinear) {
+        const int64_t w = cur.rec.row_bytes;
+        const int64_t lo = (tile - cur.rec.tile_first) << cur.rec.tile_shift;
+        if (lo >= (cur.seg.dst_row + cur.seg.n_rows) * w) {
+          cur.e = find_segment(a.segs, cur.e, cur.rec.e_end, lo, w);
+          cur.seg = a.segs[cur.e];
+        }
+      }
+    }
+    codes[tile] = code_of_tile(a, pv, cur, tile);
+  }
 }
 
 // What the generic path needs about its tile.
@@ -561,7 +612,8 @@ __global__ __launch_bounds__(kCopyThreads) void inverse_kernel(const InverseArgs
 
 void launch_tile_codes(const CopyArgs& a, void* tile_codes, hipStream_t stream) {
   if (a.n_tiles <= 0) return;
-  const unsigned grid = (unsigned)((a.n_tiles + kCodeThreads - 1) / kCodeThreads);
+  const int64_t per_group = (int64_t)kCodeThreads * kTilesPerLane;
+  const unsigned grid = (unsigned)((a.n_tiles + per_group - 1) / per_group);
   hipLaunchKernelGGL(tile_code_kernel, dim3(grid), dim3(kCodeThreads), 0, stream, a,
                      static_cast<TileCode*>(tile_codes));
 }
