@@ -35,7 +35,7 @@ HBM_PEAK_GBPS = 8000.0
 # (scaled by a plain copy kernel of known size, see profiles/), keyed by the sha256 of the kernel
 # source the counters were taken on.  A changed kernel reports null until re-measured.
 MEASURED_TRAFFIC = {
-    "41bd168a1413dc3a49faefb5ac22eb5797a7c061cf004da48e0ec2363645f699":
+    "dbea4ae40c819944f64ade2dd344661caa927b1d0de0ad8310eaab956ee6e4ce":
         {"heavy": 52969750638, "longctx": 47532742366},
 }
 
@@ -53,9 +53,12 @@ WORKLOAD_NOTES = {
 
 
 def kernel_source_hash() -> str:
-    path = os.path.join(ROOT, "paper_2510_05943_amd", "csrc", "earl_copy.hip")
-    with open(path, "rb") as f:
-        return hashlib.sha256(f.read()).hexdigest()
+    """sha256 over the sources the re-layout kernels are built from (kernel file + constants)."""
+    h = hashlib.sha256()
+    for name in ("earl_copy.hip", "earl_internal.h"):
+        with open(os.path.join(ROOT, "paper_2510_05943_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
 
 
 class HipEvents:
