@@ -259,6 +259,15 @@ def test_field_shape_limits(H):
     H.B.plan_destroy(plan)
 
 
+def test_dispatch_at_the_largest_sequence_parallel_degree(H):
+    """sp = 64 with zigzag: 128 chunks per sequence, most of them a few rows, many all padding."""
+    rng = np.random.default_rng(64)
+    fields = (synth.F_ID, synth.F_MASK, synth.bytes_field("v", 2, 24, 0x7E57))
+    w = synth.custom_workload(rng.integers(1, 700, size=90), n_groups=3, replication=2, dp=2, sp=64,
+                              zigzag=1, pad_multiple=1, mb_token_budget=20000, fields=fields, seed=64)
+    _dispatch_and_inverse_equal_oracle(H, w)
+
+
 def test_explicit_source_rows_with_gaps(H):
     rng = np.random.default_rng(21)
     L = rng.integers(1, 300, size=37)
@@ -311,6 +320,12 @@ def test_explicit_source_rows_with_gaps(H):
     ("loads_beyond_32_bits", dict(L=[1 << 30] * 5 + [(1 << 30) - 12345] * 6, dp=3, sp=1, B=(1 << 31) - 1)),
     ("equal_lengths_round_robin", dict(L=[64] * 96, dp=8, sp=2, B=1 << 20)),
     ("budget_exactly_one_sequence", dict(L=[16] * 40, dp=2, sp=2, zigzag=1, B=16)),
+    ("sp_64_zigzag_128_chunks", dict(L=[(i * 37) % 900 + 1 for i in range(120)], G=3, dp=3, sp=64,
+                                     zigzag=1, pad=2, B=40000)),
+    ("src_shards_4096", dict(L=[(i * 11) % 40 + 1 for i in range(6000)], G=2048, R=2, dp=2, sp=2,
+                             B=100000)),
+    ("dp_1024_sp_4_groups_64", dict(L=[(i * 29) % 300 + 1 for i in range(5000)], G=64, dp=1024, sp=4,
+                                    zigzag=1, B=100000)),
 ])
 def test_plan_edge_cases(H, desc, kw):
     w = synth.custom_workload(kw["L"], n_groups=kw.get("G", 1), replication=kw.get("R", 1),
