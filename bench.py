@@ -35,8 +35,8 @@ HBM_PEAK_GBPS = 8000.0
 # (scaled by a plain copy kernel of known size, see profiles/), keyed by the sha256 of the kernel
 # source the counters were taken on.  A changed kernel reports null until re-measured.
 MEASURED_TRAFFIC = {
-    "dbea4ae40c819944f64ade2dd344661caa927b1d0de0ad8310eaab956ee6e4ce":
-        {"heavy": 52969750638, "longctx": 47532742366},
+    "54360346681b115518ce2c10185e1ac0256271a9999c58d6e66e7584c21ab317":
+        {"heavy": 52882794788, "longctx": 47518216247},
 }
 
 WORKLOAD_NOTES = {
@@ -131,6 +131,14 @@ def run_gpu(args, torch, B, synth):
 
     def step(ev=None):
         p = B.plan_build(lengths, w.n_seqs, src_l, dst_l, ws, stream=stream)
+        if args.async_dispatch:
+            # buffers are pre-allocated: the dispatch goes in right behind the plan, the summary
+            # and the device-side verdict are fetched afterwards
+            if ev is not None:
+                B.plan_set_dispatch_events(p, ev[0], ev[1])
+            B.dispatch_async(p, fields, position_ids=pos, cu_seqlens=cu, workspace=scratch, stream=stream)
+            B.plan_get_summary(p)
+            return p
         B.plan_get_summary(p)          # the consumer needs the shard sizes before it can dispatch
         if ev is not None:
             B.plan_set_dispatch_events(p, ev[0], ev[1])
@@ -154,6 +162,8 @@ def run_gpu(args, torch, B, synth):
     plans = [step() for _ in range(args.warmup)]
     torch.cuda.synchronize()
     for p in plans:
+        if args.async_dispatch and B.dispatch_async_status(p) != B.EARL_OK:
+            raise RuntimeError("asynchronous dispatch was refused on the device")
         B.plan_destroy(p)
 
     # HIP events recorded by the library on the dispatch stream, right around the re-layout kernel
@@ -164,6 +174,8 @@ def run_gpu(args, torch, B, synth):
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     for p in plans:
+        if args.async_dispatch and B.dispatch_async_status(p) != B.EARL_OK:
+            raise RuntimeError("asynchronous dispatch was refused on the device")
         B.plan_destroy(p)
 
     # the two halves on their own (outside the timed region): plan = build + summary (ends with
@@ -320,6 +332,9 @@ def main() -> int:
     ap.add_argument("--balance-policy", type=int, default=0, choices=[0, 1, 2],
                     help="0 longest-first list scheduling (default), 1 sorted snake deal, "
                          "2 list scheduling on squared padded lengths")
+    ap.add_argument("--async-dispatch", action="store_true",
+                    help="step = earl_plan_build + earl_dispatch_async + earl_plan_get_summary "
+                         "(no host wait between plan and dispatch)")
     ap.add_argument("--inverse", action="store_true",
                     help="time the reverse direction (earl_dispatch_inverse) instead of earl_dispatch")
     ap.add_argument("--reference-copy", action="store_true",
@@ -360,8 +375,10 @@ def main() -> int:
                    "dst_shards": w.dp * w.sp, "src_shards": w.n_shards,
                    "balance_policy": args.balance_policy,
                    "step": ("two passes (gather to one buffer, scatter from it), each " if args.two_pass
-                            else "") + "earl_plan_build + earl_plan_get_summary + " +
-                           ("earl_dispatch_inverse" if args.inverse else "earl_dispatch")},
+                            else "") + ("earl_plan_build + earl_dispatch_async + earl_plan_get_summary"
+                                        if args.async_dispatch else
+                                        "earl_plan_build + earl_plan_get_summary + " +
+                                        ("earl_dispatch_inverse" if args.inverse else "earl_dispatch"))},
         "whole_path_GBps": r["algo_bytes"] / (r["ms_per_step"] * 1e-3) / 1e9,
         "roofline": {"bound": "hbm", "achieved": r["achieved"], "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": r["achieved"] / HBM_PEAK_GBPS, "traffic": r["traffic"],

@@ -243,6 +243,38 @@ int32_t earl_dispatch(earl_plan* plan, const earl_field* fields, int32_t n_field
                       void* dispatch_ws_dev, size_t dispatch_ws_bytes, void* hip_stream);
 
 /*
+ * earl_dispatch without the wait for the plan.  earl_dispatch needs the shard sizes on the host
+ * (to size its launches exactly and to check every capacity before anything is enqueued), so its
+ * first call on a plan synchronises with the plan kernel.  This variant sizes its launches by the
+ * CAPACITIES the caller states and leaves the rest to the device: it can be enqueued right
+ * behind earl_plan_build with no host synchronisation in between (a serving or training loop that
+ * pre-allocates its buffers never stalls; the summary can be fetched afterwards).
+ *   fields[n_fields]               as for earl_dispatch; dst_capacity_rows AND src_capacity_rows
+ *                                  are required; nonzero_counts must be NULL.
+ *   position_ids_shard_ptrs        host array[D*C] of device int32 buffers or NULL, with
+ *   position_ids_capacity_rows     host array[D*C]: rows each of them holds (NULL iff the former is).
+ *   cu_seqlens_dev / _capacity     device int32 buffer and the entries it holds, or NULL and 0.
+ *   dispatch_ws_dev / _bytes       scratch of at least earl_dispatch_async_workspace_bytes() bytes.
+ *   hip_stream                     the stream earl_plan_build was given, or one ordered behind it.
+ * Buffers with capacity 0 may be NULL; the others must be aligned as for earl_dispatch.
+ * What cannot be checked on the host is checked on the device before any byte is written: if the
+ * plan failed (bad length, budget exceeded) or any destination, source, position-id or cu_seqlens
+ * buffer is smaller than the plan needs, the call writes NOTHING and records the status, which
+ * earl_dispatch_async_status returns (it waits for the stream): EARL_OK, the plan's status, or
+ * EARL_CAPACITY.  Rows of a destination buffer beyond the shard's size are left untouched.
+ */
+int32_t earl_dispatch_async_workspace_bytes(earl_plan* plan, const earl_field* fields,
+                                            int32_t n_fields,
+                                            const int64_t* position_ids_capacity_rows,
+                                            int64_t cu_seqlens_capacity, size_t* out_bytes);
+int32_t earl_dispatch_async(earl_plan* plan, const earl_field* fields, int32_t n_fields,
+                            int32_t* const* position_ids_shard_ptrs,
+                            const int64_t* position_ids_capacity_rows, int32_t* cu_seqlens_dev,
+                            int64_t cu_seqlens_capacity, void* dispatch_ws_dev,
+                            size_t dispatch_ws_bytes, void* hip_stream);
+int32_t earl_dispatch_async_status(earl_plan* plan, int32_t* status);
+
+/*
  * Measurement hook: the following earl_dispatch / earl_dispatch_inverse calls on this plan record
  * `event_before` on the stream right before the re-layout kernel and `event_after` right after it (both hipEvent_t created
  * by the caller with timing enabled; NULL, NULL switches the hook off).  The interval is the

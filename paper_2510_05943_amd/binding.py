@@ -22,7 +22,8 @@ EARL_MAX_FIELDS = 32
 
 EXPORTED = ("earl_plan_workspace_bytes", "earl_plan_build", "earl_plan_get_summary",
             "earl_plan_export", "earl_plan_export_segments", "earl_dispatch_workspace_bytes",
-            "earl_dispatch",
+            "earl_dispatch", "earl_dispatch_async_workspace_bytes", "earl_dispatch_async",
+            "earl_dispatch_async_status",
             "earl_dispatch_inverse", "earl_plan_set_dispatch_events", "earl_plan_destroy", "earl_status_string",
             "earl_last_error_message")
 
@@ -89,6 +90,11 @@ def load_library() -> C.CDLL:
     lib.earl_dispatch_workspace_bytes.argtypes = [vp, C.POINTER(_Field), i32, i32, i32,
                                                   C.POINTER(C.c_size_t)]
     lib.earl_dispatch.argtypes = [vp, C.POINTER(_Field), i32, C.POINTER(vp), vp, vp, C.c_size_t, vp]
+    lib.earl_dispatch_async_workspace_bytes.argtypes = [vp, C.POINTER(_Field), i32, vp, i64,
+                                                        C.POINTER(C.c_size_t)]
+    lib.earl_dispatch_async.argtypes = [vp, C.POINTER(_Field), i32, C.POINTER(vp), vp, vp, i64, vp,
+                                        C.c_size_t, vp]
+    lib.earl_dispatch_async_status.argtypes = [vp, C.POINTER(i32)]
     lib.earl_dispatch_inverse.argtypes = [vp, C.POINTER(_Field), i32, vp, C.c_size_t, vp]
     lib.earl_plan_set_dispatch_events.argtypes = [vp, vp, vp]
     lib.earl_plan_destroy.argtypes = [vp]
@@ -307,6 +313,44 @@ def dispatch(plan: Plan, fields: Sequence[Field], position_ids: Optional[Sequenc
                                         C.cast(pos, C.POINTER(C.c_void_p)) if pos is not None else None,
                                         _ptr(cu_seqlens), _ptr(workspace), _nbytes(workspace),
                                         _stream_handle(stream)))
+
+
+def _capacity_array(tensors: Optional[Sequence]):
+    if tensors is None:
+        return None
+    return (C.c_int64 * len(tensors))(*[0 if t is None else int(t.numel()) for t in tensors])
+
+
+def dispatch_async_workspace_bytes(plan: Plan, fields: Sequence[Field],
+                                   position_ids: Optional[Sequence] = None, cu_seqlens=None) -> int:
+    """earl_dispatch_async_workspace_bytes; capacities are taken from the buffers' sizes."""
+    arr, n, keep = _marshal_fields(fields)
+    out = C.c_size_t(0)
+    _check(load_library().earl_dispatch_async_workspace_bytes(
+        plan.handle, arr, n, _capacity_array(position_ids),
+        0 if cu_seqlens is None else int(cu_seqlens.numel()), C.byref(out)))
+    return int(out.value)
+
+
+def dispatch_async(plan: Plan, fields: Sequence[Field], position_ids: Optional[Sequence] = None,
+                   cu_seqlens=None, workspace=None, stream=None) -> None:
+    """earl_dispatch_async: enqueued behind the plan without waiting for it.  Position-id buffers
+    are int32 tensors (capacity = their element count), as is cu_seqlens."""
+    arr, n, keep = _marshal_fields(fields)
+    pos = None
+    if position_ids is not None:
+        pos = (C.c_void_p * len(position_ids))(*[_ptr(t) for t in position_ids])
+    _check(load_library().earl_dispatch_async(
+        plan.handle, arr, n, pos, _capacity_array(position_ids), _ptr(cu_seqlens),
+        0 if cu_seqlens is None else int(cu_seqlens.numel()), _ptr(workspace), _nbytes(workspace),
+        _stream_handle(stream)))
+
+
+def dispatch_async_status(plan: Plan) -> int:
+    """earl_dispatch_async_status: waits for the stream; EARL_OK if the last call was carried out."""
+    st = C.c_int32(-1)
+    _check(load_library().earl_dispatch_async_status(plan.handle, C.byref(st)))
+    return st.value
 
 
 def dispatch_inverse(plan: Plan, fields: Sequence[Field], workspace=None, stream=None) -> None:

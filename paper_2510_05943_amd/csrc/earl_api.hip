@@ -34,6 +34,8 @@ int32_t fail(int32_t status, const char* fmt, ...) {
       return fail(EARL_HIP_ERROR, "%s failed: %s", #expr, hipGetErrorString(e_));      \
   } while (0)
 
+static_assert(kStatusCapacity == EARL_CAPACITY, "status codes of device code");
+
 constexpr size_t kAlign = 256;
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
@@ -44,6 +46,10 @@ size_t param_block_bytes(int n_fields, int n_src, int n_dst) {
   b += align_up(sizeof(TileRec) * n_recs);
   // per field: S source pointers, D*C destination pointers, D*C counter rows
   b += align_up(sizeof(void*) * (size_t)n_fields * ((size_t)n_src + 2 * (size_t)n_dst));
+  // earl_dispatch_async: capacities of every record and of every source buffer, field flags
+  b += align_up(sizeof(int64_t) * n_recs);
+  b += align_up(sizeof(int64_t) * (size_t)n_fields * (size_t)n_src);
+  b += align_up(sizeof(int32_t) * (size_t)n_fields);
   return b;
 }
 
@@ -187,6 +193,8 @@ struct earl_plan {
   bool inverse_ready;
   void* ev_before;
   void* ev_after;
+  hipStream_t async_stream;             // stream of the last earl_dispatch_async
+  bool async_used;
   std::vector<int32_t> seg_starts;      // first segment of every destination shard (+ total)
   std::vector<unsigned char> summary;   // host copy of the workspace's summary block
   PlanHeader hdr;
@@ -264,6 +272,11 @@ struct BlockBuilder {
   int64_t* tile_start() { return reinterpret_cast<int64_t*>(bytes.data() + hd.tile_start_ofs); }
   TileRec* recs() { return reinterpret_cast<TileRec*>(bytes.data() + hd.recs_ofs); }
   const void** ptrs() { return reinterpret_cast<const void**>(bytes.data() + hd.ptrs_ofs); }
+  int64_t* rec_caps() { return reinterpret_cast<int64_t*>(bytes.data() + hd.rec_caps_ofs); }
+  int64_t* src_caps() { return reinterpret_cast<int64_t*>(bytes.data() + hd.src_caps_ofs); }
+  int32_t* src_per_sequence() {
+    return reinterpret_cast<int32_t*>(bytes.data() + hd.src_per_sequence_ofs);
+  }
   void init(int n_recs, int n_fields, int n_src, int n_dst) {
     hd.n_recs = n_recs;
     size_t off = align_up(sizeof(DispatchDev));
@@ -273,6 +286,13 @@ struct BlockBuilder {
     off += align_up(sizeof(TileRec) * (size_t)n_recs);
     hd.ptrs_ofs = (uint32_t)off;
     off += align_up(sizeof(void*) * (size_t)n_fields * ((size_t)n_src + 2 * (size_t)n_dst));
+    hd.n_fields = n_fields;
+    hd.rec_caps_ofs = (uint32_t)off;
+    off += align_up(sizeof(int64_t) * (size_t)n_recs);
+    hd.src_caps_ofs = (uint32_t)off;
+    off += align_up(sizeof(int64_t) * (size_t)n_fields * (size_t)n_src);
+    hd.src_per_sequence_ofs = (uint32_t)off;
+    off += align_up(sizeof(int32_t) * (size_t)n_fields);
     hd.total_bytes = (uint32_t)off;
     bytes.assign(off, 0);
     std::memcpy(bytes.data(), &hd, sizeof(hd));
@@ -720,6 +740,223 @@ int32_t earl_dispatch(earl_plan* p, const earl_field* fields, int32_t n_fields,
   hipError_t e = hipGetLastError();
   if (e != hipSuccess)
     return fail(EARL_HIP_ERROR, "re-layout kernel launch failed: %s", hipGetErrorString(e));
+  return EARL_OK;
+}
+
+namespace {
+
+// Tile codes of an asynchronous dispatch: as count_tiles, from buffer capacities.
+int64_t count_tiles_by_capacity(const earl_plan* p, const earl_field* fields, int32_t n_fields,
+                                const int64_t* position_ids_capacity_rows,
+                                int64_t cu_seqlens_capacity) {
+  const int n_dst = p->d.D * p->d.C;
+  int64_t tiles = 0;
+  for (int f = 0; f < n_fields + (position_ids_capacity_rows ? 1 : 0); ++f) {
+    const int64_t w = f < n_fields ? (int64_t)fields[f].scalar_bytes * fields[f].width : 4;
+    const int64_t* cap = f < n_fields ? fields[f].dst_capacity_rows : position_ids_capacity_rows;
+    const int64_t tb = tile_bytes_of(w, kFieldCopy);
+    for (int q = 0; q < n_dst; ++q) tiles += (cap[q] * w + tb - 1) / tb;
+  }
+  if (cu_seqlens_capacity > 0) tiles += (4 * cu_seqlens_capacity + kTileBytes - 1) / kTileBytes;
+  return tiles;
+}
+
+// Host-side checks of an asynchronous dispatch: everything that does not need the plan's result.
+int32_t check_async_args(const earl_plan* p, const earl_field* fields, int32_t n_fields,
+                         int32_t* const* position_ids_shard_ptrs,
+                         const int64_t* position_ids_capacity_rows, const int32_t* cu_seqlens_dev,
+                         int64_t cu_seqlens_capacity) {
+  int32_t st = check_field_shapes(fields, n_fields);
+  if (st != EARL_OK) return st;
+  const int n_dst = p->d.D * p->d.C, S = p->d.S;
+  if ((position_ids_shard_ptrs == nullptr) != (position_ids_capacity_rows == nullptr))
+    return fail(EARL_INVALID_ARG, "position ids need both pointers and capacities");
+  if (cu_seqlens_capacity < 0 || (cu_seqlens_dev == nullptr) != (cu_seqlens_capacity == 0))
+    return fail(EARL_INVALID_ARG, "cu_seqlens needs a buffer and a positive capacity, or neither");
+  if (cu_seqlens_capacity > 0x7fffffffll)
+    return fail(EARL_INVALID_ARG, "cu_seqlens capacity out of range");
+  if (cu_seqlens_dev && reinterpret_cast<uintptr_t>(cu_seqlens_dev) % kVecBytes)
+    return fail(EARL_INVALID_ARG, "cu_seqlens buffer is misaligned");
+  for (int f = 0; f < n_fields; ++f) {
+    const earl_field& uf = fields[f];
+    const int64_t w = (int64_t)uf.scalar_bytes * uf.width;
+    if (!uf.src_shard_ptrs || !uf.dst_shard_ptrs || !uf.dst_capacity_rows || !uf.src_capacity_rows)
+      return fail(EARL_INVALID_ARG, "field %d: null pointer or capacity array", f);
+    if (uf.per_sequence != 0 && uf.per_sequence != 1)
+      return fail(EARL_INVALID_ARG, "field %d: per_sequence must be 0 or 1", f);
+    if (uf.per_sequence && w != 1 && w != 2 && w != 4 && w != 8)
+      return fail(EARL_INVALID_ARG, "field %d: a per-sequence field needs 1, 2, 4 or 8 row bytes", f);
+    if (uf.nonzero_counts)
+      return fail(EARL_INVALID_ARG, "field %d: nonzero_counts needs earl_dispatch", f);
+    for (int q = 0; q < n_dst; ++q) {
+      if (uf.dst_capacity_rows[q] < 0 || uf.dst_capacity_rows[q] > ((int64_t)1 << 40))
+        return fail(EARL_INVALID_ARG, "field %d: capacity of destination %d out of range", f, q);
+      if (uf.dst_capacity_rows[q] == 0) continue;
+      if (!uf.dst_shard_ptrs[q] || reinterpret_cast<uintptr_t>(uf.dst_shard_ptrs[q]) % kVecBytes)
+        return fail(EARL_INVALID_ARG, "field %d: destination %d is null or misaligned", f, q);
+    }
+    for (int s = 0; s < S; ++s) {
+      if (uf.src_capacity_rows[s] < 0)
+        return fail(EARL_INVALID_ARG, "field %d: capacity of source %d is negative", f, s);
+      if (uf.src_capacity_rows[s] == 0) continue;
+      if (!uf.src_shard_ptrs[s] ||
+          reinterpret_cast<uintptr_t>(uf.src_shard_ptrs[s]) % (uf.per_sequence ? w : uf.scalar_bytes))
+        return fail(EARL_INVALID_ARG, "field %d: source %d is null or misaligned", f, s);
+    }
+  }
+  if (position_ids_shard_ptrs)
+    for (int q = 0; q < n_dst; ++q) {
+      if (position_ids_capacity_rows[q] < 0 || position_ids_capacity_rows[q] > ((int64_t)1 << 40))
+        return fail(EARL_INVALID_ARG, "position ids: capacity of shard %d out of range", q);
+      if (position_ids_capacity_rows[q] == 0) continue;
+      if (!position_ids_shard_ptrs[q] ||
+          reinterpret_cast<uintptr_t>(position_ids_shard_ptrs[q]) % kVecBytes)
+        return fail(EARL_INVALID_ARG, "position ids of shard %d are null or misaligned", q);
+    }
+  return EARL_OK;
+}
+
+}  // namespace
+
+int32_t earl_dispatch_async_workspace_bytes(earl_plan* p, const earl_field* fields,
+                                            int32_t n_fields,
+                                            const int64_t* position_ids_capacity_rows,
+                                            int64_t cu_seqlens_capacity, size_t* out_bytes) {
+  if (!p || !out_bytes) return fail(EARL_INVALID_ARG, "null argument");
+  int32_t st = check_field_shapes(fields, n_fields);
+  if (st != EARL_OK) return st;
+  for (int f = 0; f < n_fields; ++f)
+    if (!fields[f].dst_capacity_rows) return fail(EARL_INVALID_ARG, "field %d: no capacities", f);
+  if (cu_seqlens_capacity < 0) return fail(EARL_INVALID_ARG, "negative cu_seqlens capacity");
+  const int F = n_fields + (position_ids_capacity_rows ? 1 : 0) + (cu_seqlens_capacity ? 1 : 0);
+  const int64_t tiles = count_tiles_by_capacity(p, fields, n_fields, position_ids_capacity_rows,
+                                                cu_seqlens_capacity);
+  *out_bytes = param_block_bytes(F, p->d.S, p->d.D * p->d.C) + kTileCodeBytes * (size_t)tiles;
+  return EARL_OK;
+}
+
+int32_t earl_dispatch_async(earl_plan* p, const earl_field* fields, int32_t n_fields,
+                            int32_t* const* position_ids_shard_ptrs,
+                            const int64_t* position_ids_capacity_rows, int32_t* cu_seqlens_dev,
+                            int64_t cu_seqlens_capacity, void* dispatch_ws_dev,
+                            size_t dispatch_ws_bytes, void* hip_stream) {
+  if (!p) return fail(EARL_INVALID_ARG, "null plan");
+  int32_t st = check_async_args(p, fields, n_fields, position_ids_shard_ptrs,
+                                position_ids_capacity_rows, cu_seqlens_dev, cu_seqlens_capacity);
+  if (st != EARL_OK) return st;
+  const int n_dst = p->d.D * p->d.C, S = p->d.S;
+  const int F = n_fields + (position_ids_shard_ptrs ? 1 : 0) + (cu_seqlens_dev ? 1 : 0);
+  if (F == 0) return EARL_OK;
+  BlockBuilder b;
+  b.init(F * n_dst, F, S, n_dst);
+  int64_t* ts = b.tile_start();
+  TileRec* recs = b.recs();
+  const void** ptrs = b.ptrs();
+  int64_t* rec_caps = b.rec_caps();
+  int64_t* src_caps = b.src_caps();
+  int32_t* src_per_sequence = b.src_per_sequence();
+  std::vector<TileRec> protos((size_t)F);
+  std::vector<const int64_t*> caps((size_t)F, nullptr);
+  uint32_t pi = 0;
+  for (int f = 0; f < F; ++f) {
+    TileRec& proto = protos[f];
+    proto = TileRec{};
+    proto.src_ptr_index = pi;
+    proto.dst_ptr_index = kNoCounters;
+    src_per_sequence[f] = 0;
+    for (int s = 0; s < S; ++s) src_caps[(size_t)f * S + s] = -1;
+    if (f < n_fields) {
+      const earl_field& uf = fields[f];
+      proto.kind = kFieldCopy;
+      proto.scalar_bytes = uf.scalar_bytes;
+      proto.row_bytes = uf.scalar_bytes * uf.width;
+      proto.pad_scalar = replicate_scalar(uf.pad_scalar, uf.scalar_bytes);
+      proto.per_sequence = (int16_t)uf.per_sequence;
+      src_per_sequence[f] = uf.per_sequence;
+      caps[f] = uf.dst_capacity_rows;
+      for (int s = 0; s < S; ++s) {
+        ptrs[pi + s] = uf.src_shard_ptrs[s];
+        src_caps[(size_t)f * S + s] = uf.src_capacity_rows[s];
+      }
+      for (int q = 0; q < n_dst; ++q) ptrs[pi + S + q] = uf.dst_shard_ptrs[q];
+    } else if (position_ids_shard_ptrs && f == n_fields) {
+      proto.kind = kFieldPositionIds;
+      proto.scalar_bytes = 4;
+      proto.row_bytes = 4;
+      caps[f] = position_ids_capacity_rows;
+      for (int q = 0; q < n_dst; ++q) ptrs[pi + S + q] = position_ids_shard_ptrs[q];
+    } else {
+      proto.kind = kFieldLinear;
+      proto.scalar_bytes = 4;
+      proto.row_bytes = 4;
+      ptrs[pi] = p->dev.cu_seqlens;
+      ptrs[pi + S] = cu_seqlens_dev;
+    }
+    proto.tile_shift = (int16_t)tile_shift_of(proto.row_bytes, proto.kind);
+    pi += S + 2 * n_dst;
+  }
+  // records in launch order (1 KiB tiles first); e_begin carries the shard number until the
+  // resolve kernel replaces it, end_bytes the capacity that sizes the grid
+  int64_t tiles = 0, fine = 0;
+  size_t n_rec = 0;
+  for (int pass = 0; pass < 2; ++pass) {
+    for (int f = 0; f < F; ++f) {
+      const TileRec& proto = protos[f];
+      if ((proto.tile_shift == kFineTileShift) != (pass == 0)) continue;
+      const int64_t tb = (int64_t)1 << proto.tile_shift;
+      for (int q = 0; q < n_dst; ++q) {
+        TileRec& r = recs[n_rec];
+        r = proto;
+        r.tile_first = tiles;
+        r.dst = const_cast<void*>(ptrs[proto.src_ptr_index + S + q]);
+        r.e_begin = q;
+        const int64_t cap = proto.kind == kFieldLinear ? (q == 0 ? cu_seqlens_capacity : 0) : caps[f][q];
+        rec_caps[n_rec] = cap;
+        r.end_bytes = cap * (int64_t)proto.row_bytes;
+        ts[n_rec++] = tiles;
+        tiles += (r.end_bytes + tb - 1) / tb;
+      }
+    }
+    if (pass == 0) fine = tiles;
+  }
+  ts[n_rec] = tiles;
+  if (fine + (tiles - fine) * kSubTiles > 0x7fffffffll)
+    return fail(EARL_INVALID_ARG, "too many tiles for one launch");
+  const size_t codes_off = b.bytes.size();
+  const size_t need = codes_off + kTileCodeBytes * (size_t)tiles;
+  if (!dispatch_ws_dev || reinterpret_cast<uintptr_t>(dispatch_ws_dev) % kAlign)
+    return fail(EARL_INVALID_ARG, "dispatch scratch is null or not %zu-byte aligned", kAlign);
+  if (dispatch_ws_bytes < need)
+    return fail(EARL_CAPACITY, "dispatch scratch has %zu bytes, %zu needed", dispatch_ws_bytes, need);
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  st = upload_params(b.bytes, dispatch_ws_dev, stream);
+  if (st != EARL_OK) return st;
+  launch_async_resolve(static_cast<DispatchDev*>(dispatch_ws_dev), p->dev, stream);
+  p->async_stream = stream;
+  p->async_used = true;
+  if (tiles > 0) {
+    CopyArgs ca = copy_args(p, dispatch_ws_dev, tiles);
+    ca.n_fine_tiles = fine;
+    void* codes = static_cast<unsigned char*>(dispatch_ws_dev) + codes_off;
+    launch_tile_codes(ca, codes, stream);
+    if (p->ev_before) HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(p->ev_before), stream));
+    launch_copy(ca, codes, stream);
+    if (p->ev_after) HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(p->ev_after), stream));
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess)
+    return fail(EARL_HIP_ERROR, "kernel launch failed: %s", hipGetErrorString(e));
+  return EARL_OK;
+}
+
+int32_t earl_dispatch_async_status(earl_plan* p, int32_t* status) {
+  if (!p || !status) return fail(EARL_INVALID_ARG, "null argument");
+  if (!p->async_used) return fail(EARL_INVALID_ARG, "no earl_dispatch_async call on this plan");
+  int64_t word = 0;
+  HIP_TRY(hipStreamSynchronize(p->async_stream));
+  HIP_TRY(hipMemcpy(&word, reinterpret_cast<unsigned char*>(p->dev.hdr) + offsetof(PlanHeader, async_status),
+                    sizeof(word), hipMemcpyDeviceToHost));
+  *status = (int32_t)word;
   return EARL_OK;
 }
 

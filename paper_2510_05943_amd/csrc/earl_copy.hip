@@ -152,6 +152,8 @@ enum TileAction : uint64_t {
   kActGeneric = 3,   // a = record index << 32 | segment of the tile's first byte
   kActCopyCount = 4, // as kActCopy for a 1 KiB tile of a counting field: tile_counter[tile] says
                      // which counter receives the tile's number of non-zero scalars
+  kActSkip = 5,      // nothing to do: the tile lies behind the end of its shard (a grid sized by
+                     // buffer capacities, earl_dispatch_async)
 };
 struct TileCode {
   uint64_t a, b;
@@ -206,6 +208,10 @@ __device__ __forceinline__ TileCode code_of_tile(const CopyArgs& a, const ParamV
   TileCode c;
   c.a = (uint64_t)(uint32_t)cur.x << 32;
   c.b = dst | kActGeneric;
+  if (lo >= rec.end_bytes) {
+    c.b = dst | kActSkip;
+    return c;
+  }
   if (rec.kind == kFieldLinear) {
     if (hi <= rec.end_bytes) {
       c.a = reinterpret_cast<uint64_t>(static_cast<const u8*>(pv.ptrs[rec.src_ptr_index]) + lo);
@@ -258,8 +264,10 @@ __global__ __launch_bounds__(kCodeThreads) void tile_code_kernel(const CopyArgs 
                         (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)first);
   const int x0 = last_le(pv.tile_start, 0, pv.n_recs, tile0);
   const TileRec rec0 = pv.recs[x0];
+  // (a shard without segments has no rows: all its tiles, if a capacity-sized grid gave it any,
+  // are skipped before a segment is looked at)
   int e_guess = rec0.e_begin;
-  if (rec0.kind != kFieldLinear)
+  if (rec0.kind != kFieldLinear && rec0.e_begin < rec0.e_end)
     e_guess = find_segment(a.segs, rec0.e_begin, rec0.e_end,
                            (tile0 - rec0.tile_first) << rec0.tile_shift, rec0.row_bytes);
 
@@ -267,7 +275,7 @@ __global__ __launch_bounds__(kCodeThreads) void tile_code_kernel(const CopyArgs 
   cursor_set_record(pv, cur, first < pv.tile_start[x0 + 1] ? x0
                                                              : last_le(pv.tile_start, x0, pv.n_recs, first));
   cur.e = cur.rec.e_begin;
-  if (cur.rec.kind != kFieldLinear) {
+  if (cur.rec.kind != kFieldLinear && cur.rec.e_begin < cur.rec.e_end) {
     const int64_t w = cur.rec.row_bytes;
     const int64_t lo = (first - cur.rec.tile_first) << cur.rec.tile_shift;
     if (cur.x == x0) {
@@ -286,9 +294,9 @@ __global__ __launch_bounds__(kCodeThreads) void tile_code_kernel(const CopyArgs 
         // next record (records without tiles are skipped by the search)
         cursor_set_record(pv, cur, last_le(pv.tile_start, cur.x, pv.n_recs, tile));
         cur.e = cur.rec.e_begin;
-        if (cur.rec.kind != kFieldLinear) cur.seg = a.segs[cur.e];
+        if (cur.rec.kind != kFieldLinear && cur.rec.e_begin < cur.rec.e_end) cur.seg = a.segs[cur.e];
       }
-      if (cur.rec.kind != kFieldLinear) {
+      if (cur.rec.kind != kFieldLinear && cur.rec.e_begin < cur.rec.e_end) {
         const int64_t w = cur.rec.row_bytes;
         const int64_t lo = (tile - cur.rec.tile_first) << cur.rec.tile_shift;
         if (lo >= (cur.seg.dst_row + cur.seg.n_rows) * w) {
@@ -417,18 +425,22 @@ __device__ __forceinline__ void counting_copy_tile(const CopyArgs a, const TileC
   if (lane == 0) add_to_counter(reinterpret_cast<int64_t*>(word & ~(uint64_t)7), n);
 }
 
-__device__ __noinline__ void rare_tile(const CopyArgs a, const TileCode c, const int64_t tile,
+__device__ __forceinline__ void rare_tile(const CopyArgs a, const TileCode c, const int64_t tile,
                                        const uint32_t vec0) {
-  if ((c.b & 15u) == kActCopyCount) counting_copy_tile(a, c, tile);
+  const uint64_t act = c.b & 15u;
+  if (act == kActSkip) return;
+  if (act == kActCopyCount) counting_copy_tile(a, c, tile);
   else generic_tile(a, c, tile, vec0);
 }
 
 // Pass 2: one-wavefront workgroups, one 16-byte vector per lane: one workgroup per 1 KiB tile
 // code (the first n_fine_tiles codes), kSubTiles workgroups per 4 KiB tile code (the rest).
-// The second launch bound asks for 8 wavefronts per SIMD (at most 64 VGPRs): the rare path alone
-// would need a few more registers, and at 7 wavefronts per SIMD the copy measured 2.5 % slower:
-// every wavefront waits for its tile code and then for its data, so the bytes in flight, and
-// with them the bandwidth, follow the number of resident wavefronts.
+// The second launch bound asks for 8 wavefronts per SIMD (at most 64 VGPRs): at 7 the copy
+// measured 2.5 % slower; every wavefront waits for its tile code and then for its data, so the
+// bytes in flight, and with them the bandwidth, follow the number of resident wavefronts.  The
+// rare path is inlined: as a called function it kept its uniform arguments in vector registers
+// and saved callee-saved registers to scratch memory, and a kernel that owns scratch memory
+// starts about 9 us later, which is a third of the kernel's time on the small workloads.
 __global__ __launch_bounds__(kCopyThreads, 8) void relayout_kernel(const CopyArgs a,
                                                                    const TileCode* __restrict__ codes) {
   // consecutive workgroups go to different XCDs; grouping a tile's workgroups on one XCD
@@ -457,6 +469,51 @@ __global__ __launch_bounds__(kCopyThreads, 8) void relayout_kernel(const CopyArg
   } else {
     rare_tile(a, c, tile, vec0);
   }
+}
+
+// earl_dispatch_async: the host built the records from buffer capacities, with the destination
+// shard number in e_begin; one workgroup checks the plan's status and every capacity against the
+// plan in device memory and completes the records (segment range, bytes of the shard).  If
+// anything is wrong every record gets zero bytes, so the two passes that follow write nothing.
+constexpr int kResolveThreads = 256;
+__global__ __launch_bounds__(kResolveThreads) void async_resolve_kernel(DispatchDev* params,
+                                                                        const PlanDev plan) {
+  u8* base = reinterpret_cast<u8*>(params);
+  const DispatchDev hd = *params;
+  TileRec* recs = reinterpret_cast<TileRec*>(base + hd.recs_ofs);
+  const int64_t* rec_caps = reinterpret_cast<const int64_t*>(base + hd.rec_caps_ofs);
+  const int64_t* src_caps = reinterpret_cast<const int64_t*>(base + hd.src_caps_ofs);
+  const int32_t* per_seq = reinterpret_cast<const int32_t*>(base + hd.src_per_sequence_ofs);
+  const PlanHeader* ph = plan.hdr;
+  const int tid = threadIdx.x;
+  int fits = 1;
+  for (int x = tid; x < hd.n_recs; x += kResolveThreads) {
+    const int q = recs[x].e_begin;
+    const int64_t rows = recs[x].kind == kFieldLinear ? (q == 0 ? ph->cu_seqlens_len : 0)
+                                                      : plan.shard_rows[q];
+    if (rows > rec_caps[x]) fits = 0;
+  }
+  for (int x = tid; x < hd.n_fields * plan.S; x += kResolveThreads) {
+    const int f = x / plan.S, sh = x - f * plan.S;
+    const int64_t need = per_seq[f] ? plan.src_seqs_needed[sh] : plan.src_rows_needed[sh];
+    if (src_caps[x] >= 0 && need > src_caps[x]) fits = 0;
+  }
+  const int all_fit = __syncthreads_and(fits);
+  const int32_t plan_status = ph->status;
+  const bool go = plan_status == 0 && all_fit;
+  for (int x = tid; x < hd.n_recs; x += kResolveThreads) {
+    TileRec r = recs[x];
+    const int q = r.e_begin;
+    const int64_t rows = r.kind == kFieldLinear ? (q == 0 ? ph->cu_seqlens_len : 0)
+                                                : plan.shard_rows[q];
+    // a failed plan leaves no segment table behind: empty ranges, nothing is looked up
+    r.e_begin = go ? plan.shard_seg_start[q] : 0;
+    r.e_end = go ? plan.shard_seg_start[q + 1] : 0;
+    r.end_bytes = go ? rows * (r.kind == kFieldLinear ? 4 : (int64_t)r.row_bytes) : 0;
+    recs[x] = r;
+  }
+  if (tid == 0)
+    plan.hdr->async_status = plan_status != 0 ? plan_status : (all_fit ? 0 : (int64_t)kStatusCapacity);
 }
 
 __global__ void zero_i64_kernel(int64_t* p, int64_t n) {
@@ -547,7 +604,7 @@ __global__ __launch_bounds__(kCodeThreads) void inverse_code_kernel(const Invers
   codes[tile] = c;
 }
 
-__device__ __noinline__ void generic_inverse_tile(const InverseArgs a, const TileCode c,
+__device__ __forceinline__ void generic_inverse_tile(const InverseArgs a, const TileCode c,
                                                   const int64_t tile, const uint32_t vec0) {
   const ParamView pv = view_params(a.c.params);
   const TileRec rec = pv.recs[(uint32_t)(c.b >> 32)];
@@ -588,7 +645,7 @@ __device__ __noinline__ void generic_inverse_tile(const InverseArgs a, const Til
   }
 }
 
-__global__ __launch_bounds__(kCopyThreads) void inverse_kernel(const InverseArgs a,
+__global__ __launch_bounds__(kCopyThreads, 8) void inverse_kernel(const InverseArgs a,
                                                                const TileCode* __restrict__ codes) {
   // as in the forward kernel: one workgroup per 1 KiB tile code, kSubTiles per 4 KiB tile code
   int64_t tile = blockIdx.x;
@@ -629,6 +686,10 @@ void launch_zero_counters(int64_t* counters, int64_t n, hipStream_t stream) {
   if (n <= 0) return;
   hipLaunchKernelGGL(zero_i64_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream,
                      counters, n);
+}
+
+void launch_async_resolve(DispatchDev* params, const PlanDev& plan, hipStream_t stream) {
+  hipLaunchKernelGGL(async_resolve_kernel, dim3(1), dim3(kResolveThreads), 0, stream, params, plan);
 }
 
 void launch_real_prefix(const SegRec* segs, int64_t* prefix, int n_seg, hipStream_t stream) {

@@ -30,6 +30,8 @@ constexpr int kTilesPerLane = 4;     // tile-code kernel: consecutive tiles per 
                                      // than 8, 1.3x faster than 1 on the 12 M tiles of the largest workload)
 constexpr int kCodeThreads = 256;    // tile-code kernel workgroup
 
+constexpr int kStatusCapacity = 3;   // EARL_CAPACITY, for device code
+
 // First bytes of the workspace; copied to the host together with the arrays that follow it.
 struct PlanHeader {
   int32_t status;
@@ -43,7 +45,8 @@ struct PlanHeader {
   int64_t total_dst_rows;
   int64_t rank_load_min;
   int64_t rank_load_max;
-  int64_t reserved_[10];
+  int64_t async_status;    // written by the last earl_dispatch_async on this plan (0 = carried out)
+  int64_t reserved_[9];
 };
 static_assert(sizeof(PlanHeader) == 144, "PlanHeader layout");
 
@@ -141,11 +144,18 @@ static_assert(sizeof(TileRec) == 64, "TileRec layout");
 // every record, then the total), recs[n_recs], pointer table.
 struct DispatchDev {
   int32_t n_recs;
-  int32_t pad_;
+  int32_t n_fields;         // earl_dispatch_async only: rows of src_caps
   uint32_t tile_start_ofs;  // byte offsets from the start of the block
   uint32_t recs_ofs;
   uint32_t ptrs_ofs;
   uint32_t total_bytes;
+  // earl_dispatch_async only: rec_caps[n_recs] rows (kFieldLinear: entries) each record's
+  // buffer holds; src_caps[n_fields][S] rows each source buffer holds (-1 = not checked);
+  // src_per_sequence[n_fields]
+  uint32_t rec_caps_ofs;
+  uint32_t src_caps_ofs;
+  uint32_t src_per_sequence_ofs;
+  uint32_t pad_;
 };
 
 struct CopyArgs {
@@ -169,6 +179,8 @@ void launch_tile_codes(const CopyArgs& a, void* tile_codes, hipStream_t stream);
 void launch_copy(const CopyArgs& a, const void* tile_codes, hipStream_t stream);
 // seg_real_prefix[e] = real rows of the segments before e (n_seg+1 entries)
 void launch_zero_counters(int64_t* counters, int64_t n, hipStream_t stream);
+// earl_dispatch_async: completes the records of a parameter block from the plan in device memory
+void launch_async_resolve(DispatchDev* params, const PlanDev& plan, hipStream_t stream);
 void launch_real_prefix(const SegRec* segs, int64_t* prefix, int n_seg, hipStream_t stream);
 void launch_copy_inverse(const CopyArgs& a, const int64_t* seg_real_prefix,
                          const int32_t* seg_dst_shard, int n_seg, void* tile_codes,
