@@ -287,10 +287,14 @@ __device__ void lpt_packed(const PlanDev& p, const uint64_t* keys) {
       if (kSteps >= 2) mn = dpp_min_all_rows<kDppQuadXor2>(mn);
       if (kSteps >= 3) mn = dpp_min_all_rows<kDppRowHalfMirror>(mn);
       if (kSteps >= 4) mn = dpp_min_all_rows<kDppRowMirror>(mn);
-      // the winner is the lane whose own word is the minimum (all words are distinct); its
-      // updated word is prepared beside the reduction, so the chain is butterfly, compare, select
-      const uint32_t grown = word + lp_s;
-      const bool win = valid && mn == word;
+      // the winner is the lane whose own word is the minimum (all words are distinct; a lane
+      // without a rank holds all ones and never equals the minimum of a group that has a rank,
+      // and a group without any rank is never read).  Its updated word is prepared beside the
+      // reduction, so the chain is butterfly, compare, select; the empty statement keeps the
+      // compiler from turning the select into select-then-add, which puts the add on the chain
+      uint32_t grown = word + lp_s;
+      asm volatile("" : "+v"(grown));
+      const bool win = mn == word;
       word = win ? grown : word;
       if (s < 32) won_lo |= win ? (1u << s) : 0u;
       else won_hi |= win ? (1u << (s - 32)) : 0u;
