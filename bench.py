@@ -342,7 +342,7 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU's share of the re-layout (all destination shards in one "
-              "HBM); there is no multi-GPU path in this build: run with --gpus 1", file=sys.stderr)
+              "HBM); this library has no multi-GPU path: run with --gpus 1", file=sys.stderr)
         return 2
 
     import torch
