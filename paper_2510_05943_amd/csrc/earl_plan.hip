@@ -12,6 +12,8 @@
 // workgroup: phases are separated by workgroup barriers, wide phases use all 1024 lanes, the
 // serial chain runs in wavefront 0 with the rank loads held one per lane and the arg-min taken
 // by DPP cross-lane operations.
+#include <utility>
+
 #include "earl_internal.h"
 
 namespace earl {
@@ -39,6 +41,8 @@ constexpr int kDppRowMirror = 0x140;
 constexpr int kDppRowBcast15 = 0x142;
 constexpr int kDppRowBcast31 = 0x143;
 constexpr int kDppRowShr = 0x110;       // + n
+constexpr int kDppRowShl1 = 0x101;      // row_shl:1, lane i reads lane i+1 of its row of 16
+constexpr int kDppWaveShl1 = 0x130;     // wave_shl:1, the same over all 64 lanes
 
 // Inclusive prefix sum over the 64 lanes: Hillis-Steele inside each row of 16 lanes with
 // row_shr, then the row totals are carried across rows with row_bcast.
@@ -257,79 +261,58 @@ __device__ __forceinline__ uint32_t wave_min_low(uint32_t x) {
   return (uint32_t)__builtin_amdgcn_readlane((int)x, kSteps >= 5 ? 63 : 0);
 }
 
-// D <= 16, one rank per lane, loads small enough that (load << 6 | lane) fits 32 bits for the
-// whole run: the lane number rides in the low six bits of the compared word, so one butterfly
-// yields the minimum load AND the lowest rank that has it (the lane bits make all words
-// distinct, and equal loads order by lane).  Lanes >= D hold 0xffffffff and never win.
-// After the butterfly every lane of the group holds the winning word, so the whole step stays
-// in the vector ALU (no scalar round trip): compare the low bits with the own lane number, add
-// the padded length if they match, and note the step in a 64-bit "won" mask.  After 64 steps
-// the masks are turned into ranks.  Items past N have length 0 and come last, so running full
-// blocks of 64 steps changes nothing.
-template <int kSteps>
-__device__ void lpt_packed(const PlanDev& p, const uint64_t* keys) {
-  static_assert(kSteps <= 4, "the butterfly must stay inside one row of 16 lanes");
+// D <= 64, loads small enough that (load << 6 | rank) fits 32 bits for the whole run.
+//
+// The ranks are kept SORTED by that word across the lanes (lane 0 holds the least loaded rank,
+// the lowest one among equals since the rank number sits in the low bits; lanes >= D hold all
+// ones).  A step takes the head, adds the sequence's padded length and puts the word back in
+// its place: with w'[i] = w[i+1] (the list without its head) the new list is
+//     w_new[i] = min(w'[i], max(w[i], grown))
+// (below the insertion point w'[i] < grown, so the min keeps w'[i]; at it w[i] < grown < w'[i]
+// gives grown; above it w[i] > grown and w[i] < w'[i] keep w[i]).  That is one v_max and one
+// v_min with a DPP lane shift, against a log2(D)-step butterfly plus compare and select when
+// the loads stay in place and the minimum is searched; head and grown word travel through
+// scalar registers, and the winner (head & 63) is written into lane s of `ranks`.
+// kShift: row_shl:1 when the ranks fit one row of 16 lanes, else wave_shl:1.
+// Items past N have length 0 and come last: the head is put back where it was.
+template <int kLane>
+__device__ __forceinline__ void writelane_const(uint32_t& v, uint32_t value) {
+  // v_writelane_b32 has no builtin in this compiler; lane number is an immediate
+  asm volatile("v_writelane_b32 %0, %1, %2" : "+v"(v) : "s"(value), "n"(kLane));
+}
+
+template <int kShift, int kItem>
+__device__ __forceinline__ void lpt_sorted_step(uint32_t& word, uint32_t& ranks, uint32_t lp6) {
+  const uint32_t lp_s = (uint32_t)__builtin_amdgcn_readlane((int)lp6, kItem);
+  const uint32_t head = (uint32_t)__builtin_amdgcn_readfirstlane((int)word);
+  const uint32_t grown = head + lp_s;
+  const uint32_t t = word > grown ? word : grown;
+  // lanes without a right-hand neighbour (end of the row or of the wavefront) read all ones
+  const uint32_t next = (uint32_t)__builtin_amdgcn_update_dpp((int)0xffffffffu, (int)word, kShift,
+                                                              0xf, 0xf, false);
+  word = next < t ? next : t;
+  writelane_const<kItem>(ranks, head & 63u);
+}
+
+template <int kShift, int... kItems>
+__device__ __forceinline__ void lpt_sorted_block(uint32_t& word, uint32_t& ranks, uint32_t lp6,
+                                                 std::integer_sequence<int, kItems...>) {
+  (lpt_sorted_step<kShift, kItems>(word, ranks, lp6), ...);
+}
+
+template <int kShift>
+__device__ void lpt_sorted(const PlanDev& p, const uint64_t* keys) {
   const int lane = lane_id();
-  const int N = p.N, D = p.D;
-  const bool valid = lane < D;
-  uint32_t word = valid ? (uint32_t)lane : 0xffffffffu;   // load << 6 | lane
+  const int N = p.N;
+  uint32_t word = lane < p.D ? (uint32_t)lane : 0xffffffffu;   // load << 6 | rank
   for (int start = 0; start < N; start += kWave) {
     const int i = start + lane;
     const uint64_t key = i < N ? keys[i] : ~0ull;
     const uint32_t lp6 = i < N ? (uint32_t)(0x7fffffff - (int32_t)(key >> 32)) << 6 : 0u;
     const int32_t idx = (int32_t)(key & 0xffffffffu);
-    uint32_t won_lo = 0, won_hi = 0;
-#pragma unroll
-    for (int s = 0; s < kWave; ++s) {
-      const uint32_t lp_s = (uint32_t)__builtin_amdgcn_readlane((int)lp6, s);
-      uint32_t mn = word;
-      if (kSteps >= 1) mn = dpp_min_all_rows<kDppQuadXor1>(mn);
-      if (kSteps >= 2) mn = dpp_min_all_rows<kDppQuadXor2>(mn);
-      if (kSteps >= 3) mn = dpp_min_all_rows<kDppRowHalfMirror>(mn);
-      if (kSteps >= 4) mn = dpp_min_all_rows<kDppRowMirror>(mn);
-      // the winner is the lane whose own word is the minimum (all words are distinct; a lane
-      // without a rank holds all ones and never equals the minimum of a group that has a rank,
-      // and a group without any rank is never read).  Its updated word is prepared beside the
-      // reduction, so the chain is butterfly, compare, select; the empty statement keeps the
-      // compiler from turning the select into select-then-add, which puts the add on the chain
-      uint32_t grown = word + lp_s;
-      asm volatile("" : "+v"(grown));
-      const bool win = mn == word;
-      word = win ? grown : word;
-      if (s < 32) won_lo |= win ? (1u << s) : 0u;
-      else won_hi |= win ? (1u << (s - 32)) : 0u;
-    }
-    int my_rank = 0;
-    for (int r = 0; r < D; ++r) {
-      const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)won_lo, r);
-      const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)won_hi, r);
-      const uint64_t steps = ((uint64_t)hi << 32) | lo;
-      if ((steps >> lane) & 1ull) my_rank = r;
-    }
-    if (i < N) p.rank[idx] = my_rank;
-  }
-}
-
-// 16 < D <= 64 with small loads: the same packed word, reduced over all 64 lanes and read back
-// through a scalar register.
-__device__ void lpt_packed_wave(const PlanDev& p, const uint64_t* keys) {
-  const int lane = lane_id();
-  const int N = p.N;
-  uint32_t word = lane < p.D ? (uint32_t)lane : 0xffffffffu;   // load << 6 | lane
-  for (int start = 0; start < N; start += kWave) {
-    const int i = start + lane;
-    const uint64_t key = i < N ? keys[i] : ~0ull;
-    const uint32_t lp6 = (uint32_t)(0x7fffffff - (int32_t)(key >> 32)) << 6;
-    const int32_t idx = (int32_t)(key & 0xffffffffu);
-    int my_rank = 0;
-    const int cnt = min(kWave, N - start);
-    for (int s = 0; s < cnt; ++s) {
-      const uint32_t lp_s = (uint32_t)__builtin_amdgcn_readlane((int)lp6, s);
-      const int wl = (int)(wave_min_low<6>(word) & 63u);
-      word += lane == wl ? lp_s : 0u;
-      my_rank = lane == s ? wl : my_rank;
-    }
-    if (i < N) p.rank[idx] = my_rank;
+    uint32_t ranks = 0;   // lane s: rank of the s-th item of this block
+    lpt_sorted_block<kShift>(word, ranks, lp6, std::make_integer_sequence<int, kWave>{});
+    if (i < N) p.rank[idx] = (int32_t)ranks;
   }
 }
 
@@ -427,16 +410,10 @@ __device__ void lpt_wave0(const PlanDev& p, const uint64_t* keys, int64_t* lds_l
   } else if (((int64_t)p.N * max_lp / D + max_lp) >= (1 << 26)) {
     // some load could reach 2^26: the packed word would overflow
     lpt_one_per_lane(p, keys);
-  } else if (D <= 2) {
-    lpt_packed<1>(p, keys);
-  } else if (D <= 4) {
-    lpt_packed<2>(p, keys);
-  } else if (D <= 8) {
-    lpt_packed<3>(p, keys);
   } else if (D <= 16) {
-    lpt_packed<4>(p, keys);
+    lpt_sorted<kDppRowShl1>(p, keys);
   } else {
-    lpt_packed_wave(p, keys);
+    lpt_sorted<kDppWaveShl1>(p, keys);
   }
 }
 
