@@ -13,6 +13,7 @@ import os
 
 import numpy as np
 import pytest
+from hypothesis import HealthCheck, given, settings, strategies as st
 
 import checkers
 from oracle import earl_oracle as O
@@ -460,6 +461,29 @@ def _read_rows(plan, s, rows):
         if int(plan.seq_shard[i]) == s:
             sel[int(plan.seq_row[i]): int(plan.seq_row[i]) + int(plan.L[i])] = True
     return sel
+
+
+@settings(max_examples=120, deadline=None, derandomize=True,
+          suppress_health_check=[HealthCheck.too_slow, HealthCheck.data_too_large])
+@given(st.data())
+def test_all_pins_on_drawn_batches(data):
+    """The same pins on batches drawn by hypothesis (fixed seed): layouts with more ranks than
+    sequences, single-row sequences, budgets that fit exactly one sequence, scattered groups."""
+    n = data.draw(st.integers(1, 18), label="N")
+    C = data.draw(st.sampled_from([1, 2, 3, 4, 5]), label="C")
+    z = data.draw(st.integers(0, 1), label="zigzag")
+    P = data.draw(st.sampled_from([1, 1, 2, 3, 8]), label="P")
+    L = np.array(data.draw(st.lists(st.integers(1, 70), min_size=n, max_size=n), label="L"))
+    G = data.draw(st.integers(1, 4), label="G")
+    K = 2 * C if (z and C > 1) else C
+    worst = K * P * (-(-(-(-int(L.max()) // K)) // P))
+    case = dict(L=L, G=G, R=data.draw(st.sampled_from([1, 2, 3]), label="R"),
+                D=data.draw(st.integers(1, 6), label="D"), C=C, z=z, P=P,
+                B=worst + data.draw(st.integers(0, 3 * worst), label="extra budget"),
+                grp=(np.array(data.draw(st.lists(st.integers(0, G - 1), min_size=n, max_size=n),
+                                        label="groups")) if data.draw(st.booleans()) else None),
+                seed=data.draw(st.integers(0, 1000), label="seed"))
+    all_pins_on_small_case(case)
 
 
 @pytest.mark.parametrize("case", small_cases(), ids=lambda c: f"case{c['seed']}")
