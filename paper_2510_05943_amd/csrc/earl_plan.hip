@@ -316,28 +316,45 @@ __device__ void lpt_sorted(const PlanDev& p, const uint64_t* keys) {
   }
 }
 
-// D <= 64, one rank per lane, any padded length: minimum first, then the first lane that has it.
-__device__ void lpt_one_per_lane(const PlanDev& p, const uint64_t* keys) {
+// The same sorted list with 64-bit words (two registers per lane), for loads that do not fit 26
+// bits: huge padded lengths, or the quadratic cost (kQuadratic: a rank's load grows by the
+// square of the padded length).  D <= 64 and loads below 2^58.
+template <bool kQuadratic, int kItem>
+__device__ __forceinline__ void lpt_sorted64_step(uint64_t& word, uint32_t& ranks, uint32_t lp) {
+  const uint32_t lp_s = (uint32_t)__builtin_amdgcn_readlane((int)lp, kItem);
+  const uint64_t cost = kQuadratic ? (uint64_t)lp_s * lp_s : (uint64_t)lp_s;
+  const uint32_t head_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)word);
+  const uint32_t head_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(word >> 32));
+  const uint64_t grown = (((uint64_t)head_hi << 32) | head_lo) + (cost << 6);
+  const uint64_t t = word > grown ? word : grown;
+  const uint32_t next_lo = (uint32_t)__builtin_amdgcn_update_dpp(
+      (int)0xffffffffu, (int)(uint32_t)word, kDppWaveShl1, 0xf, 0xf, false);
+  const uint32_t next_hi = (uint32_t)__builtin_amdgcn_update_dpp(
+      (int)0xffffffffu, (int)(uint32_t)(word >> 32), kDppWaveShl1, 0xf, 0xf, false);
+  const uint64_t next = ((uint64_t)next_hi << 32) | next_lo;
+  word = next < t ? next : t;
+  writelane_const<kItem>(ranks, head_lo & 63u);
+}
+
+template <bool kQuadratic, int... kItems>
+__device__ __forceinline__ void lpt_sorted64_block(uint64_t& word, uint32_t& ranks, uint32_t lp,
+                                                   std::integer_sequence<int, kItems...>) {
+  (lpt_sorted64_step<kQuadratic, kItems>(word, ranks, lp), ...);
+}
+
+template <bool kQuadratic>
+__device__ void lpt_sorted64(const PlanDev& p, const uint64_t* keys) {
   const int lane = lane_id();
   const int N = p.N;
-  const bool valid = lane < p.D;
-  uint32_t rel = valid ? 0u : 0xffffffffu;   // load - min load
+  uint64_t word = lane < p.D ? (uint64_t)lane : ~0ull;   // load << 6 | rank
   for (int start = 0; start < N; start += kWave) {
     const int i = start + lane;
     const uint64_t key = i < N ? keys[i] : ~0ull;
-    const uint32_t lp = (uint32_t)(0x7fffffff - (int32_t)(key >> 32));
+    const uint32_t lp = i < N ? (uint32_t)(0x7fffffff - (int32_t)(key >> 32)) : 0u;
     const int32_t idx = (int32_t)(key & 0xffffffffu);
-    int my_rank = 0;
-    const int cnt = min(kWave, N - start);
-    for (int s = 0; s < cnt; ++s) {
-      const uint32_t lp_s = (uint32_t)__builtin_amdgcn_readlane((int)lp, s);
-      const uint32_t mn = wave_min_low<6>(rel);
-      const int wl = __builtin_ctzll(__ballot(rel == mn));
-      const uint32_t next = rel - mn + (lane == wl ? lp_s : 0u);
-      rel = valid ? next : rel;
-      my_rank = lane == s ? wl : my_rank;
-    }
-    if (i < N) p.rank[idx] = my_rank;
+    uint32_t ranks = 0;
+    lpt_sorted64_block<kQuadratic>(word, ranks, lp, std::make_integer_sequence<int, kWave>{});
+    if (i < N) p.rank[idx] = (int32_t)ranks;
   }
 }
 
@@ -403,13 +420,17 @@ __device__ void lpt_blocks(const PlanDev& p, const uint64_t* keys, int64_t* lds_
 __device__ void lpt_wave0(const PlanDev& p, const uint64_t* keys, int64_t* lds_load) {
   const int D = p.D;
   const int64_t max_lp = 0x7fffffffll - (int64_t)(keys[0] >> 32);   // keys are sorted
-  if (p.policy == 2) {
-    lpt_blocks<true>(p, keys, lds_load);
-  } else if (D > kWave) {
-    lpt_blocks<false>(p, keys, lds_load);
-  } else if (((int64_t)p.N * max_lp / D + max_lp) >= (1 << 26)) {
-    // some load could reach 2^26: the packed word would overflow
-    lpt_one_per_lane(p, keys);
+  const bool quadratic = p.policy == 2;
+  // no load exceeds total / D + the largest cost (the bound of list scheduling)
+  const int64_t max_cost = quadratic ? max_lp * max_lp : max_lp;      // <= 2^42, N * it <= 2^62
+  const int64_t load_bound = (int64_t)p.N * max_cost / D + max_cost;
+  if (D > kWave || load_bound >= (1ll << 58)) {
+    if (quadratic) lpt_blocks<true>(p, keys, lds_load);
+    else lpt_blocks<false>(p, keys, lds_load);
+  } else if (quadratic) {
+    lpt_sorted64<true>(p, keys);
+  } else if (load_bound >= (1 << 26)) {
+    lpt_sorted64<false>(p, keys);
   } else if (D <= 16) {
     lpt_sorted<kDppRowShl1>(p, keys);
   } else {
