@@ -168,7 +168,10 @@ int32_t earl_plan_workspace_bytes(int32_t n_seqs, const earl_src_layout* src,
                                   const earl_dst_layout* dst, size_t* out_bytes);
 
 /*
- * Computes the dispatch plan on the device (asynchronously on the stream):
+ * Computes the dispatch plan on the device (asynchronously on the stream).  This is the decision
+ * part of Section 2, "Data Dispatcher" (dispatch logic that follows the current data layout and the
+ * consumer's parallelism configuration, every piece sent from where it was computed to where it is
+ * needed); the paper gives no rules, the ones below are this library's:
  *   source row offsets (segmented scan of lengths per group) and the replica each sequence is read
  *   from; chunk length m = P*ceil(ceil(L/K)/P) with K = 2*sp (zigzag, sp > 1) or sp, padded length
  *   K*m; longest-first assignment of sequences to DP ranks (ties: lower index, lower rank);
@@ -226,7 +229,10 @@ int32_t earl_dispatch_workspace_bytes(earl_plan* plan, const earl_field* fields,
 
 /*
  * Materialises every destination shard of every field (asynchronously on the stream; the first call
- * on a plan waits for the plan as earl_plan_get_summary does).
+ * on a plan waits for the plan as earl_plan_get_summary does).  This is the data movement of
+ * Section 2, "Data Dispatcher": every row goes straight from the buffer it was produced in to its
+ * place in the training layout, with no gathered intermediate copy (Section 1: the volume of these
+ * batches is the bottleneck).
  *   fields[n_fields]             0 <= n_fields <= EARL_MAX_FIELDS.
  *   position_ids_shard_ptrs      host array[D*C] of device int32 buffers (16-byte aligned, at least
  *                                shard_rows[q] entries), or NULL: logical position of every row,
@@ -283,8 +289,8 @@ int32_t earl_dispatch_async_status(earl_plan* plan, int32_t* status);
 int32_t earl_plan_set_dispatch_events(earl_plan* plan, void* event_before, void* event_after);
 
 /*
- * The reverse direction (training layout back to the rollout layout, for the stages that run
- * between several models): every real row of every destination shard is copied back to the source
+ * The reverse direction (training layout back to the rollout layout; Section 2 describes dispatches
+ * between several stages of a step, so data also has to come back): every real row of every destination shard is copied back to the source
  * row it was read from.  Field descriptors as in earl_dispatch with the roles of the two pointer
  * arrays unchanged (dst_shard_ptrs is read, src_shard_ptrs is written; both only need alignment to
  * scalar_bytes).  Rows of the source buffers that the plan does not read are left untouched.
