@@ -205,7 +205,8 @@ def run_gpu(args, torch, B, synth):
     achieved = algo_bytes / (kern_avg_ms * 1e-3) / 1e9
     traffic = None if (args.inverse or args.balance_policy) else MEASURED_TRAFFIC.get(kernel_source_hash(), {}).get(args.workload)
     return dict(w=w, sm=sm, ms_per_step=ms_per_step, kern_avg_ms=kern_avg_ms,
-                kern_min_ms=float(np.min(kern_ms)), achieved=achieved, algo_bytes=algo_bytes,
+                kern_min_ms=float(np.min(kern_ms)), kern_median_ms=float(np.median(kern_ms)),
+                achieved=achieved, algo_bytes=algo_bytes,
                 traffic=traffic, stage_s=stage_s, row_bytes=row_bytes,
                 plan_ms=float(np.median(plan_ms)), dispatch_ms=float(np.median(dispatch_ms)))
 
@@ -385,7 +386,8 @@ def main() -> int:
                      "kernel": ("inverse_kernel" if args.inverse else
                                 "relayout_kernel (both passes)" if args.two_pass else "relayout_kernel"),
                      "algorithmic_bytes_per_launch": r["algo_bytes"],
-                     "kernel_ms_avg": r["kern_avg_ms"], "kernel_ms_min": r["kern_min_ms"]},
+                     "kernel_ms_avg": r["kern_avg_ms"], "kernel_ms_min": r["kern_min_ms"],
+                     "kernel_ms_median": r.get("kern_median_ms")},
         "input_staging_s": r["stage_s"],
     }
     if "plan_ms" in r:
