@@ -561,6 +561,23 @@ def test_batch_volume_matches_the_papers_table():
                 sent + plan.total_dst_rows * bpt
 
 
+def test_payload_per_worker_matches_section_3_3():
+    """The three per-worker payloads Section 3.3 prints for its log-probability tensors: the rows
+    one source worker sends (its row of the all-to-all counts) times 4 bytes, truncated to MiB."""
+    g = gold("section33_payload_per_worker.json")
+    lo, hi = g["n_range_that_reproduces_all_three"]
+    for n in (lo - 1, lo, g["n_seqs_per_worker"], hi, hi + 1):
+        got = []
+        for ctx in g["context_length"]:
+            # two source workers of n sequences each, consumers in a DP4 x SP2 layout
+            plan = O.build_plan(np.full((2 * n,), ctx), n_groups=2, dp=4, sp=2, zigzag=1,
+                                pad_multiple=1, mb_token_budget=1 << 40)
+            sent = plan.a2a_counts.sum(axis=1) * g["bytes_per_token"]
+            assert sent[0] == sent[1]
+            got.append(int(sent[0]) >> 20)
+        assert (got == g["payload_MiB_truncated"]) == (lo <= n <= hi), (n, got)
+
+
 def test_plan_ignores_field_contents_and_is_deterministic():
     w = synth.make_workload("mid", seed=2, scale=0.125)
     a, b = plan_of(w), plan_of(w)
