@@ -35,8 +35,8 @@ HBM_PEAK_GBPS = 8000.0
 # (scaled by a plain copy kernel of known size, see profiles/), keyed by the sha256 of the kernel
 # source the counters were taken on.  A changed kernel reports null until re-measured.
 MEASURED_TRAFFIC = {
-    "8bbb185e9b7f3047d04a08184759a20834dab4abb5de45160daa31ec217296f2":
-        {"heavy": 52882794788, "longctx": 47518216247},
+    "d0a85392b766bbb5432e4f6108622688dcbd08379d546725dfed660a5521bdfe":
+        {"heavy": 52882862112, "longctx": 47518210557},
 }
 
 WORKLOAD_NOTES = {

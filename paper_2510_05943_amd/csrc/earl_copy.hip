@@ -540,6 +540,7 @@ __global__ __launch_bounds__(kPlanThreads) void real_prefix_kernel(const SegRec*
   const int b = (int64_t)tid * per < n_seg ? tid * per : n_seg;
   const int e = b + per < n_seg ? b + per : n_seg;
   int64_t s = 0;
+#pragma unroll 8
   for (int x = b; x < e; ++x) s += segs[x].n_real;
   int64_t incl = s;
   for (int d = 1; d < kWave; d <<= 1) {
@@ -577,31 +578,63 @@ struct InverseArgs {
 
 // Inverse tile codes: a = training-layout pointer of the tile's first byte (0 = generic tile,
 // then b = record << 32 | first segment), b = rollout-layout pointer (any alignment).
+// Organised like tile_code_kernel: the wavefront's first tile is searched with uniform values,
+// every lane writes kTilesPerLane consecutive codes and carries its segment along.
 __global__ __launch_bounds__(kCodeThreads) void inverse_code_kernel(const InverseArgs a,
                                                                    TileCode* codes) {
-  const int64_t tile = (int64_t)blockIdx.x * kCodeThreads + threadIdx.x;
-  if (tile >= a.c.n_tiles) return;
+  const int64_t first = ((int64_t)blockIdx.x * kCodeThreads + threadIdx.x) * kTilesPerLane;
+  if (first >= a.c.n_tiles) return;
   const ParamView pv = view_params(a.c.params);
-  const int f = last_le(pv.tile_start, 0, pv.n_recs, tile);   // one record per field
-  const TileRec rec = pv.recs[f];
-  const int64_t w = rec.row_bytes;
-  const int64_t lo = (tile - rec.tile_first) << rec.tile_shift;
-  const int64_t tile_bytes = (int64_t)1 << rec.tile_shift;
-  const int e = find_stream_segment(a.seg_real_prefix, 0, a.n_seg, lo, w);
-  const SegRec r = a.c.segs[e];
-  const int64_t s_lo = a.seg_real_prefix[e] * w;
-  TileCode c;
-  c.a = 0;
-  c.b = (uint64_t)(uint32_t)f << 32 | (uint32_t)e;
-  if (lo + tile_bytes <= s_lo + (int64_t)r.n_real * w) {
-    c.a = reinterpret_cast<uint64_t>(
-        static_cast<const u8*>(pv.ptrs[rec.dst_ptr_index + a.seg_dst_shard[e]]) + r.dst_row * w +
-        (lo - s_lo));
-    c.b = reinterpret_cast<uint64_t>(
-        static_cast<const u8*>(pv.ptrs[rec.src_ptr_index + r.src_shard]) + r.src_row * w +
-        (lo - s_lo));
+  const int64_t tile0 = ((int64_t)__builtin_amdgcn_readfirstlane((int)(first >> 32)) << 32) |
+                        (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)first);
+  const int x0 = last_le(pv.tile_start, 0, pv.n_recs, tile0);   // one record per field
+  const TileRec rec0 = pv.recs[x0];
+  const int e_guess = find_stream_segment(a.seg_real_prefix, 0, a.n_seg,
+                                          (tile0 - rec0.tile_first) << rec0.tile_shift,
+                                          rec0.row_bytes);
+  int x = first < pv.tile_start[x0 + 1] ? x0 : last_le(pv.tile_start, x0, pv.n_recs, first);
+  TileRec rec = pv.recs[x];
+  int64_t x_end = pv.tile_start[x + 1];
+  int64_t w = rec.row_bytes;
+  int64_t lo = (first - rec.tile_first) << rec.tile_shift;
+  int e;
+  if (x == x0 && lo < a.seg_real_prefix[e_guess + 1] * w) e = e_guess;
+  else e = find_stream_segment(a.seg_real_prefix, x == x0 ? e_guess : 0, a.n_seg, lo, w);
+  SegRec r = a.c.segs[e];
+  int64_t s_lo = a.seg_real_prefix[e] * w;
+  const int64_t last = first + kTilesPerLane < a.c.n_tiles ? first + kTilesPerLane : a.c.n_tiles;
+  for (int64_t tile = first; tile < last; ++tile) {
+    if (tile != first) {
+      bool moved = false;
+      if (tile >= x_end) {
+        x = last_le(pv.tile_start, x, pv.n_recs, tile);
+        rec = pv.recs[x];
+        x_end = pv.tile_start[x + 1];
+        w = rec.row_bytes;
+        e = 0;
+        moved = true;
+      }
+      lo = (tile - rec.tile_first) << rec.tile_shift;
+      if (moved || lo >= s_lo + (int64_t)r.n_real * w) {
+        e = find_stream_segment(a.seg_real_prefix, e, a.n_seg, lo, w);
+        r = a.c.segs[e];
+        s_lo = a.seg_real_prefix[e] * w;
+      }
+    }
+    const int64_t tile_bytes = (int64_t)1 << rec.tile_shift;
+    TileCode c;
+    c.a = 0;
+    c.b = (uint64_t)(uint32_t)x << 32 | (uint32_t)e;
+    if (lo + tile_bytes <= s_lo + (int64_t)r.n_real * w) {
+      c.a = reinterpret_cast<uint64_t>(
+          static_cast<const u8*>(pv.ptrs[rec.dst_ptr_index + a.seg_dst_shard[e]]) + r.dst_row * w +
+          (lo - s_lo));
+      c.b = reinterpret_cast<uint64_t>(
+          static_cast<const u8*>(pv.ptrs[rec.src_ptr_index + r.src_shard]) + r.src_row * w +
+          (lo - s_lo));
+    }
+    codes[tile] = c;
   }
-  codes[tile] = c;
 }
 
 __device__ __forceinline__ void generic_inverse_tile(const InverseArgs a, const TileCode c,
@@ -702,7 +735,8 @@ void launch_copy_inverse(const CopyArgs& a, const int64_t* seg_real_prefix,
   if (a.n_tiles <= 0) return;
   InverseArgs ia{a, seg_real_prefix, seg_dst_shard, n_seg};
   TileCode* codes = static_cast<TileCode*>(tile_codes);
-  const unsigned g1 = (unsigned)((a.n_tiles + kCodeThreads - 1) / kCodeThreads);
+  const int64_t per_group = (int64_t)kCodeThreads * kTilesPerLane;
+  const unsigned g1 = (unsigned)((a.n_tiles + per_group - 1) / per_group);
   hipLaunchKernelGGL(inverse_code_kernel, dim3(g1), dim3(kCodeThreads), 0, stream, ia, codes);
   if (before) (void)hipEventRecord(before, stream);
   const int64_t grid = a.n_fine_tiles + (a.n_tiles - a.n_fine_tiles) * kSubTiles;
