@@ -35,8 +35,8 @@ HBM_PEAK_GBPS = 8000.0
 # (scaled by a plain copy kernel of known size, see profiles/), keyed by the sha256 of the kernel
 # source the counters were taken on.  A changed kernel reports null until re-measured.
 MEASURED_TRAFFIC = {
-    "d0a85392b766bbb5432e4f6108622688dcbd08379d546725dfed660a5521bdfe":
-        {"heavy": 52882862112, "longctx": 47518210557},
+    "0614b5c3f4fd210e0b390a1e21961470683445ff932acc77247338dbd4f96765":
+        {"heavy": 52882772579, "longctx": 47518214276},
 }
 
 WORKLOAD_NOTES = {

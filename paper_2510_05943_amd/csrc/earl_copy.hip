@@ -255,9 +255,9 @@ __device__ __forceinline__ TileCode code_of_tile(const CopyArgs& a, const ParamV
   return c;
 }
 
-__global__ __launch_bounds__(kCodeThreads) void tile_code_kernel(const CopyArgs a, TileCode* codes) {
-  const int64_t first = ((int64_t)blockIdx.x * kCodeThreads + threadIdx.x) * kTilesPerLane;
-  if (first >= a.n_tiles) return;
+// The codes of the kTilesPerLane tiles that start at `first` (first < n_tiles), written to out[0..].
+__device__ __forceinline__ void tile_codes_of_lane(const CopyArgs& a, const int64_t first,
+                                                   TileCode* out) {
   const ParamView pv = view_params(a.params);
   // the wavefront's first tile: uniform, searched with scalar loads
   const int64_t tile0 = ((int64_t)__builtin_amdgcn_readfirstlane((int)(first >> 32)) << 32) |
@@ -305,7 +305,28 @@ __global__ __launch_bounds__(kCodeThreads) void tile_code_kernel(const CopyArgs 
         }
       }
     }
-    codes[tile] = code_of_tile(a, pv, cur, tile);
+    out[tile - first] = code_of_tile(a, pv, cur, tile);
+  }
+}
+
+
+__global__ __launch_bounds__(kCodeThreads) void tile_code_kernel(const CopyArgs a, TileCode* codes) {
+  // A lane's kTilesPerLane codes are consecutive, so storing them straight from the lanes would
+  // scatter 16-byte pieces at a 64-byte stride; they pass through LDS instead and leave as whole
+  // 1 KiB rows of the wavefront's 256 codes.  Only lanes of one wavefront exchange data here and
+  // LDS operations of a wavefront complete in order, so no barrier is needed.
+  __shared__ TileCode s_codes[kCodeThreads / kWave][kWave * kTilesPerLane];
+  const int lane = threadIdx.x & (kWave - 1);
+  TileCode* mine = s_codes[threadIdx.x / kWave];
+  const int64_t wave_first =
+      ((int64_t)blockIdx.x * kCodeThreads + (threadIdx.x - lane)) * kTilesPerLane;
+  if (wave_first >= a.n_tiles) return;   // uniform per wavefront
+  const int64_t first = wave_first + (int64_t)lane * kTilesPerLane;
+  if (first < a.n_tiles) tile_codes_of_lane(a, first, mine + lane * kTilesPerLane);
+#pragma unroll
+  for (int j = 0; j < kTilesPerLane; ++j) {
+    const int64_t tile = wave_first + j * kWave + lane;
+    if (tile < a.n_tiles) codes[tile] = mine[j * kWave + lane];
   }
 }
 
@@ -580,10 +601,8 @@ struct InverseArgs {
 // then b = record << 32 | first segment), b = rollout-layout pointer (any alignment).
 // Organised like tile_code_kernel: the wavefront's first tile is searched with uniform values,
 // every lane writes kTilesPerLane consecutive codes and carries its segment along.
-__global__ __launch_bounds__(kCodeThreads) void inverse_code_kernel(const InverseArgs a,
-                                                                   TileCode* codes) {
-  const int64_t first = ((int64_t)blockIdx.x * kCodeThreads + threadIdx.x) * kTilesPerLane;
-  if (first >= a.c.n_tiles) return;
+__device__ __forceinline__ void inverse_codes_of_lane(const InverseArgs& a, const int64_t first,
+                                                      TileCode* out) {
   const ParamView pv = view_params(a.c.params);
   const int64_t tile0 = ((int64_t)__builtin_amdgcn_readfirstlane((int)(first >> 32)) << 32) |
                         (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)first);
@@ -633,7 +652,25 @@ __global__ __launch_bounds__(kCodeThreads) void inverse_code_kernel(const Invers
           static_cast<const u8*>(pv.ptrs[rec.src_ptr_index + r.src_shard]) + r.src_row * w +
           (lo - s_lo));
     }
-    codes[tile] = c;
+    out[tile - first] = c;
+  }
+}
+
+__global__ __launch_bounds__(kCodeThreads) void inverse_code_kernel(const InverseArgs a,
+                                                                   TileCode* codes) {
+  // codes leave through LDS as whole rows of the wavefront's 256 codes, as in tile_code_kernel
+  __shared__ TileCode s_codes[kCodeThreads / kWave][kWave * kTilesPerLane];
+  const int lane = threadIdx.x & (kWave - 1);
+  TileCode* mine = s_codes[threadIdx.x / kWave];
+  const int64_t wave_first =
+      ((int64_t)blockIdx.x * kCodeThreads + (threadIdx.x - lane)) * kTilesPerLane;
+  if (wave_first >= a.c.n_tiles) return;   // uniform per wavefront
+  const int64_t first = wave_first + (int64_t)lane * kTilesPerLane;
+  if (first < a.c.n_tiles) inverse_codes_of_lane(a, first, mine + lane * kTilesPerLane);
+#pragma unroll
+  for (int j = 0; j < kTilesPerLane; ++j) {
+    const int64_t tile = wave_first + j * kWave + lane;
+    if (tile < a.c.n_tiles) codes[tile] = mine[j * kWave + lane];
   }
 }
 

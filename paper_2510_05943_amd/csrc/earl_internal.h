@@ -26,8 +26,8 @@ constexpr int kTileBytes = 4096;     // destination bytes described by one tile 
 constexpr int kFineTileShift = 10;   // fields with rows under 16 bytes: 1 KiB per tile code
 constexpr int kCopyThreads = 64;     // re-layout workgroup: one wavefront, 1 KiB of a tile
 constexpr int kSubTiles = kTileBytes / (kCopyThreads * kVecBytes);   // workgroups per 4 KiB tile
-constexpr int kTilesPerLane = 4;     // tile-code kernel: consecutive tiles per lane (2x faster
-                                     // than 8, 1.3x faster than 1 on the 12 M tiles of the largest workload)
+constexpr int kTilesPerLane = 4;     // code kernels: consecutive tiles per lane (measured best among
+                                     // 1, 2, 4, 8, 16 on the 12 M tiles of the largest workload)
 constexpr int kCodeThreads = 256;    // tile-code kernel workgroup
 
 constexpr int kStatusCapacity = 3;   // EARL_CAPACITY, for device code
