@@ -35,8 +35,8 @@ HBM_PEAK_GBPS = 8000.0
 # (scaled by a plain copy kernel of known size, see profiles/), keyed by the sha256 of the kernel
 # source the counters were taken on.  A changed kernel reports null until re-measured.
 MEASURED_TRAFFIC = {
-    "0614b5c3f4fd210e0b390a1e21961470683445ff932acc77247338dbd4f96765":
-        {"heavy": 52882772579, "longctx": 47518214276},
+    "a9b49484a65209c256c1d856cd49a6200fdd70b18845382e075c7d8e5bf33e1b":
+        {"heavy": 52882838527, "longctx": 47518212261},
 }
 
 WORKLOAD_NOTES = {

@@ -54,6 +54,17 @@ __device__ __forceinline__ void store16_any(u8* p, u32x4 v) {
   __builtin_nontemporal_store(v, (EARL_GLOBAL u32x4_u*)p);
 }
 
+// Between LDS writes of some lanes and LDS reads of other lanes of the SAME wavefront: without it
+// the compiler may hoist a read above a write it can prove to be to a different address for the
+// reading lane itself (seen in the ISA of an earlier kernel: the values then came out stale).
+// Wavefront scope costs no instruction; the hardware already keeps a wavefront's LDS
+// operations in order.
+__device__ __forceinline__ void wave_exchange_fence() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 __device__ __forceinline__ uint64_t load_scalar(const u8* p, int sb) {
   switch (sb) {
     case 1: return *p;
@@ -313,8 +324,10 @@ __device__ __forceinline__ void tile_codes_of_lane(const CopyArgs& a, const int6
 __global__ __launch_bounds__(kCodeThreads) void tile_code_kernel(const CopyArgs a, TileCode* codes) {
   // A lane's kTilesPerLane codes are consecutive, so storing them straight from the lanes would
   // scatter 16-byte pieces at a 64-byte stride; they pass through LDS instead and leave as whole
-  // 1 KiB rows of the wavefront's 256 codes.  Only lanes of one wavefront exchange data here and
-  // LDS operations of a wavefront complete in order, so no barrier is needed.
+  // 1 KiB rows of the wavefront's 256 codes.  Only lanes of one wavefront exchange data, and the
+  // hardware completes a wavefront's LDS operations in order, so no s_barrier is needed; the
+  // compiler, however, must be told not to move the reads above the other lanes' writes
+  // (wave_exchange_fence).
   __shared__ TileCode s_codes[kCodeThreads / kWave][kWave * kTilesPerLane];
   const int lane = threadIdx.x & (kWave - 1);
   TileCode* mine = s_codes[threadIdx.x / kWave];
@@ -323,6 +336,7 @@ __global__ __launch_bounds__(kCodeThreads) void tile_code_kernel(const CopyArgs 
   if (wave_first >= a.n_tiles) return;   // uniform per wavefront
   const int64_t first = wave_first + (int64_t)lane * kTilesPerLane;
   if (first < a.n_tiles) tile_codes_of_lane(a, first, mine + lane * kTilesPerLane);
+  wave_exchange_fence();
 #pragma unroll
   for (int j = 0; j < kTilesPerLane; ++j) {
     const int64_t tile = wave_first + j * kWave + lane;
@@ -667,6 +681,7 @@ __global__ __launch_bounds__(kCodeThreads) void inverse_code_kernel(const Invers
   if (wave_first >= a.c.n_tiles) return;   // uniform per wavefront
   const int64_t first = wave_first + (int64_t)lane * kTilesPerLane;
   if (first < a.c.n_tiles) inverse_codes_of_lane(a, first, mine + lane * kTilesPerLane);
+  wave_exchange_fence();
 #pragma unroll
   for (int j = 0; j < kTilesPerLane; ++j) {
     const int64_t tile = wave_first + j * kWave + lane;
