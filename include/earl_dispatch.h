@@ -112,7 +112,7 @@ typedef struct {
  *                       ONE row per sequence (row k of a group's buffer = its k-th sequence in index
  *                       order, whatever seq_row says) and the dispatch broadcasts it to every real
  *                       token of the sequence while it copies (e.g. a sequence-level advantage or
- *                       reward, Section 4 of the paper); padding rows get pad_scalar.  Needs
+ *                       reward, Section 5 of the paper); padding rows get pad_scalar.  Needs
  *                       scalar_bytes * width in {1, 2, 4, 8} and source buffers aligned to that;
  *                       not accepted by earl_dispatch_inverse.
  *   nonzero_counts      NULL, or device int64[D*C][n_mb_max] (8-byte aligned): while the field is
@@ -243,6 +243,11 @@ int32_t earl_dispatch_workspace_bytes(earl_plan* plan, const earl_field* fields,
  *                                in use until the call's work has finished on the stream.
  * Every check (plan status, alignment, capacities) happens before anything is enqueued: a failed
  * call writes nothing.  Calls that share a scratch buffer must be ordered on one stream.
+ * The call's parameter block (about 100 bytes per field and destination shard) reaches the device
+ * through a pinned host block of 2 MiB that the library allocates at the first dispatch call of the
+ * process and keeps until the process ends; it is used in slots of 256 KiB, so a block above
+ * 2 MiB (some 20000 (field, shard) pairs) makes the call wait on the host for the work that
+ * precedes it on the stream.  The same holds for earl_dispatch_async and earl_dispatch_inverse.
  */
 int32_t earl_dispatch(earl_plan* plan, const earl_field* fields, int32_t n_fields,
                       int32_t* const* position_ids_shard_ptrs, int32_t* cu_seqlens_dev,
@@ -281,10 +286,12 @@ int32_t earl_dispatch_async(earl_plan* plan, const earl_field* fields, int32_t n
 int32_t earl_dispatch_async_status(earl_plan* plan, int32_t* status);
 
 /*
- * Measurement hook: the following earl_dispatch / earl_dispatch_inverse calls on this plan record
- * `event_before` on the stream right before the re-layout kernel and `event_after` right after it (both hipEvent_t created
- * by the caller with timing enabled; NULL, NULL switches the hook off).  The interval is the
- * duration of the copy kernel alone, without the tile-code pass and the parameter upload.
+ * Measurement hook (no passage of the paper: it serves the benchmark): the following
+ * earl_dispatch / earl_dispatch_async / earl_dispatch_inverse calls on this plan record
+ * `event_before` on the stream right before the first kernel that moves or decodes data and
+ * `event_after` right after the last one (both hipEvent_t created by the caller with timing
+ * enabled; NULL, NULL switches the hook off).  The interval covers every kernel of the re-layout
+ * (decode pass and copy), without the upload of the call's parameter block.
  */
 int32_t earl_plan_set_dispatch_events(earl_plan* plan, void* event_before, void* event_after);
 
@@ -294,8 +301,10 @@ int32_t earl_plan_set_dispatch_events(earl_plan* plan, void* event_before, void*
  * row it was read from.  Field descriptors as in earl_dispatch with the roles of the two pointer
  * arrays unchanged (dst_shard_ptrs is read, src_shard_ptrs is written; both only need alignment to
  * scalar_bytes).  Rows of the source buffers that the plan does not read are left untouched.
- * The scratch buffer only holds the parameter block here: earl_dispatch_workspace_bytes() with the
- * same fields is always enough.
+ * The scratch buffer holds the call's parameter block and one 16-byte record per tile of the
+ * stream of real rows; earl_dispatch_workspace_bytes() with the same fields is always enough.
+ * Any stream may be used: the first inverse call on a plan computes a per-segment prefix of real
+ * rows on its stream, and later calls on other streams are ordered behind it by an event.
  */
 int32_t earl_dispatch_inverse(earl_plan* plan, const earl_field* fields, int32_t n_fields,
                               void* dispatch_ws_dev, size_t dispatch_ws_bytes, void* hip_stream);

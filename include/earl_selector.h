@@ -5,14 +5,14 @@
  * candidate parallelism configuration is measured at several context lengths, and the best
  * configuration is kept for every context-length range; during training the averaged context
  * length of the generated sequences is monitored, and when it enters another range the system
- * switches to that range's configuration before the next Rollout stage.  Section 3, "Metrics":
+ * switches to that range's configuration before the next Rollout stage.  Section 3.1, "Metrics":
  * throughput is tokens per GPU per second (TGS), and Equation 1 defines the relative speedup of
  * one configuration over another.
  *
  * The paper gives no further rule; this library's reading:
  *   - the table is measured at context lengths l_0 < l_1 < ... < l_{M-1}; a measurement that is
  *     not a positive finite number marks a configuration that failed there (out of memory,
- *     Section 3.1) and is never chosen for that length;
+ *     Section 3.2) and is never chosen for that length;
  *   - the best configuration at l_j is the feasible one with the largest TGS, the lowest index
  *     among equals;
  *   - an averaged context length x belongs to the first measured length that is >= x (what was

@@ -408,7 +408,7 @@ def dispatch_field_shard(plan: Plan, q: int, src_bufs: Sequence, scalar_dtype, w
     source row seq_row[i] + p of buffer seq_shard[i] when p < L[i], else the padding row.
 
     per_sequence: the source buffers hold ONE row per sequence (row seq_k[i] of buffer
-    seq_shard[i]), e.g. a sequence-level advantage or reward (Section 4 names them as the next
+    seq_shard[i]), e.g. a sequence-level advantage or reward (Section 5 names them as the next
     tensors to dispatch); every real position of the sequence receives that row.
     """
     C, K = plan.C, plan.K

@@ -7,8 +7,8 @@ What it follows.  Section 2 of the paper ("Parallelism Selector"): throughput is
 start of training for every candidate parallelism configuration at several context lengths, the
 best configuration is remembered for every context-length range, the averaged context length is
 monitored during training, and the configuration of the range it falls into is switched to
-before the next Rollout stage.  Section 3 ("Metrics", Equation 1) defines the relative speedup
-of one configuration over another from their tokens-per-GPU-per-second (TGS); Section 3.1
+before the next Rollout stage.  Section 3.1 ("Metrics", Equation 1) defines the relative speedup
+of one configuration over another from their tokens-per-GPU-per-second (TGS); Section 3.2
 reports that a configuration can fail with out-of-memory at a length where another still runs.
 
 The paper states no tie-break, no rule for lengths between two measured ones and no

@@ -178,6 +178,7 @@ constexpr int kStageSlots = 8;
 constexpr size_t kStageBytes = 256 * 1024;
 std::mutex g_stage_mu;
 StageSlot g_stage[kStageSlots];
+bool g_stage_ready = false;
 int g_stage_next = 0;
 
 }  // namespace
@@ -191,6 +192,8 @@ struct earl_plan {
   bool summary_ready;
   int32_t status;
   bool inverse_ready;
+  void* inverse_prefix_done;            // hipEvent_t recorded behind the prefix kernel
+  hipStream_t inverse_stream;           // stream that kernel ran on
   void* ev_before;
   void* ev_after;
   hipStream_t async_stream;             // stream of the last earl_dispatch_async
@@ -238,46 +241,62 @@ const Tv* summary_ptr(const earl_plan* p, size_t off) {
   return reinterpret_cast<const Tv*>(p->summary.data() + off);
 }
 
-// Copies a host-built parameter block into the workspace, ordered on the stream.
-int32_t upload_params(const std::vector<unsigned char>& block, void* dev_dst, hipStream_t stream) {
-  if (block.size() > kStageBytes) {
-    // too large for a staging slot: blocking copy
-    HIP_TRY(hipStreamSynchronize(stream));
-    HIP_TRY(hipMemcpy(dev_dst, block.data(), block.size(), hipMemcpyHostToDevice));
-    return EARL_OK;
-  }
+// Copies a host-built parameter block into the workspace, ordered on the stream, in pieces of
+// one staging slot each.  A slot is reused once the copy that last read it has finished, so a
+// block larger than all slots together (2 MiB) makes the caller wait for earlier pieces, and
+// with them for the work that precedes them on the stream.
+int32_t upload_params(const unsigned char* block, size_t bytes, void* dev_dst, hipStream_t stream) {
   std::lock_guard<std::mutex> lock(g_stage_mu);
-  if (!g_stage[0].host) {
-    // first use: one pinned allocation for all slots
+  if (!g_stage_ready) {
+    // first use: one pinned allocation for all slots, kept until the process ends; the slots
+    // are published only when every one of them is complete
+    StageSlot fresh[kStageSlots];
     void* base = nullptr;
     HIP_TRY(hipHostMalloc(&base, kStageBytes * kStageSlots, hipHostMallocDefault));
     for (int k = 0; k < kStageSlots; ++k) {
-      HIP_TRY(hipEventCreateWithFlags(&g_stage[k].done, hipEventDisableTiming));
-      g_stage[k].host = static_cast<unsigned char*>(base) + (size_t)k * kStageBytes;
+      hipError_t e = hipEventCreateWithFlags(&fresh[k].done, hipEventDisableTiming);
+      if (e != hipSuccess) {
+        for (int j = 0; j < k; ++j) (void)hipEventDestroy(fresh[j].done);
+        (void)hipHostFree(base);
+        return fail(EARL_HIP_ERROR, "hipEventCreateWithFlags failed: %s", hipGetErrorString(e));
+      }
+      fresh[k].host = static_cast<unsigned char*>(base) + (size_t)k * kStageBytes;
     }
+    for (int k = 0; k < kStageSlots; ++k) g_stage[k] = fresh[k];
+    g_stage_ready = true;
   }
-  StageSlot& s = g_stage[g_stage_next];
-  g_stage_next = (g_stage_next + 1) % kStageSlots;
-  if (s.in_flight) HIP_TRY(hipEventSynchronize(s.done));
-  std::memcpy(s.host, block.data(), block.size());
-  HIP_TRY(hipMemcpyAsync(dev_dst, s.host, block.size(), hipMemcpyHostToDevice, stream));
-  HIP_TRY(hipEventRecord(s.done, stream));
-  s.in_flight = true;
+  for (size_t off = 0; off < bytes; off += kStageBytes) {
+    const size_t n = bytes - off < kStageBytes ? bytes - off : kStageBytes;
+    StageSlot& s = g_stage[g_stage_next];
+    g_stage_next = (g_stage_next + 1) % kStageSlots;
+    if (s.in_flight) HIP_TRY(hipEventSynchronize(s.done));
+    std::memcpy(s.host, block + off, n);
+    HIP_TRY(hipMemcpyAsync(static_cast<unsigned char*>(dev_dst) + off, s.host, n,
+                           hipMemcpyHostToDevice, stream));
+    HIP_TRY(hipEventRecord(s.done, stream));
+    s.in_flight = true;
+  }
   return EARL_OK;
 }
 
+// The parameter block of one call, built in host memory: the builder's own vector, or a buffer
+// the caller lends (`fixed`, for the entry point that must not allocate).
 struct BlockBuilder {
-  std::vector<unsigned char> bytes;
+  std::vector<unsigned char> owned;
+  unsigned char* data = nullptr;
+  size_t size = 0;
   DispatchDev hd{};
-  int64_t* tile_start() { return reinterpret_cast<int64_t*>(bytes.data() + hd.tile_start_ofs); }
-  TileRec* recs() { return reinterpret_cast<TileRec*>(bytes.data() + hd.recs_ofs); }
-  const void** ptrs() { return reinterpret_cast<const void**>(bytes.data() + hd.ptrs_ofs); }
-  int64_t* rec_caps() { return reinterpret_cast<int64_t*>(bytes.data() + hd.rec_caps_ofs); }
-  int64_t* src_caps() { return reinterpret_cast<int64_t*>(bytes.data() + hd.src_caps_ofs); }
+  int64_t* tile_start() { return reinterpret_cast<int64_t*>(data + hd.tile_start_ofs); }
+  TileRec* recs() { return reinterpret_cast<TileRec*>(data + hd.recs_ofs); }
+  const void** ptrs() { return reinterpret_cast<const void**>(data + hd.ptrs_ofs); }
+  int64_t* rec_caps() { return reinterpret_cast<int64_t*>(data + hd.rec_caps_ofs); }
+  int64_t* src_caps() { return reinterpret_cast<int64_t*>(data + hd.src_caps_ofs); }
   int32_t* src_per_sequence() {
-    return reinterpret_cast<int32_t*>(bytes.data() + hd.src_per_sequence_ofs);
+    return reinterpret_cast<int32_t*>(data + hd.src_per_sequence_ofs);
   }
-  void init(int n_recs, int n_fields, int n_src, int n_dst) {
+  // false: the block does not fit the lent buffer
+  bool init(int n_recs, int n_fields, int n_src, int n_dst, unsigned char* fixed = nullptr,
+            size_t fixed_bytes = 0) {
     hd.n_recs = n_recs;
     size_t off = align_up(sizeof(DispatchDev));
     hd.tile_start_ofs = (uint32_t)off;
@@ -294,8 +313,17 @@ struct BlockBuilder {
     hd.src_per_sequence_ofs = (uint32_t)off;
     off += align_up(sizeof(int32_t) * (size_t)n_fields);
     hd.total_bytes = (uint32_t)off;
-    bytes.assign(off, 0);
-    std::memcpy(bytes.data(), &hd, sizeof(hd));
+    size = off;
+    if (fixed) {
+      if (off > fixed_bytes) return false;
+      data = fixed;
+      std::memset(data, 0, off);
+    } else {
+      owned.assign(off, 0);
+      data = owned.data();
+    }
+    std::memcpy(data, &hd, sizeof(hd));
+    return true;
   }
 };
 
@@ -409,6 +437,13 @@ int32_t earl_plan_build(const int32_t* lengths_dev, int32_t n_seqs, const earl_s
   p->summary_ready = false;
   p->status = EARL_OK;
   p->inverse_ready = false;
+  p->inverse_prefix_done = nullptr;
+  p->inverse_stream = nullptr;
+  p->async_stream = nullptr;
+  p->async_used = false;
+  // host arrays the dispatch calls fill are sized here, so that those calls allocate nothing
+  p->summary.resize(l.summary_end);
+  p->seg_starts.resize((size_t)d.D * d.C + 1);
   p->ev_before = nullptr;
   p->ev_after = nullptr;
 
@@ -583,42 +618,14 @@ int32_t check_field_shapes(const earl_field* fields, int32_t n_fields) {
   return EARL_OK;
 }
 
-}  // namespace
 
-extern "C" {
-
-int32_t earl_dispatch_workspace_bytes(earl_plan* p, const earl_field* fields, int32_t n_fields,
-                                      int32_t with_position_ids, int32_t with_cu_seqlens,
-                                      size_t* out_bytes) {
-  if (!p || !out_bytes) return fail(EARL_INVALID_ARG, "null argument");
-  int32_t st = check_field_shapes(fields, n_fields);
-  if (st != EARL_OK) return st;
-  st = ensure_summary(p);
-  if (st != EARL_OK) return st;
-  const int F = n_fields + (with_position_ids ? 1 : 0) + (with_cu_seqlens ? 1 : 0);
-  int64_t tiles = count_tiles(p, fields, n_fields, with_position_ids != 0, with_cu_seqlens != 0);
-  // the same scratch must do for earl_dispatch_inverse with these fields
-  int64_t inverse_tiles = 0;
-  for (int f = 0; f < n_fields; ++f) {
-    const int64_t w = (int64_t)fields[f].scalar_bytes * fields[f].width;
-    const int64_t tb = tile_bytes_of(w, kFieldCopy);
-    inverse_tiles += (p->hdr.total_real_rows * w + tb - 1) / tb;
-  }
-  if (inverse_tiles > tiles) tiles = inverse_tiles;
-  // one word per tile code on top (only the 1 KiB codes of counting fields use theirs)
-  *out_bytes = param_block_bytes(F, p->d.S, p->d.D * p->d.C) +
-               (kTileCodeBytes + sizeof(uint64_t)) * (size_t)tiles;
-  return EARL_OK;
-}
-
-int32_t earl_dispatch(earl_plan* p, const earl_field* fields, int32_t n_fields,
+// earl_dispatch after the plan's summary is on the host.  fixed_block != null: the parameter
+// block is built in that host buffer instead of a vector of its own.
+int32_t dispatch_impl(earl_plan* p, const earl_field* fields, int32_t n_fields,
                       int32_t* const* position_ids_shard_ptrs, int32_t* cu_seqlens_dev,
-                      void* dispatch_ws_dev, size_t dispatch_ws_bytes, void* hip_stream) {
-  if (!p) return fail(EARL_INVALID_ARG, "null plan");
-  int32_t st = check_field_shapes(fields, n_fields);
-  if (st != EARL_OK) return st;
-  st = ensure_summary(p);
-  if (st != EARL_OK) return st;
+                      void* dispatch_ws_dev, size_t dispatch_ws_bytes, hipStream_t stream,
+                      unsigned char* fixed_block, size_t fixed_block_bytes) {
+  int32_t st = EARL_OK;
   const int n_dst = p->d.D * p->d.C, S = p->d.S;
   const int64_t* shard_rows = summary_ptr<int64_t>(p, p->l.shard_rows);
   for (int f = 0; f < n_fields; ++f) {
@@ -640,19 +647,22 @@ int32_t earl_dispatch(earl_plan* p, const earl_field* fields, int32_t n_fields,
   const int F = n_fields + extra;
   if (F == 0) return EARL_OK;
   BlockBuilder b;
-  b.init(F * n_dst, F, S, n_dst);
+  if (!b.init(F * n_dst, F, S, n_dst, fixed_block, fixed_block_bytes))
+    return fail(EARL_CAPACITY, "the parameter block of this call needs %zu bytes, %zu available",
+                b.size, fixed_block_bytes);
   int64_t* ts = b.tile_start();
   TileRec* recs = b.recs();
   const void** ptrs = b.ptrs();
   // pointer tables and one prototype record per field
-  std::vector<TileRec> protos((size_t)F);
-  std::vector<uint32_t> counter_slot((size_t)F, kNoCounters);   // first counter row pointer
+  TileRec protos[EARL_MAX_FIELDS + 2];
+  uint32_t counter_slot[EARL_MAX_FIELDS + 2];   // first counter row pointer
   const int64_t n_mb_max = p->hdr.n_mb_max;
   bool counting = false;
   uint32_t pi = 0;
   for (int f = 0; f < F; ++f) {
     TileRec& proto = protos[f];
     proto = TileRec{};
+    counter_slot[f] = kNoCounters;
     proto.src_ptr_index = pi;
     proto.dst_ptr_index = pi + S;
     if (f < n_fields) {
@@ -713,15 +723,14 @@ int32_t earl_dispatch(earl_plan* p, const earl_field* fields, int32_t n_fields,
   if (fine + (tiles - fine) * kSubTiles > 0x7fffffffll)
     return fail(EARL_INVALID_ARG, "too many tiles for one launch");
   if (tiles == 0) return EARL_OK;
-  const size_t codes_off = b.bytes.size();
+  const size_t codes_off = b.size;
   const size_t counter_words_off = codes_off + kTileCodeBytes * (size_t)tiles;
   const size_t need = counter_words_off + (counting ? sizeof(uint64_t) * (size_t)fine : 0);
   if (!dispatch_ws_dev || reinterpret_cast<uintptr_t>(dispatch_ws_dev) % kAlign)
     return fail(EARL_INVALID_ARG, "dispatch scratch is null or not %zu-byte aligned", kAlign);
   if (dispatch_ws_bytes < need)
     return fail(EARL_CAPACITY, "dispatch scratch has %zu bytes, %zu needed", dispatch_ws_bytes, need);
-  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  st = upload_params(b.bytes, dispatch_ws_dev, stream);
+  st = upload_params(b.data, b.size, dispatch_ws_dev, stream);
   if (st != EARL_OK) return st;
   CopyArgs ca = copy_args(p, dispatch_ws_dev, tiles);
   ca.n_fine_tiles = fine;
@@ -733,8 +742,8 @@ int32_t earl_dispatch(earl_plan* p, const earl_field* fields, int32_t n_fields,
         launch_zero_counters(fields[f].nonzero_counts, n_mb_max * n_dst, stream);
   }
   void* codes = static_cast<unsigned char*>(dispatch_ws_dev) + codes_off;
-  launch_tile_codes(ca, codes, stream);
   if (p->ev_before) HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(p->ev_before), stream));
+  launch_tile_codes(ca, codes, stream);
   launch_copy(ca, codes, stream);
   if (p->ev_after) HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(p->ev_after), stream));
   hipError_t e = hipGetLastError();
@@ -743,9 +752,52 @@ int32_t earl_dispatch(earl_plan* p, const earl_field* fields, int32_t n_fields,
   return EARL_OK;
 }
 
+}  // namespace
+
+extern "C" {
+
+int32_t earl_dispatch_workspace_bytes(earl_plan* p, const earl_field* fields, int32_t n_fields,
+                                      int32_t with_position_ids, int32_t with_cu_seqlens,
+                                      size_t* out_bytes) {
+  if (!p || !out_bytes) return fail(EARL_INVALID_ARG, "null argument");
+  int32_t st = check_field_shapes(fields, n_fields);
+  if (st != EARL_OK) return st;
+  st = ensure_summary(p);
+  if (st != EARL_OK) return st;
+  const int F = n_fields + (with_position_ids ? 1 : 0) + (with_cu_seqlens ? 1 : 0);
+  int64_t tiles = count_tiles(p, fields, n_fields, with_position_ids != 0, with_cu_seqlens != 0);
+  // the same scratch must do for earl_dispatch_inverse with these fields
+  int64_t inverse_tiles = 0;
+  for (int f = 0; f < n_fields; ++f) {
+    const int64_t w = (int64_t)fields[f].scalar_bytes * fields[f].width;
+    const int64_t tb = tile_bytes_of(w, kFieldCopy);
+    inverse_tiles += (p->hdr.total_real_rows * w + tb - 1) / tb;
+  }
+  if (inverse_tiles > tiles) tiles = inverse_tiles;
+  // one word per tile code on top (only the 1 KiB codes of counting fields use theirs)
+  *out_bytes = param_block_bytes(F, p->d.S, p->d.D * p->d.C) +
+               (kTileCodeBytes + sizeof(uint64_t)) * (size_t)tiles;
+  return EARL_OK;
+}
+
+int32_t earl_dispatch(earl_plan* p, const earl_field* fields, int32_t n_fields,
+                      int32_t* const* position_ids_shard_ptrs, int32_t* cu_seqlens_dev,
+                      void* dispatch_ws_dev, size_t dispatch_ws_bytes, void* hip_stream) {
+  if (!p) return fail(EARL_INVALID_ARG, "null plan");
+  int32_t st = check_field_shapes(fields, n_fields);
+  if (st != EARL_OK) return st;
+  st = ensure_summary(p);
+  if (st != EARL_OK) return st;
+  return dispatch_impl(p, fields, n_fields, position_ids_shard_ptrs, cu_seqlens_dev,
+                       dispatch_ws_dev, dispatch_ws_bytes, static_cast<hipStream_t>(hip_stream),
+                       nullptr, 0);
+}
+
 namespace {
 
-// Tile codes of an asynchronous dispatch: as count_tiles, from buffer capacities.
+// Tile codes of an asynchronous dispatch: as count_tiles, from buffer capacities; -1 if a capacity
+// is out of range or the sum exceeds what one launch can hold.
+constexpr int64_t kMaxLaunchTiles = 0x7fffffffll;
 int64_t count_tiles_by_capacity(const earl_plan* p, const earl_field* fields, int32_t n_fields,
                                 const int64_t* position_ids_capacity_rows,
                                 int64_t cu_seqlens_capacity) {
@@ -755,10 +807,15 @@ int64_t count_tiles_by_capacity(const earl_plan* p, const earl_field* fields, in
     const int64_t w = f < n_fields ? (int64_t)fields[f].scalar_bytes * fields[f].width : 4;
     const int64_t* cap = f < n_fields ? fields[f].dst_capacity_rows : position_ids_capacity_rows;
     const int64_t tb = tile_bytes_of(w, kFieldCopy);
-    for (int q = 0; q < n_dst; ++q) tiles += (cap[q] * w + tb - 1) / tb;
+    for (int q = 0; q < n_dst; ++q) {
+      // cap <= 2^40 rows of w <= 2^20 bytes: one term fits, the running sum is cut off here
+      if (cap[q] < 0 || cap[q] > ((int64_t)1 << 40)) return -1;
+      tiles += (cap[q] * w + tb - 1) / tb;
+      if (tiles > kMaxLaunchTiles) return -1;
+    }
   }
   if (cu_seqlens_capacity > 0) tiles += (4 * cu_seqlens_capacity + kTileBytes - 1) / kTileBytes;
-  return tiles;
+  return tiles > kMaxLaunchTiles ? -1 : tiles;
 }
 
 // Host-side checks of an asynchronous dispatch: everything that does not need the plan's result.
@@ -831,6 +888,7 @@ int32_t earl_dispatch_async_workspace_bytes(earl_plan* p, const earl_field* fiel
   const int F = n_fields + (position_ids_capacity_rows ? 1 : 0) + (cu_seqlens_capacity ? 1 : 0);
   const int64_t tiles = count_tiles_by_capacity(p, fields, n_fields, position_ids_capacity_rows,
                                                 cu_seqlens_capacity);
+  if (tiles < 0) return fail(EARL_INVALID_ARG, "capacities out of range or too many tiles for one launch");
   *out_bytes = param_block_bytes(F, p->d.S, p->d.D * p->d.C) + kTileCodeBytes * (size_t)tiles;
   return EARL_OK;
 }
@@ -915,6 +973,8 @@ int32_t earl_dispatch_async(earl_plan* p, const earl_field* fields, int32_t n_fi
         r.end_bytes = cap * (int64_t)proto.row_bytes;
         ts[n_rec++] = tiles;
         tiles += (r.end_bytes + tb - 1) / tb;
+        // (one term is below 2^51; stopping here keeps the running sum from overflowing)
+        if (tiles > kMaxLaunchTiles) return fail(EARL_INVALID_ARG, "too many tiles for one launch");
       }
     }
     if (pass == 0) fine = tiles;
@@ -922,14 +982,14 @@ int32_t earl_dispatch_async(earl_plan* p, const earl_field* fields, int32_t n_fi
   ts[n_rec] = tiles;
   if (fine + (tiles - fine) * kSubTiles > 0x7fffffffll)
     return fail(EARL_INVALID_ARG, "too many tiles for one launch");
-  const size_t codes_off = b.bytes.size();
+  const size_t codes_off = b.size;
   const size_t need = codes_off + kTileCodeBytes * (size_t)tiles;
   if (!dispatch_ws_dev || reinterpret_cast<uintptr_t>(dispatch_ws_dev) % kAlign)
     return fail(EARL_INVALID_ARG, "dispatch scratch is null or not %zu-byte aligned", kAlign);
   if (dispatch_ws_bytes < need)
     return fail(EARL_CAPACITY, "dispatch scratch has %zu bytes, %zu needed", dispatch_ws_bytes, need);
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  st = upload_params(b.bytes, dispatch_ws_dev, stream);
+  st = upload_params(b.data, b.size, dispatch_ws_dev, stream);
   if (st != EARL_OK) return st;
   launch_async_resolve(static_cast<DispatchDev*>(dispatch_ws_dev), p->dev, stream);
   p->async_stream = stream;
@@ -938,8 +998,8 @@ int32_t earl_dispatch_async(earl_plan* p, const earl_field* fields, int32_t n_fi
     CopyArgs ca = copy_args(p, dispatch_ws_dev, tiles);
     ca.n_fine_tiles = fine;
     void* codes = static_cast<unsigned char*>(dispatch_ws_dev) + codes_off;
-    launch_tile_codes(ca, codes, stream);
     if (p->ev_before) HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(p->ev_before), stream));
+    launch_tile_codes(ca, codes, stream);
     launch_copy(ca, codes, stream);
     if (p->ev_after) HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(p->ev_after), stream));
   }
@@ -1009,17 +1069,30 @@ int32_t earl_dispatch_inverse(earl_plan* p, const earl_field* fields, int32_t n_
   ts[n_fields] = tiles;
   if (fine + (tiles - fine) * kSubTiles > 0x7fffffffll)
     return fail(EARL_INVALID_ARG, "too many tiles for one launch");
-  const size_t codes_off = b.bytes.size();
+  const size_t codes_off = b.size;
   const size_t need = codes_off + kTileCodeBytes * (size_t)tiles;
   if (!dispatch_ws_dev || reinterpret_cast<uintptr_t>(dispatch_ws_dev) % kAlign)
     return fail(EARL_INVALID_ARG, "dispatch scratch is null or not %zu-byte aligned", kAlign);
   if (dispatch_ws_bytes < need)
     return fail(EARL_CAPACITY, "dispatch scratch has %zu bytes, %zu needed", dispatch_ws_bytes, need);
+  // The per-segment prefix of real rows is computed once per plan, on the stream of the first
+  // inverse call; an event recorded behind it orders every later call, whatever its stream.
   if (!p->inverse_ready) {
+    hipEvent_t ev = nullptr;
+    HIP_TRY(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
     launch_real_prefix(p->dev.segs, prefix, p->hdr.n_segments, stream);
+    hipError_t e = hipEventRecord(ev, stream);
+    if (e != hipSuccess) {
+      (void)hipEventDestroy(ev);
+      return fail(EARL_HIP_ERROR, "hipEventRecord failed: %s", hipGetErrorString(e));
+    }
+    p->inverse_prefix_done = ev;
+    p->inverse_stream = stream;
     p->inverse_ready = true;
+  } else if (stream != p->inverse_stream) {
+    HIP_TRY(hipStreamWaitEvent(stream, static_cast<hipEvent_t>(p->inverse_prefix_done), 0));
   }
-  st = upload_params(b.bytes, dispatch_ws_dev, stream);
+  st = upload_params(b.data, b.size, dispatch_ws_dev, stream);
   if (st != EARL_OK) return st;
   CopyArgs ca = copy_args(p, dispatch_ws_dev, tiles);
   ca.n_fine_tiles = fine;
@@ -1043,6 +1116,8 @@ int32_t earl_plan_set_dispatch_events(earl_plan* p, void* event_before, void* ev
 }
 
 int32_t earl_plan_destroy(earl_plan* p) {
+  if (p && p->inverse_prefix_done)
+    (void)hipEventDestroy(static_cast<hipEvent_t>(p->inverse_prefix_done));
   delete p;
   return EARL_OK;
 }

@@ -789,8 +789,8 @@ void launch_copy_inverse(const CopyArgs& a, const int64_t* seg_real_prefix,
   TileCode* codes = static_cast<TileCode*>(tile_codes);
   const int64_t per_group = (int64_t)kCodeThreads * kTilesPerLane;
   const unsigned g1 = (unsigned)((a.n_tiles + per_group - 1) / per_group);
-  hipLaunchKernelGGL(inverse_code_kernel, dim3(g1), dim3(kCodeThreads), 0, stream, ia, codes);
   if (before) (void)hipEventRecord(before, stream);
+  hipLaunchKernelGGL(inverse_code_kernel, dim3(g1), dim3(kCodeThreads), 0, stream, ia, codes);
   const int64_t grid = a.n_fine_tiles + (a.n_tiles - a.n_fine_tiles) * kSubTiles;
   hipLaunchKernelGGL(inverse_kernel, dim3((unsigned)grid), dim3(kCopyThreads), 0, stream, ia, codes);
   if (after) (void)hipEventRecord(after, stream);

@@ -233,10 +233,14 @@ __device__ void bitonic_sort(uint64_t* keys, int n, bool keys_in_lds) {
 // Longest-first list scheduling in wavefront 0.
 //
 // keys[] holds the sequences sorted by (padded length descending, index ascending); the low
-// word is the index, the high word is 0x7fffffff - padded length.  The chain of N arg-mins is
-// serial by definition, so everything is about the latency of one step.  The greedy rule keeps
-// max - min load within one padded length, so loads are kept as 32-bit distances from the
-// current minimum (re-based every step) and the arg-min is a short v_min_u32 DPP butterfly.
+// word is the index, the high word is 0x7fffffff - padded length.  The chain of N "give the next
+// sequence to the least loaded rank" steps is serial by definition, so everything is about the
+// latency of one step.  Up to 64 ranks the loads are never searched: the ranks are kept as a
+// list SORTED by (load, rank) across the lanes, one word per lane, and a step removes the head
+// and re-inserts it with its grown load by one max and one min against the neighbouring lane
+// (lpt_sorted with 32-bit words, lpt_sorted64 with 64-bit words for large or squared loads).
+// Only beyond 64 ranks (lpt_blocks) do the loads stay in place, in LDS, and the minimum is
+// searched with a v_min_u32 DPP butterfly over 32-bit distances from the running minimum.
 // ---------------------------------------------------------------------------------------
 
 // Minimum over the first 2^kSteps lanes (kSteps <= 4) or over all 64 lanes (kSteps == 6).
@@ -275,6 +279,8 @@ __device__ __forceinline__ uint32_t wave_min_low(uint32_t x) {
 // scalar registers, and the winner (head & 63) is written into lane s of `ranks`.
 // kShift: row_shl:1 when the ranks fit one row of 16 lanes, else wave_shl:1.
 // Items past N have length 0 and come last: the head is put back where it was.
+// Lanes >= D hold 0xffffffff; a real word stays below it because the caller only takes this
+// path when every load is below 2^26 - 1 (the largest word is then (2^26 - 2) << 6 | 63).
 template <int kLane>
 __device__ __forceinline__ void writelane_const(uint32_t& v, uint32_t value) {
   // v_writelane_b32 has no builtin in this compiler; lane number is an immediate
@@ -429,7 +435,7 @@ __device__ void lpt_wave0(const PlanDev& p, const uint64_t* keys, int64_t* lds_l
     else lpt_blocks<false>(p, keys, lds_load);
   } else if (quadratic) {
     lpt_sorted64<true>(p, keys);
-  } else if (load_bound >= (1 << 26)) {
+  } else if (load_bound >= (1 << 26) - 1) {
     lpt_sorted64<false>(p, keys);
   } else if (D <= 16) {
     lpt_sorted<kDppRowShl1>(p, keys);
@@ -459,7 +465,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const PlanDev p) {
   __shared__ __align__(16) unsigned char lds_union[kLdsUnionBytes];
   __shared__ int64_t lds_load[kMaxDp];
   __shared__ BlockScratch bs;
-  __shared__ int s_invalid, s_exceeds, s_bad;
+  __shared__ int s_invalid, s_exceeds, s_bad, s_bad_invalid;
   __shared__ unsigned long long s_a2a[kLdsA2a];
 
   const int tid = threadIdx.x;
@@ -469,7 +475,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const PlanDev p) {
   const int64_t B = p.B;
 
   // ---- phase 0: clear accumulators --------------------------------------------------------
-  if (tid == 0) { s_invalid = 0; s_exceeds = 0; s_bad = -1; }
+  if (tid == 0) { s_invalid = 0; s_exceeds = 0; s_bad = -1; s_bad_invalid = -1; }
   if (S * n_dst > kLdsA2a)
     for (int64_t x = tid; x < (int64_t)S * n_dst; x += T) p.a2a[x] = 0;
   for (int x = tid; x < S; x += T) { p.src_rows_needed[x] = 0; p.src_seqs_needed[x] = 0; }
@@ -496,7 +502,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const PlanDev p) {
     p.seq_group[i] = (int32_t)g;
     p.m[i] = (int32_t)m;
     real_rows += L;
-    if (invalid) { s_invalid = 1; s_bad = i; }
+    // s_bad: the largest offending index (an invalid one counts before one over the budget)
+    if (invalid) { s_invalid = 1; atomicMax(&s_bad_invalid, i); }
     else if (exceeds) { s_exceeds = 1; atomicMax(&s_bad, i); }
   }
   __syncthreads();
@@ -504,7 +511,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const PlanDev p) {
     if (tid == 0) {
       PlanHeader h = {};
       h.status = s_invalid ? 1 : 2;
-      h.bad_index = s_bad;
+      h.bad_index = s_invalid ? s_bad_invalid : s_bad;
       *p.hdr = h;
     }
     return;

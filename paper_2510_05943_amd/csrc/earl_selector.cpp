@@ -1,5 +1,5 @@
 // Parallelism-selector table (Section 2 of the paper, "Parallelism Selector"; Equation 1 in
-// Section 3): host code only.  The reading of the paper that fixes every rule below is stated in
+// Section 3.1): host code only.  The reading of the paper that fixes every rule below is stated in
 // earl_selector.h.
 #include "earl_selector.h"
 

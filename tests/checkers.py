@@ -60,6 +60,13 @@ def trace_rows(res: Dict, D: int, C: int):
     return out
 
 
+def padding_rows_of_shard(res: Dict, L, D: int, C: int, q: int) -> np.ndarray:
+    """Boolean mask over the rows of destination shard q: True where the row is padding (its
+    traced-back position lies at or beyond the real length of its sequence)."""
+    seq_of_row, pos = trace_rows(res, D, C)[q]
+    return pos >= np.asarray(L, np.int64)[seq_of_row]
+
+
 def check_self_describing(res: Dict, L, D: int, C: int, src_group_bufs: Sequence[np.ndarray],
                           seq_group, src_row, dst_shards: Sequence[np.ndarray], pad_row) -> None:
     """Every destination row equals source(i, p) when p < L[i] and the pad row otherwise; every

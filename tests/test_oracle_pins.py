@@ -435,6 +435,22 @@ def all_pins_on_small_case(case, oracle=O):
             read = _read_rows(plan, s, back[s].shape[0])
             assert np.array_equal(back[s][read], bufs[s][read])
             assert np.all(back[s][~read] == 0x5A)
+    # the row map on its own: gathering source rows through it (padding where it says -1) gives
+    # the dispatched shard of every field, and it says -1 exactly on the padding rows (which the
+    # trace-back above has located from the metadata alone)
+    for q in range(w.dp * w.sp):
+        sh, row = oracle.source_row_map_shard(plan, q)
+        assert sh.shape == row.shape == (int(plan.shard_rows[q]),)
+        assert np.array_equal(sh < 0, row < 0)
+        assert np.array_equal(sh < 0, checkers.padding_rows_of_shard(res, w.lengths, w.dp, w.sp, q))
+        for f in fields:
+            _, bufs = shard_bufs(w, f)
+            want = oracle.dispatch_field_shard(plan, q, bufs, f.np_dtype, f.width, f.pad_scalar)
+            got = np.empty_like(want)
+            got[:] = np.full((f.width,), f.pad_scalar & ((1 << (8 * f.scalar_bytes)) - 1), f.np_dtype)
+            for d in np.flatnonzero(sh >= 0):
+                got[d] = bufs[int(sh[d])][int(row[d])]
+            assert np.array_equal(got, want)
     # segment table agrees with the per-row definition
     for q in range(w.dp * w.sp):
         sh, row = oracle.source_row_map_shard(plan, q)
@@ -678,7 +694,34 @@ def _mut_equal_mb_pads_to_most_plus_one(monkeypatch):
     monkeypatch.setattr(O, "pack_ranks", bad)
 
 
-MUTANTS = [_mut_quadratic_cost_is_linear, _mut_equal_mb_pads_to_most_plus_one,
+def _mut_row_map_forgets_chunk_offset(monkeypatch):
+    real = O.source_row_map_shard
+
+    def bad(plan, q):
+        # every chunk starts at the sequence's first source row (the chunk's logical offset dropped)
+        sh, row = real(plan, q)
+        pos = O.position_ids_shard(plan, q).astype(np.int64)
+        m_of_row = np.zeros_like(row)
+        r = q // plan.C
+        first = int(np.sum(plan.n_seq[:r]))
+        for i in plan.seq_ids[first:first + int(plan.n_seq[r])]:
+            d0, n = int(plan.dst_row[int(i)]), int(plan.loc[int(i)])
+            m_of_row[d0:d0 + n] = int(plan.m[int(i)])
+        return sh, np.where(row >= 0, row - (pos // np.maximum(m_of_row, 1)) * m_of_row, row)
+    monkeypatch.setattr(O, "source_row_map_shard", bad)
+
+
+def _mut_row_map_marks_no_padding(monkeypatch):
+    real = O.source_row_map_shard
+
+    def bad(plan, q):
+        sh, row = real(plan, q)
+        return np.where(sh < 0, 0, sh).astype(np.int32), np.where(row < 0, 0, row)
+    monkeypatch.setattr(O, "source_row_map_shard", bad)
+
+
+MUTANTS = [_mut_row_map_forgets_chunk_offset, _mut_row_map_marks_no_padding,
+           _mut_quadratic_cost_is_linear, _mut_equal_mb_pads_to_most_plus_one,
            _mut_zigzag_not_mirrored, _mut_lpt_tie_to_higher_rank, _mut_lpt_shortest_first,
            _mut_pad_ignores_multiple, _mut_budget_strict, _mut_positions_restart_per_chunk,
            _mut_replica_always_zero]

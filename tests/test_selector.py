@@ -16,7 +16,7 @@ GOLD = os.path.join(os.path.dirname(__file__), "golden")
 
 
 def gold():
-    with open(os.path.join(GOLD, "selector_section31.json")) as f:
+    with open(os.path.join(GOLD, "selector_section32.json")) as f:
         return json.load(f)
 
 
@@ -39,7 +39,7 @@ def test_equation_1_closed_forms():
         assert (s_ab > 0) == (b > a)
 
 
-def test_percentages_quoted_in_section_3_1():
+def test_percentages_quoted_in_section_3_2():
     g = gold()
     small, long_ = g["tgs_32_responses"][0], g["tgs_32_responses"][1]
     assert math.isclose(SO.speedup_percent(small[1], small[0]),
@@ -50,7 +50,7 @@ def test_percentages_quoted_in_section_3_1():
     assert SO.speedup_percent(small[0], small[1]) < 0 < SO.speedup_percent(long_[0], long_[1])
 
 
-def test_switch_points_described_in_section_3_1():
+def test_switch_points_described_in_section_3_2():
     g = gold()
     hi, cfg = SO.ranges(g["context_lengths"], g["tgs_32_responses"])
     assert hi == g["expected_range_hi"] and cfg == g["expected_range_config"]
@@ -123,7 +123,7 @@ def test_pins_catch_planted_mistake(mutant, monkeypatch):
     name, fn = MUTANTS[mutant]
     monkeypatch.setattr(SO, name, fn)
     failed = 0
-    for pin in (test_switch_points_described_in_section_3_1,
+    for pin in (test_switch_points_described_in_section_3_2,
                 test_out_of_memory_configuration_is_never_chosen,
                 test_range_rule_against_direct_lookup, test_hysteresis_hand_worked):
         try:
@@ -188,7 +188,7 @@ def test_library_matches_oracle(seed):
         S.selector_destroy(sel)
 
 
-def test_library_reproduces_section_3_1():
+def test_library_reproduces_section_3_2():
     g = gold()
     sel = S.selector_build(g["context_lengths"], g["tgs_32_responses"], 0.0, 0)
     assert S.selector_get_ranges(sel) == (g["expected_range_hi"], g["expected_range_config"])
