@@ -286,6 +286,28 @@ int32_t earl_dispatch_async(earl_plan* plan, const earl_field* fields, int32_t n
 int32_t earl_dispatch_async_status(earl_plan* plan, int32_t* status);
 
 /*
+ * earl_dispatch for callers that cannot allocate (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): same arguments without the scratch buffer, same result.
+ * The scratch (parameter block and tile codes) lives in an array of EARL_NOALLOC_SCRATCH_BYTES
+ * that is part of the library's device image: every GPU the library runs on holds one copy from
+ * the first call there until the process ends.  The call allocates nothing, on the device or on
+ * the host, waits for nothing and copies nothing through staging memory (the parameter block
+ * travels as kernel arguments), so:
+ *   - the plan's summary must already be on the host (earl_plan_get_summary has returned EARL_OK
+ *     for this plan; EARL_INVALID_ARG otherwise);
+ *   - a call whose parameter block exceeds 256 KiB or whose scratch need (what
+ *     earl_dispatch_workspace_bytes reports) exceeds the array returns EARL_CAPACITY and enqueues
+ *     nothing;
+ *   - all calls on one GPU share the array, which keeps the previous call's contents (every part a
+ *     call reads it has written first): calls whose work can overlap on the GPU, from different
+ *     streams or processes' threads, race; order them on one stream or by events.
+ */
+#define EARL_NOALLOC_SCRATCH_BYTES (32u << 20)
+int32_t earl_dispatch_noalloc(earl_plan* plan, const earl_field* fields, int32_t n_fields,
+                              int32_t* const* position_ids_shard_ptrs, int32_t* cu_seqlens_dev,
+                              void* hip_stream);
+
+/*
  * Measurement hook (no passage of the paper: it serves the benchmark): the following
  * earl_dispatch / earl_dispatch_async / earl_dispatch_inverse calls on this plan record
  * `event_before` on the stream right before the first kernel that moves or decodes data and

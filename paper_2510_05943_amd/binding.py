@@ -23,7 +23,7 @@ EARL_MAX_FIELDS = 32
 EXPORTED = ("earl_plan_workspace_bytes", "earl_plan_build", "earl_plan_get_summary",
             "earl_plan_export", "earl_plan_export_segments", "earl_dispatch_workspace_bytes",
             "earl_dispatch", "earl_dispatch_async_workspace_bytes", "earl_dispatch_async",
-            "earl_dispatch_async_status",
+            "earl_dispatch_async_status", "earl_dispatch_noalloc",
             "earl_dispatch_inverse", "earl_plan_set_dispatch_events", "earl_plan_destroy", "earl_status_string",
             "earl_last_error_message")
 
@@ -95,6 +95,7 @@ def load_library() -> C.CDLL:
     lib.earl_dispatch_async.argtypes = [vp, C.POINTER(_Field), i32, C.POINTER(vp), vp, vp, i64, vp,
                                         C.c_size_t, vp]
     lib.earl_dispatch_async_status.argtypes = [vp, C.POINTER(i32)]
+    lib.earl_dispatch_noalloc.argtypes = [vp, C.POINTER(_Field), i32, C.POINTER(vp), vp, vp]
     lib.earl_dispatch_inverse.argtypes = [vp, C.POINTER(_Field), i32, vp, C.c_size_t, vp]
     lib.earl_plan_set_dispatch_events.argtypes = [vp, vp, vp]
     lib.earl_plan_destroy.argtypes = [vp]
@@ -317,6 +318,19 @@ def dispatch(plan: Plan, fields: Sequence[Field], position_ids: Optional[Sequenc
                                         C.cast(pos, C.POINTER(C.c_void_p)) if pos is not None else None,
                                         _ptr(cu_seqlens), _ptr(workspace), _nbytes(workspace),
                                         _stream_handle(stream)))
+
+
+def dispatch_noalloc(plan: Plan, fields: Sequence[Field], position_ids: Optional[Sequence] = None,
+                     cu_seqlens=None, stream=None) -> None:
+    """earl_dispatch_noalloc: earl_dispatch on the library's own fixed scratch array; the plan's
+    summary must have been fetched."""
+    arr, n, keep = _marshal_fields(fields)
+    pos = None
+    if position_ids is not None:
+        pos = (C.c_void_p * len(position_ids))(*[_ptr(t) for t in position_ids])
+    _check(load_library().earl_dispatch_noalloc(
+        plan.handle, arr, n, C.cast(pos, C.POINTER(C.c_void_p)) if pos is not None else None,
+        _ptr(cu_seqlens), _stream_handle(stream)))
 
 
 def _capacity_array(tensors: Optional[Sequence]):

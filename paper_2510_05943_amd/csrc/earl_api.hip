@@ -619,8 +619,42 @@ int32_t check_field_shapes(const earl_field* fields, int32_t n_fields) {
 }
 
 
+// The scratch of earl_dispatch_noalloc: one array per GPU the library runs on, held until the
+// process ends.  In host code the name below is only a handle for hipGetSymbolAddress; the
+// address the kernels get is looked up once per device and kept in g_scratch_dev.
+constexpr size_t kStaticScratchBytes = EARL_NOALLOC_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
+unsigned char* g_scratch_dev[kMaxDevices] = {};
+std::mutex g_scratch_mu;
+std::mutex g_noalloc_mu;
+// host copy of the parameter block of the running earl_dispatch_noalloc call
+alignas(256) unsigned char g_noalloc_block[256 * 1024];
+
+}  // namespace
+
+static __device__ __align__(256) unsigned char scratch[EARL_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+
+int32_t static_scratch(unsigned char** out) {
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(EARL_INVALID_ARG, "device %d out of range", dev);
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_dev[dev]) {
+    void* ptr = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return fail(EARL_HIP_ERROR, "hipGetSymbolAddress returned a null address");
+    g_scratch_dev[dev] = static_cast<unsigned char*>(ptr);
+  }
+  *out = g_scratch_dev[dev];
+  return EARL_OK;
+}
+
 // earl_dispatch after the plan's summary is on the host.  fixed_block != null: the parameter
-// block is built in that host buffer instead of a vector of its own.
+// block is built in that host buffer and travels to the device as kernel arguments (nothing is
+// allocated, no staging memory is touched); else it is built in a vector and copied through a
+// pinned staging slot.
 int32_t dispatch_impl(earl_plan* p, const earl_field* fields, int32_t n_fields,
                       int32_t* const* position_ids_shard_ptrs, int32_t* cu_seqlens_dev,
                       void* dispatch_ws_dev, size_t dispatch_ws_bytes, hipStream_t stream,
@@ -730,8 +764,12 @@ int32_t dispatch_impl(earl_plan* p, const earl_field* fields, int32_t n_fields,
     return fail(EARL_INVALID_ARG, "dispatch scratch is null or not %zu-byte aligned", kAlign);
   if (dispatch_ws_bytes < need)
     return fail(EARL_CAPACITY, "dispatch scratch has %zu bytes, %zu needed", dispatch_ws_bytes, need);
-  st = upload_params(b.data, b.size, dispatch_ws_dev, stream);
-  if (st != EARL_OK) return st;
+  if (fixed_block) {
+    launch_param_chunks(dispatch_ws_dev, b.data, b.size, stream);
+  } else {
+    st = upload_params(b.data, b.size, dispatch_ws_dev, stream);
+    if (st != EARL_OK) return st;
+  }
   CopyArgs ca = copy_args(p, dispatch_ws_dev, tiles);
   ca.n_fine_tiles = fine;
   if (counting) {
@@ -791,6 +829,28 @@ int32_t earl_dispatch(earl_plan* p, const earl_field* fields, int32_t n_fields,
   return dispatch_impl(p, fields, n_fields, position_ids_shard_ptrs, cu_seqlens_dev,
                        dispatch_ws_dev, dispatch_ws_bytes, static_cast<hipStream_t>(hip_stream),
                        nullptr, 0);
+}
+
+int32_t earl_dispatch_noalloc(earl_plan* p, const earl_field* fields, int32_t n_fields,
+                              int32_t* const* position_ids_shard_ptrs, int32_t* cu_seqlens_dev,
+                              void* hip_stream) {
+  if (!p) return fail(EARL_INVALID_ARG, "null plan");
+  int32_t st = check_field_shapes(fields, n_fields);
+  if (st != EARL_OK) return st;
+  // no wait and no copy here: the caller has fetched the summary (it had to, to size its buffers)
+  if (!p->summary_ready)
+    return fail(EARL_INVALID_ARG, "earl_dispatch_noalloc needs a plan whose summary has been fetched "
+                                  "(earl_plan_get_summary)");
+  if (p->status != EARL_OK) return fail(p->status, "the plan failed");
+  unsigned char* scratch_dev = nullptr;
+  st = static_scratch(&scratch_dev);
+  if (st != EARL_OK) return st;
+  // one host block and one device array per process and GPU: calls are serialised on the host
+  // here, and must not overlap on the device (see the header)
+  std::lock_guard<std::mutex> lock(g_noalloc_mu);
+  return dispatch_impl(p, fields, n_fields, position_ids_shard_ptrs, cu_seqlens_dev, scratch_dev,
+                       kStaticScratchBytes, static_cast<hipStream_t>(hip_stream), g_noalloc_block,
+                       sizeof(g_noalloc_block));
 }
 
 namespace {

@@ -25,6 +25,8 @@
 //   * loads and stores carry the non-temporal hint: every byte is touched once (the stores of
 //     the hot paths system scope as well, see store16_sys);
 //   * position ids and cu_seqlens are further "fields" of the same launch.
+#include <cstring>
+
 #include "earl_internal.h"
 
 namespace earl {
@@ -551,6 +553,16 @@ __global__ __launch_bounds__(kResolveThreads) void async_resolve_kernel(Dispatch
     plan.hdr->async_status = plan_status != 0 ? plan_status : (all_fit ? 0 : (int64_t)kStatusCapacity);
 }
 
+// A piece of a parameter block that travels as a kernel argument: no staging memory, no copy
+// engine, nothing allocated (for the entry point that must not allocate).
+struct ParamChunk {
+  uint64_t words[kParamChunkBytes / 8];
+};
+__global__ __launch_bounds__(kWave) void param_chunk_kernel(uint64_t* dst, const ParamChunk c,
+                                                            int n_words) {
+  for (int x = threadIdx.x; x < n_words; x += kWave) dst[x] = c.words[x];
+}
+
 __global__ void zero_i64_kernel(int64_t* p, int64_t n) {
   const int64_t x = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (x < n) p[x] = 0;
@@ -771,6 +783,19 @@ void launch_zero_counters(int64_t* counters, int64_t n, hipStream_t stream) {
   if (n <= 0) return;
   hipLaunchKernelGGL(zero_i64_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream,
                      counters, n);
+}
+
+void launch_param_chunks(void* dev_dst, const unsigned char* host_block, size_t bytes,
+                         hipStream_t stream) {
+  // bytes is a multiple of 8 (every part of a parameter block is 256-byte aligned)
+  for (size_t off = 0; off < bytes; off += kParamChunkBytes) {
+    const size_t n = bytes - off < (size_t)kParamChunkBytes ? bytes - off : (size_t)kParamChunkBytes;
+    ParamChunk c;
+    std::memcpy(c.words, host_block + off, n);
+    hipLaunchKernelGGL(param_chunk_kernel, dim3(1), dim3(kWave), 0, stream,
+                       reinterpret_cast<uint64_t*>(static_cast<unsigned char*>(dev_dst) + off), c,
+                       (int)(n / 8));
+  }
 }
 
 void launch_async_resolve(DispatchDev* params, const PlanDev& plan, hipStream_t stream) {

@@ -179,6 +179,10 @@ void launch_tile_codes(const CopyArgs& a, void* tile_codes, hipStream_t stream);
 void launch_copy(const CopyArgs& a, const void* tile_codes, hipStream_t stream);
 // seg_real_prefix[e] = real rows of the segments before e (n_seg+1 entries)
 void launch_zero_counters(int64_t* counters, int64_t n, hipStream_t stream);
+// writes a host-built parameter block to device memory through kernel arguments, in pieces
+constexpr int kParamChunkBytes = 3072;
+void launch_param_chunks(void* dev_dst, const unsigned char* host_block, size_t bytes,
+                         hipStream_t stream);
 // earl_dispatch_async: completes the records of a parameter block from the plan in device memory
 void launch_async_resolve(DispatchDev* params, const PlanDev& plan, hipStream_t stream);
 void launch_real_prefix(const SegRec* segs, int64_t* prefix, int n_seg, hipStream_t stream);

@@ -81,6 +81,7 @@ def test_plan_build_rejects_bad_host_arguments_without_a_gpu():
     # null plan handles
     assert lib.earl_dispatch(None, None, 0, None, None, None, 0, None) == B.EARL_INVALID_ARG
     assert lib.earl_dispatch_inverse(None, None, 0, None, 0, None) == B.EARL_INVALID_ARG
+    assert lib.earl_dispatch_noalloc(None, None, 0, None, None, None) == B.EARL_INVALID_ARG
     assert lib.earl_dispatch_workspace_bytes(None, None, 0, 1, 1, None) == B.EARL_INVALID_ARG
     assert lib.earl_plan_get_summary(None, None) == B.EARL_INVALID_ARG
     assert lib.earl_plan_destroy(None) == B.EARL_OK
