@@ -12,6 +12,8 @@
 // workgroup: phases are separated by workgroup barriers, wide phases use all 1024 lanes, the
 // serial chain runs in wavefront 0 with the rank loads held one per lane and the arg-min taken
 // by DPP cross-lane operations.
+#include <cstdlib>
+#include <cstring>
 #include <utility>
 
 #include "earl_internal.h"
@@ -76,15 +78,17 @@ struct BlockScratch {
 };
 
 // Exclusive prefix sum of one value per thread; returns the prefix, writes the total.
-__device__ int64_t block_excl_scan(int64_t v, BlockScratch& s, int64_t* total) {
+// n_waves: wavefronts in the workgroup.
+__device__ int64_t block_excl_scan(int64_t v, BlockScratch& s, int64_t* total,
+                                   int n_waves = kPlanWaves) {
   int64_t incl = wave_incl_scan_i64(v);
   if (lane_id() == kWave - 1) s.wave_tot[wave_id()] = incl;
   __syncthreads();
   if (wave_id() == 0) {
-    int64_t t = lane_id() < kPlanWaves ? s.wave_tot[lane_id()] : 0;
+    int64_t t = lane_id() < n_waves ? s.wave_tot[lane_id()] : 0;
     int64_t ti = wave_incl_scan_i64(t);
-    if (lane_id() < kPlanWaves) s.wave_tot[lane_id()] = ti - t;
-    if (lane_id() == kPlanWaves - 1) s.total = ti;
+    if (lane_id() < n_waves) s.wave_tot[lane_id()] = ti - t;
+    if (lane_id() == n_waves - 1) s.total = ti;
   }
   __syncthreads();
   int64_t r = incl - v + s.wave_tot[wave_id()];
@@ -196,9 +200,10 @@ __device__ void label_scan(int N, int n_labels, LabF lab, ValF val, OutF out, in
 // those stages need no workgroup barrier, only program order inside the wavefront.
 template <class KeyPtr, bool kLds>
 __device__ void bitonic_sort_impl(KeyPtr keys, int n) {
+  const int nt = blockDim.x;   // a multiple of 64
   for (int k = 2; k <= n; k <<= 1) {
     for (int j = k >> 1; j > 0; j >>= 1) {
-      for (int t = threadIdx.x; t < (n >> 1); t += T) {
+      for (int t = threadIdx.x; t < (n >> 1); t += nt) {
         const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
         const int x = i | j;
         const uint64_t a = keys[i], b = keys[x];
@@ -307,7 +312,7 @@ __device__ __forceinline__ void lpt_sorted_block(uint32_t& word, uint32_t& ranks
 }
 
 template <int kShift>
-__device__ void lpt_sorted(const PlanDev& p, const uint64_t* keys) {
+__device__ void lpt_sorted(const PlanDev& p, const uint64_t* keys, int32_t* rank_out) {
   const int lane = lane_id();
   const int N = p.N;
   uint32_t word = lane < p.D ? (uint32_t)lane : 0xffffffffu;   // load << 6 | rank
@@ -318,7 +323,7 @@ __device__ void lpt_sorted(const PlanDev& p, const uint64_t* keys) {
     const int32_t idx = (int32_t)(key & 0xffffffffu);
     uint32_t ranks = 0;   // lane s: rank of the s-th item of this block
     lpt_sorted_block<kShift>(word, ranks, lp6, std::make_integer_sequence<int, kWave>{});
-    if (i < N) p.rank[idx] = (int32_t)ranks;
+    if (i < N) rank_out[idx] = (int32_t)ranks;
   }
 }
 
@@ -349,7 +354,7 @@ __device__ __forceinline__ void lpt_sorted64_block(uint64_t& word, uint32_t& ran
 }
 
 template <bool kQuadratic>
-__device__ void lpt_sorted64(const PlanDev& p, const uint64_t* keys) {
+__device__ void lpt_sorted64(const PlanDev& p, const uint64_t* keys, int32_t* rank_out) {
   const int lane = lane_id();
   const int N = p.N;
   uint64_t word = lane < p.D ? (uint64_t)lane : ~0ull;   // load << 6 | rank
@@ -360,7 +365,7 @@ __device__ void lpt_sorted64(const PlanDev& p, const uint64_t* keys) {
     const int32_t idx = (int32_t)(key & 0xffffffffu);
     uint32_t ranks = 0;
     lpt_sorted64_block<kQuadratic>(word, ranks, lp, std::make_integer_sequence<int, kWave>{});
-    if (i < N) p.rank[idx] = (int32_t)ranks;
+    if (i < N) rank_out[idx] = (int32_t)ranks;
   }
 }
 
@@ -370,7 +375,8 @@ __device__ void lpt_sorted64(const PlanDev& p, const uint64_t* keys) {
 // (padded lengths up to 2^21, so a load stays below 2^62); the distance of a load from the
 // smallest one then needs 64 bits and is reduced in two 32-bit rounds, high words first.
 template <bool kQuadratic>
-__device__ void lpt_blocks(const PlanDev& p, const uint64_t* keys, int64_t* lds_load) {
+__device__ void lpt_blocks(const PlanDev& p, const uint64_t* keys, int64_t* lds_load,
+                           int32_t* rank_out) {
   const int lane = lane_id();
   const int D = p.D, N = p.N;
   const int kper = (D + kWave - 1) / kWave;
@@ -419,11 +425,14 @@ __device__ void lpt_blocks(const PlanDev& p, const uint64_t* keys, int64_t* lds_
       }
       if (lane == s) my_rank = r;
     }
-    if (i < N) p.rank[idx] = my_rank;
+    if (i < N) rank_out[idx] = my_rank;
   }
 }
 
-__device__ void lpt_wave0(const PlanDev& p, const uint64_t* keys, int64_t* lds_load) {
+// rank_out: where rank[i] goes (the workspace array, or an LDS copy of it).  lds_load is only
+// needed beyond 64 ranks or 2^58 load units.
+__device__ void lpt_wave0(const PlanDev& p, const uint64_t* keys, int64_t* lds_load,
+                          int32_t* rank_out) {
   const int D = p.D;
   const int64_t max_lp = 0x7fffffffll - (int64_t)(keys[0] >> 32);   // keys are sorted
   const bool quadratic = p.policy == 2;
@@ -431,16 +440,16 @@ __device__ void lpt_wave0(const PlanDev& p, const uint64_t* keys, int64_t* lds_l
   const int64_t max_cost = quadratic ? max_lp * max_lp : max_lp;      // <= 2^42, N * it <= 2^62
   const int64_t load_bound = (int64_t)p.N * max_cost / D + max_cost;
   if (D > kWave || load_bound >= (1ll << 58)) {
-    if (quadratic) lpt_blocks<true>(p, keys, lds_load);
-    else lpt_blocks<false>(p, keys, lds_load);
+    if (quadratic) lpt_blocks<true>(p, keys, lds_load, rank_out);
+    else lpt_blocks<false>(p, keys, lds_load, rank_out);
   } else if (quadratic) {
-    lpt_sorted64<true>(p, keys);
+    lpt_sorted64<true>(p, keys, rank_out);
   } else if (load_bound >= (1 << 26) - 1) {
-    lpt_sorted64<false>(p, keys);
+    lpt_sorted64<false>(p, keys, rank_out);
   } else if (D <= 16) {
-    lpt_sorted<kDppRowShl1>(p, keys);
+    lpt_sorted<kDppRowShl1>(p, keys, rank_out);
   } else {
-    lpt_sorted<kDppWaveShl1>(p, keys);
+    lpt_sorted<kDppWaveShl1>(p, keys, rank_out);
   }
 }
 
@@ -597,7 +606,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const PlanDev p) {
       p.rank[(int32_t)(keys[j] & 0xffffffffu)] = (round & 1) ? D - 1 - k : k;
     }
   } else if (wave_id() == 0) {
-    lpt_wave0(p, keys, lds_load);
+    lpt_wave0(p, keys, lds_load, p.rank);
   }
   __syncthreads();
 
@@ -836,9 +845,489 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const PlanDev p) {
   }
 }
 
+// ---------------------------------------------------------------------------------------
+// The same plan for batches of up to 4096 sequences on up to 64 ranks (every workload the
+// paper's setting produces: Section 3.1 trains with a few hundred to a few thousand episodes
+// per step), with another data flow: nothing is read back from global memory.
+//
+// The kernel above keeps every intermediate array in the workspace, so each of its ~40
+// barrier-separated phases pays a store -> barrier -> load round trip through the L2 cache
+// (a microsecond each, more than the arithmetic).  Here a thread owns kIters CONSECUTIVE
+// sequences and keeps what it computes for them (length, chunk length, source offset, shard,
+// rank, slot, destination row) in registers from the first phase to the segment table; what
+// other threads need (sort keys, ranks, the packed order and its row offsets, micro-batch
+// starts) lives in LDS.  Global memory sees the input lengths once and the outputs once.
+// The workgroup is as wide as the batch needs (64 sequences run in one wavefront, where
+// barriers cost nothing).  Rules, tie-breaks and outputs are those of plan_kernel, which stays
+// the general path (more sequences, ranks or groups, explicit group labels).
+// ---------------------------------------------------------------------------------------
+constexpr int kResMaxSeqs = 4096;
+constexpr int kResMaxGroups = 256;   // source groups, and source shards
+constexpr int kResMaxRanks = 64;
+
+struct ResidentLds {
+  union {
+    uint64_t keys[kResMaxSeqs];        // sort keys, until the ranks are assigned
+    int64_t row_packed[kResMaxSeqs];   // then: destination row of the pos-th sequence, packed order
+  };
+  int32_t rank[kResMaxSeqs];           // by sequence
+  int32_t seq_ids[kResMaxSeqs];        // packed order -> sequence
+  union {
+    int32_t next_start[kResMaxSeqs];   // packed order: first slot of the following micro-batch
+    int32_t mb[kResMaxSeqs];           // then: micro-batch, by sequence
+  };
+  int32_t mb_tmp[kResMaxSeqs + kResMaxRanks];   // per rank: start slot of each micro-batch, then n
+  union {
+    unsigned long long need[2 * kResMaxGroups];   // rows / sequences every source shard must hold
+    struct {
+      int64_t sum[kPlanWaves * kResMaxRanks];
+      int32_t cnt[kPlanWaves * kResMaxRanks];
+    } tab;                                        // per (wavefront, rank) totals of the rank scan
+    unsigned long long a2a[kLdsA2a];
+  };
+  int64_t group_base[kResMaxGroups];   // rows of all sequences before the group's first one
+  int64_t rank_rows[kResMaxRanks];
+  int32_t n_seq[kResMaxRanks];
+  int32_t seq_base[kResMaxRanks + 1];
+  int32_t n_mb_own[kResMaxRanks];      // micro-batches next-fit gave the rank
+  int32_t n_mb[kResMaxRanks];          // micro-batches it reports (equal_mb: the largest count)
+  int32_t mbt_base[kResMaxRanks + 1];
+  int32_t cu_base[kResMaxRanks + 1];
+  BlockScratch bs;
+  int64_t load_max, load_min, dst_rows;
+  int32_t n_mb_max, mb_table_len, cu_len;
+  int invalid, exceeds, bad, bad_invalid;
+};
+
+// Last r in [0, D) with base[r] + r * stride_one <= x (base ascending, base[0] == 0).
+__device__ __forceinline__ int rank_of_entry(const int32_t* base, int D, int x, int stride_one) {
+  int lo = 0, hi = D;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (base[mid] + mid * stride_one <= x) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+template <int kIters>
+__global__ __launch_bounds__(kPlanThreads) void plan_resident_kernel(const PlanDev p) {
+  __shared__ ResidentLds s;
+  const int tid = threadIdx.x, nt = blockDim.x, nw = nt >> 6;
+  const int lane = lane_id(), wave = wave_id();
+  const int N = p.N, G = p.G, R = p.R, S = p.S, D = p.D, C = p.C, K = p.K, P = p.P;
+  const int halves = p.halves, n_dst = D * C;
+  const int64_t B = p.B;
+  const int i0 = tid * kIters;   // this thread owns sequences i0 .. i0 + kIters - 1
+
+  if (tid == 0) { s.invalid = 0; s.exceeds = 0; s.bad = -1; s.bad_invalid = -1; }
+  for (int x = tid; x < 2 * S; x += nt) s.need[x] = 0;
+  __syncthreads();
+
+  // ---- validation and padded chunk geometry (as phase 1 of plan_kernel) --------------------
+  const int64_t lp_cap = B < 0x7fffffffll ? B : 0x7fffffffll;
+  int32_t len[kIters], m[kIters];
+  int64_t own_rows = 0;
+#pragma unroll
+  for (int j = 0; j < kIters; ++j) {
+    const int i = i0 + j;
+    len[j] = 0;
+    m[j] = 1;
+    if (i < N) {
+      int32_t L = p.lengths[i];
+      bool invalid = false;
+      if (L < 1) { invalid = true; L = 1; }
+      if (p.seq_row_in && p.seq_row_in[i] < 0) invalid = true;
+      const int64_t per = ((int64_t)L + K - 1) / K;
+      int64_t mm = (int64_t)P * ((per + P - 1) / P);
+      const bool exceeds = mm * K > lp_cap;
+      if (exceeds) mm = 1;
+      if (p.policy == 2 && mm * K > kMaxQuadraticLp) invalid = true;
+      len[j] = L;
+      m[j] = (int32_t)mm;
+      own_rows += L;
+      if (invalid) { s.invalid = 1; atomicMax(&s.bad_invalid, i); }
+      else if (exceeds) { s.exceeds = 1; atomicMax(&s.bad, i); }
+    }
+  }
+  __syncthreads();
+  if (s.invalid || s.exceeds) {
+    if (tid == 0) {
+      PlanHeader h = {};
+      h.status = s.invalid ? 1 : 2;
+      h.bad_index = s.invalid ? s.bad_invalid : s.bad;
+      *p.hdr = h;
+    }
+    return;
+  }
+
+  // ---- source offsets and replica choice ----------------------------------------------------
+  // Groups own contiguous index ranges here (g = floor(i*G/N)), so the segmented scan is one
+  // plain scan of the lengths minus its value at the group's first sequence.
+  int64_t real_rows = 0;
+  int64_t pre[kIters];
+  {
+    int64_t acc = block_excl_scan(own_rows, s.bs, &real_rows, nw);
+#pragma unroll
+    for (int j = 0; j < kIters; ++j) {
+      pre[j] = acc;
+      acc += len[j];
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < kIters; ++j) {
+    const int i = i0 + j;
+    if (i < N) {
+      const int g = (int)(((int64_t)i * G) / N);
+      const int g_before = i > 0 ? (int)(((int64_t)(i - 1) * G) / N) : -1;
+      if (g != g_before) s.group_base[g] = pre[j];
+    }
+  }
+  __syncthreads();
+  int32_t shard[kIters], seq_k[kIters];
+  int64_t src_row[kIters];
+#pragma unroll
+  for (int j = 0; j < kIters; ++j) {
+    const int i = i0 + j;
+    shard[j] = 0; seq_k[j] = 0; src_row[j] = 0;
+    if (i < N) {
+      const int64_t g = ((int64_t)i * G) / N;
+      const int64_t first = (g * N + G - 1) / G;            // smallest index of group g
+      const int64_t next_first = ((g + 1) * N + G - 1) / G;
+      const int64_t k = i - first;
+      const int64_t row = p.seq_row_in ? p.seq_row_in[i] : pre[j] - s.group_base[g];
+      const int64_t t = R == 1 ? 0 : (k * R) / (next_first - first);
+      const int sh = (int)(g * R + t);
+      shard[j] = sh;
+      seq_k[j] = (int32_t)k;
+      src_row[j] = row;
+      atomicMax(&s.need[sh], (unsigned long long)(row + len[j]));
+      atomicMax(&s.need[S + sh], (unsigned long long)k + 1ull);
+    }
+  }
+  __syncthreads();
+  for (int x = tid; x < S; x += nt) {
+    p.src_rows_needed[x] = (int64_t)s.need[x];
+    p.src_seqs_needed[x] = (int64_t)s.need[S + x];
+  }
+
+  // ---- sort by (padded length desc, index asc), rank assignment ------------------------------
+#pragma unroll
+  for (int j = 0; j < kIters; ++j) {
+    const int i = i0 + j;
+    if (i < N) s.keys[i] = ((uint64_t)(0x7fffffffll - (int64_t)m[j] * K) << 32) | (uint32_t)i;
+  }
+  for (int x = N + tid; x < p.n_pow2; x += nt) s.keys[x] = ~0ull;
+  __syncthreads();
+  bitonic_sort(s.keys, p.n_pow2, true);
+  if (p.policy == 1) {
+    for (int x = tid; x < N; x += nt) {
+      const int round = x / D, k = x - round * D;
+      s.rank[(int32_t)(s.keys[x] & 0xffffffffu)] = (round & 1) ? D - 1 - k : k;
+    }
+  } else if (wave == 0) {
+    lpt_wave0(p, s.keys, nullptr, s.rank);   // D <= 64 and N <= 4096: the LDS load table is never used
+  }
+  __syncthreads();
+
+  // ---- position inside the rank and destination row: scan by rank, in index order -----------
+  // Per rank one wavefront scan of (count << 48 | rows); a lane's own sequences are consecutive,
+  // so their order inside the lane is index order as well.
+  int32_t rk[kIters], slot[kIters];
+  int64_t dst_row[kIters];
+#pragma unroll
+  for (int j = 0; j < kIters; ++j) {
+    rk[j] = i0 + j < N ? s.rank[i0 + j] : -1;
+    slot[j] = 0;
+    dst_row[j] = 0;
+  }
+  constexpr int64_t kRowsMask = ((int64_t)1 << 48) - 1;
+  for (int r = 0; r < D; ++r) {
+    int64_t mine = 0;
+#pragma unroll
+    for (int j = 0; j < kIters; ++j)
+      if (rk[j] == r) mine += ((int64_t)1 << 48) + (int64_t)m[j] * halves;
+    int64_t tot = 0;
+    if (__ballot(mine != 0) != 0) {
+      const int64_t incl = wave_incl_scan_i64(mine);
+      int64_t ex = incl - mine;
+#pragma unroll
+      for (int j = 0; j < kIters; ++j)
+        if (rk[j] == r) {
+          slot[j] = (int32_t)(ex >> 48);
+          dst_row[j] = ex & kRowsMask;
+          ex += ((int64_t)1 << 48) + (int64_t)m[j] * halves;
+        }
+      tot = readlane_i64(incl, kWave - 1);
+    }
+    if (lane == 0) {
+      s.tab.cnt[wave * D + r] = (int32_t)(tot >> 48);
+      s.tab.sum[wave * D + r] = tot & kRowsMask;
+    }
+  }
+  __syncthreads();
+  if (wave == 0) {
+    // lane r: prefix over the wavefronts, totals of rank r, then the scans over the ranks
+    int32_t ac = 0;
+    int64_t as = 0;
+    if (lane < D) {
+      for (int w = 0; w < nw; ++w) {
+        const int x = w * D + lane;
+        const int32_t c = s.tab.cnt[x];
+        const int64_t v = s.tab.sum[x];
+        s.tab.cnt[x] = ac;
+        s.tab.sum[x] = as;
+        ac += c;
+        as += v;
+      }
+      s.n_seq[lane] = ac;
+      s.rank_rows[lane] = as;
+      p.n_seq[lane] = ac;
+      p.rank_load[lane] = as * C;      // padded tokens = C * rows per SP rank
+      for (int c = 0; c < C; ++c) p.shard_rows[(size_t)lane * C + c] = as;
+    }
+    const int64_t incl = wave_incl_scan_i64(ac);
+    if (lane < D) s.seq_base[lane] = (int32_t)(incl - ac);
+    if (lane == 0) s.seq_base[D] = N;
+    const int64_t ld = as * C;
+    int64_t mx = lane < D ? ld : INT64_MIN, mn = lane < D ? ld : INT64_MAX;
+    for (int d = 32; d > 0; d >>= 1) {
+      const int64_t a = __shfl_xor(mx, d), b = __shfl_xor(mn, d);
+      mx = a > mx ? a : mx;
+      mn = b < mn ? b : mn;
+    }
+    const int64_t rows_incl = wave_incl_scan_i64(lane < D ? ld : 0);
+    if (lane == kWave - 1) { s.load_max = mx; s.load_min = mn; s.dst_rows = rows_incl; }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < kIters; ++j) {
+    const int i = i0 + j;
+    if (i < N) {
+      slot[j] += s.tab.cnt[wave * D + rk[j]];
+      dst_row[j] += s.tab.sum[wave * D + rk[j]];
+      const int pos = s.seq_base[rk[j]] + slot[j];
+      s.seq_ids[pos] = i;
+      s.row_packed[pos] = dst_row[j];   // the sort keys are no longer needed
+    }
+  }
+  __syncthreads();
+
+  // ---- micro-batches: next-fit along the packed order (as phase 4 of plan_kernel) -----------
+  const int n_pairs = S * n_dst;
+  for (int x = tid; x < n_pairs; x += nt) s.a2a[x] = 0;   // the scan tables are no longer needed
+#pragma unroll
+  for (int j = 0; j < kIters; ++j) {
+    const int pos = i0 + j;
+    if (pos < N) {
+      const int r = s.rank[s.seq_ids[pos]];
+      const int base = s.seq_base[r];
+      const int n = s.n_seq[r];
+      const int sl = pos - base;
+      const int64_t limit = s.row_packed[pos] * C + B;
+      int lo = sl + 1, hi = n + 1;   // smallest u in [sl+1, n] whose padded prefix exceeds limit
+      while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        const int64_t e = (mid < n ? s.row_packed[base + mid] : s.rank_rows[r]) * C;
+        if (e > limit) hi = mid; else lo = mid + 1;
+      }
+      const int nxt = lo <= n ? lo - 1 : n;
+      s.next_start[pos] = nxt > sl ? nxt : sl + 1;
+    }
+  }
+  __syncthreads();
+  if (wave == 0) {
+    int b = 0;
+    if (lane < D) {
+      const int base = s.seq_base[lane];
+      const int n = s.n_seq[lane];
+      int sl = 0;
+      while (sl < n) {
+        s.mb_tmp[base + lane + b] = sl;
+        sl = s.next_start[base + sl];
+        ++b;
+      }
+      s.mb_tmp[base + lane + b] = n;
+      s.n_mb_own[lane] = b;
+    }
+    int most = b;
+    for (int d = 32; d > 0; d >>= 1) {
+      const int o = __shfl_xor(most, d);
+      most = o > most ? o : most;
+    }
+    const int nm = p.equal_mb ? most : b;
+    const int ns = lane < D ? s.n_seq[lane] : 0;
+    const int64_t t1 = lane < D ? nm + 1 : 0, t2 = lane < D ? nm + ns : 0;
+    const int64_t i1 = wave_incl_scan_i64(t1), i2 = wave_incl_scan_i64(t2);
+    if (lane < D) {
+      s.n_mb[lane] = nm;
+      p.n_mb[lane] = nm;
+      s.mbt_base[lane] = (int32_t)(i1 - t1);
+      s.cu_base[lane] = (int32_t)(i2 - t2);
+    }
+    if (lane == kWave - 1) {
+      s.mbt_base[D] = (int32_t)i1;
+      s.cu_base[D] = (int32_t)i2;
+      s.mb_table_len = (int32_t)i1;
+      s.cu_len = (int32_t)i2;
+      s.n_mb_max = most;
+    }
+  }
+  __syncthreads();
+  const int n_mb_max = s.n_mb_max, mb_table_len = s.mb_table_len;
+  // micro-batch tables (flat, per rank n_mb + 1 entries)
+  for (int x = tid; x < N + D; x += nt) {
+    const int r = rank_of_entry(s.seq_base, D, x, 1);
+    const int b = x - (s.seq_base[r] + r);
+    if (b <= s.n_mb_own[r]) {
+      const int sl = s.mb_tmp[x];
+      const int o = s.mbt_base[r] + b;
+      p.mb_seq_start[o] = sl;
+      p.mb_row_start[o] = sl < s.n_seq[r] ? s.row_packed[s.seq_base[r] + sl] : s.rank_rows[r];
+    }
+  }
+  if (p.equal_mb) {
+    // the appended micro-batches are empty: they start at the rank's last sequence and last row
+    for (int x = tid; x < mb_table_len; x += nt) {
+      const int r = x / (n_mb_max + 1);
+      const int b = x - r * (n_mb_max + 1);
+      if (b > s.n_mb_own[r]) {
+        p.mb_seq_start[x] = s.n_seq[r];
+        p.mb_row_start[x] = s.rank_rows[r];
+      }
+    }
+  }
+  // micro-batch of every sequence; cu_seqlens (local rows, restarting in every micro-batch)
+#pragma unroll
+  for (int j = 0; j < kIters; ++j) {
+    const int pos = i0 + j;
+    if (pos < N) {
+      const int i = s.seq_ids[pos];
+      const int r = s.rank[i];
+      const int base = s.seq_base[r];
+      const int sl = pos - base;
+      const int32_t* starts = s.mb_tmp + base + r;
+      int lo = 0, hi = s.n_mb_own[r];   // last b with starts[b] <= sl
+      while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (starts[mid] <= sl) lo = mid; else hi = mid;
+      }
+      s.mb[i] = lo;   // (next_start was last read by the walk above)
+      p.cu_seqlens[s.cu_base[r] + sl + lo] =
+          (int32_t)(s.row_packed[pos] - s.row_packed[base + starts[lo]]);
+    }
+  }
+  for (int x = tid; x < mb_table_len; x += nt) {
+    const int r = rank_of_entry(s.mbt_base, D, x, 0);
+    const int b = x - s.mbt_base[r];
+    if (b < s.n_mb[r]) {
+      // the entry that closes micro-batch b: its rows (an appended empty one has none)
+      const int base = s.seq_base[r], n = s.n_seq[r], own = s.n_mb_own[r];
+      const int s0 = b <= own ? s.mb_tmp[base + r + b] : n;
+      const int s1 = b + 1 <= own ? s.mb_tmp[base + r + b + 1] : n;
+      const int64_t row0 = s0 < n ? s.row_packed[base + s0] : s.rank_rows[r];
+      const int64_t row1 = s1 < n ? s.row_packed[base + s1] : s.rank_rows[r];
+      if (row1 - row0 > 0x7fffffffll) s.invalid = 1;   // cu_seqlens entries are int32
+      p.cu_seqlens[s.cu_base[r] + s1 + b] = (int32_t)(row1 - row0);
+    }
+  }
+  for (int x = tid; x < N; x += nt) p.seq_ids[x] = s.seq_ids[x];
+  __syncthreads();   // mb[] of every sequence is complete
+
+  // ---- per-sequence outputs, segment table, all-to-all counts (as phase 5 of plan_kernel) ---
+#pragma unroll
+  for (int j = 0; j < kIters; ++j) {
+    const int i = i0 + j;
+    if (i < N) {
+      const int r = rk[j];
+      const int base = s.seq_base[r];
+      const int n = s.n_seq[r];
+      const int32_t mi = m[j];
+      const int32_t mb_i = s.mb[i];
+      const int64_t L = len[j];
+      p.rank[i] = r;
+      p.slot[i] = slot[j];
+      p.mb[i] = mb_i;
+      p.dst_row[i] = dst_row[j];
+      p.seq_shard[i] = shard[j];
+      p.seq_row[i] = src_row[j];
+      for (int c = 0; c < C; ++c) {
+        const int64_t e0 = (int64_t)halves * ((int64_t)C * base + (int64_t)c * n + slot[j]);
+        int64_t real = 0;
+        for (int h = 0; h < halves; ++h) {
+          const int kappa = h == 0 ? c : 2 * C - 1 - c;
+          const int64_t p0 = (int64_t)kappa * mi;
+          int64_t n_real = L - p0;
+          n_real = n_real < 0 ? 0 : (n_real > mi ? mi : n_real);
+          SegRec rec;
+          rec.dst_row = dst_row[j] + (int64_t)h * mi;
+          rec.src_row = src_row[j] + p0;
+          rec.n_real = (int32_t)n_real;
+          rec.n_rows = mi;
+          rec.src_shard = shard[j];
+          rec.pos0 = (int32_t)p0;
+          p.segs[e0 + h] = rec;
+          p.seg_dst_shard[e0 + h] = r * C + c;
+          p.seg_src_seq[e0 + h] = seq_k[j];
+          p.seg_mb[e0 + h] = mb_i;
+          real += n_real;
+        }
+        if (real > 0)
+          atomicAdd(&s.a2a[(size_t)shard[j] * n_dst + r * C + c], (unsigned long long)real);
+      }
+    }
+  }
+  for (int q = tid; q <= n_dst; q += nt) {
+    int64_t v = (int64_t)N * K;
+    if (q < n_dst) {
+      const int r = q / C, c = q - r * C;
+      v = (int64_t)halves * ((int64_t)C * s.seq_base[r] + (int64_t)c * s.n_seq[r]);
+    }
+    p.shard_seg_start[q] = (int32_t)v;
+  }
+  __syncthreads();
+  for (int x = tid; x < n_pairs; x += nt) p.a2a[x] = (int64_t)s.a2a[x];
+  if (tid == 0) {
+    PlanHeader h = {};
+    h.status = s.invalid ? 1 : 0;
+    h.bad_index = -1;
+    h.n_segments = N * K;
+    h.n_mb_max = n_mb_max;
+    h.cu_seqlens_len = s.cu_len;
+    h.mb_table_len = mb_table_len;
+    h.total_real_rows = real_rows;
+    h.total_dst_rows = s.dst_rows;
+    h.rank_load_min = s.load_min;
+    h.rank_load_max = s.load_max;
+    *p.hdr = h;
+  }
+}
+
+// Batches the resident kernel takes (the LDS carve-up above bounds every term).
+bool fits_resident(const PlanDev& p) {
+  return p.N <= kResMaxSeqs && p.D <= kResMaxRanks && p.G <= kResMaxGroups &&
+         p.S <= kResMaxGroups && (int64_t)p.S * p.D * p.C <= kLdsA2a && p.seq_group_in == nullptr;
+}
+
 }  // namespace
 
 void launch_plan(const PlanDev& p, hipStream_t stream) {
+  // EARL_PLAN_KERNEL=general forces the general kernel (the parity tests run both on the same
+  // inputs this way).
+  const char* force = std::getenv("EARL_PLAN_KERNEL");
+  const bool general = force && std::strcmp(force, "general") == 0;
+  if (!general && fits_resident(p)) {
+    const int iters = (p.N + kPlanThreads - 1) / kPlanThreads;         // 1 .. 4
+    const int k_iters = iters <= 1 ? 1 : iters == 2 ? 2 : 4;
+    const int per = (p.N + k_iters - 1) / k_iters;
+    const unsigned nt = (unsigned)((per + kWave - 1) / kWave * kWave);
+    if (k_iters == 1)
+      hipLaunchKernelGGL(plan_resident_kernel<1>, dim3(1), dim3(nt), 0, stream, p);
+    else if (k_iters == 2)
+      hipLaunchKernelGGL(plan_resident_kernel<2>, dim3(1), dim3(nt), 0, stream, p);
+    else
+      hipLaunchKernelGGL(plan_resident_kernel<4>, dim3(1), dim3(nt), 0, stream, p);
+    return;
+  }
   hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, stream, p);
 }
 

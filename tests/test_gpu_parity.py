@@ -78,9 +78,12 @@ def assert_dispatch_equal(w, plan, out, shards_host, fields):
 # ---------------------------------------------------------------------------------------
 # the five workloads
 # ---------------------------------------------------------------------------------------
+@pytest.mark.parametrize("kernel", ["default", "general"])
 @pytest.mark.parametrize("seed", [0, 1, 2])
 @pytest.mark.parametrize("name", synth.CONFIG_NAMES)
-def test_plan_parity_full_size(H, name, seed):
+def test_plan_parity_full_size(H, name, seed, kernel, monkeypatch):
+    if kernel == "general":
+        monkeypatch.setenv("EARL_PLAN_KERNEL", "general")
     w = synth.make_workload(name, seed=seed)
     plan = H.build_plan(w)
     res = H.plan_result(plan)
@@ -542,10 +545,15 @@ def test_two_pass_gather_then_scatter_equals_direct_dispatch(H):
         B.plan_destroy(p)
 
 
-def test_random_plans_sweep(H):
+@pytest.mark.parametrize("kernel", ["default", "general"])
+def test_random_plans_sweep(H, kernel, monkeypatch):
     """Plan-only parity on many random layouts: every size class of the rank-assignment code
     (1, 2, 4, 8, 16, 64 and more ranks), tight budgets with many micro-batches, replicated and
-    scattered source groups, all balancing policies, equal micro-batch counts on and off."""
+    scattered source groups, all balancing policies, equal micro-batch counts on and off.
+    The library has two plan kernels (one that keeps a batch of up to 4096 sequences in registers
+    and LDS, one for everything else); "general" sends every case through the second."""
+    if kernel == "general":
+        monkeypatch.setenv("EARL_PLAN_KERNEL", "general")
     rng = np.random.default_rng(2024)
     for t in range(160):
         D = int(rng.choice([1, 2, 3, 4, 5, 8, 9, 16, 17, 33, 64, 65, 130]))
@@ -554,7 +562,7 @@ def test_random_plans_sweep(H):
         P = int(rng.choice([1, 1, 4, 64]))
         G = int(rng.choice([1, 2, 5, 8]))
         R = int(rng.choice([1, 1, 2, 4]))
-        N = int(rng.integers(1, 700))
+        N = int(rng.integers(1, 700)) if t % 8 else int(rng.integers(1000, 4097))
         hi = int(rng.choice([8, 300, 5000]))
         L = rng.integers(1, hi + 1, size=N)
         K = 2 * C if (z and C > 1) else C
