@@ -235,6 +235,56 @@ __device__ void bitonic_sort(uint64_t* keys, int n, bool keys_in_lds) {
 }
 
 // ---------------------------------------------------------------------------------------
+// The same sort with the keys of a stage's partners exchanged between LANES where they are
+// fewer than 64 apart: element x is always handled by lane x & 63 of the same thread, so the
+// six stages with partner distance 32 .. 1 that end every merge run in registers on cross-lane
+// moves, with one LDS read before and one LDS write after them, and all stages of the merges
+// up to 64 keys run in registers in one go.  Only partner distances of 64 and more go through
+// LDS with a workgroup barrier per stage (10 of the 55 stages of 1024 keys).
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ uint64_t exchange_with_lane(uint64_t key, int x, int j, int k) {
+  const uint64_t other = (uint64_t)__shfl_xor((unsigned long long)key, j);
+  const bool keep_smaller = ((x & j) == 0) == ((x & k) == 0);   // lower partner of an ascending run
+  const bool smaller = key < other;
+  return smaller == keep_smaller ? key : other;
+}
+
+__device__ void bitonic_sort_lanes(uint64_t* keys_generic, int n) {
+  typedef __attribute__((address_space(3))) uint64_t* LdsKeys;
+  LdsKeys keys = (LdsKeys)keys_generic;
+  const int nt = blockDim.x;   // a multiple of 64
+  // merges of up to 64 keys: all partners inside the wavefront
+  for (int x = threadIdx.x; x < n; x += nt) {
+    uint64_t key = keys[x];
+    for (int k = 2; k <= kWave && k <= n; k <<= 1)
+      for (int j = k >> 1; j > 0; j >>= 1) key = exchange_with_lane(key, x, j, k);
+    keys[x] = key;
+  }
+  __syncthreads();
+  for (int k = 2 * kWave; k <= n; k <<= 1) {
+    for (int j = k >> 1; j >= kWave; j >>= 1) {
+      for (int t = threadIdx.x; t < (n >> 1); t += nt) {
+        const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
+        const int y = i | j;
+        const uint64_t a = keys[i], b = keys[y];
+        if ((a > b) == ((i & k) == 0)) {
+          keys[i] = b;
+          keys[y] = a;
+        }
+      }
+      __syncthreads();
+    }
+    for (int x = threadIdx.x; x < n; x += nt) {
+      uint64_t key = keys[x];
+#pragma unroll
+      for (int j = kWave >> 1; j > 0; j >>= 1) key = exchange_with_lane(key, x, j, k);
+      keys[x] = key;
+    }
+    __syncthreads();
+  }
+}
+
+// ---------------------------------------------------------------------------------------
 // Longest-first list scheduling in wavefront 0.
 //
 // keys[] holds the sequences sorted by (padded length descending, index ascending); the low
@@ -281,7 +331,9 @@ __device__ __forceinline__ uint32_t wave_min_low(uint32_t x) {
 // gives grown; above it w[i] > grown and w[i] < w'[i] keep w[i]).  That is one v_max and one
 // v_min with a DPP lane shift, against a log2(D)-step butterfly plus compare and select when
 // the loads stay in place and the minimum is searched; head and grown word travel through
-// scalar registers, and the winner (head & 63) is written into lane s of `ranks`.
+// scalar registers, and the head word (the winner is its low six bits) is written into lane s
+// of `heads`.  (The median of the three in one v_med3_u32 needs the shifted list in a register
+// of its own, one more instruction, and measured slower.)
 // kShift: row_shl:1 when the ranks fit one row of 16 lanes, else wave_shl:1.
 // Items past N have length 0 and come last: the head is put back where it was.
 // Lanes >= D hold 0xffffffff; a real word stays below it because the caller only takes this
@@ -292,23 +344,47 @@ __device__ __forceinline__ void writelane_const(uint32_t& v, uint32_t value) {
   asm volatile("v_writelane_b32 %0, %1, %2" : "+v"(v) : "s"(value), "n"(kLane));
 }
 
-template <int kShift, int kItem>
-__device__ __forceinline__ void lpt_sorted_step(uint32_t& word, uint32_t& ranks, uint32_t lp6) {
-  const uint32_t lp_s = (uint32_t)__builtin_amdgcn_readlane((int)lp6, kItem);
-  const uint32_t head = (uint32_t)__builtin_amdgcn_readfirstlane((int)word);
-  const uint32_t grown = head + lp_s;
-  const uint32_t t = word > grown ? word : grown;
-  // lanes without a right-hand neighbour (end of the row or of the wavefront) read all ones
-  const uint32_t next = (uint32_t)__builtin_amdgcn_update_dpp((int)0xffffffffu, (int)word, kShift,
-                                                              0xf, 0xf, false);
-  word = next < t ? next : t;
-  writelane_const<kItem>(ranks, head & 63u);
-}
+// Two steps of the chain, written out by hand: six instructions per step (length to a scalar
+// register, head to a scalar register, scalar add, max, record the head, min with the
+// neighbouring lane) against eight from the compiler, which masks the rank before recording it
+// and fills the one wait state that reading a fresh result across lanes needs with a no-op,
+// where here the read of the next length stands (measured: 21.7 -> 19 ns per step; a lone
+// wavefront issues an instruction every six to seven cycles).  The list alternates between the
+// registers a and b: the DPP min writes over its second operand, whose lanes without a
+// right-hand neighbour (end of the row or of the wavefront) keep max(word, grown), as if they
+// had read all ones.  kItem is even; `heads` receives in lane s the head word at step s, whose
+// low six bits are the winning rank.
+#define EARL_LPT_TWO_STEPS(SHIFT)                                                        \
+  asm volatile(                                                                          \
+      "v_readlane_b32 %[lp], %[lp6], %[k0]\n\t"                                          \
+      "v_readfirstlane_b32 %[head], %[a]\n\t"                                            \
+      "s_add_u32 %[grown], %[head], %[lp]\n\t"                                           \
+      "v_max_u32 %[b], %[grown], %[a]\n\t"                                               \
+      "v_writelane_b32 %[heads], %[head], %[k0]\n\t"                                     \
+      "v_min_u32_dpp %[b], %[a], %[b] " SHIFT " row_mask:0xf bank_mask:0xf\n\t"          \
+      "v_readlane_b32 %[lp], %[lp6], %[k1]\n\t"                                          \
+      "v_readfirstlane_b32 %[head], %[b]\n\t"                                            \
+      "s_add_u32 %[grown], %[head], %[lp]\n\t"                                           \
+      "v_max_u32 %[a], %[grown], %[b]\n\t"                                               \
+      "v_writelane_b32 %[heads], %[head], %[k1]\n\t"                                     \
+      "v_min_u32_dpp %[a], %[b], %[a] " SHIFT " row_mask:0xf bank_mask:0xf\n\t"          \
+      : [a] "+v"(a), [b] "=&v"(b), [heads] "+v"(heads), [lp] "=&s"(s_lp),                \
+        [head] "=&s"(s_head), [grown] "=&s"(s_grown)                                     \
+      : [lp6] "v"(lp6), [k0] "n"(kItem), [k1] "n"(kItem + 1)                             \
+      : "scc")
 
-template <int kShift, int... kItems>
-__device__ __forceinline__ void lpt_sorted_block(uint32_t& word, uint32_t& ranks, uint32_t lp6,
-                                                 std::integer_sequence<int, kItems...>) {
-  (lpt_sorted_step<kShift, kItems>(word, ranks, lp6), ...);
+template <int kShift, int kItem>
+__device__ __forceinline__ void lpt_sorted_two_steps(uint32_t& a, uint32_t& heads, uint32_t lp6) {
+  uint32_t b, s_lp, s_head, s_grown;
+  if (kShift == kDppRowShl1) EARL_LPT_TWO_STEPS("row_shl:1");
+  else EARL_LPT_TWO_STEPS("wave_shl:1");
+}
+#undef EARL_LPT_TWO_STEPS
+
+template <int kShift, int... kPairs>
+__device__ __forceinline__ void lpt_sorted_block(uint32_t& word, uint32_t& heads, uint32_t lp6,
+                                                 std::integer_sequence<int, kPairs...>) {
+  (lpt_sorted_two_steps<kShift, 2 * kPairs>(word, heads, lp6), ...);
 }
 
 template <int kShift>
@@ -321,9 +397,9 @@ __device__ void lpt_sorted(const PlanDev& p, const uint64_t* keys, int32_t* rank
     const uint64_t key = i < N ? keys[i] : ~0ull;
     const uint32_t lp6 = i < N ? (uint32_t)(0x7fffffff - (int32_t)(key >> 32)) << 6 : 0u;
     const int32_t idx = (int32_t)(key & 0xffffffffu);
-    uint32_t ranks = 0;   // lane s: rank of the s-th item of this block
-    lpt_sorted_block<kShift>(word, ranks, lp6, std::make_integer_sequence<int, kWave>{});
-    if (i < N) rank_out[idx] = (int32_t)ranks;
+    uint32_t heads = 0;   // lane s: the list's head word when the s-th item of this block came
+    lpt_sorted_block<kShift>(word, heads, lp6, std::make_integer_sequence<int, kWave / 2>{});
+    if (i < N) rank_out[idx] = (int32_t)(heads & 63u);
   }
 }
 
@@ -1018,7 +1094,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_resident_kernel(const PlanD
   }
   for (int x = N + tid; x < p.n_pow2; x += nt) s.keys[x] = ~0ull;
   __syncthreads();
-  bitonic_sort(s.keys, p.n_pow2, true);
+  bitonic_sort_lanes(s.keys, p.n_pow2);
   if (p.policy == 1) {
     for (int x = tid; x < N; x += nt) {
       const int round = x / D, k = x - round * D;
