@@ -403,6 +403,83 @@ __device__ void lpt_sorted(const PlanDev& p, const uint64_t* keys, int32_t* rank
   }
 }
 
+// Up to 16 ranks: the whole chain on the vector unit.  The list fits one row of 16 lanes, and
+// every row holds its own identical copy; row_newbcast (a DPP control of this chip family that
+// hands one lane of a row to all its lanes) replaces the trip through scalar registers that
+// v_readfirstlane / s_add / scalar operand make, so a step is five vector instructions: the
+// next length to all lanes (off the chain), head + length, max, min with the neighbouring lane,
+// and a masked move that records head + length (its low six bits are the winner) in the four
+// lanes of one (row, bank), item s ending up in lane s of register s mod 4.  Written by hand
+// so that the two wait states a cross-lane read of a fresh result needs are always filled.
+// lp_j: lane l holds the shifted padded length of item 16*j + (l & 15) of the block.
+#define EARL_LPT16_STEP(A, B, H, BANK, NEXTREG, NEXTLANE)                                        \
+  "v_add_u32_dpp %[g], %[" A "], %[lp] row_newbcast:0 row_mask:0xf bank_mask:0xf\n\t"            \
+  "v_max_u32 %[" B "], %[g], %[" A "]\n\t"                                                       \
+  "v_min_u32_dpp %[" B "], %[" A "], %[" B "] row_shl:1 row_mask:0xf bank_mask:0xf\n\t"          \
+  "v_mov_b32_dpp %[" H "], %[g] quad_perm:[0,1,2,3] row_mask:%[rm] bank_mask:" BANK "\n\t"       \
+  "v_mov_b32_dpp %[lp], %[" NEXTREG "] row_newbcast:" NEXTLANE " row_mask:0xf bank_mask:0xf\n\t"
+
+// Sixteen steps on the items of one lp register (lane l of lpreg: item 16*kQuarter + (l & 15)).
+// The list alternates between a and b and is back in a at the end.  lp holds the first item's
+// length in all lanes on entry and the next sixteen's first (from lpnext) on exit: the length
+// move and the record move are the two instructions that every cross-lane read of the list
+// needs between it and the instruction that wrote the list, inside a block and from one block
+// to the next.
+template <int kQuarter>
+__device__ __forceinline__ void lpt16_sixteen_steps(uint32_t& a, uint32_t& lp, uint32_t lpreg,
+                                                    uint32_t lpnext, uint32_t& h0, uint32_t& h1,
+                                                    uint32_t& h2, uint32_t& h3) {
+  uint32_t b, g;
+  asm volatile(
+      EARL_LPT16_STEP("a", "b", "h0", "1", "lpreg", "1")
+      EARL_LPT16_STEP("b", "a", "h1", "1", "lpreg", "2")
+      EARL_LPT16_STEP("a", "b", "h2", "1", "lpreg", "3")
+      EARL_LPT16_STEP("b", "a", "h3", "1", "lpreg", "4")
+      EARL_LPT16_STEP("a", "b", "h0", "2", "lpreg", "5")
+      EARL_LPT16_STEP("b", "a", "h1", "2", "lpreg", "6")
+      EARL_LPT16_STEP("a", "b", "h2", "2", "lpreg", "7")
+      EARL_LPT16_STEP("b", "a", "h3", "2", "lpreg", "8")
+      EARL_LPT16_STEP("a", "b", "h0", "4", "lpreg", "9")
+      EARL_LPT16_STEP("b", "a", "h1", "4", "lpreg", "10")
+      EARL_LPT16_STEP("a", "b", "h2", "4", "lpreg", "11")
+      EARL_LPT16_STEP("b", "a", "h3", "4", "lpreg", "12")
+      EARL_LPT16_STEP("a", "b", "h0", "8", "lpreg", "13")
+      EARL_LPT16_STEP("b", "a", "h1", "8", "lpreg", "14")
+      EARL_LPT16_STEP("a", "b", "h2", "8", "lpreg", "15")
+      EARL_LPT16_STEP("b", "a", "h3", "8", "lpnext", "0")
+      : [a] "+v"(a), [b] "=&v"(b), [g] "=&v"(g), [lp] "+v"(lp), [h0] "+v"(h0), [h1] "+v"(h1),
+        [h2] "+v"(h2), [h3] "+v"(h3)
+      : [lpreg] "v"(lpreg), [lpnext] "v"(lpnext), [rm] "n"(1 << kQuarter));
+}
+#undef EARL_LPT16_STEP
+
+__device__ void lpt_sorted16(const PlanDev& p, const uint64_t* keys, int32_t* rank_out) {
+  const int lane = lane_id();
+  const int N = p.N;
+  const int col = lane & 15;
+  uint32_t word = col < p.D ? (uint32_t)col : 0xffffffffu;   // load << 6 | rank, one list per row
+  for (int start = 0; start < N; start += kWave) {
+    uint32_t lpreg[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int x = start + 16 * j + col;
+      lpreg[j] = x < N ? (uint32_t)(0x7fffffff - (int32_t)(keys[x] >> 32)) << 6 : 0u;
+    }
+    uint32_t h0 = 0, h1 = 0, h2 = 0, h3 = 0;
+    // item 0's length to all lanes; the blocks below keep it one item ahead
+    uint32_t lp = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)lpreg[0], 0x150, 0xf, 0xf, false);
+    lpt16_sixteen_steps<0>(word, lp, lpreg[0], lpreg[1], h0, h1, h2, h3);
+    lpt16_sixteen_steps<1>(word, lp, lpreg[1], lpreg[2], h0, h1, h2, h3);
+    lpt16_sixteen_steps<2>(word, lp, lpreg[2], lpreg[3], h0, h1, h2, h3);
+    lpt16_sixteen_steps<3>(word, lp, lpreg[3], lpreg[3], h0, h1, h2, h3);
+    const int i = start + lane;
+    if (i < N) {
+      const uint32_t mine = (lane & 2) ? ((lane & 1) ? h3 : h2) : ((lane & 1) ? h1 : h0);
+      rank_out[(int32_t)(keys[i] & 0xffffffffu)] = (int32_t)(mine & 63u);
+    }
+  }
+}
+
 // The same sorted list with 64-bit words (two registers per lane), for loads that do not fit 26
 // bits: huge padded lengths, or the quadratic cost (kQuadratic: a rank's load grows by the
 // square of the padded length).  D <= 64 and loads below 2^58.
@@ -523,7 +600,7 @@ __device__ void lpt_wave0(const PlanDev& p, const uint64_t* keys, int64_t* lds_l
   } else if (load_bound >= (1 << 26) - 1) {
     lpt_sorted64<false>(p, keys, rank_out);
   } else if (D <= 16) {
-    lpt_sorted<kDppRowShl1>(p, keys, rank_out);
+    lpt_sorted16(p, keys, rank_out);
   } else {
     lpt_sorted<kDppWaveShl1>(p, keys, rank_out);
   }
@@ -922,7 +999,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const PlanDev p) {
 }
 
 // ---------------------------------------------------------------------------------------
-// The same plan for batches of up to 4096 sequences on up to 64 ranks (every workload the
+// The same plan for batches of up to 2048 sequences on up to 64 ranks (every workload the
 // paper's setting produces: Section 3.1 trains with a few hundred to a few thousand episodes
 // per step), with another data flow: nothing is read back from global memory.
 //
@@ -930,14 +1007,17 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const PlanDev p) {
 // barrier-separated phases pays a store -> barrier -> load round trip through the L2 cache
 // (a microsecond each, more than the arithmetic).  Here a thread owns kIters CONSECUTIVE
 // sequences and keeps what it computes for them (length, chunk length, source offset, shard,
-// rank, slot, destination row) in registers from the first phase to the segment table; what
-// other threads need (sort keys, ranks, the packed order and its row offsets, micro-batch
-// starts) lives in LDS.  Global memory sees the input lengths once and the outputs once.
+// rank, slot, destination row) in registers until its place in the packed order is known; what
+// other threads need (sort keys, ranks, the packed order with its row offsets and a copy of the
+// per-sequence values, micro-batch starts) lives in LDS.  Global memory sees the input lengths
+// once and the outputs once, the segment table in table order (neighbouring lanes write
+// neighbouring records; written per sequence, 32-byte records scattered over the ranks' blocks,
+// the table alone took 25 us for 2048 sequences in 8 chunks).
 // The workgroup is as wide as the batch needs (64 sequences run in one wavefront, where
 // barriers cost nothing).  Rules, tie-breaks and outputs are those of plan_kernel, which stays
 // the general path (more sequences, ranks or groups, explicit group labels).
 // ---------------------------------------------------------------------------------------
-constexpr int kResMaxSeqs = 4096;
+constexpr int kResMaxSeqs = 2048;
 constexpr int kResMaxGroups = 256;   // source groups, and source shards
 constexpr int kResMaxRanks = 64;
 
@@ -948,10 +1028,14 @@ struct ResidentLds {
   };
   int32_t rank[kResMaxSeqs];           // by sequence
   int32_t seq_ids[kResMaxSeqs];        // packed order -> sequence
-  union {
-    int32_t next_start[kResMaxSeqs];   // packed order: first slot of the following micro-batch
-    int32_t mb[kResMaxSeqs];           // then: micro-batch, by sequence
-  };
+  int32_t next_start[kResMaxSeqs];     // packed order: first slot of the following micro-batch
+  // what the segment table needs about the pos-th sequence of the packed order
+  int64_t st_src_row[kResMaxSeqs];
+  int32_t st_len[kResMaxSeqs];
+  int32_t st_m[kResMaxSeqs];
+  int32_t st_shard[kResMaxSeqs];
+  int32_t st_k[kResMaxSeqs];
+  int32_t st_mb[kResMaxSeqs];
   int32_t mb_tmp[kResMaxSeqs + kResMaxRanks];   // per rank: start slot of each micro-batch, then n
   union {
     unsigned long long need[2 * kResMaxGroups];   // rows / sequences every source shard must hold
@@ -1101,7 +1185,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_resident_kernel(const PlanD
       s.rank[(int32_t)(s.keys[x] & 0xffffffffu)] = (round & 1) ? D - 1 - k : k;
     }
   } else if (wave == 0) {
-    lpt_wave0(p, s.keys, nullptr, s.rank);   // D <= 64 and N <= 4096: the LDS load table is never used
+    lpt_wave0(p, s.keys, nullptr, s.rank);   // D <= 64 and N <= 2048: the LDS load table is never used
   }
   __syncthreads();
 
@@ -1184,6 +1268,17 @@ __global__ __launch_bounds__(kPlanThreads) void plan_resident_kernel(const PlanD
       const int pos = s.seq_base[rk[j]] + slot[j];
       s.seq_ids[pos] = i;
       s.row_packed[pos] = dst_row[j];   // the sort keys are no longer needed
+      s.st_src_row[pos] = src_row[j];
+      s.st_len[pos] = len[j];
+      s.st_m[pos] = m[j];
+      s.st_shard[pos] = shard[j];
+      s.st_k[pos] = seq_k[j];
+      // per-sequence outputs (the micro-batch follows from the packed order below)
+      p.rank[i] = rk[j];
+      p.slot[i] = slot[j];
+      p.dst_row[i] = dst_row[j];
+      p.seq_shard[i] = shard[j];
+      p.seq_row[i] = src_row[j];
     }
   }
   __syncthreads();
@@ -1287,7 +1382,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_resident_kernel(const PlanD
         const int mid = (lo + hi) >> 1;
         if (starts[mid] <= sl) lo = mid; else hi = mid;
       }
-      s.mb[i] = lo;   // (next_start was last read by the walk above)
+      s.st_mb[pos] = lo;
+      p.mb[i] = lo;
       p.cu_seqlens[s.cu_base[r] + sl + lo] =
           (int32_t)(s.row_packed[pos] - s.row_packed[base + starts[lo]]);
     }
@@ -1307,50 +1403,52 @@ __global__ __launch_bounds__(kPlanThreads) void plan_resident_kernel(const PlanD
     }
   }
   for (int x = tid; x < N; x += nt) p.seq_ids[x] = s.seq_ids[x];
-  __syncthreads();   // mb[] of every sequence is complete
+  __syncthreads();   // st_mb[] is complete
 
-  // ---- per-sequence outputs, segment table, all-to-all counts (as phase 5 of plan_kernel) ---
-#pragma unroll
-  for (int j = 0; j < kIters; ++j) {
-    const int i = i0 + j;
-    if (i < N) {
-      const int r = rk[j];
-      const int base = s.seq_base[r];
-      const int n = s.n_seq[r];
-      const int32_t mi = m[j];
-      const int32_t mb_i = s.mb[i];
-      const int64_t L = len[j];
-      p.rank[i] = r;
-      p.slot[i] = slot[j];
-      p.mb[i] = mb_i;
-      p.dst_row[i] = dst_row[j];
-      p.seq_shard[i] = shard[j];
-      p.seq_row[i] = src_row[j];
-      for (int c = 0; c < C; ++c) {
-        const int64_t e0 = (int64_t)halves * ((int64_t)C * base + (int64_t)c * n + slot[j]);
-        int64_t real = 0;
-        for (int h = 0; h < halves; ++h) {
-          const int kappa = h == 0 ? c : 2 * C - 1 - c;
-          const int64_t p0 = (int64_t)kappa * mi;
-          int64_t n_real = L - p0;
-          n_real = n_real < 0 ? 0 : (n_real > mi ? mi : n_real);
-          SegRec rec;
-          rec.dst_row = dst_row[j] + (int64_t)h * mi;
-          rec.src_row = src_row[j] + p0;
-          rec.n_real = (int32_t)n_real;
-          rec.n_rows = mi;
-          rec.src_shard = shard[j];
-          rec.pos0 = (int32_t)p0;
-          p.segs[e0 + h] = rec;
-          p.seg_dst_shard[e0 + h] = r * C + c;
-          p.seg_src_seq[e0 + h] = seq_k[j];
-          p.seg_mb[e0 + h] = mb_i;
-          real += n_real;
-        }
-        if (real > 0)
-          atomicAdd(&s.a2a[(size_t)shard[j] * n_dst + r * C + c], (unsigned long long)real);
-      }
+  // ---- segment table and all-to-all counts (as phase 5 of plan_kernel) ----------------------
+  // In table order: entry u = C*base_r + c*n_r + slot stands for the `halves` segments of one
+  // sequence on one SP rank.
+  for (int u = tid; u < N * C; u += nt) {
+    int lo = 0, hi = D;   // last rank r with C * seq_base[r] <= u
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (C * s.seq_base[mid] <= u) lo = mid; else hi = mid;
     }
+    const int r = lo;
+    const int base = s.seq_base[r];
+    const int n = s.n_seq[r];
+    const int rem = u - C * base;
+    const int c = rem / n;
+    const int pos = base + (rem - c * n);
+    const int32_t mi = s.st_m[pos];
+    const int64_t L = s.st_len[pos];
+    const int64_t src0 = s.st_src_row[pos];
+    const int64_t dst0 = s.row_packed[pos];
+    const int32_t sh = s.st_shard[pos];
+    const int32_t k_in_group = s.st_k[pos];
+    const int32_t mb_i = s.st_mb[pos];
+    const int64_t e0 = (int64_t)halves * u;
+    int64_t real = 0;
+    for (int h = 0; h < halves; ++h) {
+      const int kappa = h == 0 ? c : 2 * C - 1 - c;
+      const int64_t p0 = (int64_t)kappa * mi;
+      int64_t n_real = L - p0;
+      n_real = n_real < 0 ? 0 : (n_real > mi ? mi : n_real);
+      SegRec rec;
+      rec.dst_row = dst0 + (int64_t)h * mi;
+      rec.src_row = src0 + p0;
+      rec.n_real = (int32_t)n_real;
+      rec.n_rows = mi;
+      rec.src_shard = sh;
+      rec.pos0 = (int32_t)p0;
+      p.segs[e0 + h] = rec;
+      p.seg_dst_shard[e0 + h] = r * C + c;
+      p.seg_src_seq[e0 + h] = k_in_group;
+      p.seg_mb[e0 + h] = mb_i;
+      real += n_real;
+    }
+    if (real > 0)
+      atomicAdd(&s.a2a[(size_t)sh * n_dst + r * C + c], (unsigned long long)real);
   }
   for (int q = tid; q <= n_dst; q += nt) {
     int64_t v = (int64_t)N * K;
@@ -1392,16 +1490,13 @@ void launch_plan(const PlanDev& p, hipStream_t stream) {
   const char* force = std::getenv("EARL_PLAN_KERNEL");
   const bool general = force && std::strcmp(force, "general") == 0;
   if (!general && fits_resident(p)) {
-    const int iters = (p.N + kPlanThreads - 1) / kPlanThreads;         // 1 .. 4
-    const int k_iters = iters <= 1 ? 1 : iters == 2 ? 2 : 4;
+    const int k_iters = p.N <= kPlanThreads ? 1 : 2;
     const int per = (p.N + k_iters - 1) / k_iters;
     const unsigned nt = (unsigned)((per + kWave - 1) / kWave * kWave);
     if (k_iters == 1)
       hipLaunchKernelGGL(plan_resident_kernel<1>, dim3(1), dim3(nt), 0, stream, p);
-    else if (k_iters == 2)
-      hipLaunchKernelGGL(plan_resident_kernel<2>, dim3(1), dim3(nt), 0, stream, p);
     else
-      hipLaunchKernelGGL(plan_resident_kernel<4>, dim3(1), dim3(nt), 0, stream, p);
+      hipLaunchKernelGGL(plan_resident_kernel<2>, dim3(1), dim3(nt), 0, stream, p);
     return;
   }
   hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, stream, p);
