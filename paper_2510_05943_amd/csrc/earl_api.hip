@@ -42,7 +42,7 @@ size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 size_t param_block_bytes(int n_fields, int n_src, int n_dst) {
   const size_t n_recs = (size_t)n_fields * n_dst;
   size_t b = align_up(sizeof(DispatchDev));
-  b += align_up(sizeof(int64_t) * (n_recs + 1));
+  b += align_up(sizeof(int64_t) * (n_recs + 2));
   b += align_up(sizeof(TileRec) * n_recs);
   // per field: S source pointers, D*C destination pointers, D*C counter rows
   b += align_up(sizeof(void*) * (size_t)n_fields * ((size_t)n_src + 2 * (size_t)n_dst));
@@ -300,7 +300,7 @@ struct BlockBuilder {
     hd.n_recs = n_recs;
     size_t off = align_up(sizeof(DispatchDev));
     hd.tile_start_ofs = (uint32_t)off;
-    off += align_up(sizeof(int64_t) * ((size_t)n_recs + 1));
+    off += align_up(sizeof(int64_t) * ((size_t)n_recs + 2));
     hd.recs_ofs = (uint32_t)off;
     off += align_up(sizeof(TileRec) * (size_t)n_recs);
     hd.ptrs_ofs = (uint32_t)off;
@@ -651,6 +651,71 @@ int32_t static_scratch(unsigned char** out) {
   return EARL_OK;
 }
 
+// Launches whose fields with rows of 16 bytes and more sum to less than this go through the
+// direct kernel as a whole: below it the tile-code pass costs more than it saves.
+constexpr int64_t kDirectMaxCoarseBytes = (int64_t)64 << 20;
+constexpr int64_t kMaxLaunchTiles = 0x7fffffffll;
+constexpr int kJobShiftHost = 12;   // bytes of a direct job, as in the kernel
+
+struct RecordOrder {
+  int n_direct = 0;
+  int64_t jobs = 0;    // 4 KiB jobs of the direct records
+  int64_t tiles = 0;   // tile codes of the other records
+};
+
+// Writes the records of a forward call in launch order: first those that are decoded inside the
+// copy kernel (fields with rows under 16 bytes, position ids, cu_seqlens; every field when the
+// wide ones are small), then those that go through tile codes.  bytes_of(f, q): bytes of
+// destination shard q of field f as the launch is sized; fill(rec, f, q, index): completes a
+// record.  Returns false if one launch cannot hold the tiles.
+template <class BytesF, class FillF>
+bool order_records(BlockBuilder& b, const TileRec* protos, int F, int n_dst, BytesF bytes_of,
+                   FillF fill, RecordOrder* out) {
+  int64_t coarse_bytes = 0;
+  for (int f = 0; f < F; ++f) {
+    if (protos[f].tile_shift == kFineTileShift || protos[f].kind == kFieldLinear) continue;
+    for (int q = 0; q < n_dst && coarse_bytes <= kDirectMaxCoarseBytes; ++q)
+      coarse_bytes += bytes_of(f, q);
+  }
+  const bool all_direct = coarse_bytes <= kDirectMaxCoarseBytes;
+  int64_t* ts = b.tile_start();
+  TileRec* recs = b.recs();
+  RecordOrder o;
+  size_t n_rec = 0;
+  for (int pass = 0; pass < 2; ++pass) {
+    int64_t count = 0;
+    for (int f = 0; f < F; ++f) {
+      const TileRec& proto = protos[f];
+      const bool direct = all_direct || proto.tile_shift == kFineTileShift || proto.kind == kFieldLinear;
+      if (direct != (pass == 0)) continue;
+      const int shift = direct ? kJobShiftHost : kTileShift;
+      for (int q = 0; q < n_dst; ++q) {
+        TileRec& r = recs[n_rec];
+        r = proto;
+        r.tile_shift = (int16_t)shift;
+        r.tile_first = count;
+        fill(r, f, q, n_rec);
+        ts[n_rec + pass] = count;
+        ++n_rec;
+        count += (bytes_of(f, q) + ((int64_t)1 << shift) - 1) >> shift;
+        if (count > kMaxLaunchTiles) return false;   // (also keeps the running sum from overflowing)
+      }
+    }
+    ts[n_rec + pass] = count;   // closes this part of the table
+    if (pass == 0) {
+      o.n_direct = (int)n_rec;
+      o.jobs = count;
+    } else {
+      o.tiles = count;
+    }
+  }
+  if (o.tiles * kSubTiles > kMaxLaunchTiles) return false;
+  b.hd.n_direct = o.n_direct;
+  std::memcpy(b.data, &b.hd, sizeof(b.hd));
+  *out = o;
+  return true;
+}
+
 // earl_dispatch after the plan's summary is on the host.  fixed_block != null: the parameter
 // block is built in that host buffer and travels to the device as kernel arguments (nothing is
 // allocated, no staging memory is touched); else it is built in a vector and copied through a
@@ -684,8 +749,6 @@ int32_t dispatch_impl(earl_plan* p, const earl_field* fields, int32_t n_fields,
   if (!b.init(F * n_dst, F, S, n_dst, fixed_block, fixed_block_bytes))
     return fail(EARL_CAPACITY, "the parameter block of this call needs %zu bytes, %zu available",
                 b.size, fixed_block_bytes);
-  int64_t* ts = b.tile_start();
-  TileRec* recs = b.recs();
   const void** ptrs = b.ptrs();
   // pointer tables and one prototype record per field
   TileRec protos[EARL_MAX_FIELDS + 2];
@@ -728,38 +791,27 @@ int32_t dispatch_impl(earl_plan* p, const earl_field* fields, int32_t n_fields,
     proto.tile_shift = (int16_t)tile_shift_of(proto.row_bytes, proto.kind);
     pi += S + 2 * n_dst;
   }
-  // records in launch order: the fields with 1 KiB tiles first
-  int64_t tiles = 0, fine = 0;
-  size_t n_rec = 0;
-  for (int pass = 0; pass < 2; ++pass) {
-    for (int f = 0; f < F; ++f) {
-      const TileRec& proto = protos[f];
-      if ((proto.tile_shift == kFineTileShift) != (pass == 0)) continue;
-      const int64_t tb = (int64_t)1 << proto.tile_shift;
-      for (int q = 0; q < n_dst; ++q) {
-        TileRec& r = recs[n_rec];
-        r = proto;
-        r.tile_first = tiles;
-        r.dst = const_cast<void*>(ptrs[proto.dst_ptr_index + q]);
+  RecordOrder order;
+  const bool fits = order_records(
+      b, protos, F, n_dst,
+      [&](int f, int q) -> int64_t {
+        return protos[f].kind == kFieldLinear ? (q == 0 ? 4ll * p->hdr.cu_seqlens_len : 0)
+                                              : shard_rows[q] * (int64_t)protos[f].row_bytes;
+      },
+      [&](TileRec& r, int f, int q, size_t) {
+        r.dst = const_cast<void*>(ptrs[protos[f].dst_ptr_index + q]);
         r.dst_ptr_index = counter_slot[f] == kNoCounters ? kNoCounters : counter_slot[f] + q;
         r.e_begin = p->seg_starts[q];
         r.e_end = p->seg_starts[q + 1];
-        r.end_bytes = proto.kind == kFieldLinear
+        r.end_bytes = protos[f].kind == kFieldLinear
                           ? (q == 0 ? 4ll * p->hdr.cu_seqlens_len : 0)
-                          : shard_rows[q] * (int64_t)proto.row_bytes;
-        ts[n_rec++] = tiles;
-        tiles += (r.end_bytes + tb - 1) / tb;
-      }
-    }
-    if (pass == 0) fine = tiles;
-  }
-  ts[n_rec] = tiles;
-  if (fine + (tiles - fine) * kSubTiles > 0x7fffffffll)
-    return fail(EARL_INVALID_ARG, "too many tiles for one launch");
-  if (tiles == 0) return EARL_OK;
+                          : shard_rows[q] * (int64_t)protos[f].row_bytes;
+      },
+      &order);
+  if (!fits) return fail(EARL_INVALID_ARG, "too many tiles for one launch");
+  if (order.jobs == 0 && order.tiles == 0) return EARL_OK;
   const size_t codes_off = b.size;
-  const size_t counter_words_off = codes_off + kTileCodeBytes * (size_t)tiles;
-  const size_t need = counter_words_off + (counting ? sizeof(uint64_t) * (size_t)fine : 0);
+  const size_t need = codes_off + kTileCodeBytes * (size_t)order.tiles;
   if (!dispatch_ws_dev || reinterpret_cast<uintptr_t>(dispatch_ws_dev) % kAlign)
     return fail(EARL_INVALID_ARG, "dispatch scratch is null or not %zu-byte aligned", kAlign);
   if (dispatch_ws_bytes < need)
@@ -770,17 +822,16 @@ int32_t dispatch_impl(earl_plan* p, const earl_field* fields, int32_t n_fields,
     st = upload_params(b.data, b.size, dispatch_ws_dev, stream);
     if (st != EARL_OK) return st;
   }
-  CopyArgs ca = copy_args(p, dispatch_ws_dev, tiles);
-  ca.n_fine_tiles = fine;
+  CopyArgs ca = copy_args(p, dispatch_ws_dev, order.tiles);
+  ca.n_direct_jobs = order.jobs;
   if (counting) {
-    ca.tile_counter = reinterpret_cast<uint64_t*>(static_cast<unsigned char*>(dispatch_ws_dev) +
-                                                  counter_words_off);
     for (int f = 0; f < n_fields; ++f)
       if (fields[f].nonzero_counts)
         launch_zero_counters(fields[f].nonzero_counts, n_mb_max * n_dst, stream);
   }
   void* codes = static_cast<unsigned char*>(dispatch_ws_dev) + codes_off;
   if (p->ev_before) HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(p->ev_before), stream));
+  launch_direct(ca, stream);
   launch_tile_codes(ca, codes, stream);
   launch_copy(ca, codes, stream);
   if (p->ev_after) HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(p->ev_after), stream));
@@ -857,7 +908,6 @@ namespace {
 
 // Tile codes of an asynchronous dispatch: as count_tiles, from buffer capacities; -1 if a capacity
 // is out of range or the sum exceeds what one launch can hold.
-constexpr int64_t kMaxLaunchTiles = 0x7fffffffll;
 int64_t count_tiles_by_capacity(const earl_plan* p, const earl_field* fields, int32_t n_fields,
                                 const int64_t* position_ids_capacity_rows,
                                 int64_t cu_seqlens_capacity) {
@@ -967,8 +1017,6 @@ int32_t earl_dispatch_async(earl_plan* p, const earl_field* fields, int32_t n_fi
   if (F == 0) return EARL_OK;
   BlockBuilder b;
   b.init(F * n_dst, F, S, n_dst);
-  int64_t* ts = b.tile_start();
-  TileRec* recs = b.recs();
   const void** ptrs = b.ptrs();
   int64_t* rec_caps = b.rec_caps();
   int64_t* src_caps = b.src_caps();
@@ -1013,37 +1061,25 @@ int32_t earl_dispatch_async(earl_plan* p, const earl_field* fields, int32_t n_fi
     proto.tile_shift = (int16_t)tile_shift_of(proto.row_bytes, proto.kind);
     pi += S + 2 * n_dst;
   }
-  // records in launch order (1 KiB tiles first); e_begin carries the shard number until the
-  // resolve kernel replaces it, end_bytes the capacity that sizes the grid
-  int64_t tiles = 0, fine = 0;
-  size_t n_rec = 0;
-  for (int pass = 0; pass < 2; ++pass) {
-    for (int f = 0; f < F; ++f) {
-      const TileRec& proto = protos[f];
-      if ((proto.tile_shift == kFineTileShift) != (pass == 0)) continue;
-      const int64_t tb = (int64_t)1 << proto.tile_shift;
-      for (int q = 0; q < n_dst; ++q) {
-        TileRec& r = recs[n_rec];
-        r = proto;
-        r.tile_first = tiles;
-        r.dst = const_cast<void*>(ptrs[proto.src_ptr_index + S + q]);
+  // records in launch order; e_begin carries the shard number until the resolve kernel replaces
+  // it, end_bytes the capacity that sizes the grid
+  auto cap_of = [&](int f, int q) -> int64_t {
+    return protos[f].kind == kFieldLinear ? (q == 0 ? cu_seqlens_capacity : 0) : caps[f][q];
+  };
+  RecordOrder order;
+  const bool fits = order_records(
+      b, protos.data(), F, n_dst,
+      [&](int f, int q) -> int64_t { return cap_of(f, q) * (int64_t)protos[f].row_bytes; },
+      [&](TileRec& r, int f, int q, size_t index) {
+        r.dst = const_cast<void*>(ptrs[protos[f].src_ptr_index + S + q]);
         r.e_begin = q;
-        const int64_t cap = proto.kind == kFieldLinear ? (q == 0 ? cu_seqlens_capacity : 0) : caps[f][q];
-        rec_caps[n_rec] = cap;
-        r.end_bytes = cap * (int64_t)proto.row_bytes;
-        ts[n_rec++] = tiles;
-        tiles += (r.end_bytes + tb - 1) / tb;
-        // (one term is below 2^51; stopping here keeps the running sum from overflowing)
-        if (tiles > kMaxLaunchTiles) return fail(EARL_INVALID_ARG, "too many tiles for one launch");
-      }
-    }
-    if (pass == 0) fine = tiles;
-  }
-  ts[n_rec] = tiles;
-  if (fine + (tiles - fine) * kSubTiles > 0x7fffffffll)
-    return fail(EARL_INVALID_ARG, "too many tiles for one launch");
+        rec_caps[index] = cap_of(f, q);
+        r.end_bytes = cap_of(f, q) * (int64_t)protos[f].row_bytes;
+      },
+      &order);
+  if (!fits) return fail(EARL_INVALID_ARG, "too many tiles for one launch");
   const size_t codes_off = b.size;
-  const size_t need = codes_off + kTileCodeBytes * (size_t)tiles;
+  const size_t need = codes_off + kTileCodeBytes * (size_t)order.tiles;
   if (!dispatch_ws_dev || reinterpret_cast<uintptr_t>(dispatch_ws_dev) % kAlign)
     return fail(EARL_INVALID_ARG, "dispatch scratch is null or not %zu-byte aligned", kAlign);
   if (dispatch_ws_bytes < need)
@@ -1054,11 +1090,12 @@ int32_t earl_dispatch_async(earl_plan* p, const earl_field* fields, int32_t n_fi
   launch_async_resolve(static_cast<DispatchDev*>(dispatch_ws_dev), p->dev, stream);
   p->async_stream = stream;
   p->async_used = true;
-  if (tiles > 0) {
-    CopyArgs ca = copy_args(p, dispatch_ws_dev, tiles);
-    ca.n_fine_tiles = fine;
+  if (order.jobs > 0 || order.tiles > 0) {
+    CopyArgs ca = copy_args(p, dispatch_ws_dev, order.tiles);
+    ca.n_direct_jobs = order.jobs;
     void* codes = static_cast<unsigned char*>(dispatch_ws_dev) + codes_off;
     if (p->ev_before) HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(p->ev_before), stream));
+    launch_direct(ca, stream);
     launch_tile_codes(ca, codes, stream);
     launch_copy(ca, codes, stream);
     if (p->ev_after) HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(p->ev_after), stream));
@@ -1097,7 +1134,10 @@ int32_t earl_dispatch_inverse(earl_plan* p, const earl_field* fields, int32_t n_
   int64_t* prefix = reinterpret_cast<int64_t*>(p->ws + p->l.seg_real_prefix);
   BlockBuilder b;
   b.init(n_fields, n_fields, S, n_dst);
-  int64_t* ts = b.tile_start();
+  // (no record of an inverse call is decoded in the copy kernel: the table's first part is
+  // its closing zero alone)
+  b.tile_start()[0] = 0;
+  int64_t* ts = b.tile_start() + 1;
   TileRec* recs = b.recs();
   const void** ptrs = b.ptrs();
   // one record per field, the fields with 1 KiB tiles first (as in the forward direction)

@@ -178,14 +178,26 @@ struct ParamView {
   const void* const* ptrs;
   int n_recs;
 };
+// The records that go through tile codes (all records of an inverse call).
 __device__ __forceinline__ ParamView view_params(const DispatchDev* p) {
+  const u8* base = reinterpret_cast<const u8*>(p);
+  const DispatchDev hd = *p;
+  ParamView v;
+  v.tile_start = reinterpret_cast<const int64_t*>(base + hd.tile_start_ofs) + (hd.n_direct + 1);
+  v.recs = reinterpret_cast<const TileRec*>(base + hd.recs_ofs) + hd.n_direct;
+  v.ptrs = reinterpret_cast<const void* const*>(base + hd.ptrs_ofs);
+  v.n_recs = hd.n_recs - hd.n_direct;
+  return v;
+}
+// The records that are decoded inside the copy kernel.
+__device__ __forceinline__ ParamView view_direct_params(const DispatchDev* p) {
   const u8* base = reinterpret_cast<const u8*>(p);
   const DispatchDev hd = *p;
   ParamView v;
   v.tile_start = reinterpret_cast<const int64_t*>(base + hd.tile_start_ofs);
   v.recs = reinterpret_cast<const TileRec*>(base + hd.recs_ofs);
   v.ptrs = reinterpret_cast<const void* const*>(base + hd.ptrs_ofs);
-  v.n_recs = hd.n_recs;
+  v.n_recs = hd.n_direct;
   return v;
 }
 
@@ -369,29 +381,16 @@ __device__ __forceinline__ void seek(const SegRec* segs, const TileInfo& t, int6
   load_segment(segs, t.seg_src_seq, t.src_ptrs, w, e, sc);
 }
 
-// A tile that is not one plain copy / fill / iota: every lane places its own 16-byte vector.
-// `tile` is the tile's code index, `vec0` the first 16-byte vector of the tile this workgroup owns.
-__device__ __forceinline__ void generic_tile(const CopyArgs a, const TileCode c, const int64_t tile,
-                                          const uint32_t vec0) {
-  const ParamView pv = view_params(a.params);
-  const TileRec rec = pv.recs[(uint32_t)(c.a >> 32)];
-  const int64_t lo = (tile - rec.tile_first) << rec.tile_shift;
-  const int64_t o = lo + (int64_t)(vec0 + threadIdx.x) * kVecBytes;   // this lane's vector
+// Places the 16-byte destination vector at byte o of the record's shard on its own: aligned
+// 16-byte store and possibly unaligned 16-byte load when the whole vector lies in the real part
+// of one segment, fill or position ids when it lies in padding / one segment, scalar-sized moves
+// when it straddles a segment edge, the real/padding edge or the end of the shard.  e: a
+// segment of the shard that starts at or before byte o.
+__device__ __forceinline__ void place_vector(const CopyArgs& a, const ParamView& pv,
+                                             const TileRec& rec, int e, const int64_t o) {
   if (o >= rec.end_bytes) return;
   u8* dst = static_cast<u8*>(rec.dst);
   const int64_t o_end = o + kVecBytes;
-
-  if (rec.kind == kFieldLinear) {
-    const u8* src = static_cast<const u8*>(pv.ptrs[rec.src_ptr_index]);
-    if (o_end <= rec.end_bytes) {
-      store16(dst + o, load16(src + o));
-    } else {
-      for (int64_t b = o; b < rec.end_bytes; b += 4)
-        *reinterpret_cast<uint32_t*>(dst + b) = *reinterpret_cast<const uint32_t*>(src + b);
-    }
-    return;
-  }
-
   TileInfo t;
   t.dst = dst;
   t.end = rec.end_bytes;
@@ -406,7 +405,7 @@ __device__ __forceinline__ void generic_tile(const CopyArgs a, const TileCode c,
   t.scalar_bytes = rec.scalar_bytes;
   t.kind = rec.kind;
   SegCursor sc;
-  load_segment(a.segs, t.seg_src_seq, t.src_ptrs, rec.row_bytes, (int)(uint32_t)c.a, sc);
+  load_segment(a.segs, t.seg_src_seq, t.src_ptrs, rec.row_bytes, e, sc);
   seek(a.segs, t, o, sc);
   if (rec.kind == kFieldCopy) {
     if (o_end <= sc.real_hi) {
@@ -448,6 +447,29 @@ __device__ __forceinline__ void generic_tile(const CopyArgs a, const TileCode c,
       store_scalar(dst + b, t.pad_scalar, sb);
     }
   }
+}
+
+// A tile that is not one plain copy / fill / iota: every lane places its own 16-byte vector.
+// `tile` is the tile's code index, `vec0` the first 16-byte vector of the tile this workgroup owns.
+__device__ __forceinline__ void generic_tile(const CopyArgs a, const TileCode c, const int64_t tile,
+                                          const uint32_t vec0) {
+  const ParamView pv = view_params(a.params);
+  const TileRec rec = pv.recs[(uint32_t)(c.a >> 32)];
+  const int64_t lo = (tile - rec.tile_first) << rec.tile_shift;
+  const int64_t o = lo + (int64_t)(vec0 + threadIdx.x) * kVecBytes;   // this lane's vector
+  if (o >= rec.end_bytes) return;
+  if (rec.kind == kFieldLinear) {
+    u8* dst = static_cast<u8*>(rec.dst);
+    const u8* src = static_cast<const u8*>(pv.ptrs[rec.src_ptr_index]);
+    if (o + kVecBytes <= rec.end_bytes) {
+      store16(dst + o, load16(src + o));
+    } else {
+      for (int64_t b = o; b < rec.end_bytes; b += 4)
+        *reinterpret_cast<uint32_t*>(dst + b) = *reinterpret_cast<const uint32_t*>(src + b);
+    }
+    return;
+  }
+  place_vector(a, pv, rec, (int)(uint32_t)c.a, o);
 }
 
 // A plain-copy tile (1 KiB, one workgroup) of a counting field: copy, count the non-zero scalars
@@ -505,6 +527,303 @@ __global__ __launch_bounds__(kCopyThreads, 8) void relayout_kernel(const CopyArg
     store16_sys(dst, u32x4{p0, p0 + 1, p0 + 2, p0 + 3});
   } else {
     rare_tile(a, c, tile, vec0);
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Decode and copy in one kernel ("direct" records).
+//
+// The tile-code pass costs a second launch and, on a batch of narrow fields (a few scalars per
+// token, the paper's usual payload: Section 3.3 dispatches log-probabilities), 70 % of the
+// copy's time; and with rows shorter than a vector most tiles of such a field cross a segment
+// edge, where the coded kernel falls back to a search per lane.  Here a one-wavefront workgroup
+// owns a JOB of 4 KiB of one destination shard and finds its way with the whole wavefront:
+//   * which record, which first segment: 64-way searches (every lane probes one entry, a ballot
+//     counts the entries at or below the target), two rounds for up to 4096 entries where a
+//     binary search makes twelve dependent loads;
+//   * lane l then fetches segment e + l, so the job's segments (rarely more than a handful) sit
+//     in registers, as byte ranges relative to the job; for each of the job's four 1 KiB
+//     sub-tiles a short uniform loop hands them out with v_readlane and every lane picks the one
+//     its 16-byte vector lies in: plain copy, padding, position ids, or, for the few vectors that
+//     straddle an edge, the scalar path of place_vector.
+// Used for every field with rows under 16 bytes, position ids and cu_seqlens, and for all
+// fields of launches too small to amortise a code pass.
+// ---------------------------------------------------------------------------------------
+constexpr int kJobShift = 12;
+constexpr int kJobBytes = 1 << kJobShift;
+constexpr int kJobSubTiles = kJobBytes / (kCopyThreads * kVecBytes);
+constexpr int32_t kFar = 1 << 30;   // job-relative byte offsets are clamped to +-kFar
+
+// Last x in [0, n) with key(x) <= v, for key ascending and key(0) <= v; all lanes take part and
+// get the same answer.  Equal keys: the last one (entries without tiles are skipped).
+template <class KeyF>
+__device__ __forceinline__ int wave_last_le(int n, int64_t v, KeyF key) {
+  int lo = 0, end = n;
+  while (end - lo > 1) {
+    const int step = (end - lo + kWave - 1) >> 6;
+    const int idx = lo + (int)threadIdx.x * step;
+    const bool ok = idx < end && key(idx) <= v;   // true on a prefix of the lanes, lane 0 included
+    const int cnt = __builtin_popcountll(__ballot(ok));
+    lo += (cnt - 1) * step;
+    end = end < lo + step ? end : lo + step;
+  }
+  return lo;
+}
+
+__device__ __forceinline__ int32_t clamp_far(int64_t v) {
+  return v < -(int64_t)kFar ? -kFar : (v > (int64_t)kFar ? kFar : (int32_t)v);
+}
+__device__ __forceinline__ uint64_t readlane_u64(uint64_t x, int l) {
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)x, l);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(x >> 32), l);
+  return ((uint64_t)hi << 32) | lo;
+}
+
+enum VecMode : int { kVecNone = 0, kVecPending, kVecCopy, kVecSplat, kVecPad, kVecIota, kVecSlow };
+
+// A segment as the job sees it: byte ranges relative to the job's first byte.
+struct SegView {
+  int32_t lo, real_hi, hi;   // [lo, real_hi) real rows, [real_hi, hi) padding rows
+  uint64_t src;              // copy: address of the source byte of the job's byte 0; per-sequence:
+                             // the sequence's value replicated to 8 bytes
+  int32_t pos;               // position id of the job's byte 0
+};
+
+__global__ __launch_bounds__(kCopyThreads, 8) void relayout_direct_kernel(const CopyArgs a) {
+  const ParamView pv = view_direct_params(a.params);
+  const int lane = threadIdx.x;
+  const int64_t job = blockIdx.x;
+  const int x = wave_last_le(pv.n_recs, job, [&](int i) { return pv.tile_start[i]; });
+  const TileRec rec = pv.recs[x];
+  const int64_t lo0 = (job - rec.tile_first) << kJobShift;   // first byte of the job in its shard
+  if (lo0 >= rec.end_bytes) return;   // behind the shard's end (a grid sized by capacities)
+  u8* const dst = static_cast<u8*>(rec.dst) + lo0;
+  const int32_t job_len =
+      rec.end_bytes - lo0 < kJobBytes ? (int32_t)(rec.end_bytes - lo0) : kJobBytes;
+
+  if (rec.kind == kFieldLinear) {
+    const u8* src = static_cast<const u8*>(pv.ptrs[rec.src_ptr_index]) + lo0;
+#pragma unroll
+    for (int t = 0; t < kJobSubTiles; ++t) {
+      const int32_t o = (t * kCopyThreads + lane) * kVecBytes;
+      if (o + kVecBytes <= job_len) {
+        store16_sys(dst + o, load16(src + o));
+      } else {
+        for (int32_t b = o; b < job_len; b += 4)
+          *reinterpret_cast<uint32_t*>(dst + b) = *reinterpret_cast<const uint32_t*>(src + b);
+      }
+    }
+    return;
+  }
+
+  const int64_t w = rec.row_bytes;
+  const bool is_pos = rec.kind == kFieldPositionIds;
+  const bool per_seq = rec.per_sequence != 0;
+  const bool counting = rec.kind == kFieldCopy && rec.dst_ptr_index != kNoCounters;
+  // the segment that holds the job's first byte, then one segment per lane from there on
+  const int e0 = rec.e_begin + wave_last_le(rec.e_end - rec.e_begin, lo0, [&](int i) {
+                   return a.segs[rec.e_begin + i].dst_row * w;
+                 });
+  const int idx = e0 + lane;
+  const bool have = idx < rec.e_end;
+  SegView win;            // this lane's segment of the window
+  win.lo = win.real_hi = win.hi = kFar;
+  win.src = 0;
+  win.pos = 0;
+  int32_t seg_mb = 0;
+  if (have) {
+    const SegRec r = a.segs[idx];
+    const int64_t s_lo = r.dst_row * w;
+    win.lo = clamp_far(s_lo - lo0);
+    win.real_hi = clamp_far(s_lo + (int64_t)r.n_real * w - lo0);
+    win.hi = clamp_far(s_lo + (int64_t)r.n_rows * w - lo0);
+    if (is_pos) {
+      win.pos = r.pos0 + (int32_t)((lo0 - s_lo) >> 2);
+    } else if (r.n_real > 0) {
+      const u8* shard = static_cast<const u8*>(pv.ptrs[rec.src_ptr_index + r.src_shard]);
+      if (per_seq)
+        win.src = splat_scalar(load_scalar(shard + (int64_t)a.seg_src_seq[idx] * w, (int)w), (int)w);
+      else
+        win.src = reinterpret_cast<uint64_t>(shard + r.src_row * w + (lo0 - s_lo));
+    }
+    if (counting) seg_mb = a.seg_mb[idx];
+  }
+  const int n_win = __builtin_popcountll(__ballot(win.lo < job_len));   // the job's segments in the window
+  // The window misses some of the job's segments only when they average under 64 bytes; vectors
+  // that reach beyond it (past window_hi) then take the per-lane path as a whole.
+  const bool window_complete = n_win < kWave || e0 + kWave >= rec.e_end;
+  const int32_t window_hi = window_complete ? kFar : __builtin_amdgcn_readlane(win.hi, kWave - 1);
+
+  const int sb_log2 = 31 - __builtin_clz(rec.scalar_bytes);
+  int64_t* const counters =
+      counting ? static_cast<int64_t*>(const_cast<void*>(pv.ptrs[rec.dst_ptr_index])) : nullptr;
+  const uint64_t pad = rec.pad_scalar;
+
+  // ---- every vector of the job's four sub-tiles finds its segment ---------------------------
+  int mode[kJobSubTiles], my_k[kJobSubTiles], k_first[kJobSubTiles], k_last[kJobSubTiles];
+  uint64_t my_src[kJobSubTiles];
+  int k0 = 0;   // first window segment that ends behind the current sub-tile's first byte
+#pragma unroll
+  for (int t = 0; t < kJobSubTiles; ++t) {
+    const int32_t sub_lo = t * (kCopyThreads * kVecBytes);
+    const int32_t sub_hi = sub_lo + kCopyThreads * kVecBytes < job_len
+                               ? sub_lo + kCopyThreads * kVecBytes : job_len;
+    const int32_t o = sub_lo + lane * kVecBytes;
+    const int32_t o_end = o + kVecBytes;
+    mode[t] = o < job_len ? kVecPending : kVecNone;
+    my_k[t] = 0;
+    my_src[t] = 0;
+    k_first[t] = 0;
+    k_last[t] = -1;
+    if (sub_lo >= job_len) continue;
+    for (int k = k0; k < n_win; ++k) {
+      const int32_t dl = __builtin_amdgcn_readlane(win.lo, k);
+      if (dl >= sub_hi) break;
+      const int32_t dh = __builtin_amdgcn_readlane(win.hi, k);
+      if (dh <= sub_lo) { k0 = k + 1; continue; }
+      const int32_t drh = __builtin_amdgcn_readlane(win.real_hi, k);
+      const uint64_t sj = readlane_u64(win.src, k);
+      const int32_t pj = __builtin_amdgcn_readlane(win.pos, k);
+      if (k_last[t] < 0) k_first[t] = k;
+      k_last[t] = k;
+      if (mode[t] == kVecPending && o < dh && o_end > dl) {
+        // the first segment this vector overlaps
+        my_k[t] = k;
+        if (o_end > window_hi || o_end > job_len) {
+          // stays pending: it needs segments the window does not hold, or the shard ends inside
+          // it (one vector per shard at most): the per-lane path at the end takes it
+        } else if (o < dl || o_end > dh) {
+          mode[t] = kVecSlow;                      // crosses a segment edge
+        } else if (is_pos) {
+          mode[t] = kVecIota;
+          my_src[t] = (uint32_t)(pj + (o >> 2));
+        } else if (o_end <= drh) {
+          mode[t] = per_seq ? kVecSplat : kVecCopy;
+          my_src[t] = per_seq ? sj : sj + (uint64_t)(int64_t)o;
+        } else if (o >= drh) {
+          mode[t] = kVecPad;
+        } else {
+          mode[t] = kVecSlow;                      // crosses the real/padding edge
+        }
+      }
+    }
+  }
+
+  // ---- all loads of plain-copy vectors ---------------------------------------------------------
+  u32x4 v[kJobSubTiles];
+#pragma unroll
+  for (int t = 0; t < kJobSubTiles; ++t) {
+    v[t] = u32x4{0, 0, 0, 0};
+    if (mode[t] == kVecCopy) v[t] = load16(reinterpret_cast<const u8*>(my_src[t]));
+  }
+
+  // ---- vectors that straddle an edge: byte by byte, four vectors per round --------------------
+  // There are few of them (two per segment of the job at most), so they are taken out of the
+  // lanes that own them and spread over the wavefront: group g of 16 lanes moves the 16 bytes of
+  // the (4*round + g)-th such vector, each lane looking up the segment of its own byte in the
+  // window (rows start at scalar boundaries, so single bytes serve every scalar size; padding and
+  // per-sequence values are 8-byte patterns in phase with the shard, and a job starts at a
+  // multiple of 4096).  One load and one store instruction per round, whatever the scalar size.
+  {
+    const uint64_t m0 = __ballot(mode[0] == kVecSlow), m1 = __ballot(mode[1] == kVecSlow),
+                   m2 = __ballot(mode[2] == kVecSlow), m3 = __ballot(mode[3] == kVecSlow);
+    const int c0 = __builtin_popcountll(m0), c1 = c0 + __builtin_popcountll(m1),
+              c2 = c1 + __builtin_popcountll(m2), n_slow = c2 + __builtin_popcountll(m3);
+    for (int base = 0; base < n_slow; base += 4) {
+      int32_t vec_o = -1;   // job-relative first byte of this group's vector
+      int k = 0;            // window segment of its first byte
+#pragma unroll
+      for (int slot = 0; slot < 4; ++slot) {
+        const int i = base + slot;
+        if (i >= n_slow) break;
+        const int t = i < c0 ? 0 : (i < c1 ? 1 : (i < c2 ? 2 : 3));
+        uint64_t m = t == 0 ? m0 : (t == 1 ? m1 : (t == 2 ? m2 : m3));
+        for (int q = i - (t == 0 ? 0 : (t == 1 ? c0 : (t == 2 ? c1 : c2))); q > 0; --q) m &= m - 1;
+        const int owner = __builtin_ctzll(m);
+        const int ks = t == 0 ? my_k[0] : (t == 1 ? my_k[1] : (t == 2 ? my_k[2] : my_k[3]));
+        const int owner_k = __builtin_amdgcn_readlane(ks, owner);
+        if ((lane >> 4) == slot) {
+          vec_o = (t * kCopyThreads + owner) * kVecBytes;
+          k = owner_k;
+        }
+      }
+      const bool act = vec_o >= 0;
+      const int32_t b = vec_o + (lane & 15);
+      // the byte's segment: the vector's first one or a later one (all inside the window, or the
+      // vector would have stayed pending)
+      for (;;) {
+        const int32_t h = __shfl(win.hi, k);
+        const bool further = act && b >= h && k < kWave - 1;
+        if (__ballot(further) == 0) break;
+        if (further) ++k;
+      }
+      const int32_t g_real_hi = __shfl(win.real_hi, k);
+      const uint64_t g_src = (uint64_t)__shfl((unsigned long long)win.src, k);
+      const int32_t g_pos = __shfl(win.pos, k);
+      const int g_mb = __shfl(seg_mb, k);
+      uint32_t x = 0;
+      bool real = false;
+      if (act) {
+        if (is_pos) {
+          x = (uint32_t)(g_pos + (b >> 2)) >> (8 * (b & 3));
+        } else if (b >= g_real_hi) {
+          x = (uint32_t)(pad >> (8 * (b & 7)));
+        } else if (per_seq) {
+          x = (uint32_t)(g_src >> (8 * (b & 7)));
+          real = true;
+        } else {
+          x = *reinterpret_cast<const u8*>(g_src + (uint64_t)(int64_t)b);
+          real = true;
+        }
+        dst[b] = (u8)x;
+      }
+      if (counting) {
+        // a scalar is non-zero if one of its bytes is; its first byte's lane reports it
+        uint32_t nz = real && (x & 0xffu) != 0;
+        if (sb_log2 >= 1) nz |= __shfl_xor(nz, 1);
+        if (sb_log2 >= 2) nz |= __shfl_xor(nz, 2);
+        if (sb_log2 >= 3) nz |= __shfl_xor(nz, 4);
+        if (real && nz && (b & (rec.scalar_bytes - 1)) == 0) add_to_counter(counters + g_mb, 1);
+      }
+    }
+  }
+
+  // ---- stores ---------------------------------------------------------------------------------
+#pragma unroll
+  for (int t = 0; t < kJobSubTiles; ++t) {
+    const int32_t o = (t * kCopyThreads + lane) * kVecBytes;
+    const uint64_t ms = my_src[t];
+    if (mode[t] == kVecCopy) {
+      store16_sys(dst + o, v[t]);
+    } else if (mode[t] == kVecSplat) {
+      store16_sys(dst + o, u32x4{(uint32_t)ms, (uint32_t)(ms >> 32), (uint32_t)ms, (uint32_t)(ms >> 32)});
+    } else if (mode[t] == kVecPad) {
+      store16_sys(dst + o, u32x4{(uint32_t)pad, (uint32_t)(pad >> 32), (uint32_t)pad,
+                                 (uint32_t)(pad >> 32)});
+    } else if (mode[t] == kVecIota) {
+      const uint32_t p0 = (uint32_t)ms;
+      store16_sys(dst + o, u32x4{p0, p0 + 1, p0 + 2, p0 + 3});
+    }
+    if (counting && k_last[t] >= 0) {
+      // plain-copy vectors: one sum per segment (a segment lies in one micro-batch), one atomic
+      const int mine = mode[t] == kVecCopy ? count_nonzero16(v[t], sb_log2) : 0;
+      for (int k = k_first[t]; k <= k_last[t]; ++k) {
+        int n = mode[t] == kVecCopy && my_k[t] == k ? mine : 0;
+        for (int d = kCopyThreads / 2; d > 0; d >>= 1) n += __shfl_xor(n, d);
+        const int mb = __builtin_amdgcn_readlane(seg_mb, k);
+        if (lane == 0) add_to_counter(counters + mb, n);
+      }
+    }
+  }
+  // vectors still pending (beyond the window, or holding the shard's last bytes): per lane
+  if (__ballot(mode[0] == kVecPending || mode[1] == kVecPending || mode[2] == kVecPending ||
+               mode[3] == kVecPending) != 0) {
+#pragma nounroll
+    for (int t = 0; t < kJobSubTiles; ++t) {
+      const int mt = t == 0 ? mode[0] : (t == 1 ? mode[1] : (t == 2 ? mode[2] : mode[3]));
+      if (mt == kVecPending)
+        place_vector(a, pv, rec, e0, lo0 + (int64_t)(t * kCopyThreads + lane) * kVecBytes);
+    }
   }
 }
 
@@ -777,6 +1096,12 @@ void launch_copy(const CopyArgs& a, const void* tile_codes, hipStream_t stream) 
   const int64_t grid = a.n_fine_tiles + (a.n_tiles - a.n_fine_tiles) * kSubTiles;
   hipLaunchKernelGGL(relayout_kernel, dim3((unsigned)grid), dim3(kCopyThreads), 0, stream, a,
                      static_cast<const TileCode*>(tile_codes));
+}
+
+void launch_direct(const CopyArgs& a, hipStream_t stream) {
+  if (a.n_direct_jobs <= 0) return;
+  hipLaunchKernelGGL(relayout_direct_kernel, dim3((unsigned)a.n_direct_jobs), dim3(kCopyThreads), 0,
+                     stream, a);
 }
 
 void launch_zero_counters(int64_t* counters, int64_t n, hipStream_t stream) {

@@ -140,8 +140,10 @@ struct TileRec {
 };
 static_assert(sizeof(TileRec) == 64, "TileRec layout");
 
-// Parameter block of one call, in device memory: header, tile_start[n_recs+1] (tile_first of
-// every record, then the total), recs[n_recs], pointer table.
+// Parameter block of one call, in device memory: header, tile_start, recs[n_recs], pointer
+// table.  The first n_direct records are decoded inside the copy kernel (their tile_first counts
+// 4 KiB jobs), the others go through tile codes; tile_start holds tile_first of the direct
+// records and their total (n_direct + 1 entries), then the same for the coded records.
 struct DispatchDev {
   int32_t n_recs;
   int32_t n_fields;         // earl_dispatch_async only: rows of src_caps
@@ -155,13 +157,14 @@ struct DispatchDev {
   uint32_t rec_caps_ofs;
   uint32_t src_caps_ofs;
   uint32_t src_per_sequence_ofs;
-  uint32_t pad_;
+  int32_t n_direct;
 };
 
 struct CopyArgs {
   const DispatchDev* params;
   const SegRec* segs;
   const int32_t* seg_src_seq;
+  int64_t n_direct_jobs; // 4 KiB jobs of the records that are decoded inside the copy kernel
   int64_t n_tiles;       // tile codes in the launch
   // Forward direction: the first n_fine_tiles codes describe 1 KiB each (one workgroup per code),
   // the others 4 KiB (kSubTiles workgroups per code).
@@ -177,6 +180,7 @@ void launch_plan(const PlanDev& p, hipStream_t stream);
 constexpr size_t kTileCodeBytes = 16;
 void launch_tile_codes(const CopyArgs& a, void* tile_codes, hipStream_t stream);
 void launch_copy(const CopyArgs& a, const void* tile_codes, hipStream_t stream);
+void launch_direct(const CopyArgs& a, hipStream_t stream);
 // seg_real_prefix[e] = real rows of the segments before e (n_seg+1 entries)
 void launch_zero_counters(int64_t* counters, int64_t n, hipStream_t stream);
 // writes a host-built parameter block to device memory through kernel arguments, in pieces
