@@ -3,20 +3,26 @@
 
 A step is one pass of the whole path over one synthetic rollout batch that is already resident
 in HBM: earl_plan_build (source offsets, padded geometry, rank assignment, packing,
-micro-batches, segment table) followed by earl_dispatch (every field, every destination shard,
-position ids, cu_seqlens).  The default workload is "heavy" (2048 sequences, about 12.4 M tokens,
-2065 bytes per token, DP8 x SP4 zigzag: the largest of the five workloads by bytes moved);
-`--workload longctx` is the largest by tokens.
+micro-batches, segment table), earl_plan_get_summary (the shard sizes reach the host) and
+earl_dispatch (every field, every destination shard, position ids, cu_seqlens).  The headline
+workload is "heavy" (2048 sequences, about 12.4 M tokens, 2065 bytes per token, DP8 x SP4 zigzag:
+the largest of the five workloads by bytes moved).
 
-Prints ONE JSON line:  value = real tokens re-laid-out per second over the timed steps
-(plan + dispatch, whole job); `roofline` prices the re-layout kernel alone against the 8 TB/s
-HBM peak with algorithmic bytes (each real source row read once, each destination row written
-once, 4 bytes of position id per destination row) over its HIP-event duration; `cpu_baseline`
-is the CPU oracle timed on a bounded sample of the same workload on the host cores.
+Prints ONE JSON line:
+  value         real tokens re-laid-out per second over the timed steps (plan + dispatch);
+  roofline      the kernels of earl_dispatch (decode pass and copy; HIP events recorded by the
+                library around them) priced against the 8 TB/s HBM peak with algorithmic bytes:
+                each real source row read once, each destination row written once, 4 bytes of
+                position id per destination row;
+  secondary     the same measurements for the other four workloads (longctx, mid, agentic, tiny)
+                and for the reverse direction on the headline workload; the small workloads also
+                with the step that never waits between plan and dispatch (earl_dispatch_async);
+  cpu_baseline  the CPU oracle timed on the host cores, on the headline workload's own inputs.
 """
 from __future__ import annotations
 
 import argparse
+import gc
 import hashlib
 import json
 import os
@@ -30,14 +36,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
-
-# HBM traffic of one re-layout kernel launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# (scaled by a plain copy kernel of known size, see profiles/), keyed by the sha256 of the kernel
-# source the counters were taken on.  A changed kernel reports null until re-measured.
-MEASURED_TRAFFIC = {
-    "a9b49484a65209c256c1d856cd49a6200fdd70b18845382e075c7d8e5bf33e1b":
-        {"heavy": 52882838527, "longctx": 47518212261},
-}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic.json")
 
 WORKLOAD_NOTES = {
     "tiny": "c1 tiny: 64 seqs U[16,512], 4 src shards, 4 fields (13 B/token), DP2 SP1, budget 4096",
@@ -50,6 +49,7 @@ WORKLOAD_NOTES = {
     "longctx": "c5 long-context: 256 seqs U[32768,131072] (~21.9M tokens), 8 src shards, 5 scalar "
                "fields + bf16[512] (1041 B/token), DP2 SP8 zigzag, pad 128, budget 262144",
 }
+SMALL = ("tiny", "mid", "agentic")     # cache-resident: latency-bound, not an HBM figure
 
 
 def kernel_source_hash() -> str:
@@ -59,6 +59,19 @@ def kernel_source_hash() -> str:
         with open(os.path.join(ROOT, "paper_2510_05943_amd", "csrc", name), "rb") as f:
             h.update(f.read())
     return h.hexdigest()
+
+
+def measured_traffic(workload: str, direction: str):
+    """HBM bytes of one dispatch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/), or None
+    when the kernels have changed since the counters were taken."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            t = json.load(f)
+    except (OSError, ValueError):
+        return None
+    if t.get("kernel_source_sha256") != kernel_source_hash():
+        return None
+    return t.get(direction, {}).get(workload)
 
 
 class HipEvents:
@@ -89,129 +102,138 @@ class HipEvents:
         self.lib.hipEventDestroy(ev)
 
 
-def run_gpu(args, torch, B, synth):
-    w = synth.make_workload(args.workload, seed=args.seed)
-    t0 = time.time()
-    src = {f.name: w.device_shard_buffers(f, torch) for f in w.fields}
-    torch.cuda.synchronize()
-    stage_s = time.time() - t0
+class Staged:
+    """One workload resident in HBM: sources, destination buffers, plan workspace, scratch."""
 
-    stream = torch.cuda.current_stream()
-    src_l = B.SrcLayout(w.n_groups, w.replication)
-    dst_l = B.DstLayout(w.dp, w.sp, w.zigzag, w.pad_multiple, w.mb_token_budget, args.balance_policy)
-    lengths = torch.from_numpy(w.lengths.astype(np.int32)).cuda()
-    ws = torch.empty(B.plan_workspace_bytes(w.n_seqs, src_l, dst_l), dtype=torch.uint8, device="cuda")
-
-    # sizes of the destination shards come from a first plan
-    plan0 = B.plan_build(lengths, w.n_seqs, src_l, dst_l, ws, stream=stream)
-    sm = B.plan_get_summary(plan0)
-    shard_rows = [int(r) for r in sm["shard_rows"]]
-    fields = []
-    for f in w.fields:
-        dsts = [torch.empty((r * f.row_bytes,), dtype=torch.uint8, device="cuda") for r in shard_rows]
-        fields.append(B.Field(f.scalar_bytes, f.width, f.pad_scalar, src[f.name], dsts))
-    pos = [torch.empty((r,), dtype=torch.int32, device="cuda") for r in shard_rows]
-    cu = torch.empty((sm["cu_seqlens_len"],), dtype=torch.int32, device="cuda")
-
-    scratch = torch.empty(B.dispatch_workspace_bytes(plan0, fields), dtype=torch.uint8, device="cuda")
-    B.plan_destroy(plan0)
-
-    row_bytes = sum(f.row_bytes for f in w.fields)
-    algo_bytes = (row_bytes * sm["total_real_rows"] + row_bytes * sm["total_dst_rows"]
-                  + 4 * sm["total_dst_rows"])
-    if args.inverse:
+    def __init__(self, name, seed, balance_policy, torch, B, synth):
+        self.name, self.torch, self.B = name, torch, B
+        w = self.w = synth.make_workload(name, seed=seed)
+        t0 = time.time()
+        src = self.src = {f.name: w.device_shard_buffers(f, torch) for f in w.fields}
+        torch.cuda.synchronize()
+        self.stage_s = time.time() - t0
+        self.stream = torch.cuda.current_stream()
+        self.src_l = B.SrcLayout(w.n_groups, w.replication)
+        self.dst_l = B.DstLayout(w.dp, w.sp, w.zigzag, w.pad_multiple, w.mb_token_budget, balance_policy)
+        self.lengths = torch.from_numpy(w.lengths.astype(np.int32)).cuda()
+        self.ws = torch.empty(B.plan_workspace_bytes(w.n_seqs, self.src_l, self.dst_l),
+                              dtype=torch.uint8, device="cuda")
+        # sizes of the destination shards come from a first plan
+        plan0 = self.build()
+        sm = self.sm = B.plan_get_summary(plan0)
+        rows = [int(r) for r in sm["shard_rows"]]
+        self.fields = []
+        for f in w.fields:
+            dsts = [torch.empty((r * f.row_bytes,), dtype=torch.uint8, device="cuda") for r in rows]
+            self.fields.append(B.Field(f.scalar_bytes, f.width, f.pad_scalar, src[f.name], dsts))
+        self.pos = [torch.empty((r,), dtype=torch.int32, device="cuda") for r in rows]
+        self.cu = torch.empty((sm["cu_seqlens_len"],), dtype=torch.int32, device="cuda")
+        need = max(B.dispatch_workspace_bytes(plan0, self.fields),
+                   B.dispatch_async_workspace_bytes(plan0, self.fields, self.pos, self.cu))
+        self.scratch = torch.empty(need, dtype=torch.uint8, device="cuda")
+        B.plan_destroy(plan0)
+        self.row_bytes = sum(f.row_bytes for f in w.fields)
+        self.algo_forward = (self.row_bytes * (sm["total_real_rows"] + sm["total_dst_rows"])
+                             + 4 * sm["total_dst_rows"])
         # training layout -> rollout layout: every real row read once and written once
-        algo_bytes = 2 * row_bytes * sm["total_real_rows"]
-        p1 = B.plan_build(lengths, w.n_seqs, src_l, dst_l, ws, stream=stream)
-        B.dispatch(p1, fields, position_ids=pos, cu_seqlens=cu, workspace=scratch, stream=stream)
-        torch.cuda.synchronize()        # the destination shards now hold a real training layout
-        B.plan_destroy(p1)
+        self.algo_inverse = 2 * self.row_bytes * sm["total_real_rows"]
 
-    hip = HipEvents()
+    def build(self):
+        return self.B.plan_build(self.lengths, self.w.n_seqs, self.src_l, self.dst_l, self.ws,
+                                 stream=self.stream)
 
-    def step(ev=None):
-        p = B.plan_build(lengths, w.n_seqs, src_l, dst_l, ws, stream=stream)
-        if args.async_dispatch:
-            # buffers are pre-allocated: the dispatch goes in right behind the plan, the summary
-            # and the device-side verdict are fetched afterwards
-            if ev is not None:
-                B.plan_set_dispatch_events(p, ev[0], ev[1])
-            B.dispatch_async(p, fields, position_ids=pos, cu_seqlens=cu, workspace=scratch, stream=stream)
-            B.plan_get_summary(p)
-            return p
-        B.plan_get_summary(p)          # the consumer needs the shard sizes before it can dispatch
+    def dispatch(self, p):
+        self.B.dispatch(p, self.fields, position_ids=self.pos, cu_seqlens=self.cu,
+                        workspace=self.scratch, stream=self.stream)
+
+    def step(self, mode, ev=None):
+        """mode "sync": plan, wait for its totals, dispatch.  "async": plan, dispatch enqueued
+        right behind it (buffers are pre-allocated), totals and the device's verdict afterwards.
+        "inverse": plan, wait, reverse direction."""
+        B = self.B
+        p = self.build()
         if ev is not None:
             B.plan_set_dispatch_events(p, ev[0], ev[1])
-        if args.inverse:
-            B.dispatch_inverse(p, fields, workspace=scratch, stream=stream)
+        if mode == "async":
+            B.dispatch_async(p, self.fields, position_ids=self.pos, cu_seqlens=self.cu,
+                             workspace=self.scratch, stream=self.stream)
+            B.plan_wait(p)
+            return p
+        B.plan_wait(p)                  # earl_plan_get_summary: the shard sizes are on the host
+        if mode == "inverse":
+            B.dispatch_inverse(p, self.fields, workspace=self.scratch, stream=self.stream)
         else:
-            B.dispatch(p, fields, position_ids=pos, cu_seqlens=cu, workspace=scratch, stream=stream)
+            self.dispatch(p)
         return p
 
-    if args.reference_copy:
-        # a plain copy of known size on the same stream: the yardstick for the HBM counters
-        n = 4 << 30
-        a = torch.empty(n, dtype=torch.uint8, device="cuda")
-        b = torch.empty(n, dtype=torch.uint8, device="cuda")
-        a.view(torch.int32).fill_(1)
-        for _ in range(3):
-            b.view(torch.int32).copy_(a.view(torch.int32))
+    def finish(self, plans, mode):
+        for p in plans:
+            if mode == "async" and self.B.dispatch_async_status(p) != self.B.EARL_OK:
+                raise RuntimeError("asynchronous dispatch was refused on the device")
+            self.B.plan_destroy(p)
+
+    def timed(self, mode, steps, warmup, hip):
+        """W untimed steps, then K steps between device synchronisations; the dispatch kernels of
+        every timed step are bracketed by HIP events that the library records on the stream."""
+        torch = self.torch
+        if mode == "inverse":
+            p = self.build()
+            self.dispatch(p)            # the destination shards hold a real training layout
+            torch.cuda.synchronize()
+            self.B.plan_destroy(p)
+        plans = [self.step(mode) for _ in range(warmup)]
         torch.cuda.synchronize()
-        del a, b
-
-    plans = [step() for _ in range(args.warmup)]
-    torch.cuda.synchronize()
-    for p in plans:
-        if args.async_dispatch and B.dispatch_async_status(p) != B.EARL_OK:
-            raise RuntimeError("asynchronous dispatch was refused on the device")
-        B.plan_destroy(p)
-
-    # HIP events recorded by the library on the dispatch stream, right around the re-layout kernel
-    events = [(hip.create(), hip.create()) for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    plans = [step(events[k]) for k in range(args.steps)]
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    for p in plans:
-        if args.async_dispatch and B.dispatch_async_status(p) != B.EARL_OK:
-            raise RuntimeError("asynchronous dispatch was refused on the device")
-        B.plan_destroy(p)
-
-    # the two halves on their own (outside the timed region): plan = build + summary (ends with
-    # the library's own stream synchronisation), dispatch = enqueue + stream synchronisation
-    plan_ms, dispatch_ms = [], []
-    for _ in range(10):
-        ta = time.perf_counter()
-        p = B.plan_build(lengths, w.n_seqs, src_l, dst_l, ws, stream=stream)
-        B.plan_get_summary(p)
-        tb = time.perf_counter()
-        if args.inverse:
-            B.dispatch_inverse(p, fields, workspace=scratch, stream=stream)
-        else:
-            B.dispatch(p, fields, position_ids=pos, cu_seqlens=cu, workspace=scratch, stream=stream)
+        self.finish(plans, mode)
+        events = [(hip.create(), hip.create()) for _ in range(steps)]
         torch.cuda.synchronize()
-        tc = time.perf_counter()
-        B.plan_destroy(p)
-        plan_ms.append((tb - ta) * 1e3)
-        dispatch_ms.append((tc - tb) * 1e3)
+        t0 = time.perf_counter()
+        plans = [self.step(mode, events[k]) for k in range(steps)]
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        self.finish(plans, mode)
+        kern = [hip.elapsed_ms(a, b) for a, b in events]
+        for a, b in events:
+            hip.destroy(a)
+            hip.destroy(b)
+        return (t1 - t0) * 1e3 / steps, kern
 
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    kern_ms = [hip.elapsed_ms(a, b) for a, b in events]
-    for a, b in events:
-        hip.destroy(a)
-        hip.destroy(b)
-    kern_avg_ms = float(np.mean(kern_ms))
-    achieved = algo_bytes / (kern_avg_ms * 1e-3) / 1e9
-    traffic = None if (args.inverse or args.balance_policy) else MEASURED_TRAFFIC.get(kernel_source_hash(), {}).get(args.workload)
-    return dict(w=w, sm=sm, ms_per_step=ms_per_step, kern_avg_ms=kern_avg_ms,
-                kern_min_ms=float(np.min(kern_ms)), kern_median_ms=float(np.median(kern_ms)),
-                achieved=achieved, algo_bytes=algo_bytes,
-                traffic=traffic, stage_s=stage_s, row_bytes=row_bytes,
-                plan_ms=float(np.median(plan_ms)), dispatch_ms=float(np.median(dispatch_ms)))
+    def halves(self, mode):
+        """The two calls on their own, each ending with a wait (medians of 10): plan = build +
+        summary, dispatch = enqueue + stream synchronisation."""
+        plan_ms, dispatch_ms = [], []
+        for _ in range(10):
+            ta = time.perf_counter()
+            p = self.build()
+            self.B.plan_wait(p)
+            tb = time.perf_counter()
+            if mode == "inverse":
+                self.B.dispatch_inverse(p, self.fields, workspace=self.scratch, stream=self.stream)
+            else:
+                self.dispatch(p)
+            self.torch.cuda.synchronize()
+            tc = time.perf_counter()
+            self.B.plan_destroy(p)
+            plan_ms.append((tb - ta) * 1e3)
+            dispatch_ms.append((tc - tb) * 1e3)
+        return float(np.median(plan_ms)), float(np.median(dispatch_ms))
+
+    def measure(self, mode, steps, warmup, hip):
+        ms, kern = self.timed(mode, steps, warmup, hip)
+        algo = self.algo_inverse if mode == "inverse" else self.algo_forward
+        k_avg = float(np.mean(kern))
+        out = {"ms_per_step": ms, "steps": steps,
+               "tokens_per_s": self.sm["total_real_rows"] / (ms * 1e-3),
+               "whole_path_GBps": algo / (ms * 1e-3) / 1e9,
+               "kernels_ms_avg": k_avg, "kernels_ms_min": float(np.min(kern)),
+               "kernels_ms_median": float(np.median(kern)),
+               "algorithmic_bytes": algo, "achieved_GBps": algo / (k_avg * 1e-3) / 1e9,
+               "frac": algo / (k_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+        if mode != "async":
+            out["plan_ms"], out["dispatch_ms"] = self.halves(mode)
+        return out
 
 
-def run_gpu_two_pass(args, torch, B, synth):
+def run_two_pass(args, torch, B, synth, hip):
     """The single-controller pattern the paper argues against (Section 1: all intermediate data is
     aggregated in one place before it is redistributed), done with the same library on one GPU:
     pass 1 gathers every field into one canonical buffer (plan with dp = sp = 1), pass 2 scatters
@@ -246,18 +268,17 @@ def run_gpu_two_pass(args, torch, B, synth):
     B.plan_destroy(pa)
     B.plan_destroy(pb)
     row_bytes = sum(f.row_bytes for f in w.fields)
-    algo_bytes = (2 * row_bytes * total
-                  + row_bytes * (sm["total_real_rows"] + sm["total_dst_rows"]) + 4 * sm["total_dst_rows"])
-    hip = HipEvents()
+    algo = (2 * row_bytes * total
+            + row_bytes * (sm["total_real_rows"] + sm["total_dst_rows"]) + 4 * sm["total_dst_rows"])
 
     def step(ev=None):
         a = B.plan_build(lengths, w.n_seqs, *lay_a, ws_a, stream=stream)
-        B.plan_get_summary(a)
+        B.plan_wait(a)
         if ev is not None:
             B.plan_set_dispatch_events(a, ev[0], ev[1])
         B.dispatch(a, fields_a, workspace=scr_a, stream=stream)
         b = B.plan_build(lengths, w.n_seqs, *lay_b, ws_b, stream=stream)
-        B.plan_get_summary(b)
+        B.plan_wait(b)
         if ev is not None:
             B.plan_set_dispatch_events(b, ev[2], ev[3])
         B.dispatch(b, fields_b, position_ids=pos, cu_seqlens=cu, workspace=scr_b, stream=stream)
@@ -275,27 +296,61 @@ def run_gpu_two_pass(args, torch, B, synth):
     t1 = time.perf_counter()
     for p in plans:
         B.plan_destroy(p)
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    kern_ms = [hip.elapsed_ms(e[0], e[1]) + hip.elapsed_ms(e[2], e[3]) for e in events]
+    ms = (t1 - t0) * 1e3 / args.steps
+    kern = [hip.elapsed_ms(e[0], e[1]) + hip.elapsed_ms(e[2], e[3]) for e in events]
     for e in events:
         for x in e:
             hip.destroy(x)
-    kern_avg_ms = float(np.mean(kern_ms))
-    return dict(w=w, sm=sm, ms_per_step=ms_per_step, kern_avg_ms=kern_avg_ms,
-                kern_min_ms=float(np.min(kern_ms)), achieved=algo_bytes / (kern_avg_ms * 1e-3) / 1e9,
-                algo_bytes=algo_bytes, traffic=None, stage_s=stage_s, row_bytes=row_bytes)
+    k_avg = float(np.mean(kern))
+    res = {"ms_per_step": ms, "steps": args.steps, "tokens_per_s": sm["total_real_rows"] / (ms * 1e-3),
+           "whole_path_GBps": algo / (ms * 1e-3) / 1e9, "kernels_ms_avg": k_avg,
+           "kernels_ms_min": float(np.min(kern)), "kernels_ms_median": float(np.median(kern)),
+           "algorithmic_bytes": algo, "achieved_GBps": algo / (k_avg * 1e-3) / 1e9,
+           "frac": algo / (k_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+    return w, sm, res, stage_s, row_bytes
 
 
-def run_cpu_baseline(args, synth):
-    """The oracle as it stands (single thread: Python loops + numpy slice copies) on a bounded
-    sample of the workload: a reduced sequence count with the same length distribution, fields
-    and layouts, forward path only (plan, all fields, all shards, position ids), repeated until
-    about ten seconds of CPU time have been spent."""
+def cpu_model() -> str:
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def run_cpu_baseline(args, synth, staged_src=None):
+    """The oracle as it stands (one thread: Python loops + numpy slice copies) on the inputs of
+    the benchmarked workload itself (same generator, same seed): plan, every field, every
+    destination shard, position ids, one pass.  The oracle emits one destination shard at a
+    time, so only the source buffers (25.6 GB for the heavy workload) stay in host memory;
+    they are the staged input buffers copied back from the GPU (the generator draws the wide
+    field much faster there, with the same bytes).  If they do not fit the host's memory, a
+    1/8-sequence-count sample of the same distribution is timed instead."""
     from oracle import earl_oracle as O
-    scale = {"tiny": 1.0, "mid": 1.0, "agentic": 1.0, "heavy": 1.0 / 8, "longctx": 1.0 / 8}[args.workload]
-    w = synth.make_workload(args.workload, seed=args.seed, scale=scale)
-    host = {f.name: [w.group_buffer(f, s // w.replication) for s in range(w.n_shards)]
-            for f in w.fields}
+    sample = None
+    try:
+        w = synth.make_workload(args.workload, seed=args.seed)
+        host = {f.name: [None] * w.n_shards for f in w.fields}
+        for f in w.fields:
+            for g in range(w.n_groups):
+                if staged_src is not None:
+                    buf = staged_src[f.name][g * w.replication].cpu().numpy().view(f.np_dtype).reshape(
+                        -1, f.width)
+                else:
+                    buf = w.group_buffer(f, g)
+                for t in range(w.replication):
+                    host[f.name][g * w.replication + t] = buf
+    except MemoryError:
+        host = None
+        gc.collect()
+        w = synth.make_workload(args.workload, seed=args.seed, scale=1.0 / 8)
+        host = {f.name: [w.group_buffer(f, s // w.replication) for s in range(w.n_shards)]
+                for f in w.fields}
+        sample = "the source buffers of the whole workload did not fit the host's memory: "
+    row_bytes = sum(f.row_bytes for f in w.fields)
     passes = 0
     t0 = time.perf_counter()
     while True:
@@ -310,14 +365,16 @@ def run_cpu_baseline(args, synth):
         dt = time.perf_counter() - t0
         if dt >= 10.0 or passes >= 200:
             break
-    row_bytes = sum(f.row_bytes for f in w.fields)
     algo = row_bytes * (plan.total_real_rows + plan.total_dst_rows) + 4 * plan.total_dst_rows
+    what = (f"{w.n_seqs} sequences drawn like the workload" if sample else
+            f"the benchmarked inputs themselves (workload {args.workload}, seed {args.seed}, "
+            f"{w.n_seqs} sequences)")
     return {"value": passes * w.total_tokens / dt, "unit": "tokens/s", "cores": 1, "kind": "oracle",
-            "GBps": passes * algo / dt / 1e9,
-            "sample": f"{w.n_seqs} sequences drawn like the workload ({w.total_tokens} tokens, "
-                      f"{algo / 1e9:.2f} GB moved per pass), all fields, all {w.dp * w.sp} destination "
-                      f"shards, plan + dispatch, {passes} passes in {dt:.1f} s on one core "
-                      f"(host reports {os.cpu_count()} logical cpus)"}
+            "GBps": passes * algo / dt / 1e9, "ms_per_pass": dt * 1e3 / passes,
+            "cpu_model": cpu_model(), "host_logical_cpus": os.cpu_count(),
+            "sample": (sample or "") + f"{what}: {w.total_tokens} tokens, {algo / 1e9:.2f} GB moved per "
+                      f"pass, plan + all fields + all {w.dp * w.sp} destination shards + position ids, "
+                      f"{passes} pass(es) in {dt:.1f} s on one core"}
 
 
 def main() -> int:
@@ -328,6 +385,8 @@ def main() -> int:
     ap.add_argument("--workload", default="heavy", choices=list(WORKLOAD_NOTES))
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-secondary", action="store_true",
+                    help="only the headline workload (profiling runs)")
     ap.add_argument("--two-pass", action="store_true",
                     help="gather into one canonical buffer, then scatter (single-controller pattern)")
     ap.add_argument("--balance-policy", type=int, default=0, choices=[0, 1, 2],
@@ -354,9 +413,63 @@ def main() -> int:
         return 2
     B.load_library()
     torch.cuda.set_device(0)
+    hip = HipEvents()
+    mode = "inverse" if args.inverse else ("async" if args.async_dispatch else "sync")
 
-    r = run_gpu_two_pass(args, torch, B, synth) if args.two_pass else run_gpu(args, torch, B, synth)
-    w, sm = r["w"], r["sm"]
+    if args.reference_copy:
+        # a plain copy of known size on the same stream: the yardstick for the HBM counters
+        n = 4 << 30
+        a = torch.empty(n, dtype=torch.uint8, device="cuda")
+        b = torch.empty(n, dtype=torch.uint8, device="cuda")
+        a.view(torch.int32).fill_(1)
+        for _ in range(3):
+            b.view(torch.int32).copy_(a.view(torch.int32))
+        torch.cuda.synchronize()
+        del a, b
+
+    secondary = {}
+    cpu = None
+    if args.two_pass:
+        w, sm, r, stage_s, row_bytes = run_two_pass(args, torch, B, synth, hip)
+        kernel_name = "all kernels of both dispatches"
+        traffic = None
+    else:
+        st = Staged(args.workload, args.seed, args.balance_policy, torch, B, synth)
+        w, sm, stage_s, row_bytes = st.w, st.sm, st.stage_s, st.row_bytes
+        r = st.measure(mode, args.steps, args.warmup, hip)
+        kernel_name = ("inverse_code_kernel + inverse_kernel" if args.inverse else
+                       "relayout_direct_kernel + tile_code_kernel + relayout_kernel")
+        traffic = None if args.balance_policy else measured_traffic(
+            args.workload, "inverse" if args.inverse else "forward")
+        if not args.no_secondary and mode == "sync" and not args.balance_policy:
+            secondary[args.workload + "_inverse"] = st.measure("inverse", args.steps, args.warmup, hip)
+        if not args.no_cpu_baseline:
+            cpu = run_cpu_baseline(args, synth, st.src)
+        del st
+        gc.collect()
+        torch.cuda.empty_cache()
+        if not args.no_secondary and mode == "sync" and not args.balance_policy:
+            for name in ("longctx", "heavy", "mid", "agentic", "tiny"):
+                if name == args.workload:
+                    continue
+                s2 = Staged(name, args.seed, 0, torch, B, synth)
+                small = name in SMALL
+                steps = max(args.steps, 200) if small else args.steps
+                entry = s2.measure("sync", steps, max(args.warmup, 3), hip)
+                entry["config"] = WORKLOAD_NOTES[name]
+                entry["real_tokens"] = s2.sm["total_real_rows"]
+                if small:
+                    a2 = s2.measure("async", steps, max(args.warmup, 3), hip)
+                    entry["ms_per_step_async"] = a2["ms_per_step"]
+                    entry["tokens_per_s_async"] = a2["tokens_per_s"]
+                    entry["kernels_ms_avg_async"] = a2["kernels_ms_avg"]
+                    entry["note"] = ("cache-resident batch: latency-bound, frac is not an HBM figure; "
+                                     "async = earl_plan_build + earl_dispatch_async + earl_plan_get_summary")
+                secondary[name] = entry
+                del s2
+                gc.collect()
+                torch.cuda.empty_cache()
+
     line = {
         "metric": "re-layout throughput: tokens/s and achieved HBM GB/s (% of peak) at 1 GPU",
         "value": sm["total_real_rows"] / (r["ms_per_step"] * 1e-3),
@@ -372,7 +485,7 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": WORKLOAD_NOTES[args.workload], "name": args.workload,
                    "seed": args.seed, "n_seqs": w.n_seqs, "real_tokens": sm["total_real_rows"],
-                   "dst_rows": sm["total_dst_rows"], "bytes_per_token_row": r["row_bytes"],
+                   "dst_rows": sm["total_dst_rows"], "bytes_per_token_row": row_bytes,
                    "dst_shards": w.dp * w.sp, "src_shards": w.n_shards,
                    "balance_policy": args.balance_policy,
                    "step": ("two passes (gather to one buffer, scatter from it), each " if args.two_pass
@@ -380,22 +493,24 @@ def main() -> int:
                                         if args.async_dispatch else
                                         "earl_plan_build + earl_plan_get_summary + " +
                                         ("earl_dispatch_inverse" if args.inverse else "earl_dispatch"))},
-        "whole_path_GBps": r["algo_bytes"] / (r["ms_per_step"] * 1e-3) / 1e9,
-        "roofline": {"bound": "hbm", "achieved": r["achieved"], "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": r["achieved"] / HBM_PEAK_GBPS, "traffic": r["traffic"],
-                     "kernel": ("inverse_kernel" if args.inverse else
-                                "relayout_kernel (both passes)" if args.two_pass else "relayout_kernel"),
-                     "algorithmic_bytes_per_launch": r["algo_bytes"],
-                     "kernel_ms_avg": r["kern_avg_ms"], "kernel_ms_min": r["kern_min_ms"],
-                     "kernel_ms_median": r.get("kern_median_ms")},
-        "input_staging_s": r["stage_s"],
+        "whole_path_GBps": r["whole_path_GBps"],
+        "roofline": {"bound": "hbm", "achieved": r["achieved_GBps"], "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": r["frac"], "traffic": traffic,
+                     "kernel": kernel_name,
+                     "interval": "HIP events around every kernel of the dispatch call (decode pass "
+                                 "and copy), parameter upload excluded",
+                     "algorithmic_bytes_per_launch": r["algorithmic_bytes"],
+                     "kernel_ms_avg": r["kernels_ms_avg"], "kernel_ms_min": r["kernels_ms_min"],
+                     "kernel_ms_median": r["kernels_ms_median"]},
+        "input_staging_s": stage_s,
     }
     if "plan_ms" in r:
-        # the two calls on their own, each ending with a stream synchronisation (medians of 10)
         line["plan_ms"] = r["plan_ms"]
         line["dispatch_ms"] = r["dispatch_ms"]
+    if secondary:
+        line["secondary"] = secondary
     if not args.no_cpu_baseline:
-        line["cpu_baseline"] = run_cpu_baseline(args, synth)
+        line["cpu_baseline"] = cpu if cpu is not None else run_cpu_baseline(args, synth)
     print(json.dumps(line))
     return 0
 

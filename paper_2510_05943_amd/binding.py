@@ -232,6 +232,15 @@ def plan_get_summary(plan: Plan) -> Dict:
     return out
 
 
+def plan_wait(plan: Plan) -> int:
+    """earl_plan_get_summary without host copies of its arrays: returns (with n_mb_max) once the
+    plan's totals are on the host, which is all a loop with pre-allocated buffers needs
+    between earl_plan_build and earl_dispatch."""
+    s = _Summary()
+    _check(load_library().earl_plan_get_summary(plan.handle, C.byref(s)))
+    return int(s.n_mb_max)
+
+
 def plan_export(plan: Plan) -> Dict[str, np.ndarray]:
     sm = plan_get_summary(plan)
     n = plan.n_seqs

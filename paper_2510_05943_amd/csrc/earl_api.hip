@@ -4,6 +4,8 @@
 // per-call parameter block to the re-layout kernel.
 #include "earl_dispatch.h"
 
+#include <atomic>
+#include <chrono>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -181,6 +183,63 @@ StageSlot g_stage[kStageSlots];
 bool g_stage_ready = false;
 int g_stage_next = 0;
 
+// Mailboxes in pinned, coherent host memory: the plan kernel copies its summary block into one
+// and then stores the plan's token into the mailbox's last eight bytes.  The host polls that
+// word instead of enqueueing a device-to-host copy and synchronising the stream, which costs
+// some 20 us more than the kernel itself on a small batch.  One allocation of 1 MiB at the first
+// plan of the process, kept until the process ends.  A plan whose summary block is larger than
+// a mailbox, or that finds none free, falls back to the copy.
+constexpr size_t kMailboxBytes = 16 * 1024;
+constexpr size_t kMailboxFlagOffset = kMailboxBytes - 8;
+constexpr int kMailboxes = 64;
+struct Mailboxes {
+  std::mutex mu;
+  unsigned char* base = nullptr;
+  bool tried = false;
+  // 0 free, 1 held by a plan, 2 abandoned before its kernel was seen to finish (draining)
+  int state[kMailboxes] = {};
+  uint64_t token[kMailboxes] = {};
+  uint64_t next_token = 1;
+};
+Mailboxes g_mail;
+
+volatile uint64_t* mailbox_flag(int slot) {
+  return reinterpret_cast<volatile uint64_t*>(g_mail.base + (size_t)slot * kMailboxBytes +
+                                              kMailboxFlagOffset);
+}
+
+// A free mailbox with its flag cleared, or -1.
+int acquire_mailbox(size_t summary_bytes, uint64_t* token) {
+  if (summary_bytes > kMailboxFlagOffset) return -1;
+  std::lock_guard<std::mutex> lock(g_mail.mu);
+  if (!g_mail.tried) {
+    g_mail.tried = true;
+    void* base = nullptr;
+    if (hipHostMalloc(&base, kMailboxBytes * kMailboxes, hipHostMallocCoherent) == hipSuccess)
+      g_mail.base = static_cast<unsigned char*>(base);
+    else
+      (void)hipGetLastError();   // no mailboxes: every plan takes the copy path
+  }
+  if (!g_mail.base) return -1;
+  for (int k = 0; k < kMailboxes; ++k) {
+    if (g_mail.state[k] == 2 && *mailbox_flag(k) == g_mail.token[k]) g_mail.state[k] = 0;
+    if (g_mail.state[k] != 0) continue;
+    g_mail.state[k] = 1;
+    g_mail.token[k] = g_mail.next_token++;
+    *mailbox_flag(k) = 0;
+    std::atomic_thread_fence(std::memory_order_seq_cst);
+    *token = g_mail.token[k];
+    return k;
+  }
+  return -1;
+}
+
+// done: the kernel's token has been seen, nothing will write the mailbox any more.
+void release_mailbox(int slot, bool done) {
+  std::lock_guard<std::mutex> lock(g_mail.mu);
+  g_mail.state[slot] = done ? 0 : 2;
+}
+
 }  // namespace
 
 struct earl_plan {
@@ -190,6 +249,8 @@ struct earl_plan {
   unsigned char* ws;
   hipStream_t stream;
   bool summary_ready;
+  int mailbox;                          // pinned host mailbox the kernel reports to, or -1
+  uint64_t mailbox_token;
   int32_t status;
   bool inverse_ready;
   void* inverse_prefix_done;            // hipEvent_t recorded behind the prefix kernel
@@ -205,12 +266,40 @@ struct earl_plan {
 
 namespace {
 
+// Waits until the plan kernel's token shows in the mailbox: polls for up to a quarter of a
+// millisecond (a plan kernel takes 10 to 150 us), then lets the runtime wait for the stream.
+bool wait_for_mailbox(earl_plan* p) {
+  volatile uint64_t* flag = mailbox_flag(p->mailbox);
+  const auto t0 = std::chrono::steady_clock::now();
+  for (unsigned spin = 0; *flag != p->mailbox_token; ++spin) {
+    __builtin_ia32_pause();
+    if ((spin & 255u) == 255u &&
+        std::chrono::steady_clock::now() - t0 > std::chrono::microseconds(250)) {
+      if (hipStreamSynchronize(p->stream) != hipSuccess) return false;
+      break;
+    }
+  }
+  std::atomic_thread_fence(std::memory_order_acquire);
+  return *flag == p->mailbox_token;
+}
+
 int32_t ensure_summary(earl_plan* p) {
   if (p->summary_ready) return p->status;
   p->summary.resize(p->l.summary_end);
-  HIP_TRY(hipMemcpyAsync(p->summary.data(), p->ws, p->l.summary_end, hipMemcpyDeviceToHost,
-                         p->stream));
-  HIP_TRY(hipStreamSynchronize(p->stream));
+  bool have = false;
+  if (p->mailbox >= 0) {
+    have = wait_for_mailbox(p);
+    if (have)
+      std::memcpy(p->summary.data(), g_mail.base + (size_t)p->mailbox * kMailboxBytes,
+                  p->l.summary_end);
+    release_mailbox(p->mailbox, have);
+    p->mailbox = -1;
+  }
+  if (!have) {
+    HIP_TRY(hipMemcpyAsync(p->summary.data(), p->ws, p->l.summary_end, hipMemcpyDeviceToHost,
+                           p->stream));
+    HIP_TRY(hipStreamSynchronize(p->stream));
+  }
   std::memcpy(&p->hdr, p->summary.data() + p->l.hdr, sizeof(PlanHeader));
   p->status = p->hdr.status;
   p->summary_ready = true;
@@ -392,6 +481,7 @@ int32_t check_field(const earl_plan* p, const earl_field& f, int idx, bool inver
 CopyArgs copy_args(const earl_plan* p, const void* params_dev, int64_t n_tiles) {
   CopyArgs a{};
   a.params = static_cast<const DispatchDev*>(params_dev);
+  a.n_src_shards = p->d.S;
   a.segs = p->dev.segs;
   a.seg_src_seq = p->dev.seg_src_seq;
   a.seg_mb = p->dev.seg_mb;
@@ -435,6 +525,7 @@ int32_t earl_plan_build(const int32_t* lengths_dev, int32_t n_seqs, const earl_s
   p->ws = static_cast<unsigned char*>(workspace_dev);
   p->stream = static_cast<hipStream_t>(hip_stream);
   p->summary_ready = false;
+  p->mailbox = acquire_mailbox(l.summary_end, &p->mailbox_token);
   p->status = EARL_OK;
   p->inverse_ready = false;
   p->inverse_prefix_done = nullptr;
@@ -454,6 +545,10 @@ int32_t earl_plan_build(const int32_t* lengths_dev, int32_t n_seqs, const earl_s
   v.seq_row_in = src->seq_row;
   v.N = d.N; v.G = d.G; v.R = d.R; v.S = d.S; v.D = d.D; v.C = d.C; v.K = d.K;
   v.halves = d.halves; v.P = d.P; v.n_pow2 = d.n_pow2; v.B = d.B; v.policy = d.policy; v.equal_mb = d.equal_mb;
+  v.host_summary = p->mailbox >= 0 ? g_mail.base + (size_t)p->mailbox * kMailboxBytes : nullptr;
+  v.host_token = p->mailbox_token;
+  v.summary_bytes = (uint32_t)l.summary_end;
+  v.host_flag_offset = (uint32_t)kMailboxFlagOffset;
   v.hdr = reinterpret_cast<PlanHeader*>(w + l.hdr);
   v.shard_rows = reinterpret_cast<int64_t*>(w + l.shard_rows);
   v.src_rows_needed = reinterpret_cast<int64_t*>(w + l.src_rows_needed);
@@ -492,6 +587,7 @@ int32_t earl_plan_build(const int32_t* lengths_dev, int32_t n_seqs, const earl_s
   launch_plan(v, p->stream);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) {
+    if (p->mailbox >= 0) release_mailbox(p->mailbox, true);   // nothing was launched
     delete p;
     return fail(EARL_HIP_ERROR, "plan kernel launch failed: %s", hipGetErrorString(e));
   }
@@ -716,6 +812,16 @@ bool order_records(BlockBuilder& b, const TileRec* protos, int F, int n_dst, Byt
   return true;
 }
 
+// Where the direct records of a parameter block will sit in device memory.
+void set_direct_view(CopyArgs& ca, const BlockBuilder& b, const RecordOrder& order, void* block_dev) {
+  unsigned char* base = static_cast<unsigned char*>(block_dev);
+  ca.n_direct_jobs = order.jobs;
+  ca.n_direct = order.n_direct;
+  ca.direct_tile_start = reinterpret_cast<const int64_t*>(base + b.hd.tile_start_ofs);
+  ca.direct_recs = reinterpret_cast<const TileRec*>(base + b.hd.recs_ofs);
+  ca.ptrs = reinterpret_cast<const void* const*>(base + b.hd.ptrs_ofs);
+}
+
 // earl_dispatch after the plan's summary is on the host.  fixed_block != null: the parameter
 // block is built in that host buffer and travels to the device as kernel arguments (nothing is
 // allocated, no staging memory is touched); else it is built in a vector and copied through a
@@ -823,7 +929,7 @@ int32_t dispatch_impl(earl_plan* p, const earl_field* fields, int32_t n_fields,
     if (st != EARL_OK) return st;
   }
   CopyArgs ca = copy_args(p, dispatch_ws_dev, order.tiles);
-  ca.n_direct_jobs = order.jobs;
+  set_direct_view(ca, b, order, dispatch_ws_dev);
   if (counting) {
     for (int f = 0; f < n_fields; ++f)
       if (fields[f].nonzero_counts)
@@ -1092,7 +1198,7 @@ int32_t earl_dispatch_async(earl_plan* p, const earl_field* fields, int32_t n_fi
   p->async_used = true;
   if (order.jobs > 0 || order.tiles > 0) {
     CopyArgs ca = copy_args(p, dispatch_ws_dev, order.tiles);
-    ca.n_direct_jobs = order.jobs;
+    set_direct_view(ca, b, order, dispatch_ws_dev);
     void* codes = static_cast<unsigned char*>(dispatch_ws_dev) + codes_off;
     if (p->ev_before) HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(p->ev_before), stream));
     launch_direct(ca, stream);
@@ -1216,6 +1322,8 @@ int32_t earl_plan_set_dispatch_events(earl_plan* p, void* event_before, void* ev
 }
 
 int32_t earl_plan_destroy(earl_plan* p) {
+  // a plan that was never waited for: its kernel may still write the mailbox
+  if (p && p->mailbox >= 0) release_mailbox(p->mailbox, false);
   if (p && p->inverse_prefix_done)
     (void)hipEventDestroy(static_cast<hipEvent_t>(p->inverse_prefix_done));
   delete p;

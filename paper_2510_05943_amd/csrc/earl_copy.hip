@@ -189,18 +189,6 @@ __device__ __forceinline__ ParamView view_params(const DispatchDev* p) {
   v.n_recs = hd.n_recs - hd.n_direct;
   return v;
 }
-// The records that are decoded inside the copy kernel.
-__device__ __forceinline__ ParamView view_direct_params(const DispatchDev* p) {
-  const u8* base = reinterpret_cast<const u8*>(p);
-  const DispatchDev hd = *p;
-  ParamView v;
-  v.tile_start = reinterpret_cast<const int64_t*>(base + hd.tile_start_ofs);
-  v.recs = reinterpret_cast<const TileRec*>(base + hd.recs_ofs);
-  v.ptrs = reinterpret_cast<const void* const*>(base + hd.ptrs_ofs);
-  v.n_recs = hd.n_direct;
-  return v;
-}
-
 // Pass 1: every lane writes the codes of kTilesPerLane consecutive tiles.
 //
 // The searches (which record, which segment) are chains of dependent loads, a few microseconds
@@ -589,12 +577,51 @@ struct SegView {
   int32_t pos;               // position id of the job's byte 0
 };
 
+// A record held by one lane, handed to all lanes.
+__device__ __forceinline__ TileRec broadcast_record(const TileRec& mine, int from_lane) {
+  union {
+    TileRec rec;
+    uint32_t word[sizeof(TileRec) / 4];
+  } in, out;
+  in.rec = mine;
+#pragma unroll
+  for (int k = 0; k < (int)(sizeof(TileRec) / 4); ++k)
+    out.word[k] = (uint32_t)__builtin_amdgcn_readlane((int)in.word[k], from_lane);
+  return out.rec;
+}
+
 __global__ __launch_bounds__(kCopyThreads, 8) void relayout_direct_kernel(const CopyArgs a) {
-  const ParamView pv = view_direct_params(a.params);
+  // Everything up to the first data load is a chain of dependent memory round trips (each about
+  // two microseconds when the plan and the parameter block were written on another XCD), and on a
+  // small batch the kernel's time is that chain: it is kept to three or four.  Record and first
+  // segment are found by 64-way probes that narrow the range, and the last probe of each search
+  // fetches whole entries, so that the lane that holds the answer hands the record to the
+  // wavefront, and the lanes behind the first segment already hold the job's segments.  The
+  // field's source pointers are fetched one per lane while the segments are searched.
+  ParamView pv;
+  pv.tile_start = a.direct_tile_start;
+  pv.recs = a.direct_recs;
+  pv.ptrs = a.ptrs;
+  pv.n_recs = a.n_direct;
   const int lane = threadIdx.x;
   const int64_t job = blockIdx.x;
-  const int x = wave_last_le(pv.n_recs, job, [&](int i) { return pv.tile_start[i]; });
-  const TileRec rec = pv.recs[x];
+  TileRec rec;
+  {
+    // last record with tile_first <= job (records without jobs share it with their successor)
+    int lo = 0, end = pv.n_recs;
+    while (end - lo > kWave) {
+      const int step = (end - lo + kWave - 1) >> 6;
+      const int idx = lo + lane * step;
+      const bool ok = idx < end && pv.recs[idx].tile_first <= job;
+      lo += (__builtin_popcountll(__ballot(ok)) - 1) * step;
+      end = end < lo + step ? end : lo + step;
+    }
+    TileRec mine = {};
+    const bool valid = lo + lane < end;
+    if (valid) mine = pv.recs[lo + lane];
+    const int holder = __builtin_popcountll(__ballot(valid && mine.tile_first <= job)) - 1;
+    rec = broadcast_record(mine, holder);
+  }
   const int64_t lo0 = (job - rec.tile_first) << kJobShift;   // first byte of the job in its shard
   if (lo0 >= rec.end_bytes) return;   // behind the shard's end (a grid sized by capacities)
   u8* const dst = static_cast<u8*>(rec.dst) + lo0;
@@ -620,39 +647,81 @@ __global__ __launch_bounds__(kCopyThreads, 8) void relayout_direct_kernel(const 
   const bool is_pos = rec.kind == kFieldPositionIds;
   const bool per_seq = rec.per_sequence != 0;
   const bool counting = rec.kind == kFieldCopy && rec.dst_ptr_index != kNoCounters;
-  // the segment that holds the job's first byte, then one segment per lane from there on
-  const int e0 = rec.e_begin + wave_last_le(rec.e_end - rec.e_begin, lo0, [&](int i) {
-                   return a.segs[rec.e_begin + i].dst_row * w;
-                 });
-  const int idx = e0 + lane;
-  const bool have = idx < rec.e_end;
-  SegView win;            // this lane's segment of the window
+  // source pointers of the field, one per lane (up to 64 shards; more are looked up per segment)
+  const bool ptrs_in_lanes = !is_pos && a.n_src_shards <= kWave;
+  uint64_t lane_ptr = 0;
+  if (ptrs_in_lanes && lane < a.n_src_shards)
+    lane_ptr = reinterpret_cast<uint64_t>(pv.ptrs[rec.src_ptr_index + lane]);
+
+  // the segment that holds the job's first byte: narrow to at most 8 candidates, then fetch 64
+  // whole segments from the first candidate on
+  const int n_seg = rec.e_end - rec.e_begin;
+  int first = 0;
+  {
+    int end = n_seg;
+    while (end - first > 8) {
+      const int step = (end - first + kWave - 1) >> 6;
+      const int idx = first + lane * step;
+      const bool ok = idx < end && a.segs[rec.e_begin + idx].dst_row * w <= lo0;
+      first += (__builtin_popcountll(__ballot(ok)) - 1) * step;
+      end = end < first + step ? end : first + step;
+    }
+  }
+  const int idx = rec.e_begin + first + lane;
+  const bool fetched = first + lane < n_seg;
+  SegRec r = {};
+  int32_t seq_row = 0, seg_mb = 0;
+  if (fetched) {
+    r = a.segs[idx];
+    if (per_seq) seq_row = a.seg_src_seq[idx];
+    if (counting) seg_mb = a.seg_mb[idx];
+  }
+  const int64_t s_lo = r.dst_row * w;
+  const int shift = __builtin_popcountll(__ballot(fetched && s_lo <= lo0)) - 1;   // lane of the job's first segment
+  const int e0 = rec.e_begin + first + shift;
+  SegView win;            // this lane's segment, as the job sees it
   win.lo = win.real_hi = win.hi = kFar;
   win.src = 0;
   win.pos = 0;
-  int32_t seg_mb = 0;
-  if (have) {
-    const SegRec r = a.segs[idx];
-    const int64_t s_lo = r.dst_row * w;
-    win.lo = clamp_far(s_lo - lo0);
-    win.real_hi = clamp_far(s_lo + (int64_t)r.n_real * w - lo0);
-    win.hi = clamp_far(s_lo + (int64_t)r.n_rows * w - lo0);
-    if (is_pos) {
-      win.pos = r.pos0 + (int32_t)((lo0 - s_lo) >> 2);
-    } else if (r.n_real > 0) {
-      const u8* shard = static_cast<const u8*>(pv.ptrs[rec.src_ptr_index + r.src_shard]);
-      if (per_seq)
-        win.src = splat_scalar(load_scalar(shard + (int64_t)a.seg_src_seq[idx] * w, (int)w), (int)w);
-      else
-        win.src = reinterpret_cast<uint64_t>(shard + r.src_row * w + (lo0 - s_lo));
+  {
+    uint64_t shard_ptr = (uint64_t)__shfl((unsigned long long)lane_ptr, r.src_shard);
+    if (fetched) {
+      win.lo = clamp_far(s_lo - lo0);
+      win.real_hi = clamp_far(s_lo + (int64_t)r.n_real * w - lo0);
+      win.hi = clamp_far(s_lo + (int64_t)r.n_rows * w - lo0);
+      if (is_pos) {
+        win.pos = r.pos0 + (int32_t)((lo0 - s_lo) >> 2);
+      } else if (r.n_real > 0) {
+        if (!ptrs_in_lanes) shard_ptr = reinterpret_cast<uint64_t>(pv.ptrs[rec.src_ptr_index + r.src_shard]);
+        const u8* shard = reinterpret_cast<const u8*>(shard_ptr);
+        if (per_seq)
+          win.src = splat_scalar(load_scalar(shard + (int64_t)seq_row * w, (int)w), (int)w);
+        else
+          win.src = reinterpret_cast<uint64_t>(shard + r.src_row * w + (lo0 - s_lo));
+      }
     }
-    if (counting) seg_mb = a.seg_mb[idx];
   }
+  // move the window down so that lane k holds segment e0 + k
+  {
+    const int from = lane + shift;
+    const bool in = from < kWave;
+    const int32_t lo_ = __shfl(win.lo, from), rh_ = __shfl(win.real_hi, from), hi_ = __shfl(win.hi, from);
+    const uint64_t src_ = (uint64_t)__shfl((unsigned long long)win.src, from);
+    const int32_t pos_ = __shfl(win.pos, from), mb_ = __shfl(seg_mb, from);
+    win.lo = in ? lo_ : kFar;
+    win.real_hi = in ? rh_ : kFar;
+    win.hi = in ? hi_ : kFar;
+    win.src = src_;
+    win.pos = pos_;
+    seg_mb = mb_;
+  }
+  const int window_lanes = kWave - shift;   // segments the window can hold
   const int n_win = __builtin_popcountll(__ballot(win.lo < job_len));   // the job's segments in the window
   // The window misses some of the job's segments only when they average under 64 bytes; vectors
   // that reach beyond it (past window_hi) then take the per-lane path as a whole.
-  const bool window_complete = n_win < kWave || e0 + kWave >= rec.e_end;
-  const int32_t window_hi = window_complete ? kFar : __builtin_amdgcn_readlane(win.hi, kWave - 1);
+  const bool window_complete = n_win < window_lanes || e0 + window_lanes >= rec.e_end;
+  const int32_t window_hi =
+      window_complete ? kFar : __builtin_amdgcn_readlane(win.hi, window_lanes - 1);
 
   const int sb_log2 = 31 - __builtin_clz(rec.scalar_bytes);
   int64_t* const counters =

@@ -75,6 +75,13 @@ struct PlanDev {
                                  // 2 list scheduling on squared padded lengths
   int32_t equal_mb;              // 1: every rank reports the largest micro-batch count
   int64_t B;
+  // Mailbox in pinned host memory (null: none): the kernel copies the finished summary block
+  // there and then stores host_token into the mailbox's last eight bytes, so that the host can
+  // see the plan's totals without a copy command and a stream synchronisation.
+  unsigned char* host_summary;
+  uint64_t host_token;
+  uint32_t summary_bytes;        // bytes of the summary block (a multiple of 256)
+  uint32_t host_flag_offset;     // byte offset of the token inside the mailbox
   // summary block (contiguous, copied to the host in one piece)
   PlanHeader* hdr;
   int64_t* shard_rows;           // [D*C]
@@ -165,6 +172,13 @@ struct CopyArgs {
   const SegRec* segs;
   const int32_t* seg_src_seq;
   int64_t n_direct_jobs; // 4 KiB jobs of the records that are decoded inside the copy kernel
+  // the parts of the parameter block those records use, so that the kernel need not read the
+  // block's header first
+  const int64_t* direct_tile_start;
+  const TileRec* direct_recs;
+  const void* const* ptrs;
+  int32_t n_direct;
+  int32_t n_src_shards;
   int64_t n_tiles;       // tile codes in the launch
   // Forward direction: the first n_fine_tiles codes describe 1 KiB each (one workgroup per code),
   // the others 4 KiB (kSubTiles workgroups per code).

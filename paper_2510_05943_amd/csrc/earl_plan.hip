@@ -114,6 +114,22 @@ __device__ int64_t block_reduce_min(int64_t v, BlockScratch& s) {
   return -block_reduce_max(-v, s);
 }
 
+// Hands the finished summary block (the first bytes of the workspace, header included) to the
+// host through its mailbox, if the plan has one.  Every thread of the workgroup calls it, after
+// the header has been written.
+__device__ void publish_summary(const PlanDev& p) {
+  if (!p.host_summary) return;
+  __syncthreads();   // the whole block is written and visible to this workgroup
+  const uint4* from = reinterpret_cast<const uint4*>(p.hdr);
+  uint4* to = reinterpret_cast<uint4*>(p.host_summary);
+  for (uint32_t x = threadIdx.x; x < p.summary_bytes / 16; x += blockDim.x) to[x] = from[x];
+  __threadfence_system();
+  __syncthreads();
+  if (threadIdx.x == 0)
+    __hip_atomic_store(reinterpret_cast<uint64_t*>(p.host_summary + p.host_flag_offset), p.host_token,
+                       __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
 // ---------------------------------------------------------------------------------------
 // Segmented prefix scan by label, in index order.
 //
@@ -676,6 +692,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const PlanDev p) {
       h.bad_index = s_invalid ? s_bad_invalid : s_bad;
       *p.hdr = h;
     }
+    publish_summary(p);
     return;
   }
   {
@@ -996,6 +1013,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const PlanDev p) {
     h.rank_load_max = load_max;
     *p.hdr = h;
   }
+  publish_summary(p);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1117,6 +1135,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_resident_kernel(const PlanD
       h.bad_index = s.invalid ? s.bad_invalid : s.bad;
       *p.hdr = h;
     }
+    publish_summary(p);
     return;
   }
 
@@ -1474,6 +1493,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_resident_kernel(const PlanD
     h.rank_load_max = s.load_max;
     *p.hdr = h;
   }
+  publish_summary(p);
 }
 
 // Batches the resident kernel takes (the LDS carve-up above bounds every term).

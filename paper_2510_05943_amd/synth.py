@@ -68,7 +68,7 @@ def _f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
     return r.astype(np.uint16)
 
 
-_POOL_ROWS = 1 << 13
+_POOL_ROWS = 1 << 16
 
 
 @dataclasses.dataclass
