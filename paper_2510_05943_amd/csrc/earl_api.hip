@@ -969,9 +969,9 @@ int32_t earl_dispatch_workspace_bytes(earl_plan* p, const earl_field* fields, in
     inverse_tiles += (p->hdr.total_real_rows * w + tb - 1) / tb;
   }
   if (inverse_tiles > tiles) tiles = inverse_tiles;
-  // one word per tile code on top (only the 1 KiB codes of counting fields use theirs)
-  *out_bytes = param_block_bytes(F, p->d.S, p->d.D * p->d.C) +
-               (kTileCodeBytes + sizeof(uint64_t)) * (size_t)tiles;
+  // (an upper bound for the forward direction, where only the fields with rows of 16 bytes and
+  // more of a large launch get tile codes)
+  *out_bytes = param_block_bytes(F, p->d.S, p->d.D * p->d.C) + kTileCodeBytes * (size_t)tiles;
   return EARL_OK;
 }
 

@@ -156,15 +156,13 @@ __device__ __forceinline__ void add_to_counter(int64_t* counter, int n) {
   if (n) atomicAdd(reinterpret_cast<unsigned long long*>(counter), (unsigned long long)n);
 }
 
-// Tile codes.  `b` holds the destination pointer of the tile's first byte (16-byte aligned) with
-// the action in its low four bits; `a` depends on the action.
+// Tile codes (fields with rows of 16 bytes and more, in launches large enough to pay for the code
+// pass).  `b` holds the destination pointer of the tile's first byte (16-byte aligned) with the
+// action in its low four bits; `a` depends on the action.
 enum TileAction : uint64_t {
   kActCopy = 0,      // a = source pointer of the tile's first byte: the tile is a straight copy
-  kActFill = 1,      // a = scalar replicated to 8 bytes: the whole tile repeats it
-  kActIota = 2,      // a = position id of the tile's first row: consecutive int32
+  kActFill = 1,      // a = padding scalar replicated to 8 bytes: the whole tile repeats it
   kActGeneric = 3,   // a = record index << 32 | segment of the tile's first byte
-  kActCopyCount = 4, // as kActCopy for a 1 KiB tile of a counting field: tile_counter[tile] says
-                     // which counter receives the tile's number of non-zero scalars
   kActSkip = 5,      // nothing to do: the tile lies behind the end of its shard (a grid sized by
                      // buffer capacities, earl_dispatch_async)
 };
@@ -225,13 +223,6 @@ __device__ __forceinline__ TileCode code_of_tile(const CopyArgs& a, const ParamV
     c.b = dst | kActSkip;
     return c;
   }
-  if (rec.kind == kFieldLinear) {
-    if (hi <= rec.end_bytes) {
-      c.a = reinterpret_cast<uint64_t>(static_cast<const u8*>(pv.ptrs[rec.src_ptr_index]) + lo);
-      c.b = dst | kActCopy;
-    }
-    return c;
-  }
   const int64_t w = rec.row_bytes;
   const SegRec& r = cur.seg;
   const int64_t s_lo = r.dst_row * w;
@@ -239,28 +230,10 @@ __device__ __forceinline__ TileCode code_of_tile(const CopyArgs& a, const ParamV
   const int64_t s_hi = (r.dst_row + r.n_rows) * w;
   c.a |= (uint32_t)cur.e;
   if (hi > rec.end_bytes) return c;
-  if (rec.kind == kFieldPositionIds) {
-    if (hi <= s_hi) {
-      c.a = (uint64_t)(uint32_t)(r.pos0 + (int32_t)((lo - s_lo) >> 2));
-      c.b = dst | kActIota;
-    }
-  } else if (hi <= s_real_hi) {
+  if (hi <= s_real_hi) {
     const u8* shard = static_cast<const u8*>(pv.ptrs[rec.src_ptr_index + r.src_shard]);
-    if (rec.per_sequence) {
-      // the whole tile repeats the sequence's value
-      c.a = splat_scalar(load_scalar(shard + (int64_t)a.seg_src_seq[cur.e] * w, (int)w), (int)w);
-      c.b = dst | kActFill;
-    } else {
-      c.a = reinterpret_cast<uint64_t>(shard + r.src_row * w + (lo - s_lo));
-      c.b = dst | kActCopy;
-      if (rec.dst_ptr_index != kNoCounters) {
-        // a counting field (always 1 KiB tiles): the whole tile belongs to one micro-batch
-        int64_t* row = static_cast<int64_t*>(const_cast<void*>(pv.ptrs[rec.dst_ptr_index]));
-        a.tile_counter[tile] = reinterpret_cast<uint64_t>(row + a.seg_mb[cur.e]) |
-                               (uint64_t)(31 - __builtin_clz(rec.scalar_bytes));
-        c.b = dst | kActCopyCount;
-      }
-    }
+    c.a = reinterpret_cast<uint64_t>(shard + r.src_row * w + (lo - s_lo));
+    c.b = dst | kActCopy;
   } else if (lo >= s_real_hi && hi <= s_hi) {
     c.a = rec.pad_scalar;
     c.b = dst | kActFill;
@@ -280,7 +253,7 @@ __device__ __forceinline__ void tile_codes_of_lane(const CopyArgs& a, const int6
   // (a shard without segments has no rows: all its tiles, if a capacity-sized grid gave it any,
   // are skipped before a segment is looked at)
   int e_guess = rec0.e_begin;
-  if (rec0.kind != kFieldLinear && rec0.e_begin < rec0.e_end)
+  if (rec0.e_begin < rec0.e_end)
     e_guess = find_segment(a.segs, rec0.e_begin, rec0.e_end,
                            (tile0 - rec0.tile_first) << rec0.tile_shift, rec0.row_bytes);
 
@@ -288,7 +261,7 @@ __device__ __forceinline__ void tile_codes_of_lane(const CopyArgs& a, const int6
   cursor_set_record(pv, cur, first < pv.tile_start[x0 + 1] ? x0
                                                              : last_le(pv.tile_start, x0, pv.n_recs, first));
   cur.e = cur.rec.e_begin;
-  if (cur.rec.kind != kFieldLinear && cur.rec.e_begin < cur.rec.e_end) {
+  if (cur.rec.e_begin < cur.rec.e_end) {
     const int64_t w = cur.rec.row_bytes;
     const int64_t lo = (first - cur.rec.tile_first) << cur.rec.tile_shift;
     if (cur.x == x0) {
@@ -307,9 +280,9 @@ __device__ __forceinline__ void tile_codes_of_lane(const CopyArgs& a, const int6
         // next record (records without tiles are skipped by the search)
         cursor_set_record(pv, cur, last_le(pv.tile_start, cur.x, pv.n_recs, tile));
         cur.e = cur.rec.e_begin;
-        if (cur.rec.kind != kFieldLinear && cur.rec.e_begin < cur.rec.e_end) cur.seg = a.segs[cur.e];
+        if (cur.rec.e_begin < cur.rec.e_end) cur.seg = a.segs[cur.e];
       }
-      if (cur.rec.kind != kFieldLinear && cur.rec.e_begin < cur.rec.e_end) {
+      if (cur.rec.e_begin < cur.rec.e_end) {
         const int64_t w = cur.rec.row_bytes;
         const int64_t lo = (tile - cur.rec.tile_first) << cur.rec.tile_shift;
         if (lo >= (cur.seg.dst_row + cur.seg.n_rows) * w) {
@@ -446,75 +419,35 @@ __device__ __forceinline__ void generic_tile(const CopyArgs a, const TileCode c,
   const int64_t lo = (tile - rec.tile_first) << rec.tile_shift;
   const int64_t o = lo + (int64_t)(vec0 + threadIdx.x) * kVecBytes;   // this lane's vector
   if (o >= rec.end_bytes) return;
-  if (rec.kind == kFieldLinear) {
-    u8* dst = static_cast<u8*>(rec.dst);
-    const u8* src = static_cast<const u8*>(pv.ptrs[rec.src_ptr_index]);
-    if (o + kVecBytes <= rec.end_bytes) {
-      store16(dst + o, load16(src + o));
-    } else {
-      for (int64_t b = o; b < rec.end_bytes; b += 4)
-        *reinterpret_cast<uint32_t*>(dst + b) = *reinterpret_cast<const uint32_t*>(src + b);
-    }
-    return;
-  }
   place_vector(a, pv, rec, (int)(uint32_t)c.a, o);
 }
 
-// A plain-copy tile (1 KiB, one workgroup) of a counting field: copy, count the non-zero scalars
-// of the whole tile with a wavefront reduction, one atomic add.
-__device__ __forceinline__ void counting_copy_tile(const CopyArgs a, const TileCode c, const int64_t tile) {
-  const uint64_t word = a.tile_counter[tile];
-  const uint32_t lane = threadIdx.x;
-  const u32x4 v = load16(reinterpret_cast<const u8*>(c.a) + lane * kVecBytes);
-  store16(reinterpret_cast<u8*>(c.b & ~(uint64_t)15) + lane * kVecBytes, v);
-  int n = count_nonzero16(v, (int)(word & 7u));
-  for (int d = kCopyThreads / 2; d > 0; d >>= 1) n += __shfl_xor(n, d);
-  if (lane == 0) add_to_counter(reinterpret_cast<int64_t*>(word & ~(uint64_t)7), n);
-}
-
-__device__ __forceinline__ void rare_tile(const CopyArgs a, const TileCode c, const int64_t tile,
-                                       const uint32_t vec0) {
-  const uint64_t act = c.b & 15u;
-  if (act == kActSkip) return;
-  if (act == kActCopyCount) counting_copy_tile(a, c, tile);
-  else generic_tile(a, c, tile, vec0);
-}
-
-// Pass 2: one-wavefront workgroups, one 16-byte vector per lane: one workgroup per 1 KiB tile
-// code (the first n_fine_tiles codes), kSubTiles workgroups per 4 KiB tile code (the rest).
-// The second launch bound asks for 8 wavefronts per SIMD (at most 64 VGPRs): at 7 the copy
-// measured 2.5 % slower; every wavefront waits for its tile code and then for its data, so the
-// bytes in flight, and with them the bandwidth, follow the number of resident wavefronts.  The
-// rare path is inlined: as a called function it kept its uniform arguments in vector registers
-// and saved callee-saved registers to scratch memory, and a kernel that owns scratch memory
-// starts about 9 us later, which is a third of the kernel's time on the small workloads.
+// Pass 2: one-wavefront workgroups, one 16-byte vector per lane, kSubTiles workgroups per 4 KiB
+// tile code.  The second launch bound asks for 8 wavefronts per SIMD (at most 64 VGPRs): at 7
+// the copy measured 2.5 % slower; every wavefront waits for its tile code and then for its data,
+// so the bytes in flight, and with them the bandwidth, follow the number of resident wavefronts.
+// The rare path is inlined: as a called function it kept its uniform arguments in vector
+// registers and saved callee-saved registers to scratch memory, and a kernel that owns scratch
+// memory starts about 9 us later.
 __global__ __launch_bounds__(kCopyThreads, 8) void relayout_kernel(const CopyArgs a,
                                                                    const TileCode* __restrict__ codes) {
   // consecutive workgroups go to different XCDs; grouping a tile's workgroups on one XCD
   // measured 5-12 % slower, so the hardware order is kept
-  int64_t tile = blockIdx.x;
-  uint32_t vec0 = 0;
-  if (tile >= a.n_fine_tiles) {
-    const int64_t rest = tile - a.n_fine_tiles;
-    tile = a.n_fine_tiles + rest / kSubTiles;
-    vec0 = (uint32_t)(rest % kSubTiles) * kCopyThreads;
-  }
+  const int64_t tile = blockIdx.x / kSubTiles;
+  const uint32_t vec0 = (uint32_t)(blockIdx.x % kSubTiles) * kCopyThreads;
   const TileCode c = codes[tile];
   const uint64_t act = c.b & 15u;
   const uint32_t v = vec0 + threadIdx.x;   // vector in the tile
   u8* dst = reinterpret_cast<u8*>(c.b & ~(uint64_t)15) + v * kVecBytes;
-  // the plain copy first and on its own: nearly every workgroup of a wide field takes it
+  // the plain copy first and on its own: nearly every workgroup takes it
   if (__builtin_expect(act == kActCopy, 1)) {
     store16_sys(dst, load16(reinterpret_cast<const u8*>(c.a) + v * kVecBytes));
     return;
   }
   if (act == kActFill) {
     store16_sys(dst, u32x4{(uint32_t)c.a, (uint32_t)(c.a >> 32), (uint32_t)c.a, (uint32_t)(c.a >> 32)});
-  } else if (act == kActIota) {
-    const uint32_t p0 = (uint32_t)c.a + v * 4;
-    store16_sys(dst, u32x4{p0, p0 + 1, p0 + 2, p0 + 3});
-  } else {
-    rare_tile(a, c, tile, vec0);
+  } else if (act == kActGeneric) {
+    generic_tile(a, c, tile, vec0);
   }
 }
 
@@ -1162,7 +1095,7 @@ void launch_tile_codes(const CopyArgs& a, void* tile_codes, hipStream_t stream) 
 
 void launch_copy(const CopyArgs& a, const void* tile_codes, hipStream_t stream) {
   if (a.n_tiles <= 0) return;
-  const int64_t grid = a.n_fine_tiles + (a.n_tiles - a.n_fine_tiles) * kSubTiles;
+  const int64_t grid = a.n_tiles * kSubTiles;
   hipLaunchKernelGGL(relayout_kernel, dim3((unsigned)grid), dim3(kCopyThreads), 0, stream, a,
                      static_cast<const TileCode*>(tile_codes));
 }

@@ -180,13 +180,10 @@ struct CopyArgs {
   int32_t n_direct;
   int32_t n_src_shards;
   int64_t n_tiles;       // tile codes in the launch
-  // Forward direction: the first n_fine_tiles codes describe 1 KiB each (one workgroup per code),
+  // Reverse direction: the first n_fine_tiles codes describe 1 KiB each (one workgroup per code),
   // the others 4 KiB (kSubTiles workgroups per code).
   int64_t n_fine_tiles;
-  // Non-zero counting (forward, fields that ask for it): micro-batch of every segment, and one
-  // word per 1 KiB tile code: the counter a plain-copy tile adds to | log2(scalar bytes).
-  const int32_t* seg_mb;
-  uint64_t* tile_counter;
+  const int32_t* seg_mb;  // micro-batch of every segment (fields that ask for non-zero counts)
 };
 
 void launch_plan(const PlanDev& p, hipStream_t stream);
