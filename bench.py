@@ -310,6 +310,46 @@ def run_two_pass(args, torch, B, synth, hip):
     return w, sm, res, stage_s, row_bytes
 
 
+def run_copy_ceiling(torch, gib: int = 8, iters: int = 10):
+    """What the chip does on plain copies of the shape the re-layout kernels use (one 16-byte load
+    and one 16-byte store per lane, one-wavefront workgroups), on reads alone and on writes alone:
+    the yardstick kernels of tests/yardstick/copy_ceiling.hip, timed with HIP events."""
+    import ctypes
+    lib = ctypes.CDLL(os.path.join(ROOT, "tests", "yardstick", "libcopy_ceiling.so"))
+    vp, u64 = ctypes.c_void_p, ctypes.c_uint64
+    lib.yardstick_copy.argtypes = [vp, vp, u64, vp]
+    lib.yardstick_read.argtypes = [vp, vp, u64, vp]
+    lib.yardstick_write.argtypes = [vp, u64, vp]
+    n = gib << 30
+    src = torch.empty(n, dtype=torch.uint8, device="cuda")
+    dst = torch.empty(n, dtype=torch.uint8, device="cuda")
+    sink = torch.zeros(64, dtype=torch.int32, device="cuda")
+    src.view(torch.int32).fill_(1)
+    dst.view(torch.int32).fill_(2)
+    stream = torch.cuda.current_stream().cuda_stream
+    runs = {"copy": (lambda: lib.yardstick_copy(src.data_ptr(), dst.data_ptr(), n, stream), 2 * n),
+            "read": (lambda: lib.yardstick_read(src.data_ptr(), sink.data_ptr(), n, stream), n),
+            "write": (lambda: lib.yardstick_write(dst.data_ptr(), n, stream), n),
+            "torch_copy_": (lambda: (dst.view(torch.int32).copy_(src.view(torch.int32)), 0)[1], 2 * n)}
+    out = {"bytes": n}
+    for name, (fn, moved) in runs.items():
+        for _ in range(3):
+            if fn():
+                raise RuntimeError(f"yardstick {name} failed")
+        ms = []
+        for _ in range(iters):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            fn()
+            b.record()
+            torch.cuda.synchronize()
+            ms.append(a.elapsed_time(b))
+        t = float(np.median(ms))
+        out[name] = {"ms_median": t, "ms_min": float(np.min(ms)), "GBps": moved / t / 1e6,
+                     "frac_of_peak": moved / t / 1e6 / HBM_PEAK_GBPS}
+    return out
+
+
 def cpu_model() -> str:
     try:
         with open("/proc/cpuinfo") as f:
@@ -397,6 +437,8 @@ def main() -> int:
                          "(no host wait between plan and dispatch)")
     ap.add_argument("--inverse", action="store_true",
                     help="time the reverse direction (earl_dispatch_inverse) instead of earl_dispatch")
+    ap.add_argument("--copy-ceiling", action="store_true",
+                    help="only time the plain-copy yardstick kernels (8 GiB) and print their rates")
     ap.add_argument("--reference-copy", action="store_true",
                     help="also run three plain 4 GiB device copies (for scaling profiler counters)")
     args = ap.parse_args()
@@ -413,6 +455,9 @@ def main() -> int:
         return 2
     B.load_library()
     torch.cuda.set_device(0)
+    if args.copy_ceiling:
+        print(json.dumps({"copy_ceiling": run_copy_ceiling(torch)}))
+        return 0
     hip = HipEvents()
     mode = "inverse" if args.inverse else ("async" if args.async_dispatch else "sync")
 

@@ -244,9 +244,9 @@ int32_t earl_dispatch_workspace_bytes(earl_plan* plan, const earl_field* fields,
  * Every check (plan status, alignment, capacities) happens before anything is enqueued: a failed
  * call writes nothing.  Calls that share a scratch buffer must be ordered on one stream.
  * The call's parameter block (about 100 bytes per field and destination shard) reaches the device
- * through a pinned host block of 2 MiB that the library allocates at the first dispatch call of the
+ * through a pinned host block of 8 MiB that the library allocates at the first dispatch call of the
  * process and keeps until the process ends; it is used in slots of 256 KiB, so a block above
- * 2 MiB (some 20000 (field, shard) pairs) makes the call wait on the host for the work that
+ * 8 MiB (some 80000 (field, shard) pairs) makes the call wait on the host for the work that
  * precedes it on the stream.  The same holds for earl_dispatch_async and earl_dispatch_inverse.
  */
 int32_t earl_dispatch(earl_plan* plan, const earl_field* fields, int32_t n_fields,

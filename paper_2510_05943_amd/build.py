@@ -20,13 +20,17 @@ def hipcc() -> str:
     raise RuntimeError("hipcc not found")
 
 
-def build(verbose: bool = True) -> str:
+YARDSTICK_SRC = os.path.join(ROOT, "tests", "yardstick", "copy_ceiling.hip")
+YARDSTICK_LIB = os.path.join(ROOT, "tests", "yardstick", "libcopy_ceiling.so")
+
+
+def _compile(sources, out, includes, verbose):
     cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-Wall", "-Wno-unused-command-line-argument",
-           "-I", os.path.join(ROOT, "include"), "-I", CSRC]
-    cmd += [os.path.join(CSRC, s) for s in SOURCES]
-    cmd += ["-o", LIB_PATH]
+           "-Wall", "-Wno-unused-command-line-argument"]
+    for inc in includes:
+        cmd += ["-I", inc]
+    cmd += list(sources) + ["-o", out]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
@@ -36,6 +40,15 @@ def build(verbose: bool = True) -> str:
         raise RuntimeError(f"hipcc failed:\n{err}")
     if verbose and err.strip():
         print(err, file=sys.stderr)
+    return out
+
+
+def build(verbose: bool = True) -> str:
+    """The library, and the plain-copy yardstick the benchmark compares it with (a shared object
+    of its own under tests/, not part of the library)."""
+    _compile([os.path.join(CSRC, s) for s in SOURCES], LIB_PATH,
+             [os.path.join(ROOT, "include"), CSRC], verbose)
+    _compile([YARDSTICK_SRC], YARDSTICK_LIB, [], verbose)
     return LIB_PATH
 
 

@@ -176,7 +176,7 @@ struct StageSlot {
   hipEvent_t done = nullptr;
   bool in_flight = false;
 };
-constexpr int kStageSlots = 8;
+constexpr int kStageSlots = 32;
 constexpr size_t kStageBytes = 256 * 1024;
 std::mutex g_stage_mu;
 StageSlot g_stage[kStageSlots];
@@ -332,7 +332,7 @@ const Tv* summary_ptr(const earl_plan* p, size_t off) {
 
 // Copies a host-built parameter block into the workspace, ordered on the stream, in pieces of
 // one staging slot each.  A slot is reused once the copy that last read it has finished, so a
-// block larger than all slots together (2 MiB) makes the caller wait for earlier pieces, and
+// block larger than all slots together (8 MiB) makes the caller wait for earlier pieces, and
 // with them for the work that precedes them on the stream.
 int32_t upload_params(const unsigned char* block, size_t bytes, void* dev_dst, hipStream_t stream) {
   std::lock_guard<std::mutex> lock(g_stage_mu);

@@ -207,3 +207,45 @@ def test_async_argument_checks(H):
                                             for a in src_dev["token_id"]], np.uint32, 1, 0)
     assert np.array_equal(dsts[1].cpu().numpy().view(np.uint32).reshape(-1, 1), want)
     B.plan_destroy(plan)
+
+
+def test_async_dispatch_does_not_wait_for_the_stream_with_4096_destination_shards(H):
+    """dp = 1024, sp = 4 and six fields (eight with position ids and cu_seqlens): a parameter block
+    of some 3 MB, more than one staging slot.  The call must come back while work that was
+    enqueued before it is still running (the block goes up in pieces, nothing blocks), and the
+    result is still the oracle's."""
+    import time
+    import torch
+    B = H.B
+    rng = np.random.default_rng(77)
+    fields = tuple(synth.bytes_field(f"f{k}", sb, wd, 0x11 * (k + 1))
+                   for k, (sb, wd) in enumerate([(4, 1), (1, 1), (2, 1), (8, 1), (4, 3), (2, 16)]))
+    w = synth.custom_workload(rng.integers(1, 40, size=3000), n_groups=4, dp=1024, sp=4, zigzag=1,
+                              pad_multiple=1, mb_token_budget=4096, fields=fields, seed=5)
+    oplan = oracle_plan(w)
+    _, shards = H.host_sources(w, fields)
+    src_bufs = {f.name: [H.to_dev(a) for a in shards[f.name]] for f in fields}
+    dst_rows = [int(r) for r in oplan.shard_rows]
+    # several milliseconds of work in front of the calls
+    ballast = torch.empty(1 << 30, dtype=torch.int32, device="cuda")
+    torch.cuda.synchronize()
+    for _ in range(12):
+        ballast.fill_(7)
+    t0 = time.perf_counter()
+    plan, bufs, pos, cu, scratch = enqueue(H, w, fields, dst_rows, src_bufs, len(oplan.cu_seqlens))
+    host_s = time.perf_counter() - t0
+    behind = torch.cuda.Event()
+    behind.record()
+    still_running = not behind.query()
+    torch.cuda.synchronize()
+    assert still_running, f"the calls took {host_s * 1e3:.1f} ms on the host and the stream was idle after them"
+    assert B.dispatch_async_status(plan) == B.EARL_OK
+    for q in range(w.dp * w.sp):
+        assert np.array_equal(pos[q].cpu().numpy(), O.position_ids_shard(oplan, q)), q
+    for f in fields:
+        for q in range(0, w.dp * w.sp, 97):
+            want = O.dispatch_field_shard(oplan, q, shards[f.name], f.np_dtype, f.width, f.pad_scalar)
+            got = bufs[f.name][q].cpu().numpy().view(f.np_dtype).reshape(-1, f.width)
+            assert np.array_equal(got, want), (f.name, q)
+    assert np.array_equal(cu.cpu().numpy(), oplan.cu_seqlens)
+    B.plan_destroy(plan)
