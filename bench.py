@@ -350,6 +350,67 @@ def run_copy_ceiling(torch, gib: int = 8, iters: int = 10):
     return out
 
 
+def run_path_histogram(args, torch, B, synth):
+    """Which path the destination bytes of every field take, computed on the host from the plan's
+    exported segment table with the kernels' own rules.  Direct records (rows under 16 bytes,
+    position ids, every field of a small launch) are classified per 16-byte vector: plain copy
+    (inside the real rows of one segment), padding fill, position ids (inside one segment),
+    straddling (crosses a segment edge or the real/padding edge: moved byte by byte), shard end
+    (holds the shard's last bytes: per-lane path).  Coded records (rows of 16 bytes and more in a
+    launch above 64 MiB of them) are classified per 4 KiB tile: copy, fill, generic."""
+    w = synth.make_workload(args.workload, seed=args.seed)
+    stream = torch.cuda.current_stream()
+    src_l = B.SrcLayout(w.n_groups, w.replication)
+    dst_l = B.DstLayout(w.dp, w.sp, w.zigzag, w.pad_multiple, w.mb_token_budget, args.balance_policy)
+    lengths = torch.from_numpy(w.lengths.astype(np.int32)).cuda()
+    ws = torch.empty(B.plan_workspace_bytes(w.n_seqs, src_l, dst_l), dtype=torch.uint8, device="cuda")
+    plan = B.plan_build(lengths, w.n_seqs, src_l, dst_l, ws, stream=stream)
+    sm = B.plan_get_summary(plan)
+    seg = B.plan_export_segments(plan)
+    B.plan_destroy(plan)
+    rows = sm["shard_rows"].astype(np.int64)
+    coarse_bytes = sum(int(rows.sum()) * f.row_bytes for f in w.fields if f.row_bytes >= 16)
+    names = [(f.name, f.row_bytes, False) for f in w.fields] + [("position_ids", 4, True)]
+    table = []
+    for name, wb, is_pos in names:
+        coded = wb >= 16 and coarse_bytes > (64 << 20)
+        unit = 4096 if coded else 16
+        counts = {}
+        for q in range(len(rows)):
+            e0, e1 = int(seg["shard_seg_start"][q]), int(seg["shard_seg_start"][q + 1])
+            end = int(rows[q]) * wb
+            if end == 0:
+                continue
+            lo = seg["dst_row"][e0:e1].astype(np.int64) * wb
+            real_hi = lo + seg["n_real"][e0:e1].astype(np.int64) * wb
+            hi = lo + seg["n_rows"][e0:e1].astype(np.int64) * wb
+            first = np.arange(0, end, unit, dtype=np.int64)
+            last = first + unit
+            e = np.searchsorted(lo, first, side="right") - 1
+            in_seg = last <= hi[e]
+            beyond = last > end
+            if is_pos and not coded:
+                kinds = {"position ids": in_seg & ~beyond}
+            else:
+                kinds = {"copy": in_seg & (last <= real_hi[e]) & ~beyond,
+                         ("fill" if coded else "padding"): in_seg & (first >= real_hi[e]) & ~beyond}
+            taken = np.zeros(first.shape, bool)
+            for k, m in kinds.items():
+                counts[k] = counts.get(k, 0) + int(m.sum())
+                taken |= m
+            rest = ~taken
+            if coded:
+                counts["generic"] = counts.get("generic", 0) + int(rest.sum())
+            else:
+                counts["shard end"] = counts.get("shard end", 0) + int((rest & beyond).sum())
+                counts["straddling"] = counts.get("straddling", 0) + int((rest & ~beyond).sum())
+        total = sum(counts.values())
+        table.append({"field": name, "row_bytes": wb, "path": "tile codes (4 KiB tiles)" if coded else
+                      "direct (16-byte vectors)", "units": total,
+                      "share": {k: v / total for k, v in counts.items()}, "counts": counts})
+    return {"workload": args.workload, "seed": args.seed, "fields": table}
+
+
 def cpu_model() -> str:
     try:
         with open("/proc/cpuinfo") as f:
@@ -437,6 +498,9 @@ def main() -> int:
                          "(no host wait between plan and dispatch)")
     ap.add_argument("--inverse", action="store_true",
                     help="time the reverse direction (earl_dispatch_inverse) instead of earl_dispatch")
+    ap.add_argument("--path-histogram", action="store_true",
+                    help="only print which path (plain copy, padding, straddling, ...) the bytes of "
+                         "every field of --workload take")
     ap.add_argument("--copy-ceiling", action="store_true",
                     help="only time the plain-copy yardstick kernels (8 GiB) and print their rates")
     ap.add_argument("--reference-copy", action="store_true",
@@ -457,6 +521,9 @@ def main() -> int:
     torch.cuda.set_device(0)
     if args.copy_ceiling:
         print(json.dumps({"copy_ceiling": run_copy_ceiling(torch)}))
+        return 0
+    if args.path_histogram:
+        print(json.dumps({"path_histogram": run_path_histogram(args, torch, B, synth)}))
         return 0
     hip = HipEvents()
     mode = "inverse" if args.inverse else ("async" if args.async_dispatch else "sync")

@@ -62,7 +62,7 @@ struct Layout {
   size_t seq_ids, next_start, mb_tmp, mb_seq_start, mb_row_start, cu_seqlens;
   size_t rank_seq_base, rank_mbt_base, rank_cu_base;
   size_t segs, seg_dst_shard, seg_src_seq, seg_mb;
-  size_t shard_seg_start, seg_real_prefix;
+  size_t shard_seg_start, seg_real_prefix, segs_src, seg_dst_shard_src;
   size_t sort_keys, lab_sum, lab_cnt;
   size_t total;
 };
@@ -117,6 +117,9 @@ Layout make_layout(const Dims& d) {
   l.seg_mb = take(4 * NK);
   l.shard_seg_start = take(4 * (DC + 1));
   l.seg_real_prefix = take(8 * (NK + 1));
+  // the reverse direction's copy of the segment table in source order (see earl_dispatch_inverse)
+  l.segs_src = take(sizeof(SegRec) * NK);
+  l.seg_dst_shard_src = take(4 * NK);
   l.sort_keys = take(8 * (size_t)d.n_pow2);
   const size_t lmax = (size_t)(d.G > d.D ? d.G : d.D);
   const size_t tab = (2 * (size_t)kPlanWaves + 1) * lmax;
@@ -253,6 +256,7 @@ struct earl_plan {
   uint64_t mailbox_token;
   int32_t status;
   bool inverse_ready;
+  bool source_order;                    // the reverse direction walks the segments by source position
   void* inverse_prefix_done;            // hipEvent_t recorded behind the prefix kernel
   hipStream_t inverse_stream;           // stream that kernel ran on
   void* ev_before;
@@ -528,6 +532,8 @@ int32_t earl_plan_build(const int32_t* lengths_dev, int32_t n_seqs, const earl_s
   p->mailbox = acquire_mailbox(l.summary_end, &p->mailbox_token);
   p->status = EARL_OK;
   p->inverse_ready = false;
+  // packed source layout with contiguous groups: sequence index order is source order
+  p->source_order = src->seq_group == nullptr && src->seq_row == nullptr;
   p->inverse_prefix_done = nullptr;
   p->inverse_stream = nullptr;
   p->async_stream = nullptr;
@@ -1238,23 +1244,38 @@ int32_t earl_dispatch_inverse(earl_plan* p, const earl_field* fields, int32_t n_
   if (n_fields == 0 || p->hdr.total_real_rows == 0) return EARL_OK;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   int64_t* prefix = reinterpret_cast<int64_t*>(p->ws + p->l.seg_real_prefix);
+  // the order the stream of real rows is cut in: by source position where the source layout is
+  // the packed one (the launch then writes the rollout buffers front to back), else the segment
+  // table's own
+  const SegRec* segs = p->dev.segs;
+  const int32_t* seg_dst_shard = p->dev.seg_dst_shard;
+  if (p->source_order) {
+    segs = reinterpret_cast<const SegRec*>(p->ws + p->l.segs_src);
+    seg_dst_shard = reinterpret_cast<const int32_t*>(p->ws + p->l.seg_dst_shard_src);
+  }
   BlockBuilder b;
   b.init(n_fields, n_fields, S, n_dst);
-  // (no record of an inverse call is decoded in the copy kernel: the table's first part is
-  // its closing zero alone)
-  b.tile_start()[0] = 0;
-  int64_t* ts = b.tile_start() + 1;
+  int64_t* ts = b.tile_start();
   TileRec* recs = b.recs();
   const void** ptrs = b.ptrs();
-  // one record per field, the fields with 1 KiB tiles first (as in the forward direction)
-  int64_t tiles = 0, fine = 0;
+  // one record per field: first the fields that are decoded inside the copy kernel (rows under
+  // 16 bytes; all of them when the wide ones are small), then those that go through tile codes
+  int64_t coarse_bytes = 0;
+  for (int f = 0; f < n_fields; ++f) {
+    const int64_t w = (int64_t)fields[f].scalar_bytes * fields[f].width;
+    if (w >= kVecBytes && coarse_bytes <= kDirectMaxCoarseBytes) coarse_bytes += p->hdr.total_real_rows * w;
+  }
+  const bool all_direct = coarse_bytes <= kDirectMaxCoarseBytes;
+  RecordOrder order;
   int n_rec = 0;
   for (int pass = 0; pass < 2; ++pass) {
+    int64_t count = 0;
     for (int f = 0; f < n_fields; ++f) {
       const earl_field& uf = fields[f];
       const int64_t w = (int64_t)uf.scalar_bytes * uf.width;
-      const int shift = tile_shift_of(w, kFieldCopy);
-      if ((shift == kFineTileShift) != (pass == 0)) continue;
+      const bool direct = all_direct || w < kVecBytes;
+      if (direct != (pass == 0)) continue;
+      const int shift = direct ? kJobShiftHost : kTileShift;
       const uint32_t pi = (uint32_t)f * (uint32_t)(S + n_dst);
       TileRec& r = recs[n_rec];
       r.kind = kFieldCopy;
@@ -1263,30 +1284,45 @@ int32_t earl_dispatch_inverse(earl_plan* p, const earl_field* fields, int32_t n_
       r.src_ptr_index = pi;
       r.dst_ptr_index = pi + S;
       r.tile_shift = (int16_t)shift;
-      for (int s = 0; s < S; ++s) ptrs[pi + s] = uf.src_shard_ptrs[s];
+      for (int s2 = 0; s2 < S; ++s2) ptrs[pi + s2] = uf.src_shard_ptrs[s2];
       for (int q = 0; q < n_dst; ++q) ptrs[pi + S + q] = uf.dst_shard_ptrs[q];
-      r.tile_first = tiles;
+      r.tile_first = count;
       r.end_bytes = p->hdr.total_real_rows * w;
-      ts[n_rec++] = tiles;
-      tiles += (r.end_bytes + ((int64_t)1 << shift) - 1) >> shift;
+      ts[n_rec + pass] = count;
+      ++n_rec;
+      count += (r.end_bytes + ((int64_t)1 << shift) - 1) >> shift;
+      if (count > kMaxLaunchTiles) return fail(EARL_INVALID_ARG, "too many tiles for one launch");
     }
-    if (pass == 0) fine = tiles;
+    ts[n_rec + pass] = count;
+    if (pass == 0) {
+      order.n_direct = n_rec;
+      order.jobs = count;
+    } else {
+      order.tiles = count;
+    }
   }
-  ts[n_fields] = tiles;
-  if (fine + (tiles - fine) * kSubTiles > 0x7fffffffll)
+  if (order.tiles * kSubTiles > kMaxLaunchTiles)
     return fail(EARL_INVALID_ARG, "too many tiles for one launch");
+  b.hd.n_direct = order.n_direct;
+  std::memcpy(b.data, &b.hd, sizeof(b.hd));
   const size_t codes_off = b.size;
-  const size_t need = codes_off + kTileCodeBytes * (size_t)tiles;
+  const size_t need = codes_off + kTileCodeBytes * (size_t)order.tiles;
   if (!dispatch_ws_dev || reinterpret_cast<uintptr_t>(dispatch_ws_dev) % kAlign)
     return fail(EARL_INVALID_ARG, "dispatch scratch is null or not %zu-byte aligned", kAlign);
   if (dispatch_ws_bytes < need)
     return fail(EARL_CAPACITY, "dispatch scratch has %zu bytes, %zu needed", dispatch_ws_bytes, need);
-  // The per-segment prefix of real rows is computed once per plan, on the stream of the first
-  // inverse call; an event recorded behind it orders every later call, whatever its stream.
+  // The source-ordered copy of the segment table and the per-segment prefix of real rows are
+  // computed once per plan, on the stream of the first inverse call; an event recorded behind
+  // them orders every later call, whatever its stream.
   if (!p->inverse_ready) {
     hipEvent_t ev = nullptr;
     HIP_TRY(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
-    launch_real_prefix(p->dev.segs, prefix, p->hdr.n_segments, stream);
+    if (p->source_order)
+      launch_source_order(p->dev.segs, p->dev.seg_dst_shard, p->dev.seg_src_seq,
+                          reinterpret_cast<SegRec*>(p->ws + p->l.segs_src),
+                          reinterpret_cast<int32_t*>(p->ws + p->l.seg_dst_shard_src),
+                          p->hdr.n_segments, p->d.N, p->d.G, p->d.R, p->d.K, stream);
+    launch_real_prefix(segs, prefix, p->hdr.n_segments, stream);
     hipError_t e = hipEventRecord(ev, stream);
     if (e != hipSuccess) {
       (void)hipEventDestroy(ev);
@@ -1300,10 +1336,11 @@ int32_t earl_dispatch_inverse(earl_plan* p, const earl_field* fields, int32_t n_
   }
   st = upload_params(b.data, b.size, dispatch_ws_dev, stream);
   if (st != EARL_OK) return st;
-  CopyArgs ca = copy_args(p, dispatch_ws_dev, tiles);
-  ca.n_fine_tiles = fine;
-  launch_copy_inverse(ca, prefix, p->dev.seg_dst_shard,
-                      p->hdr.n_segments, static_cast<unsigned char*>(dispatch_ws_dev) + codes_off,
+  CopyArgs ca = copy_args(p, dispatch_ws_dev, order.tiles);
+  ca.segs = segs;
+  set_direct_view(ca, b, order, dispatch_ws_dev);
+  launch_copy_inverse(ca, prefix, seg_dst_shard, p->hdr.n_segments, n_dst,
+                      static_cast<unsigned char*>(dispatch_ws_dev) + codes_off,
                       static_cast<hipEvent_t>(p->ev_before), static_cast<hipEvent_t>(p->ev_after),
                       stream);
   hipError_t e = hipGetLastError();

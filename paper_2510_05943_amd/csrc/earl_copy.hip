@@ -523,6 +523,25 @@ __device__ __forceinline__ TileRec broadcast_record(const TileRec& mine, int fro
   return out.rec;
 }
 
+// The last record with tile_first <= job (records without jobs share it with their successor),
+// found by the whole wavefront and handed to all its lanes.
+__device__ __forceinline__ TileRec record_of_job(const ParamView& pv, int64_t job) {
+  const int lane = threadIdx.x;
+  int lo = 0, end = pv.n_recs;
+  while (end - lo > kWave) {
+    const int step = (end - lo + kWave - 1) >> 6;
+    const int idx = lo + lane * step;
+    const bool ok = idx < end && pv.recs[idx].tile_first <= job;
+    lo += (__builtin_popcountll(__ballot(ok)) - 1) * step;
+    end = end < lo + step ? end : lo + step;
+  }
+  TileRec mine = {};
+  const bool valid = lo + lane < end;
+  if (valid) mine = pv.recs[lo + lane];
+  const int holder = __builtin_popcountll(__ballot(valid && mine.tile_first <= job)) - 1;
+  return broadcast_record(mine, holder);
+}
+
 __global__ __launch_bounds__(kCopyThreads, 8) void relayout_direct_kernel(const CopyArgs a) {
   // Everything up to the first data load is a chain of dependent memory round trips (each about
   // two microseconds when the plan and the parameter block were written on another XCD), and on a
@@ -538,23 +557,7 @@ __global__ __launch_bounds__(kCopyThreads, 8) void relayout_direct_kernel(const 
   pv.n_recs = a.n_direct;
   const int lane = threadIdx.x;
   const int64_t job = blockIdx.x;
-  TileRec rec;
-  {
-    // last record with tile_first <= job (records without jobs share it with their successor)
-    int lo = 0, end = pv.n_recs;
-    while (end - lo > kWave) {
-      const int step = (end - lo + kWave - 1) >> 6;
-      const int idx = lo + lane * step;
-      const bool ok = idx < end && pv.recs[idx].tile_first <= job;
-      lo += (__builtin_popcountll(__ballot(ok)) - 1) * step;
-      end = end < lo + step ? end : lo + step;
-    }
-    TileRec mine = {};
-    const bool valid = lo + lane < end;
-    if (valid) mine = pv.recs[lo + lane];
-    const int holder = __builtin_popcountll(__ballot(valid && mine.tile_first <= job)) - 1;
-    rec = broadcast_record(mine, holder);
-  }
+  const TileRec rec = record_of_job(pv, job);
   const int64_t lo0 = (job - rec.tile_first) << kJobShift;   // first byte of the job in its shard
   if (lo0 >= rec.end_bytes) return;   // behind the shard's end (a grid sized by capacities)
   u8* const dst = static_cast<u8*>(rec.dst) + lo0;
@@ -937,12 +940,39 @@ __device__ __forceinline__ int find_stream_segment(const int64_t* prefix, int lo
   return lo;
 }
 
+// c.segs, seg_dst_shard and seg_real_prefix describe the segments in the order the stream of
+// real rows is cut in: by source position where the plan's source layout is the packed one (then
+// a launch advances through the rollout buffers front to back and its WRITES are sequential, as
+// the forward direction's are; with the reads sequential and the writes hopping from segment to
+// segment the wide field of the largest workload measured 1.2 % slower), else the segment
+// table's own order.
 struct InverseArgs {
   CopyArgs c;
   const int64_t* seg_real_prefix;   // [n_seg+1]
   const int32_t* seg_dst_shard;     // [n_seg]
   int32_t n_seg;
+  int32_t n_dst_shards;
 };
+
+// Copies the segment table into source order: segment (sequence i, chunk kappa) goes to entry
+// i*K + kappa.  For the packed source layout with contiguous groups that is ascending (shard
+// buffer, row).  i follows from the segment's source shard (its group's first sequence) and
+// its sequence's rank inside the group; kappa from the position of its first row.
+__global__ __launch_bounds__(256) void source_order_kernel(const SegRec* segs,
+                                                           const int32_t* seg_dst_shard,
+                                                           const int32_t* seg_src_seq, SegRec* out,
+                                                           int32_t* out_dst_shard, int n_seg, int N,
+                                                           int G, int R, int K) {
+  const int e = blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= n_seg) return;
+  const SegRec r = segs[e];
+  const int64_t g = r.src_shard / R;
+  const int64_t first = (g * N + G - 1) / G;
+  const int64_t i = first + seg_src_seq[e];
+  const int kappa = r.pos0 / r.n_rows;
+  out[i * K + kappa] = r;
+  out_dst_shard[i * K + kappa] = seg_dst_shard[e];
+}
 
 // Inverse tile codes: a = training-layout pointer of the tile's first byte (0 = generic tile,
 // then b = record << 32 | first segment), b = rollout-layout pointer (any alignment).
@@ -1022,20 +1052,17 @@ __global__ __launch_bounds__(kCodeThreads) void inverse_code_kernel(const Invers
   }
 }
 
-__device__ __forceinline__ void generic_inverse_tile(const InverseArgs a, const TileCode c,
-                                                  const int64_t tile, const uint32_t vec0) {
-  const ParamView pv = view_params(a.c.params);
-  const TileRec rec = pv.recs[(uint32_t)(c.b >> 32)];
+// The 16-byte piece at byte o of the record's stream of real rows, moved by its lane alone: one
+// load and one (possibly unaligned) store when it lies in one segment, scalar by scalar when it
+// crosses into the next.  e: a segment that starts at or before stream byte o.
+__device__ __forceinline__ void inverse_place_vector(const InverseArgs& a, const ParamView& pv,
+                                                     const TileRec& rec, int e, const int64_t o) {
   const int64_t w = rec.row_bytes;
   const int sb = rec.scalar_bytes;
   const int64_t total = rec.end_bytes;   // bytes of the real-row stream of this field
-  const int64_t lo = (tile - rec.tile_first) << rec.tile_shift;
-  const int64_t o = lo + (int64_t)(vec0 + threadIdx.x) * kVecBytes;
   if (o >= total) return;
   const void* const* src_ptrs = pv.ptrs + rec.src_ptr_index;
   const void* const* dst_ptrs = pv.ptrs + rec.dst_ptr_index;
-
-  int e = (int)(uint32_t)c.b;
   int64_t s_lo = 0, s_hi = 0;     // stream byte range of the cached segment
   const u8* from = nullptr;       // training-layout byte of stream byte s_lo
   u8* to = nullptr;               // rollout-layout byte of stream byte s_lo
@@ -1063,16 +1090,201 @@ __device__ __forceinline__ void generic_inverse_tile(const InverseArgs a, const 
   }
 }
 
+__device__ __forceinline__ void generic_inverse_tile(const InverseArgs a, const TileCode c,
+                                                  const int64_t tile, const uint32_t vec0) {
+  const ParamView pv = view_params(a.c.params);
+  const TileRec rec = pv.recs[(uint32_t)(c.b >> 32)];
+  const int64_t lo = (tile - rec.tile_first) << rec.tile_shift;
+  inverse_place_vector(a, pv, rec, (int)(uint32_t)c.b,
+                       lo + (int64_t)(vec0 + threadIdx.x) * kVecBytes);
+}
+
+// The reverse direction decoded inside the copy kernel (narrow fields, small launches), built like
+// relayout_direct_kernel: a wavefront owns 4 KiB of one field's stream of real rows, finds record
+// and first segment with 64-way probes, keeps the job's segments one per lane (their stream byte
+// range and the addresses of the job's first byte in the training and in the rollout layout),
+// lets every lane pick the segment of each of its four vectors, issues all loads, and moves the
+// pieces that cross a segment edge byte by byte, four pieces per round.
+__global__ __launch_bounds__(kCopyThreads, 8) void inverse_direct_kernel(const InverseArgs a) {
+  ParamView pv;
+  pv.tile_start = a.c.direct_tile_start;
+  pv.recs = a.c.direct_recs;
+  pv.ptrs = a.c.ptrs;
+  pv.n_recs = a.c.n_direct;
+  const int lane = threadIdx.x;
+  const int64_t job = blockIdx.x;
+  const TileRec rec = record_of_job(pv, job);
+  const int64_t lo0 = (job - rec.tile_first) << kJobShift;   // first stream byte of the job
+  if (lo0 >= rec.end_bytes) return;
+  const int32_t job_len =
+      rec.end_bytes - lo0 < kJobBytes ? (int32_t)(rec.end_bytes - lo0) : kJobBytes;
+  const int64_t w = rec.row_bytes;
+  // the field's buffers in both layouts, one pointer per lane where there are at most 64
+  const bool src_in_lanes = a.c.n_src_shards <= kWave, dst_in_lanes = a.n_dst_shards <= kWave;
+  uint64_t lane_src = 0, lane_dst = 0;
+  if (src_in_lanes && lane < a.c.n_src_shards)
+    lane_src = reinterpret_cast<uint64_t>(pv.ptrs[rec.src_ptr_index + lane]);
+  if (dst_in_lanes && lane < a.n_dst_shards)
+    lane_dst = reinterpret_cast<uint64_t>(pv.ptrs[rec.dst_ptr_index + lane]);
+
+  // the last segment whose stream prefix is at or before the job's first byte (empty segments
+  // share their prefix with their successor, and the last one is taken)
+  int first = 0;
+  {
+    int end = a.n_seg;
+    while (end - first > 8) {
+      const int step = (end - first + kWave - 1) >> 6;
+      const int idx = first + lane * step;
+      const bool ok = idx < end && a.seg_real_prefix[idx] * w <= lo0;
+      first += (__builtin_popcountll(__ballot(ok)) - 1) * step;
+      end = end < first + step ? end : first + step;
+    }
+  }
+  const int idx = first + lane;
+  const bool fetched = idx < a.n_seg;
+  SegRec r = {};
+  int64_t s_lo = 0;
+  int32_t dshard = 0;
+  if (fetched) {
+    r = a.c.segs[idx];
+    s_lo = a.seg_real_prefix[idx] * w;
+    dshard = a.seg_dst_shard[idx];
+  }
+  const int shift = __builtin_popcountll(__ballot(fetched && s_lo <= lo0)) - 1;
+  const int e0 = first + shift;
+  int32_t win_lo = kFar, win_hi = kFar;   // the segment's real rows in the stream, relative to the job
+  uint64_t win_from = 0, win_to = 0;      // training / rollout address of the job's byte 0
+  {
+    uint64_t src_ptr = (uint64_t)__shfl((unsigned long long)lane_src, r.src_shard);
+    uint64_t dst_ptr = (uint64_t)__shfl((unsigned long long)lane_dst, dshard);
+    if (fetched) {
+      win_lo = clamp_far(s_lo - lo0);
+      win_hi = clamp_far(s_lo + (int64_t)r.n_real * w - lo0);
+      if (r.n_real > 0) {
+        if (!src_in_lanes) src_ptr = reinterpret_cast<uint64_t>(pv.ptrs[rec.src_ptr_index + r.src_shard]);
+        if (!dst_in_lanes) dst_ptr = reinterpret_cast<uint64_t>(pv.ptrs[rec.dst_ptr_index + dshard]);
+        win_from = dst_ptr + (uint64_t)(r.dst_row * w + (lo0 - s_lo));
+        win_to = src_ptr + (uint64_t)(r.src_row * w + (lo0 - s_lo));
+      }
+    }
+  }
+  {
+    // move the window down so that lane k holds segment e0 + k
+    const int from_lane = lane + shift;
+    const bool in = from_lane < kWave;
+    const int32_t lo_ = __shfl(win_lo, from_lane), hi_ = __shfl(win_hi, from_lane);
+    const uint64_t f_ = (uint64_t)__shfl((unsigned long long)win_from, from_lane);
+    const uint64_t t_ = (uint64_t)__shfl((unsigned long long)win_to, from_lane);
+    win_lo = in ? lo_ : kFar;
+    win_hi = in ? hi_ : kFar;
+    win_from = f_;
+    win_to = t_;
+  }
+  const int window_lanes = kWave - shift;
+  const int n_win = __builtin_popcountll(__ballot(win_lo < job_len));
+  const bool window_complete = n_win < window_lanes || e0 + window_lanes >= a.n_seg;
+  const int32_t window_hi =
+      window_complete ? kFar : __builtin_amdgcn_readlane(win_hi, window_lanes - 1);
+
+  int mode[kJobSubTiles], my_k[kJobSubTiles];
+  uint64_t my_from[kJobSubTiles], my_to[kJobSubTiles];
+  int k0 = 0;
+#pragma unroll
+  for (int t = 0; t < kJobSubTiles; ++t) {
+    const int32_t sub_lo = t * (kCopyThreads * kVecBytes);
+    const int32_t sub_hi = sub_lo + kCopyThreads * kVecBytes < job_len
+                               ? sub_lo + kCopyThreads * kVecBytes : job_len;
+    const int32_t o = sub_lo + lane * kVecBytes;
+    const int32_t o_end = o + kVecBytes;
+    mode[t] = o < job_len ? kVecPending : kVecNone;
+    my_k[t] = 0;
+    my_from[t] = my_to[t] = 0;
+    if (sub_lo >= job_len) continue;
+    for (int k = k0; k < n_win; ++k) {
+      const int32_t dl = __builtin_amdgcn_readlane(win_lo, k);
+      if (dl >= sub_hi) break;
+      const int32_t dh = __builtin_amdgcn_readlane(win_hi, k);
+      if (dh <= sub_lo) { k0 = k + 1; continue; }
+      const uint64_t fj = readlane_u64(win_from, k), tj = readlane_u64(win_to, k);
+      if (mode[t] == kVecPending && o < dh && o_end > dl) {
+        my_k[t] = k;
+        if (o_end > window_hi || o_end > job_len) {
+          // stays pending: beyond the window, or the stream ends inside it
+        } else if (o < dl || o_end > dh) {
+          mode[t] = kVecSlow;
+        } else {
+          mode[t] = kVecCopy;
+          my_from[t] = fj + (uint64_t)(int64_t)o;
+          my_to[t] = tj + (uint64_t)(int64_t)o;
+        }
+      }
+    }
+  }
+  u32x4 v[kJobSubTiles];
+#pragma unroll
+  for (int t = 0; t < kJobSubTiles; ++t) {
+    v[t] = u32x4{0, 0, 0, 0};
+    if (mode[t] == kVecCopy) v[t] = load16(reinterpret_cast<const u8*>(my_from[t]));
+  }
+  {
+    // pieces that cross a segment edge: group g of 16 lanes moves the 16 bytes of the
+    // (4*round + g)-th of them, each lane looking up its own byte's segment in the window
+    const uint64_t m0 = __ballot(mode[0] == kVecSlow), m1 = __ballot(mode[1] == kVecSlow),
+                   m2 = __ballot(mode[2] == kVecSlow), m3 = __ballot(mode[3] == kVecSlow);
+    const int c0 = __builtin_popcountll(m0), c1 = c0 + __builtin_popcountll(m1),
+              c2 = c1 + __builtin_popcountll(m2), n_slow = c2 + __builtin_popcountll(m3);
+    for (int base = 0; base < n_slow; base += 4) {
+      int32_t vec_o = -1;
+      int k = 0;
+#pragma unroll
+      for (int slot = 0; slot < 4; ++slot) {
+        const int i = base + slot;
+        if (i >= n_slow) break;
+        const int t = i < c0 ? 0 : (i < c1 ? 1 : (i < c2 ? 2 : 3));
+        uint64_t m = t == 0 ? m0 : (t == 1 ? m1 : (t == 2 ? m2 : m3));
+        for (int q = i - (t == 0 ? 0 : (t == 1 ? c0 : (t == 2 ? c1 : c2))); q > 0; --q) m &= m - 1;
+        const int owner = __builtin_ctzll(m);
+        const int ks = t == 0 ? my_k[0] : (t == 1 ? my_k[1] : (t == 2 ? my_k[2] : my_k[3]));
+        const int owner_k = __builtin_amdgcn_readlane(ks, owner);
+        if ((lane >> 4) == slot) {
+          vec_o = (t * kCopyThreads + owner) * kVecBytes;
+          k = owner_k;
+        }
+      }
+      const bool act = vec_o >= 0;
+      const int32_t b = vec_o + (lane & 15);
+      for (;;) {
+        const int32_t h = __shfl(win_hi, k);
+        const bool further = act && b >= h && k < kWave - 1;
+        if (__ballot(further) == 0) break;
+        if (further) ++k;
+      }
+      const uint64_t g_from = (uint64_t)__shfl((unsigned long long)win_from, k);
+      const uint64_t g_to = (uint64_t)__shfl((unsigned long long)win_to, k);
+      if (act)
+        *reinterpret_cast<u8*>(g_to + (uint64_t)(int64_t)b) =
+            *reinterpret_cast<const u8*>(g_from + (uint64_t)(int64_t)b);
+    }
+  }
+#pragma unroll
+  for (int t = 0; t < kJobSubTiles; ++t)
+    if (mode[t] == kVecCopy) store16_any(reinterpret_cast<u8*>(my_to[t]), v[t]);
+  if (__ballot(mode[0] == kVecPending || mode[1] == kVecPending || mode[2] == kVecPending ||
+               mode[3] == kVecPending) != 0) {
+#pragma nounroll
+    for (int t = 0; t < kJobSubTiles; ++t) {
+      const int mt = t == 0 ? mode[0] : (t == 1 ? mode[1] : (t == 2 ? mode[2] : mode[3]));
+      if (mt == kVecPending)
+        inverse_place_vector(a, pv, rec, e0, lo0 + (int64_t)(t * kCopyThreads + lane) * kVecBytes);
+    }
+  }
+}
+
 __global__ __launch_bounds__(kCopyThreads, 8) void inverse_kernel(const InverseArgs a,
                                                                const TileCode* __restrict__ codes) {
-  // as in the forward kernel: one workgroup per 1 KiB tile code, kSubTiles per 4 KiB tile code
-  int64_t tile = blockIdx.x;
-  uint32_t vec0 = 0;
-  if (tile >= a.c.n_fine_tiles) {
-    const int64_t rest = tile - a.c.n_fine_tiles;
-    tile = a.c.n_fine_tiles + rest / kSubTiles;
-    vec0 = (uint32_t)(rest % kSubTiles) * kCopyThreads;
-  }
+  // as in the forward kernel: kSubTiles workgroups per 4 KiB tile code
+  const int64_t tile = blockIdx.x / kSubTiles;
+  const uint32_t vec0 = (uint32_t)(blockIdx.x % kSubTiles) * kCopyThreads;
   const TileCode c = codes[tile];
   if (c.a != 0) {
     const uint32_t v = vec0 + threadIdx.x;
@@ -1133,18 +1345,31 @@ void launch_real_prefix(const SegRec* segs, int64_t* prefix, int n_seg, hipStrea
   hipLaunchKernelGGL(real_prefix_kernel, dim3(1), dim3(kPlanThreads), 0, stream, segs, prefix, n_seg);
 }
 
+void launch_source_order(const SegRec* segs, const int32_t* seg_dst_shard,
+                         const int32_t* seg_src_seq, SegRec* out, int32_t* out_dst_shard, int n_seg,
+                         int N, int G, int R, int K, hipStream_t stream) {
+  if (n_seg <= 0) return;
+  hipLaunchKernelGGL(source_order_kernel, dim3((unsigned)((n_seg + 255) / 256)), dim3(256), 0, stream,
+                     segs, seg_dst_shard, seg_src_seq, out, out_dst_shard, n_seg, N, G, R, K);
+}
+
 void launch_copy_inverse(const CopyArgs& a, const int64_t* seg_real_prefix,
-                         const int32_t* seg_dst_shard, int n_seg, void* tile_codes,
-                         hipEvent_t before, hipEvent_t after, hipStream_t stream) {
-  if (a.n_tiles <= 0) return;
-  InverseArgs ia{a, seg_real_prefix, seg_dst_shard, n_seg};
-  TileCode* codes = static_cast<TileCode*>(tile_codes);
-  const int64_t per_group = (int64_t)kCodeThreads * kTilesPerLane;
-  const unsigned g1 = (unsigned)((a.n_tiles + per_group - 1) / per_group);
+                         const int32_t* seg_dst_shard, int n_seg, int n_dst_shards,
+                         void* tile_codes, hipEvent_t before, hipEvent_t after,
+                         hipStream_t stream) {
+  InverseArgs ia{a, seg_real_prefix, seg_dst_shard, n_seg, n_dst_shards};
   if (before) (void)hipEventRecord(before, stream);
-  hipLaunchKernelGGL(inverse_code_kernel, dim3(g1), dim3(kCodeThreads), 0, stream, ia, codes);
-  const int64_t grid = a.n_fine_tiles + (a.n_tiles - a.n_fine_tiles) * kSubTiles;
-  hipLaunchKernelGGL(inverse_kernel, dim3((unsigned)grid), dim3(kCopyThreads), 0, stream, ia, codes);
+  if (a.n_direct_jobs > 0)
+    hipLaunchKernelGGL(inverse_direct_kernel, dim3((unsigned)a.n_direct_jobs), dim3(kCopyThreads), 0,
+                       stream, ia);
+  if (a.n_tiles > 0) {
+    TileCode* codes = static_cast<TileCode*>(tile_codes);
+    const int64_t per_group = (int64_t)kCodeThreads * kTilesPerLane;
+    const unsigned g1 = (unsigned)((a.n_tiles + per_group - 1) / per_group);
+    hipLaunchKernelGGL(inverse_code_kernel, dim3(g1), dim3(kCodeThreads), 0, stream, ia, codes);
+    hipLaunchKernelGGL(inverse_kernel, dim3((unsigned)(a.n_tiles * kSubTiles)), dim3(kCopyThreads), 0,
+                       stream, ia, codes);
+  }
   if (after) (void)hipEventRecord(after, stream);
 }
 

@@ -180,9 +180,6 @@ struct CopyArgs {
   int32_t n_direct;
   int32_t n_src_shards;
   int64_t n_tiles;       // tile codes in the launch
-  // Reverse direction: the first n_fine_tiles codes describe 1 KiB each (one workgroup per code),
-  // the others 4 KiB (kSubTiles workgroups per code).
-  int64_t n_fine_tiles;
   const int32_t* seg_mb;  // micro-batch of every segment (fields that ask for non-zero counts)
 };
 
@@ -201,8 +198,12 @@ void launch_param_chunks(void* dev_dst, const unsigned char* host_block, size_t 
 // earl_dispatch_async: completes the records of a parameter block from the plan in device memory
 void launch_async_resolve(DispatchDev* params, const PlanDev& plan, hipStream_t stream);
 void launch_real_prefix(const SegRec* segs, int64_t* prefix, int n_seg, hipStream_t stream);
+void launch_source_order(const SegRec* segs, const int32_t* seg_dst_shard,
+                         const int32_t* seg_src_seq, SegRec* out, int32_t* out_dst_shard, int n_seg,
+                         int N, int G, int R, int K, hipStream_t stream);
 void launch_copy_inverse(const CopyArgs& a, const int64_t* seg_real_prefix,
-                         const int32_t* seg_dst_shard, int n_seg, void* tile_codes,
-                         hipEvent_t before, hipEvent_t after, hipStream_t stream);
+                         const int32_t* seg_dst_shard, int n_seg, int n_dst_shards,
+                         void* tile_codes, hipEvent_t before, hipEvent_t after,
+                         hipStream_t stream);
 
 }  // namespace earl
