@@ -116,18 +116,31 @@ __device__ int64_t block_reduce_min(int64_t v, BlockScratch& s) {
 
 // Hands the finished summary block (the first bytes of the workspace, header included) to the
 // host through its mailbox, if the plan has one.  Every thread of the workgroup calls it, after
-// the header has been written.
-__device__ void publish_summary(const PlanDev& p) {
+// the header has been written.  copy: the block is read back from the workspace and copied;
+// false where every entry went to the mailbox as it was stored (put_summary).
+__device__ void publish_summary(const PlanDev& p, bool copy = true) {
   if (!p.host_summary) return;
-  __syncthreads();   // the whole block is written and visible to this workgroup
-  const uint4* from = reinterpret_cast<const uint4*>(p.hdr);
-  uint4* to = reinterpret_cast<uint4*>(p.host_summary);
-  for (uint32_t x = threadIdx.x; x < p.summary_bytes / 16; x += blockDim.x) to[x] = from[x];
+  if (copy) {
+    __syncthreads();   // the whole block is written and visible to this workgroup
+    const uint4* from = reinterpret_cast<const uint4*>(p.hdr);
+    uint4* to = reinterpret_cast<uint4*>(p.host_summary);
+    for (uint32_t x = threadIdx.x; x < p.summary_bytes / 16; x += blockDim.x) to[x] = from[x];
+  }
   __threadfence_system();
   __syncthreads();
   if (threadIdx.x == 0)
     __hip_atomic_store(reinterpret_cast<uint64_t*>(p.host_summary + p.host_flag_offset), p.host_token,
                        __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
+// Stores one entry of the summary block: in the workspace and, if the plan has a mailbox, at the
+// same offset there.
+template <class Tv>
+__device__ __forceinline__ void put_summary(const PlanDev& p, Tv* where, const Tv& value) {
+  *where = value;
+  if (p.host_summary)
+    *reinterpret_cast<Tv*>(p.host_summary + (reinterpret_cast<const unsigned char*>(where) -
+                                             reinterpret_cast<const unsigned char*>(p.hdr))) = value;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1133,9 +1146,9 @@ __global__ __launch_bounds__(kPlanThreads) void plan_resident_kernel(const PlanD
       PlanHeader h = {};
       h.status = s.invalid ? 1 : 2;
       h.bad_index = s.invalid ? s.bad_invalid : s.bad;
-      *p.hdr = h;
+      put_summary(p, p.hdr, h);
     }
-    publish_summary(p);
+    publish_summary(p, false);
     return;
   }
 
@@ -1185,8 +1198,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_resident_kernel(const PlanD
   }
   __syncthreads();
   for (int x = tid; x < S; x += nt) {
-    p.src_rows_needed[x] = (int64_t)s.need[x];
-    p.src_seqs_needed[x] = (int64_t)s.need[S + x];
+    put_summary(p, &p.src_rows_needed[x], (int64_t)s.need[x]);
+    put_summary(p, &p.src_seqs_needed[x], (int64_t)s.need[S + x]);
   }
 
   // ---- sort by (padded length desc, index asc), rank assignment ------------------------------
@@ -1260,9 +1273,9 @@ __global__ __launch_bounds__(kPlanThreads) void plan_resident_kernel(const PlanD
       }
       s.n_seq[lane] = ac;
       s.rank_rows[lane] = as;
-      p.n_seq[lane] = ac;
-      p.rank_load[lane] = as * C;      // padded tokens = C * rows per SP rank
-      for (int c = 0; c < C; ++c) p.shard_rows[(size_t)lane * C + c] = as;
+      put_summary(p, &p.n_seq[lane], ac);
+      put_summary(p, &p.rank_load[lane], as * C);      // padded tokens = C * rows per SP rank
+      for (int c = 0; c < C; ++c) put_summary(p, &p.shard_rows[(size_t)lane * C + c], as);
     }
     const int64_t incl = wave_incl_scan_i64(ac);
     if (lane < D) s.seq_base[lane] = (int32_t)(incl - ac);
@@ -1350,7 +1363,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_resident_kernel(const PlanD
     const int64_t i1 = wave_incl_scan_i64(t1), i2 = wave_incl_scan_i64(t2);
     if (lane < D) {
       s.n_mb[lane] = nm;
-      p.n_mb[lane] = nm;
+      put_summary(p, &p.n_mb[lane], nm);
       s.mbt_base[lane] = (int32_t)(i1 - t1);
       s.cu_base[lane] = (int32_t)(i2 - t2);
     }
@@ -1478,7 +1491,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_resident_kernel(const PlanD
     p.shard_seg_start[q] = (int32_t)v;
   }
   __syncthreads();
-  for (int x = tid; x < n_pairs; x += nt) p.a2a[x] = (int64_t)s.a2a[x];
+  for (int x = tid; x < n_pairs; x += nt) put_summary(p, &p.a2a[x], (int64_t)s.a2a[x]);
   if (tid == 0) {
     PlanHeader h = {};
     h.status = s.invalid ? 1 : 0;
@@ -1491,9 +1504,9 @@ __global__ __launch_bounds__(kPlanThreads) void plan_resident_kernel(const PlanD
     h.total_dst_rows = s.dst_rows;
     h.rank_load_min = s.load_min;
     h.rank_load_max = s.load_max;
-    *p.hdr = h;
+    put_summary(p, p.hdr, h);
   }
-  publish_summary(p);
+  publish_summary(p, false);
 }
 
 // Batches the resident kernel takes (the LDS carve-up above bounds every term).
