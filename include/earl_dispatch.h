@@ -187,8 +187,13 @@ int32_t earl_plan_build(const int32_t* lengths_dev, int32_t n_seqs, const earl_s
                         const earl_dst_layout* dst, void* workspace_dev, size_t workspace_bytes,
                         void* hip_stream, earl_plan** out_plan);
 
-/* Waits for the plan on its stream (once per plan), copies the totals to the host and returns the
- * plan's status (EARL_OK, EARL_INVALID_ARG, EARL_SEQ_EXCEEDS_BUDGET, EARL_HIP_ERROR). */
+/* Waits for the plan's totals (once per plan), copies them to the host and returns the plan's
+ * status (EARL_OK, EARL_INVALID_ARG, EARL_SEQ_EXCEEDS_BUDGET, EARL_HIP_ERROR).  The plan kernel
+ * stores its totals into a mailbox in pinned host memory and the call polls it (for a quarter of
+ * a millisecond, then it waits for the stream); the mailboxes are 1 MiB that the library allocates
+ * at the first earl_plan_build of the process and keeps until the process ends.  A plan whose
+ * totals exceed 16 KiB (large a2a_counts), or that finds all 64 mailboxes held by plans that
+ * were built and not yet asked for their summary, is copied from the device instead. */
 int32_t earl_plan_get_summary(earl_plan* plan, earl_plan_summary* out);
 
 /*
