@@ -232,6 +232,43 @@ def _dispatch_and_inverse_equal_oracle(H, w):
     H.B.plan_destroy(plan)
 
 
+DIRECT_KERNEL_CASES = [
+    # more segments in a 4 KiB job than the 64 a wavefront keeps: single-row sequences cut into
+    # many chunks, one-byte and two-byte rows (the per-lane path beyond the window)
+    ("segments_of_one_byte", dict(L=[1 + (i % 3) for i in range(1500)], dp=2, sp=2, zigzag=1,
+                                  B=64), (synth.F_MASK, synth.bytes_field("h", 2, 1, 0x0101))),
+    ("segments_of_a_few_bytes", dict(L=[(i * 7) % 5 + 1 for i in range(900)], G=3, R=2, dp=3, sp=4,
+                                     zigzag=1, pad=2, B=512),
+     (synth.F_MASK, synth.F_ID, synth.bytes_field("b6", 2, 3, 0x7777))),
+    # more than 64 source shards and more than 64 destination shards: pointers looked up per
+    # segment instead of held one per lane (both directions)
+    ("source_shards_96", dict(L=[(i * 37) % 200 + 1 for i in range(700)], G=48, R=2, dp=4, sp=2,
+                              zigzag=1, B=4096), (synth.F_ID, synth.F_MASK, synth.F_OLD)),
+    ("destination_shards_130", dict(L=[(i * 53) % 300 + 1 for i in range(800)], G=4, dp=65, sp=2,
+                                    B=8192), (synth.F_ID, synth.F_MASK)),
+    # wide rows in a small launch (decoded in the copy kernel as well), odd widths, rows that are
+    # not a multiple of 16 bytes, padding that is not zero
+    ("wide_rows_small_launch", dict(L=[(i * 101) % 700 + 1 for i in range(300)], G=4, dp=4, sp=2,
+                                    zigzag=1, pad=8, B=8192),
+     (synth.bytes_field("bf16x1024", 2, 1024, 0x3F80), synth.bytes_field("w24", 8, 3, 0x1122334455667788),
+      synth.bytes_field("w50", 2, 25, 0xBEEF), synth.F_MASK)),
+    # many records (a field table of more than 64 entries), shards of a few rows, empty ranks
+    ("many_small_shards", dict(L=[(i * 11) % 9 + 1 for i in range(90)], G=2, dp=40, sp=3, zigzag=1,
+                               B=64), (synth.F_ID, synth.F_MASK, synth.F_OLD, synth.F_ADV)),
+]
+
+
+@pytest.mark.parametrize("desc,kw,fields", DIRECT_KERNEL_CASES, ids=[c[0] for c in DIRECT_KERNEL_CASES])
+def test_rare_paths_of_the_direct_kernels(H, desc, kw, fields):
+    """Dispatch and reverse dispatch against the oracle on batches built to leave the common path
+    of the kernels that decode inside the copy."""
+    w = synth.custom_workload(kw["L"], n_groups=kw.get("G", 1), replication=kw.get("R", 1),
+                              dp=kw["dp"], sp=kw["sp"], zigzag=kw.get("zigzag", 0),
+                              pad_multiple=kw.get("pad", 1), mb_token_budget=kw["B"], fields=fields,
+                              seed=len(kw["L"]))
+    _dispatch_and_inverse_equal_oracle(H, w)
+
+
 def test_field_shape_limits(H):
     """The widest row the library accepts (1 MiB), a row one scalar short of it (so rows are not
     a multiple of 16 bytes and every vector load is unaligned), and the largest number of
