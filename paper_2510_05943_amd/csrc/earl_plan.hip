@@ -63,6 +63,20 @@ __device__ __forceinline__ int64_t wave_incl_scan_i64(int64_t x) {
   x = dpp_add_i64<kDppRowBcast31, 0xc>(x);
   return x;
 }
+__device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t x) {
+  x += dpp_u32<kDppRowShr + 1, 0xf>(0u, x);
+  x += dpp_u32<kDppRowShr + 2, 0xf>(0u, x);
+  x += dpp_u32<kDppRowShr + 4, 0xf>(0u, x);
+  x += dpp_u32<kDppRowShr + 8, 0xf>(0u, x);
+  x += dpp_u32<kDppRowBcast15, 0xa>(0u, x);
+  x += dpp_u32<kDppRowBcast31, 0xc>(0u, x);
+  return x;
+}
+// number of set bits of mask below this lane
+__device__ __forceinline__ int count_below(uint64_t mask) {
+  return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                        __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
 __device__ __forceinline__ int64_t readlane_i64(int64_t x, int l) {
   uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)x, l);
   uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)((uint64_t)x >> 32), l);
@@ -314,10 +328,103 @@ __device__ void bitonic_sort_lanes(uint64_t* keys_generic, int n) {
 }
 
 // ---------------------------------------------------------------------------------------
+// The same sort for 32-bit keys.  The partner at lane distance 1, 2, 4 or 8 is inside the
+// lane's row of 16 and comes through a DPP move (distance 4 has no control of its own: two
+// moves, each written in the two banks of four lanes whose partner lies on that side);
+// distances 16 and 32 cross rows and go through ds_bpermute.
+// ---------------------------------------------------------------------------------------
+constexpr int kDppRowShl4 = 0x104, kDppRowShr4 = 0x114, kDppRowRor8 = 0x128;
+
+template <int kJ>
+__device__ __forceinline__ uint32_t from_lane_xor(uint32_t v) {
+  if constexpr (kJ == 1) {
+    return dpp_u32<kDppQuadXor1, 0xf>(v, v);
+  } else if constexpr (kJ == 2) {
+    return dpp_u32<kDppQuadXor2, 0xf>(v, v);
+  } else if constexpr (kJ == 4) {
+    const uint32_t t =
+        (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, kDppRowShl4, 0xf, 0x5, false);
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)t, (int)v, kDppRowShr4, 0xf, 0xa, false);
+  } else if constexpr (kJ == 8) {
+    return dpp_u32<kDppRowRor8, 0xf>(v, v);
+  } else {
+    return (uint32_t)__shfl_xor((int)v, kJ);
+  }
+}
+
+// Compare-exchange stages with partner distance kJ, kJ/2, .. 1 of the merge into runs of k keys.
+template <int kJ>
+__device__ __forceinline__ uint32_t lane_stages(uint32_t key, int x, int k) {
+  const uint32_t other = from_lane_xor<kJ>(key);
+  const bool keep_smaller = ((x & kJ) == 0) == ((x & k) == 0);   // lower partner of an ascending run
+  const uint32_t lo = key < other ? key : other, hi = key < other ? other : key;
+  key = keep_smaller ? lo : hi;
+  if constexpr (kJ > 1) key = lane_stages<kJ / 2>(key, x, k);
+  return key;
+}
+
+__device__ void bitonic_sort_lanes32(uint32_t* keys_generic, int n) {
+  typedef __attribute__((address_space(3))) uint32_t* LdsKeys;
+  LdsKeys keys = (LdsKeys)keys_generic;
+  const int nt = blockDim.x;   // a multiple of 64
+  for (int x = threadIdx.x; x < n; x += nt) {
+    uint32_t key = keys[x];
+    if (n >= 2) key = lane_stages<1>(key, x, 2);
+    if (n >= 4) key = lane_stages<2>(key, x, 4);
+    if (n >= 8) key = lane_stages<4>(key, x, 8);
+    if (n >= 16) key = lane_stages<8>(key, x, 16);
+    if (n >= 32) key = lane_stages<16>(key, x, 32);
+    if (n >= 64) key = lane_stages<32>(key, x, 64);
+    keys[x] = key;
+  }
+  __syncthreads();
+  for (int k = 2 * kWave; k <= n; k <<= 1) {
+    for (int j = k >> 1; j >= kWave; j >>= 1) {
+      for (int t = threadIdx.x; t < (n >> 1); t += nt) {
+        const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
+        const int y = i | j;
+        const uint32_t a = keys[i], b = keys[y];
+        if ((a > b) == ((i & k) == 0)) {
+          keys[i] = b;
+          keys[y] = a;
+        }
+      }
+      __syncthreads();
+    }
+    for (int x = threadIdx.x; x < n; x += nt) keys[x] = lane_stages<32>(keys[x], x, k);
+    __syncthreads();
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Sort keys: (padded length descending, index ascending) in one word, all ones after the last
+// sequence (a padded length is at least 1, so no sequence has that key).
+// ---------------------------------------------------------------------------------------
+struct Key64 {   // any padded length below 2^31, any index
+  typedef uint64_t Word;
+  static constexpr Word kLast = ~0ull;
+  static __device__ __forceinline__ Word make(int64_t lp, int i) {
+    return ((uint64_t)(0x7fffffffll - lp) << 32) | (uint32_t)i;
+  }
+  static __device__ __forceinline__ int32_t lp(Word k) { return 0x7fffffff - (int32_t)(k >> 32); }
+  static __device__ __forceinline__ int32_t index(Word k) { return (int32_t)(k & 0xffffffffu); }
+};
+struct Key32 {   // padded lengths below 2^21 and indices below 2^11
+  typedef uint32_t Word;
+  static constexpr Word kLast = ~0u;
+  static constexpr int kLpBits = 21, kIndexBits = 11;
+  static __device__ __forceinline__ Word make(int64_t lp, int i) {
+    return ((uint32_t)(0x1fffff - (int32_t)lp) << kIndexBits) | (uint32_t)i;
+  }
+  static __device__ __forceinline__ int32_t lp(Word k) { return 0x1fffff - (int32_t)(k >> kIndexBits); }
+  static __device__ __forceinline__ int32_t index(Word k) { return (int32_t)(k & 0x7ffu); }
+};
+
+// ---------------------------------------------------------------------------------------
 // Longest-first list scheduling in wavefront 0.
 //
-// keys[] holds the sequences sorted by (padded length descending, index ascending); the low
-// word is the index, the high word is 0x7fffffff - padded length.  The chain of N "give the next
+// keys[] holds the sequences sorted by (padded length descending, index ascending), packed as
+// Key64 or Key32 above (Kc names the packing).  The chain of N "give the next
 // sequence to the least loaded rank" steps is serial by definition, so everything is about the
 // latency of one step.  Up to 64 ranks the loads are never searched: the ranks are kept as a
 // list SORTED by (load, rank) across the lanes, one word per lane, and a step removes the head
@@ -361,8 +468,10 @@ __device__ __forceinline__ uint32_t wave_min_low(uint32_t x) {
 // v_min with a DPP lane shift, against a log2(D)-step butterfly plus compare and select when
 // the loads stay in place and the minimum is searched; head and grown word travel through
 // scalar registers, and the head word (the winner is its low six bits) is written into lane s
-// of `heads`.  (The median of the three in one v_med3_u32 needs the shifted list in a register
-// of its own, one more instruction, and measured slower.)
+// of `heads`.  (The median of the three in one v_med3_u32, on a shifted copy of the list kept in
+// a register of its own, shortens the dependency chain by one instruction and measured 8 %
+// slower: the lone wavefront's time follows the bytes of code it runs through, 0.4 ns per byte,
+// not the chain's length, and v_med3_u32 takes eight bytes where v_max_u32 takes four.)
 // kShift: row_shl:1 when the ranks fit one row of 16 lanes, else wave_shl:1.
 // Items past N have length 0 and come last: the head is put back where it was.
 // Lanes >= D hold 0xffffffff; a real word stays below it because the caller only takes this
@@ -416,16 +525,16 @@ __device__ __forceinline__ void lpt_sorted_block(uint32_t& word, uint32_t& heads
   (lpt_sorted_two_steps<kShift, 2 * kPairs>(word, heads, lp6), ...);
 }
 
-template <int kShift>
-__device__ void lpt_sorted(const PlanDev& p, const uint64_t* keys, int32_t* rank_out) {
+template <class Kc, int kShift>
+__device__ void lpt_sorted(const PlanDev& p, const typename Kc::Word* keys, int32_t* rank_out) {
   const int lane = lane_id();
   const int N = p.N;
   uint32_t word = lane < p.D ? (uint32_t)lane : 0xffffffffu;   // load << 6 | rank
   for (int start = 0; start < N; start += kWave) {
     const int i = start + lane;
-    const uint64_t key = i < N ? keys[i] : ~0ull;
-    const uint32_t lp6 = i < N ? (uint32_t)(0x7fffffff - (int32_t)(key >> 32)) << 6 : 0u;
-    const int32_t idx = (int32_t)(key & 0xffffffffu);
+    const typename Kc::Word key = i < N ? keys[i] : Kc::kLast;
+    const uint32_t lp6 = i < N ? (uint32_t)Kc::lp(key) << 6 : 0u;
+    const int32_t idx = Kc::index(key);
     uint32_t heads = 0;   // lane s: the list's head word when the s-th item of this block came
     lpt_sorted_block<kShift>(word, heads, lp6, std::make_integer_sequence<int, kWave / 2>{});
     if (i < N) rank_out[idx] = (int32_t)(heads & 63u);
@@ -482,7 +591,8 @@ __device__ __forceinline__ void lpt16_sixteen_steps(uint32_t& a, uint32_t& lp, u
 }
 #undef EARL_LPT16_STEP
 
-__device__ void lpt_sorted16(const PlanDev& p, const uint64_t* keys, int32_t* rank_out) {
+template <class Kc>
+__device__ void lpt_sorted16(const PlanDev& p, const typename Kc::Word* keys, int32_t* rank_out) {
   const int lane = lane_id();
   const int N = p.N;
   const int col = lane & 15;
@@ -492,7 +602,7 @@ __device__ void lpt_sorted16(const PlanDev& p, const uint64_t* keys, int32_t* ra
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int x = start + 16 * j + col;
-      lpreg[j] = x < N ? (uint32_t)(0x7fffffff - (int32_t)(keys[x] >> 32)) << 6 : 0u;
+      lpreg[j] = x < N ? (uint32_t)Kc::lp(keys[x]) << 6 : 0u;
     }
     uint32_t h0 = 0, h1 = 0, h2 = 0, h3 = 0;
     // item 0's length to all lanes; the blocks below keep it one item ahead
@@ -504,7 +614,7 @@ __device__ void lpt_sorted16(const PlanDev& p, const uint64_t* keys, int32_t* ra
     const int i = start + lane;
     if (i < N) {
       const uint32_t mine = (lane & 2) ? ((lane & 1) ? h3 : h2) : ((lane & 1) ? h1 : h0);
-      rank_out[(int32_t)(keys[i] & 0xffffffffu)] = (int32_t)(mine & 63u);
+      rank_out[Kc::index(keys[i])] = (int32_t)(mine & 63u);
     }
   }
 }
@@ -535,16 +645,16 @@ __device__ __forceinline__ void lpt_sorted64_block(uint64_t& word, uint32_t& ran
   (lpt_sorted64_step<kQuadratic, kItems>(word, ranks, lp), ...);
 }
 
-template <bool kQuadratic>
-__device__ void lpt_sorted64(const PlanDev& p, const uint64_t* keys, int32_t* rank_out) {
+template <class Kc, bool kQuadratic>
+__device__ void lpt_sorted64(const PlanDev& p, const typename Kc::Word* keys, int32_t* rank_out) {
   const int lane = lane_id();
   const int N = p.N;
   uint64_t word = lane < p.D ? (uint64_t)lane : ~0ull;   // load << 6 | rank
   for (int start = 0; start < N; start += kWave) {
     const int i = start + lane;
-    const uint64_t key = i < N ? keys[i] : ~0ull;
-    const uint32_t lp = i < N ? (uint32_t)(0x7fffffff - (int32_t)(key >> 32)) : 0u;
-    const int32_t idx = (int32_t)(key & 0xffffffffu);
+    const typename Kc::Word key = i < N ? keys[i] : Kc::kLast;
+    const uint32_t lp = i < N ? (uint32_t)Kc::lp(key) : 0u;
+    const int32_t idx = Kc::index(key);
     uint32_t ranks = 0;
     lpt_sorted64_block<kQuadratic>(word, ranks, lp, std::make_integer_sequence<int, kWave>{});
     if (i < N) rank_out[idx] = (int32_t)ranks;
@@ -556,8 +666,8 @@ __device__ void lpt_sorted64(const PlanDev& p, const uint64_t* keys, int32_t* ra
 // that holds the minimum.  kQuadratic: a rank's load grows by the square of the padded length
 // (padded lengths up to 2^21, so a load stays below 2^62); the distance of a load from the
 // smallest one then needs 64 bits and is reduced in two 32-bit rounds, high words first.
-template <bool kQuadratic>
-__device__ void lpt_blocks(const PlanDev& p, const uint64_t* keys, int64_t* lds_load,
+template <class Kc, bool kQuadratic>
+__device__ void lpt_blocks(const PlanDev& p, const typename Kc::Word* keys, int64_t* lds_load,
                            int32_t* rank_out) {
   const int lane = lane_id();
   const int D = p.D, N = p.N;
@@ -572,9 +682,9 @@ __device__ void lpt_blocks(const PlanDev& p, const uint64_t* keys, int64_t* lds_
 
   for (int start = 0; start < N; start += kWave) {
     const int i = start + lane;
-    const uint64_t key = i < N ? keys[i] : ~0ull;
-    const int32_t lp = 0x7fffffff - (int32_t)(key >> 32);
-    const int32_t idx = (int32_t)(key & 0xffffffffu);
+    const typename Kc::Word key = i < N ? keys[i] : Kc::kLast;
+    const int32_t lp = Kc::lp(key);
+    const int32_t idx = Kc::index(key);
     int my_rank = 0;
     const int cnt = min(kWave, N - start);
     for (int s = 0; s < cnt; ++s) {
@@ -613,25 +723,26 @@ __device__ void lpt_blocks(const PlanDev& p, const uint64_t* keys, int64_t* lds_
 
 // rank_out: where rank[i] goes (the workspace array, or an LDS copy of it).  lds_load is only
 // needed beyond 64 ranks or 2^58 load units.
-__device__ void lpt_wave0(const PlanDev& p, const uint64_t* keys, int64_t* lds_load,
+template <class Kc>
+__device__ void lpt_wave0(const PlanDev& p, const typename Kc::Word* keys, int64_t* lds_load,
                           int32_t* rank_out) {
   const int D = p.D;
-  const int64_t max_lp = 0x7fffffffll - (int64_t)(keys[0] >> 32);   // keys are sorted
+  const int64_t max_lp = Kc::lp(keys[0]);   // keys are sorted
   const bool quadratic = p.policy == 2;
   // no load exceeds total / D + the largest cost (the bound of list scheduling)
   const int64_t max_cost = quadratic ? max_lp * max_lp : max_lp;      // <= 2^42, N * it <= 2^62
   const int64_t load_bound = (int64_t)p.N * max_cost / D + max_cost;
   if (D > kWave || load_bound >= (1ll << 58)) {
-    if (quadratic) lpt_blocks<true>(p, keys, lds_load, rank_out);
-    else lpt_blocks<false>(p, keys, lds_load, rank_out);
+    if (quadratic) lpt_blocks<Kc, true>(p, keys, lds_load, rank_out);
+    else lpt_blocks<Kc, false>(p, keys, lds_load, rank_out);
   } else if (quadratic) {
-    lpt_sorted64<true>(p, keys, rank_out);
+    lpt_sorted64<Kc, true>(p, keys, rank_out);
   } else if (load_bound >= (1 << 26) - 1) {
-    lpt_sorted64<false>(p, keys, rank_out);
+    lpt_sorted64<Kc, false>(p, keys, rank_out);
   } else if (D <= 16) {
-    lpt_sorted16(p, keys, rank_out);
+    lpt_sorted16<Kc>(p, keys, rank_out);
   } else {
-    lpt_sorted<kDppWaveShl1>(p, keys, rank_out);
+    lpt_sorted<Kc, kDppWaveShl1>(p, keys, rank_out);
   }
 }
 
@@ -789,7 +900,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const PlanDev p) {
       p.rank[(int32_t)(keys[j] & 0xffffffffu)] = (round & 1) ? D - 1 - k : k;
     }
   } else if (wave_id() == 0) {
-    lpt_wave0(p, keys, lds_load, p.rank);
+    lpt_wave0<Key64>(p, keys, lds_load, p.rank);
   }
   __syncthreads();
 
@@ -1055,28 +1166,32 @@ constexpr int kResMaxRanks = 64;
 struct ResidentLds {
   union {
     uint64_t keys[kResMaxSeqs];        // sort keys, until the ranks are assigned
+    uint32_t keys32[kResMaxSeqs];      // (the narrow packing, when every padded length allows it)
     int64_t row_packed[kResMaxSeqs];   // then: destination row of the pos-th sequence, packed order
   };
   int32_t rank[kResMaxSeqs];           // by sequence
   int32_t seq_ids[kResMaxSeqs];        // packed order -> sequence
   int32_t next_start[kResMaxSeqs];     // packed order: first slot of the following micro-batch
   // what the segment table needs about the pos-th sequence of the packed order
-  int64_t st_src_row[kResMaxSeqs];
+  union {
+    int64_t st_src_row[kResMaxSeqs];
+    int64_t rows_before[kResMaxSeqs];  // by sequence, until the ranks are assigned: real rows of
+                                       // all sequences before it
+  };
   int32_t st_len[kResMaxSeqs];
   int32_t st_m[kResMaxSeqs];
   int32_t st_shard[kResMaxSeqs];
   int32_t st_k[kResMaxSeqs];
   int32_t st_mb[kResMaxSeqs];
   int32_t mb_tmp[kResMaxSeqs + kResMaxRanks];   // per rank: start slot of each micro-batch, then n
+  unsigned long long need[2 * kResMaxGroups];   // rows / sequences every source shard must hold
   union {
-    unsigned long long need[2 * kResMaxGroups];   // rows / sequences every source shard must hold
     struct {
       int64_t sum[kPlanWaves * kResMaxRanks];
       int32_t cnt[kPlanWaves * kResMaxRanks];
     } tab;                                        // per (wavefront, rank) totals of the rank scan
     unsigned long long a2a[kLdsA2a];
   };
-  int64_t group_base[kResMaxGroups];   // rows of all sequences before the group's first one
   int64_t rank_rows[kResMaxRanks];
   int32_t n_seq[kResMaxRanks];
   int32_t seq_base[kResMaxRanks + 1];
@@ -1088,6 +1203,7 @@ struct ResidentLds {
   int64_t load_max, load_min, dst_rows;
   int32_t n_mb_max, mb_table_len, cu_len;
   int invalid, exceeds, bad, bad_invalid;
+  int wide;   // some padded length needs the 64-bit sort keys
 };
 
 // Last r in [0, D) with base[r] + r * stride_one <= x (base ascending, base[0] == 0).
@@ -1110,7 +1226,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_resident_kernel(const PlanD
   const int64_t B = p.B;
   const int i0 = tid * kIters;   // this thread owns sequences i0 .. i0 + kIters - 1
 
-  if (tid == 0) { s.invalid = 0; s.exceeds = 0; s.bad = -1; s.bad_invalid = -1; }
+  if (tid == 0) { s.invalid = 0; s.exceeds = 0; s.bad = -1; s.bad_invalid = -1; s.wide = 0; }
   for (int x = tid; x < 2 * S; x += nt) s.need[x] = 0;
   __syncthreads();
 
@@ -1128,10 +1244,12 @@ __global__ __launch_bounds__(kPlanThreads) void plan_resident_kernel(const PlanD
       bool invalid = false;
       if (L < 1) { invalid = true; L = 1; }
       if (p.seq_row_in && p.seq_row_in[i] < 0) invalid = true;
-      const int64_t per = ((int64_t)L + K - 1) / K;
-      int64_t mm = (int64_t)P * ((per + P - 1) / P);
+      // L, K and P are below 2^31, so the roundings fit unsigned 32-bit division
+      const uint32_t per = ((uint32_t)L + (uint32_t)K - 1u) / (uint32_t)K;
+      int64_t mm = (int64_t)P * (int64_t)((per + (uint32_t)P - 1u) / (uint32_t)P);
       const bool exceeds = mm * K > lp_cap;
       if (exceeds) mm = 1;
+      if (mm * K >= (1 << Key32::kLpBits)) s.wide = 1;
       if (p.policy == 2 && mm * K > kMaxQuadraticLp) invalid = true;
       len[j] = L;
       m[j] = (int32_t)mm;
@@ -1152,9 +1270,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_resident_kernel(const PlanD
     return;
   }
 
-  // ---- source offsets and replica choice ----------------------------------------------------
-  // Groups own contiguous index ranges here (g = floor(i*G/N)), so the segmented scan is one
-  // plain scan of the lengths minus its value at the group's first sequence.
+  // ---- real rows before every sequence (for the source offsets below) ----------------------
   int64_t real_rows = 0;
   int64_t pre[kIters];
   {
@@ -1162,33 +1278,60 @@ __global__ __launch_bounds__(kPlanThreads) void plan_resident_kernel(const PlanD
 #pragma unroll
     for (int j = 0; j < kIters; ++j) {
       pre[j] = acc;
+      if (i0 + j < N) s.rows_before[i0 + j] = acc;
       acc += len[j];
     }
   }
+
+  // ---- sort by (padded length desc, index asc), rank assignment ------------------------------
+  // With every padded length below 2^21 (and N <= 2048) key, index and row offsets fit 32 bits.
+  const bool narrow = s.wide == 0 && kResMaxSeqs <= (1 << Key32::kIndexBits);
+  if (narrow) {
 #pragma unroll
-  for (int j = 0; j < kIters; ++j) {
-    const int i = i0 + j;
-    if (i < N) {
-      const int g = (int)(((int64_t)i * G) / N);
-      const int g_before = i > 0 ? (int)(((int64_t)(i - 1) * G) / N) : -1;
-      if (g != g_before) s.group_base[g] = pre[j];
-    }
+    for (int j = 0; j < kIters; ++j)
+      if (i0 + j < N) s.keys32[i0 + j] = Key32::make((int64_t)m[j] * K, i0 + j);
+    for (int x = N + tid; x < p.n_pow2; x += nt) s.keys32[x] = Key32::kLast;
+    __syncthreads();
+    bitonic_sort_lanes32(s.keys32, p.n_pow2);
+  } else {
+#pragma unroll
+    for (int j = 0; j < kIters; ++j)
+      if (i0 + j < N) s.keys[i0 + j] = Key64::make((int64_t)m[j] * K, i0 + j);
+    for (int x = N + tid; x < p.n_pow2; x += nt) s.keys[x] = Key64::kLast;
+    __syncthreads();
+    bitonic_sort_lanes(s.keys, p.n_pow2);
   }
-  __syncthreads();
+  if (p.policy == 1) {
+    for (int x = tid; x < N; x += nt) {
+      const int round = x / D, k = x - round * D;
+      const int i = narrow ? Key32::index(s.keys32[x]) : Key64::index(s.keys[x]);
+      s.rank[i] = (round & 1) ? D - 1 - k : k;
+    }
+  } else if (wave == 0) {
+    // D <= 64 and N <= 2048: the LDS load table is never used
+    if (narrow) lpt_wave0<Key32>(p, s.keys32, nullptr, s.rank);
+    else lpt_wave0<Key64>(p, s.keys, nullptr, s.rank);
+  }
+
+  // ---- source offsets and replica choice ----------------------------------------------------
+  // Nothing here depends on the ranks: the other wavefronts do it while wavefront 0 walks the
+  // chain above, and wavefront 0 follows for its own sequences.  Groups own contiguous index
+  // ranges (g = floor(i*G/N)), so the segmented scan is the plain scan of the lengths minus its
+  // value at the group's first sequence.  i, G, R and N are small enough for 32-bit products.
   int32_t shard[kIters], seq_k[kIters];
   int64_t src_row[kIters];
 #pragma unroll
   for (int j = 0; j < kIters; ++j) {
-    const int i = i0 + j;
+    const uint32_t i = (uint32_t)(i0 + j);
     shard[j] = 0; seq_k[j] = 0; src_row[j] = 0;
-    if (i < N) {
-      const int64_t g = ((int64_t)i * G) / N;
-      const int64_t first = (g * N + G - 1) / G;            // smallest index of group g
-      const int64_t next_first = ((g + 1) * N + G - 1) / G;
-      const int64_t k = i - first;
-      const int64_t row = p.seq_row_in ? p.seq_row_in[i] : pre[j] - s.group_base[g];
-      const int64_t t = R == 1 ? 0 : (k * R) / (next_first - first);
-      const int sh = (int)(g * R + t);
+    if ((int)i < N) {
+      const uint32_t g = i * (uint32_t)G / (uint32_t)N;
+      const uint32_t first = (g * (uint32_t)N + (uint32_t)G - 1u) / (uint32_t)G;   // smallest index of group g
+      const uint32_t next_first = ((g + 1u) * (uint32_t)N + (uint32_t)G - 1u) / (uint32_t)G;
+      const uint32_t k = i - first;
+      const int64_t row = p.seq_row_in ? p.seq_row_in[i] : pre[j] - s.rows_before[first];
+      const uint32_t t = R == 1 ? 0u : k * (uint32_t)R / (next_first - first);
+      const int sh = (int)(g * (uint32_t)R + t);
       shard[j] = sh;
       seq_k[j] = (int32_t)k;
       src_row[j] = row;
@@ -1202,25 +1345,6 @@ __global__ __launch_bounds__(kPlanThreads) void plan_resident_kernel(const PlanD
     put_summary(p, &p.src_seqs_needed[x], (int64_t)s.need[S + x]);
   }
 
-  // ---- sort by (padded length desc, index asc), rank assignment ------------------------------
-#pragma unroll
-  for (int j = 0; j < kIters; ++j) {
-    const int i = i0 + j;
-    if (i < N) s.keys[i] = ((uint64_t)(0x7fffffffll - (int64_t)m[j] * K) << 32) | (uint32_t)i;
-  }
-  for (int x = N + tid; x < p.n_pow2; x += nt) s.keys[x] = ~0ull;
-  __syncthreads();
-  bitonic_sort_lanes(s.keys, p.n_pow2);
-  if (p.policy == 1) {
-    for (int x = tid; x < N; x += nt) {
-      const int round = x / D, k = x - round * D;
-      s.rank[(int32_t)(s.keys[x] & 0xffffffffu)] = (round & 1) ? D - 1 - k : k;
-    }
-  } else if (wave == 0) {
-    lpt_wave0(p, s.keys, nullptr, s.rank);   // D <= 64 and N <= 2048: the LDS load table is never used
-  }
-  __syncthreads();
-
   // ---- position inside the rank and destination row: scan by rank, in index order -----------
   // Per rank one wavefront scan of (count << 48 | rows); a lane's own sequences are consecutive,
   // so their order inside the lane is index order as well.
@@ -1233,6 +1357,41 @@ __global__ __launch_bounds__(kPlanThreads) void plan_resident_kernel(const PlanD
     dst_row[j] = 0;
   }
   constexpr int64_t kRowsMask = ((int64_t)1 << 48) - 1;
+  if (narrow) {
+    // row offsets stay below N * 2^21 <= 2^32: one 32-bit scan of the rows per rank, and the
+    // position from the lanes' vote
+    for (int r = 0; r < D; ++r) {
+      uint32_t mine = 0;
+      uint64_t vote[kIters];
+      int n_here = 0;
+#pragma unroll
+      for (int j = 0; j < kIters; ++j) {
+        vote[j] = __ballot(rk[j] == r);
+        n_here += __builtin_popcountll(vote[j]);
+        if (rk[j] == r) mine += (uint32_t)(m[j] * halves);
+      }
+      uint32_t tot = 0;
+      if (n_here != 0) {
+        const uint32_t incl = wave_incl_scan_u32(mine);
+        uint32_t ex = incl - mine;
+        int before = 0;
+#pragma unroll
+        for (int j = 0; j < kIters; ++j) before += count_below(vote[j]);
+#pragma unroll
+        for (int j = 0; j < kIters; ++j)
+          if (rk[j] == r) {
+            slot[j] = before++;
+            dst_row[j] = ex;
+            ex += (uint32_t)(m[j] * halves);
+          }
+        tot = (uint32_t)__builtin_amdgcn_readlane((int)incl, kWave - 1);
+      }
+      if (lane == 0) {
+        s.tab.cnt[wave * D + r] = n_here;
+        s.tab.sum[wave * D + r] = tot;
+      }
+    }
+  } else
   for (int r = 0; r < D; ++r) {
     int64_t mine = 0;
 #pragma unroll
