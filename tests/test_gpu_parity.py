@@ -359,6 +359,13 @@ def test_explicit_source_rows_with_gaps(H):
                                 zigzag=1, pad=16, B=20000)),
     ("loads_beyond_32_bits", dict(L=[1 << 30] * 5 + [(1 << 30) - 12345] * 6, dp=3, sp=1, B=(1 << 31) - 1)),
     ("equal_lengths_round_robin", dict(L=[64] * 96, dp=8, sp=2, B=1 << 20)),
+    # sort keys: one padded length of 2^21 or more switches the whole batch to the 64-bit packing
+    ("wide_keys_1500_sequences", dict(L=[(i * 7919) % 5000 + 1 for i in range(1500)] +
+                                      [3 << 20, 1 << 21, (1 << 21) - 1], dp=24, sp=2, zigzag=1, B=1 << 30)),
+    ("narrow_keys_at_their_limit", dict(L=[(1 << 21) - 1 - (i % 3) for i in range(2048)], dp=1, sp=1,
+                                        B=1 << 30)),
+    ("narrow_keys_at_their_limit_dp_9", dict(L=[(1 << 21) - 1 - i for i in range(70)] +
+                                             [(i * 13) % 999 + 1 for i in range(500)], dp=9, sp=1)),
     ("budget_exactly_one_sequence", dict(L=[16] * 40, dp=2, sp=2, zigzag=1, B=16)),
     ("sp_64_zigzag_128_chunks", dict(L=[(i * 37) % 900 + 1 for i in range(120)], G=3, dp=3, sp=64,
                                      zigzag=1, pad=2, B=40000)),
