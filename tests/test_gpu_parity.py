@@ -386,6 +386,40 @@ def test_plan_edge_cases(H, desc, kw):
     H.B.plan_destroy(plan)
 
 
+def test_more_plans_alive_than_summary_mailboxes(H):
+    """The library hands a plan's totals to the host through one of 64 pinned mailboxes; plans
+    beyond that read their totals with a copy.  All 80 plans built here are alive at once, every
+    one is compared with the oracle, in an order that differs from the order they were built in."""
+    works = [synth.custom_workload([(i * (7 + k)) % 97 + 1 for i in range(40 + 3 * k)], n_groups=2,
+                                   dp=1 + k % 5, sp=1 + k % 3, zigzag=k % 2, pad_multiple=1 + k % 4,
+                                   mb_token_budget=4096) for k in range(80)]
+    plans = [H.build_plan(w) for w in works]
+    for k in list(range(79, -1, -2)) + list(range(0, 80, 2)):
+        assert_plan_equal(H.plan_result(plans[k]), oracle_plan(works[k]))
+    for plan in plans:
+        H.B.plan_destroy(plan)
+
+
+def test_one_workspace_reused_by_batches_of_different_shape(H):
+    """Plans built one after the other in the SAME workspace (the earlier plan destroyed first):
+    nothing of an earlier batch may show in a later one, whichever kernel serves it."""
+    import torch
+    shapes = [dict(n=1500, dp=24, sp=2, zz=1), dict(n=40, dp=3, sp=1, zz=0), dict(n=700, dp=16, sp=4, zz=1),
+              dict(n=2048, dp=64, sp=1, zz=0), dict(n=2300, dp=8, sp=2, zz=1), dict(n=64, dp=16, sp=2, zz=1)]
+    works = [synth.custom_workload([(i * 7919 + 13 * k) % (3000 // (k + 1)) + 1 for i in range(sh["n"])],
+                                   n_groups=4, dp=sh["dp"], sp=sh["sp"], zigzag=sh["zz"],
+                                   mb_token_budget=1 << 16) for k, sh in enumerate(shapes)]
+    layouts = [H.layouts_of(w, False, None, 0, 0) for w in works]
+    size = max(H.B.plan_workspace_bytes(w.n_seqs, src, dst) for w, (src, dst, _) in zip(works, layouts))
+    ws = torch.empty(size, dtype=torch.uint8, device="cuda")
+    for rounds in range(2):
+        for w, (src, dst, keep) in zip(works, layouts):
+            lengths = H.to_dev(w.lengths.astype(np.int32))
+            plan = H.B.plan_build(lengths, w.n_seqs, src, dst, ws)
+            assert_plan_equal(H.plan_result(plan), oracle_plan(w))
+            H.B.plan_destroy(plan)
+
+
 @pytest.mark.parametrize("name,scale", [("tiny", 1.0), ("mid", 1.0), ("agentic", 1.0), ("heavy", 1.0),
                                         ("longctx", 1.0), ("mid", 0.02)])
 def test_snake_deal_policy(H, name, scale):
