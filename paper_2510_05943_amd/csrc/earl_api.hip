@@ -757,7 +757,10 @@ int32_t static_scratch(unsigned char** out) {
 // direct kernel as a whole: below it the tile-code pass costs more than it saves.
 constexpr int64_t kDirectMaxCoarseBytes = (int64_t)64 << 20;
 constexpr int64_t kMaxLaunchTiles = 0x7fffffffll;
-constexpr int kJobShiftHost = 12;   // bytes of a direct job, as in the kernel
+constexpr int kJobShiftHost = 12;   // log2 of the bytes of a direct job: 4 KiB ...
+constexpr int kJobShiftMin = 10;    // ... down to 1 KiB in small launches (forward direction)
+constexpr int64_t kSmallLaunchBytes = (int64_t)8 << 20;   // direct records of a "small launch"
+constexpr int64_t kSmallLaunchJobs = 1024;                // jobs a small launch is cut into, about
 
 struct RecordOrder {
   int n_direct = 0;
@@ -780,6 +783,27 @@ bool order_records(BlockBuilder& b, const TileRec* protos, int F, int n_dst, Byt
       coarse_bytes += bytes_of(f, q);
   }
   const bool all_direct = coarse_bytes <= kDirectMaxCoarseBytes;
+  // Bytes of a direct job.  A launch of a few hundred jobs leaves every wavefront alone on its
+  // compute unit, where it issues an instruction every six cycles or so, and the call waits for
+  // the longest job: such launches use jobs of 1 or 2 KiB (more wavefronts, each with less to
+  // do), and their fields with rows of one or two bytes, whose 4 KiB jobs would span the most
+  // segments, jobs of at most 1024 rows.  (On launches that fill the chip smaller jobs measured
+  // 5-8 % slower: every job pays the searches again.)
+  int64_t direct_bytes = 0, direct_recs = 0;
+  for (int f = 0; f < F; ++f) {
+    const TileRec& proto = protos[f];
+    if (!(all_direct || proto.tile_shift == kFineTileShift || proto.kind == kFieldLinear)) continue;
+    for (int q = 0; q < n_dst && direct_bytes <= kSmallLaunchBytes; ++q, ++direct_recs)
+      direct_bytes += bytes_of(f, q);
+  }
+  const bool small_launch = direct_bytes <= kSmallLaunchBytes;
+  int small_job_shift = kJobShiftHost;
+  if (small_launch) {
+    small_job_shift = kJobShiftMin;
+    while (small_job_shift < kJobShiftHost &&
+           (direct_bytes >> small_job_shift) + direct_recs > kSmallLaunchJobs)
+      ++small_job_shift;
+  }
   int64_t* ts = b.tile_start();
   TileRec* recs = b.recs();
   RecordOrder o;
@@ -790,7 +814,12 @@ bool order_records(BlockBuilder& b, const TileRec* protos, int F, int n_dst, Byt
       const TileRec& proto = protos[f];
       const bool direct = all_direct || proto.tile_shift == kFineTileShift || proto.kind == kFieldLinear;
       if (direct != (pass == 0)) continue;
-      const int shift = direct ? kJobShiftHost : kTileShift;
+      int shift = kTileShift;
+      if (direct) {
+        shift = small_job_shift;
+        if (small_launch && proto.kind != kFieldLinear && proto.row_bytes <= 2)
+          shift = proto.row_bytes == 1 ? kJobShiftMin : (shift < kJobShiftMin + 1 ? shift : kJobShiftMin + 1);
+      }
       for (int q = 0; q < n_dst; ++q) {
         TileRec& r = recs[n_rec];
         r = proto;

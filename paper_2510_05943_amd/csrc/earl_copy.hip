@@ -558,11 +558,13 @@ __global__ __launch_bounds__(kCopyThreads, 8) void relayout_direct_kernel(const 
   const int lane = threadIdx.x;
   const int64_t job = blockIdx.x;
   const TileRec rec = record_of_job(pv, job);
-  const int64_t lo0 = (job - rec.tile_first) << kJobShift;   // first byte of the job in its shard
+  // a job is 4 KiB of the shard, or 1 or 2 KiB where the host chose that for the record (rows of
+  // one or two bytes, whose jobs would otherwise span many segments)
+  const int64_t lo0 = (job - rec.tile_first) << rec.tile_shift;   // first byte of the job in its shard
   if (lo0 >= rec.end_bytes) return;   // behind the shard's end (a grid sized by capacities)
   u8* const dst = static_cast<u8*>(rec.dst) + lo0;
-  const int32_t job_len =
-      rec.end_bytes - lo0 < kJobBytes ? (int32_t)(rec.end_bytes - lo0) : kJobBytes;
+  const int32_t job_bytes = 1 << rec.tile_shift;
+  const int32_t job_len = rec.end_bytes - lo0 < job_bytes ? (int32_t)(rec.end_bytes - lo0) : job_bytes;
 
   if (rec.kind == kFieldLinear) {
     const u8* src = static_cast<const u8*>(pv.ptrs[rec.src_ptr_index]) + lo0;
