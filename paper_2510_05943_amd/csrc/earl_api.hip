@@ -1295,6 +1295,23 @@ int32_t earl_dispatch_inverse(earl_plan* p, const earl_field* fields, int32_t n_
     if (w >= kVecBytes && coarse_bytes <= kDirectMaxCoarseBytes) coarse_bytes += p->hdr.total_real_rows * w;
   }
   const bool all_direct = coarse_bytes <= kDirectMaxCoarseBytes;
+  // job size of the direct records, as in the forward direction (order_records)
+  int64_t direct_bytes = 0, direct_recs = 0;
+  for (int f = 0; f < n_fields && direct_bytes <= kSmallLaunchBytes; ++f) {
+    const int64_t w = (int64_t)fields[f].scalar_bytes * fields[f].width;
+    if (all_direct || w < kVecBytes) {
+      direct_bytes += p->hdr.total_real_rows * w;
+      ++direct_recs;
+    }
+  }
+  const bool small_launch = direct_bytes <= kSmallLaunchBytes;
+  int small_job_shift = kJobShiftHost;
+  if (small_launch) {
+    small_job_shift = kJobShiftMin;
+    while (small_job_shift < kJobShiftHost &&
+           (direct_bytes >> small_job_shift) + direct_recs > kSmallLaunchJobs)
+      ++small_job_shift;
+  }
   RecordOrder order;
   int n_rec = 0;
   for (int pass = 0; pass < 2; ++pass) {
@@ -1304,7 +1321,12 @@ int32_t earl_dispatch_inverse(earl_plan* p, const earl_field* fields, int32_t n_
       const int64_t w = (int64_t)uf.scalar_bytes * uf.width;
       const bool direct = all_direct || w < kVecBytes;
       if (direct != (pass == 0)) continue;
-      const int shift = direct ? kJobShiftHost : kTileShift;
+      int shift = kTileShift;
+      if (direct) {
+        shift = small_job_shift;
+        if (small_launch && w <= 2)
+          shift = w == 1 ? kJobShiftMin : (shift < kJobShiftMin + 1 ? shift : kJobShiftMin + 1);
+      }
       const uint32_t pi = (uint32_t)f * (uint32_t)(S + n_dst);
       TileRec& r = recs[n_rec];
       r.kind = kFieldCopy;

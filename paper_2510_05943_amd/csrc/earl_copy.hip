@@ -1116,10 +1116,10 @@ __global__ __launch_bounds__(kCopyThreads, 8) void inverse_direct_kernel(const I
   const int lane = threadIdx.x;
   const int64_t job = blockIdx.x;
   const TileRec rec = record_of_job(pv, job);
-  const int64_t lo0 = (job - rec.tile_first) << kJobShift;   // first stream byte of the job
+  const int64_t lo0 = (job - rec.tile_first) << rec.tile_shift;   // first stream byte of the job
   if (lo0 >= rec.end_bytes) return;
-  const int32_t job_len =
-      rec.end_bytes - lo0 < kJobBytes ? (int32_t)(rec.end_bytes - lo0) : kJobBytes;
+  const int32_t job_bytes = 1 << rec.tile_shift;   // 4 KiB, or the host's smaller choice
+  const int32_t job_len = rec.end_bytes - lo0 < job_bytes ? (int32_t)(rec.end_bytes - lo0) : job_bytes;
   const int64_t w = rec.row_bytes;
   // the field's buffers in both layouts, one pointer per lane where there are at most 64
   const bool src_in_lanes = a.c.n_src_shards <= kWave, dst_in_lanes = a.n_dst_shards <= kWave;
