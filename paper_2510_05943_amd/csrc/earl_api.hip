@@ -758,13 +758,13 @@ int32_t static_scratch(unsigned char** out) {
 constexpr int64_t kDirectMaxCoarseBytes = (int64_t)64 << 20;
 constexpr int64_t kMaxLaunchTiles = 0x7fffffffll;
 constexpr int kJobShiftHost = 12;   // log2 of the bytes of a direct job: 4 KiB ...
-constexpr int kJobShiftMin = 10;    // ... down to 1 KiB in small launches (forward direction)
+constexpr int kJobShiftMin = 10;    // ... down to 1 KiB in small launches (both directions)
 constexpr int64_t kSmallLaunchBytes = (int64_t)8 << 20;   // direct records of a "small launch"
 constexpr int64_t kSmallLaunchJobs = 1024;                // jobs a small launch is cut into, about
 
 struct RecordOrder {
   int n_direct = 0;
-  int64_t jobs = 0;    // 4 KiB jobs of the direct records
+  int64_t jobs = 0;    // jobs of the direct records (4 KiB each, less in small launches)
   int64_t tiles = 0;   // tile codes of the other records
 };
 
