@@ -149,7 +149,7 @@ static_assert(sizeof(TileRec) == 64, "TileRec layout");
 
 // Parameter block of one call, in device memory: header, tile_start, recs[n_recs], pointer
 // table.  The first n_direct records are decoded inside the copy kernel (their tile_first counts
-// 4 KiB jobs), the others go through tile codes; tile_start holds tile_first of the direct
+// jobs of 1 << tile_shift bytes), the others go through tile codes; tile_start holds tile_first of the direct
 // records and their total (n_direct + 1 entries), then the same for the coded records.
 struct DispatchDev {
   int32_t n_recs;
@@ -171,7 +171,7 @@ struct CopyArgs {
   const DispatchDev* params;
   const SegRec* segs;
   const int32_t* seg_src_seq;
-  int64_t n_direct_jobs; // 4 KiB jobs of the records that are decoded inside the copy kernel
+  int64_t n_direct_jobs; // jobs of the records that are decoded inside the copy kernel
   // the parts of the parameter block those records use, so that the kernel need not read the
   // block's header first
   const int64_t* direct_tile_start;
