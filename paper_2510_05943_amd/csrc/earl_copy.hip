@@ -678,52 +678,47 @@ __global__ __launch_bounds__(kCopyThreads, 8) void relayout_direct_kernel(const 
   const uint64_t pad = rec.pad_scalar;
 
   // ---- every vector of the job's four sub-tiles finds its segment ---------------------------
+  // One pass over the job's segments; each is handed out once (v_readlane) and every sub-tile it
+  // overlaps classifies its vectors against it.
   int mode[kJobSubTiles], my_k[kJobSubTiles], k_first[kJobSubTiles], k_last[kJobSubTiles];
   uint64_t my_src[kJobSubTiles];
-  int k0 = 0;   // first window segment that ends behind the current sub-tile's first byte
 #pragma unroll
   for (int t = 0; t < kJobSubTiles; ++t) {
-    const int32_t sub_lo = t * (kCopyThreads * kVecBytes);
-    const int32_t sub_hi = sub_lo + kCopyThreads * kVecBytes < job_len
-                               ? sub_lo + kCopyThreads * kVecBytes : job_len;
-    const int32_t o = sub_lo + lane * kVecBytes;
-    const int32_t o_end = o + kVecBytes;
-    mode[t] = o < job_len ? kVecPending : kVecNone;
+    mode[t] = (t * kCopyThreads + lane) * kVecBytes < job_len ? kVecPending : kVecNone;
     my_k[t] = 0;
     my_src[t] = 0;
     k_first[t] = 0;
     k_last[t] = -1;
-    if (sub_lo >= job_len) continue;
-    for (int k = k0; k < n_win; ++k) {
-      const int32_t dl = __builtin_amdgcn_readlane(win.lo, k);
-      if (dl >= sub_hi) break;
-      const int32_t dh = __builtin_amdgcn_readlane(win.hi, k);
-      if (dh <= sub_lo) { k0 = k + 1; continue; }
-      const int32_t drh = __builtin_amdgcn_readlane(win.real_hi, k);
-      const uint64_t sj = readlane_u64(win.src, k);
-      const int32_t pj = __builtin_amdgcn_readlane(win.pos, k);
+  }
+  for (int k = 0; k < n_win; ++k) {
+    const int32_t dl = __builtin_amdgcn_readlane(win.lo, k);
+    const int32_t dh = __builtin_amdgcn_readlane(win.hi, k);
+    const int32_t drh = __builtin_amdgcn_readlane(win.real_hi, k);
+    const uint64_t sj = readlane_u64(win.src, k);
+    const int32_t pj = __builtin_amdgcn_readlane(win.pos, k);
+#pragma unroll
+    for (int t = 0; t < kJobSubTiles; ++t) {
+      const int32_t sub_lo = t * (kCopyThreads * kVecBytes);
+      const int32_t sub_hi = sub_lo + kCopyThreads * kVecBytes < job_len
+                                 ? sub_lo + kCopyThreads * kVecBytes : job_len;
+      if (sub_lo >= job_len || dl >= sub_hi || dh <= sub_lo) continue;   // uniform
+      const int32_t o = sub_lo + lane * kVecBytes;
+      const int32_t o_end = o + kVecBytes;
       if (k_last[t] < 0) k_first[t] = k;
       k_last[t] = k;
-      if (mode[t] == kVecPending && o < dh && o_end > dl) {
-        // the first segment this vector overlaps
-        my_k[t] = k;
-        if (o_end > window_hi || o_end > job_len) {
-          // stays pending: it needs segments the window does not hold, or the shard ends inside
-          // it (one vector per shard at most): the per-lane path at the end takes it
-        } else if (o < dl || o_end > dh) {
-          mode[t] = kVecSlow;                      // crosses a segment edge
-        } else if (is_pos) {
-          mode[t] = kVecIota;
-          my_src[t] = (uint32_t)(pj + (o >> 2));
-        } else if (o_end <= drh) {
-          mode[t] = per_seq ? kVecSplat : kVecCopy;
-          my_src[t] = per_seq ? sj : sj + (uint64_t)(int64_t)o;
-        } else if (o >= drh) {
-          mode[t] = kVecPad;
-        } else {
-          mode[t] = kVecSlow;                      // crosses the real/padding edge
-        }
-      }
+      // the first segment this vector overlaps decides what becomes of it (selects, no branches:
+      // as nested branches every case cost its own pair of exec-mask instructions)
+      const bool first_hit = mode[t] == kVecPending && o < dh && o_end > dl;
+      // stays pending: it needs segments the window does not hold, or the shard ends inside it
+      // (one vector per shard at most): the per-lane path at the end takes it
+      const bool stays = o_end > window_hi || o_end > job_len;
+      const bool crosses = o < dl || o_end > dh || (!is_pos && o < drh && o_end > drh);
+      const int whole = is_pos ? kVecIota : (o >= drh ? kVecPad : (per_seq ? kVecSplat : kVecCopy));
+      const uint64_t from = is_pos ? (uint64_t)(uint32_t)(pj + (o >> 2))
+                                   : (per_seq ? sj : sj + (uint64_t)(int64_t)o);
+      mode[t] = first_hit ? (stays ? kVecPending : (crosses ? kVecSlow : whole)) : mode[t];
+      my_k[t] = first_hit ? k : my_k[t];
+      my_src[t] = first_hit ? from : my_src[t];
     }
   }
 
