@@ -58,7 +58,7 @@ size_t param_block_bytes(int n_fields, int n_src, int n_dst) {
 // Byte offsets of every array inside the workspace.
 struct Layout {
   size_t hdr, shard_rows, src_rows_needed, src_seqs_needed, n_seq, n_mb, rank_load, a2a, summary_end;
-  size_t seq_group, seq_shard, seq_k, seq_row, m, rank, slot, mb, dst_row;
+  size_t seq_group, seq_shard, seq_k, seq_row, m, rank, slot, mb, dst_row, seq_pre;
   size_t seq_ids, next_start, mb_tmp, mb_seq_start, mb_row_start, cu_seqlens;
   size_t rank_seq_base, rank_mbt_base, rank_cu_base;
   size_t segs, seg_dst_shard, seg_src_seq, seg_mb;
@@ -99,6 +99,7 @@ Layout make_layout(const Dims& d) {
   l.slot = take(4 * N);
   l.mb = take(4 * N);
   l.dst_row = take(8 * N);
+  l.seq_pre = take(8 * (N + 1));
   l.seq_ids = take(4 * N);
   l.next_start = take(4 * N);
   l.mb_tmp = take(4 * (N + D));
@@ -257,6 +258,7 @@ struct earl_plan {
   int32_t status;
   bool inverse_ready;
   bool source_order;                    // the reverse direction walks the segments by source position
+  bool has_seq_pre = false;             // the plan kernel wrote seq_pre (see launch_plan)
   void* inverse_prefix_done;            // hipEvent_t recorded behind the prefix kernel
   hipStream_t inverse_stream;           // stream that kernel ran on
   void* ev_before;
@@ -572,6 +574,7 @@ int32_t earl_plan_build(const int32_t* lengths_dev, int32_t n_seqs, const earl_s
   v.slot = reinterpret_cast<int32_t*>(w + l.slot);
   v.mb = reinterpret_cast<int32_t*>(w + l.mb);
   v.dst_row = reinterpret_cast<int64_t*>(w + l.dst_row);
+  v.seq_pre = reinterpret_cast<int64_t*>(w + l.seq_pre);
   v.seq_ids = reinterpret_cast<int32_t*>(w + l.seq_ids);
   v.next_start = reinterpret_cast<int32_t*>(w + l.next_start);
   v.mb_tmp = reinterpret_cast<int32_t*>(w + l.mb_tmp);
@@ -590,7 +593,7 @@ int32_t earl_plan_build(const int32_t* lengths_dev, int32_t n_seqs, const earl_s
   v.lab_sum = reinterpret_cast<int64_t*>(w + l.lab_sum);
   v.lab_cnt = reinterpret_cast<int32_t*>(w + l.lab_cnt);
 
-  launch_plan(v, p->stream);
+  p->has_seq_pre = launch_plan(v, p->stream);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) {
     if (p->mailbox >= 0) release_mailbox(p->mailbox, true);   // nothing was launched
@@ -1368,12 +1371,15 @@ int32_t earl_dispatch_inverse(earl_plan* p, const earl_field* fields, int32_t n_
   if (!p->inverse_ready) {
     hipEvent_t ev = nullptr;
     HIP_TRY(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
+    // (in source order the prefix has a closed form, given the plan kernel's scan of the lengths)
+    const bool closed_form = p->source_order && p->has_seq_pre;
     if (p->source_order)
       launch_source_order(p->dev.segs, p->dev.seg_dst_shard, p->dev.seg_src_seq,
                           reinterpret_cast<SegRec*>(p->ws + p->l.segs_src),
                           reinterpret_cast<int32_t*>(p->ws + p->l.seg_dst_shard_src),
-                          p->hdr.n_segments, p->d.N, p->d.G, p->d.R, p->d.K, stream);
-    launch_real_prefix(segs, prefix, p->hdr.n_segments, stream);
+                          p->hdr.n_segments, p->d.N, p->d.G, p->d.R, p->d.K,
+                          closed_form ? p->dev.seq_pre : nullptr, prefix, stream);
+    if (!closed_form) launch_real_prefix(segs, prefix, p->hdr.n_segments, stream);
     hipError_t e = hipEventRecord(ev, stream);
     if (e != hipSuccess) {
       (void)hipEventDestroy(ev);

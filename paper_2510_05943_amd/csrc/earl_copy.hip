@@ -966,11 +966,16 @@ struct InverseArgs {
 // i*K + kappa.  For the packed source layout with contiguous groups that is ascending (shard
 // buffer, row).  i follows from the segment's source shard (its group's first sequence) and
 // its sequence's rank inside the group; kappa from the position of its first row.
+// In that order the real rows in front of an entry need no scan over the table: they are the
+// rows of all earlier sequences (seq_pre, if the plan kernel left it) plus the sequence's own
+// rows in front of the chunk, min(length, position of the chunk's first row).
 __global__ __launch_bounds__(256) void source_order_kernel(const SegRec* segs,
                                                            const int32_t* seg_dst_shard,
                                                            const int32_t* seg_src_seq, SegRec* out,
                                                            int32_t* out_dst_shard, int n_seg, int N,
-                                                           int G, int R, int K) {
+                                                           int G, int R, int K,
+                                                           const int64_t* seq_pre,
+                                                           int64_t* prefix_out) {
   const int e = blockIdx.x * blockDim.x + threadIdx.x;
   if (e >= n_seg) return;
   const SegRec r = segs[e];
@@ -980,6 +985,11 @@ __global__ __launch_bounds__(256) void source_order_kernel(const SegRec* segs,
   const int kappa = r.pos0 / r.n_rows;
   out[i * K + kappa] = r;
   out_dst_shard[i * K + kappa] = seg_dst_shard[e];
+  if (seq_pre) {
+    const int64_t before = seq_pre[i], length = seq_pre[i + 1] - before;
+    prefix_out[i * K + kappa] = before + (r.pos0 < length ? r.pos0 : length);
+    if (e == 0) prefix_out[n_seg] = seq_pre[N];
+  }
 }
 
 // Inverse tile codes: a = training-layout pointer of the tile's first byte (0 = generic tile,
@@ -1355,10 +1365,12 @@ void launch_real_prefix(const SegRec* segs, int64_t* prefix, int n_seg, hipStrea
 
 void launch_source_order(const SegRec* segs, const int32_t* seg_dst_shard,
                          const int32_t* seg_src_seq, SegRec* out, int32_t* out_dst_shard, int n_seg,
-                         int N, int G, int R, int K, hipStream_t stream) {
+                         int N, int G, int R, int K, const int64_t* seq_pre, int64_t* prefix_out,
+                         hipStream_t stream) {
   if (n_seg <= 0) return;
   hipLaunchKernelGGL(source_order_kernel, dim3((unsigned)((n_seg + 255) / 256)), dim3(256), 0, stream,
-                     segs, seg_dst_shard, seg_src_seq, out, out_dst_shard, n_seg, N, G, R, K);
+                     segs, seg_dst_shard, seg_src_seq, out, out_dst_shard, n_seg, N, G, R, K, seq_pre,
+                     prefix_out);
 }
 
 void launch_copy_inverse(const CopyArgs& a, const int64_t* seg_real_prefix,

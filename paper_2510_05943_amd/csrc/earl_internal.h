@@ -101,6 +101,8 @@ struct PlanDev {
   int32_t* slot;                 // [N]
   int32_t* mb;                   // [N]
   int64_t* dst_row;              // [N]
+  int64_t* seq_pre;              // [N+1] real rows of all sequences before i (written by the kernel
+                                 // that keeps the batch in LDS only; entry N is the total)
   // per rank / packed order
   int32_t* seq_ids;              // [N]
   int32_t* next_start;           // [N] scratch: first slot of the following micro-batch
@@ -183,7 +185,8 @@ struct CopyArgs {
   const int32_t* seg_mb;  // micro-batch of every segment (fields that ask for non-zero counts)
 };
 
-void launch_plan(const PlanDev& p, hipStream_t stream);
+// Returns true if the kernel that keeps the batch in LDS took the plan (it also writes seq_pre).
+bool launch_plan(const PlanDev& p, hipStream_t stream);
 // tile_codes: 16 bytes of scratch per tile
 constexpr size_t kTileCodeBytes = 16;
 void launch_tile_codes(const CopyArgs& a, void* tile_codes, hipStream_t stream);
@@ -198,9 +201,12 @@ void launch_param_chunks(void* dev_dst, const unsigned char* host_block, size_t 
 // earl_dispatch_async: completes the records of a parameter block from the plan in device memory
 void launch_async_resolve(DispatchDev* params, const PlanDev& plan, hipStream_t stream);
 void launch_real_prefix(const SegRec* segs, int64_t* prefix, int n_seg, hipStream_t stream);
+// seq_pre/prefix_out: if seq_pre is given, also writes the prefix of real rows over the
+// source-ordered table (n_seg + 1 entries), which has a closed form there
 void launch_source_order(const SegRec* segs, const int32_t* seg_dst_shard,
                          const int32_t* seg_src_seq, SegRec* out, int32_t* out_dst_shard, int n_seg,
-                         int N, int G, int R, int K, hipStream_t stream);
+                         int N, int G, int R, int K, const int64_t* seq_pre, int64_t* prefix_out,
+                         hipStream_t stream);
 void launch_copy_inverse(const CopyArgs& a, const int64_t* seg_real_prefix,
                          const int32_t* seg_dst_shard, int n_seg, int n_dst_shards,
                          void* tile_codes, hipEvent_t before, hipEvent_t after,

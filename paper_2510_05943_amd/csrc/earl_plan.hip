@@ -1278,9 +1278,13 @@ __global__ __launch_bounds__(kPlanThreads) void plan_resident_kernel(const PlanD
 #pragma unroll
     for (int j = 0; j < kIters; ++j) {
       pre[j] = acc;
-      if (i0 + j < N) s.rows_before[i0 + j] = acc;
+      if (i0 + j < N) {
+        s.rows_before[i0 + j] = acc;
+        p.seq_pre[i0 + j] = acc;
+      }
       acc += len[j];
     }
+    if (tid == 0) p.seq_pre[N] = real_rows;
   }
 
   // ---- sort by (padded length desc, index asc), rank assignment ------------------------------
@@ -1676,7 +1680,7 @@ bool fits_resident(const PlanDev& p) {
 
 }  // namespace
 
-void launch_plan(const PlanDev& p, hipStream_t stream) {
+bool launch_plan(const PlanDev& p, hipStream_t stream) {
   // EARL_PLAN_KERNEL=general forces the general kernel (the parity tests run both on the same
   // inputs this way).
   const char* force = std::getenv("EARL_PLAN_KERNEL");
@@ -1689,9 +1693,10 @@ void launch_plan(const PlanDev& p, hipStream_t stream) {
       hipLaunchKernelGGL(plan_resident_kernel<1>, dim3(1), dim3(nt), 0, stream, p);
     else
       hipLaunchKernelGGL(plan_resident_kernel<2>, dim3(1), dim3(nt), 0, stream, p);
-    return;
+    return true;
   }
   hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, stream, p);
+  return false;
 }
 
 }  // namespace earl

@@ -232,6 +232,21 @@ def _dispatch_and_inverse_equal_oracle(H, w):
     H.B.plan_destroy(plan)
 
 
+@pytest.mark.parametrize("n,dp,sp,zigzag,groups,rep", [(300, 3, 2, 1, 4, 1), (2500, 8, 2, 1, 8, 1),
+                                                      (700, 5, 4, 0, 2, 3)])
+def test_both_directions_behind_the_general_plan_kernel(H, monkeypatch, n, dp, sp, zigzag, groups, rep):
+    """The reverse direction takes the prefix of real rows from the plan kernel's scan of the
+    lengths when the kernel that keeps the batch in LDS built the plan, and from a scan over the
+    segment table otherwise: this is the second case (forced for the small batches, natural for the
+    one beyond 2048 sequences), compared with the oracle like the first."""
+    monkeypatch.setenv("EARL_PLAN_KERNEL", "general")
+    w = synth.custom_workload([(i * 7919) % 211 + 1 for i in range(n)], n_groups=groups, replication=rep,
+                              dp=dp, sp=sp, zigzag=zigzag, pad_multiple=2, mb_token_budget=4096,
+                              fields=(synth.F_ID, synth.F_MASK, synth.bytes_field("w40", 8, 5, 0x0102030405060708)),
+                              seed=n)
+    _dispatch_and_inverse_equal_oracle(H, w)
+
+
 DIRECT_KERNEL_CASES = [
     # more segments in a 4 KiB job than the 64 a wavefront keeps: single-row sequences cut into
     # many chunks, one-byte and two-byte rows (the per-lane path beyond the window)
