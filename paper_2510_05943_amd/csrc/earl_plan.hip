@@ -409,15 +409,19 @@ struct Key64 {   // any padded length below 2^31, any index
   static __device__ __forceinline__ int32_t lp(Word k) { return 0x7fffffff - (int32_t)(k >> 32); }
   static __device__ __forceinline__ int32_t index(Word k) { return (int32_t)(k & 0xffffffffu); }
 };
-struct Key32 {   // padded lengths below 2^21 and indices below 2^11
+template <int kIndexBitsT>   // indices below 2^kIndexBitsT, padded lengths below 2^(32 - kIndexBitsT)
+struct Key32 {
   typedef uint32_t Word;
   static constexpr Word kLast = ~0u;
-  static constexpr int kLpBits = 21, kIndexBits = 11;
+  static constexpr int kIndexBits = kIndexBitsT, kLpBits = 32 - kIndexBitsT;
+  static constexpr int32_t kLpMax = (int32_t)((1u << kLpBits) - 1u);
   static __device__ __forceinline__ Word make(int64_t lp, int i) {
-    return ((uint32_t)(0x1fffff - (int32_t)lp) << kIndexBits) | (uint32_t)i;
+    return ((uint32_t)(kLpMax - (int32_t)lp) << kIndexBits) | (uint32_t)i;
   }
-  static __device__ __forceinline__ int32_t lp(Word k) { return 0x1fffff - (int32_t)(k >> kIndexBits); }
-  static __device__ __forceinline__ int32_t index(Word k) { return (int32_t)(k & 0x7ffu); }
+  static __device__ __forceinline__ int32_t lp(Word k) { return kLpMax - (int32_t)(k >> kIndexBits); }
+  static __device__ __forceinline__ int32_t index(Word k) {
+    return (int32_t)(k & ((1u << kIndexBits) - 1u));
+  }
 };
 
 // ---------------------------------------------------------------------------------------
@@ -1141,7 +1145,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const PlanDev p) {
 }
 
 // ---------------------------------------------------------------------------------------
-// The same plan for batches of up to 2048 sequences on up to 64 ranks (every workload the
+// The same plan for batches of up to 4096 sequences on up to 64 ranks (every workload the
 // paper's setting produces: Section 3.1 trains with a few hundred to a few thousand episodes
 // per step), with another data flow: nothing is read back from global memory.
 //
@@ -1159,31 +1163,34 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const PlanDev p) {
 // barriers cost nothing).  Rules, tie-breaks and outputs are those of plan_kernel, which stays
 // the general path (more sequences, ranks or groups, explicit group labels).
 // ---------------------------------------------------------------------------------------
-constexpr int kResMaxSeqs = 2048;
-constexpr int kResMaxGroups = 256;   // source groups, and source shards
+constexpr int kResStagedSeqs = 2048;   // up to here the segment table's inputs are staged in LDS
+constexpr int kResMaxSeqs = 4096;      // up to here the rest of the batch still fits
+constexpr int kResMaxGroups = 256;     // source groups, and source shards
 constexpr int kResMaxRanks = 64;
 
+// kCap: sequences the arrays hold.  kStaged: a packed-order copy of what the segment table needs
+// about every sequence is kept in LDS (7 arrays; with 4096 sequences they do not fit, and the
+// segment table reads the per-sequence outputs back from the workspace instead).
+template <int kCap, bool kStaged>
 struct ResidentLds {
+  static constexpr int kStage = kStaged ? kCap : 1;
   union {
-    uint64_t keys[kResMaxSeqs];        // sort keys, until the ranks are assigned
-    uint32_t keys32[kResMaxSeqs];      // (the narrow packing, when every padded length allows it)
-    int64_t row_packed[kResMaxSeqs];   // then: destination row of the pos-th sequence, packed order
+    uint64_t keys[kCap];        // sort keys, until the ranks are assigned
+    uint32_t keys32[kCap];      // (the narrow packing, when every padded length allows it)
+    int64_t row_packed[kCap];   // then: destination row of the pos-th sequence, packed order
   };
-  int32_t rank[kResMaxSeqs];           // by sequence
-  int32_t seq_ids[kResMaxSeqs];        // packed order -> sequence
-  int32_t next_start[kResMaxSeqs];     // packed order: first slot of the following micro-batch
+  int32_t rank[kCap];           // by sequence
+  int32_t seq_ids[kCap];        // packed order -> sequence
+  int32_t next_start[kCap];     // packed order: first slot of the following micro-batch
+  int64_t rows_before[kCap];    // by sequence: real rows of all sequences before it
   // what the segment table needs about the pos-th sequence of the packed order
-  union {
-    int64_t st_src_row[kResMaxSeqs];
-    int64_t rows_before[kResMaxSeqs];  // by sequence, until the ranks are assigned: real rows of
-                                       // all sequences before it
-  };
-  int32_t st_len[kResMaxSeqs];
-  int32_t st_m[kResMaxSeqs];
-  int32_t st_shard[kResMaxSeqs];
-  int32_t st_k[kResMaxSeqs];
-  int32_t st_mb[kResMaxSeqs];
-  int32_t mb_tmp[kResMaxSeqs + kResMaxRanks];   // per rank: start slot of each micro-batch, then n
+  int64_t st_src_row[kStage];
+  int32_t st_len[kStage];
+  int32_t st_m[kStage];
+  int32_t st_shard[kStage];
+  int32_t st_k[kStage];
+  int32_t st_mb[kStage];
+  int32_t mb_tmp[kCap + kResMaxRanks];   // per rank: start slot of each micro-batch, then n
   unsigned long long need[2 * kResMaxGroups];   // rows / sequences every source shard must hold
   union {
     struct {
@@ -1216,9 +1223,11 @@ __device__ __forceinline__ int rank_of_entry(const int32_t* base, int D, int x, 
   return lo;
 }
 
-template <int kIters>
+template <int kIters, int kCap, bool kStaged>
 __global__ __launch_bounds__(kPlanThreads) void plan_resident_kernel(const PlanDev p) {
-  __shared__ ResidentLds s;
+  typedef Key32<kCap == 4096 ? 12 : 11> K32;   // index bits for kCap sequences, the rest for the length
+  static_assert(kCap <= (1 << K32::kIndexBits), "index bits of the narrow keys");
+  __shared__ ResidentLds<kCap, kStaged> s;
   const int tid = threadIdx.x, nt = blockDim.x, nw = nt >> 6;
   const int lane = lane_id(), wave = wave_id();
   const int N = p.N, G = p.G, R = p.R, S = p.S, D = p.D, C = p.C, K = p.K, P = p.P;
@@ -1249,7 +1258,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_resident_kernel(const PlanD
       int64_t mm = (int64_t)P * (int64_t)((per + (uint32_t)P - 1u) / (uint32_t)P);
       const bool exceeds = mm * K > lp_cap;
       if (exceeds) mm = 1;
-      if (mm * K >= (1 << Key32::kLpBits)) s.wide = 1;
+      if (mm * K >= ((int64_t)1 << K32::kLpBits)) s.wide = 1;
       if (p.policy == 2 && mm * K > kMaxQuadraticLp) invalid = true;
       len[j] = L;
       m[j] = (int32_t)mm;
@@ -1288,13 +1297,14 @@ __global__ __launch_bounds__(kPlanThreads) void plan_resident_kernel(const PlanD
   }
 
   // ---- sort by (padded length desc, index asc), rank assignment ------------------------------
-  // With every padded length below 2^21 (and N <= 2048) key, index and row offsets fit 32 bits.
-  const bool narrow = s.wide == 0 && kResMaxSeqs <= (1 << Key32::kIndexBits);
+  // With every padded length below 2^21 (2^20 beyond 2048 sequences) key and index fit 32 bits,
+  // and so do the row offsets (fewer than 2^32 / largest padded length sequences).
+  const bool narrow = s.wide == 0;
   if (narrow) {
 #pragma unroll
     for (int j = 0; j < kIters; ++j)
-      if (i0 + j < N) s.keys32[i0 + j] = Key32::make((int64_t)m[j] * K, i0 + j);
-    for (int x = N + tid; x < p.n_pow2; x += nt) s.keys32[x] = Key32::kLast;
+      if (i0 + j < N) s.keys32[i0 + j] = K32::make((int64_t)m[j] * K, i0 + j);
+    for (int x = N + tid; x < p.n_pow2; x += nt) s.keys32[x] = K32::kLast;
     __syncthreads();
     bitonic_sort_lanes32(s.keys32, p.n_pow2);
   } else {
@@ -1308,12 +1318,12 @@ __global__ __launch_bounds__(kPlanThreads) void plan_resident_kernel(const PlanD
   if (p.policy == 1) {
     for (int x = tid; x < N; x += nt) {
       const int round = x / D, k = x - round * D;
-      const int i = narrow ? Key32::index(s.keys32[x]) : Key64::index(s.keys[x]);
+      const int i = narrow ? K32::index(s.keys32[x]) : Key64::index(s.keys[x]);
       s.rank[i] = (round & 1) ? D - 1 - k : k;
     }
   } else if (wave == 0) {
-    // D <= 64 and N <= 2048: the LDS load table is never used
-    if (narrow) lpt_wave0<Key32>(p, s.keys32, nullptr, s.rank);
+    // D <= 64 and N <= 4096: the LDS load table is never used
+    if (narrow) lpt_wave0<K32>(p, s.keys32, nullptr, s.rank);
     else lpt_wave0<Key64>(p, s.keys, nullptr, s.rank);
   }
 
@@ -1463,11 +1473,17 @@ __global__ __launch_bounds__(kPlanThreads) void plan_resident_kernel(const PlanD
       const int pos = s.seq_base[rk[j]] + slot[j];
       s.seq_ids[pos] = i;
       s.row_packed[pos] = dst_row[j];   // the sort keys are no longer needed
-      s.st_src_row[pos] = src_row[j];
-      s.st_len[pos] = len[j];
-      s.st_m[pos] = m[j];
-      s.st_shard[pos] = shard[j];
-      s.st_k[pos] = seq_k[j];
+      if (kStaged) {
+        s.st_src_row[pos] = src_row[j];
+        s.st_len[pos] = len[j];
+        s.st_m[pos] = m[j];
+        s.st_shard[pos] = shard[j];
+        s.st_k[pos] = seq_k[j];
+      } else {
+        // the segment table reads these back (with seq_shard, seq_row and mb below)
+        p.m[i] = m[j];
+        p.seq_k[i] = seq_k[j];
+      }
       // per-sequence outputs (the micro-batch follows from the packed order below)
       p.rank[i] = rk[j];
       p.slot[i] = slot[j];
@@ -1577,7 +1593,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_resident_kernel(const PlanD
         const int mid = (lo + hi) >> 1;
         if (starts[mid] <= sl) lo = mid; else hi = mid;
       }
-      s.st_mb[pos] = lo;
+      if (kStaged) s.st_mb[pos] = lo;
       p.mb[i] = lo;
       p.cu_seqlens[s.cu_base[r] + sl + lo] =
           (int32_t)(s.row_packed[pos] - s.row_packed[base + starts[lo]]);
@@ -1598,7 +1614,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_resident_kernel(const PlanD
     }
   }
   for (int x = tid; x < N; x += nt) p.seq_ids[x] = s.seq_ids[x];
-  __syncthreads();   // st_mb[] is complete
+  __syncthreads();   // st_mb[] is complete (not staged: so are this workgroup's stores of mb[])
 
   // ---- segment table and all-to-all counts (as phase 5 of plan_kernel) ----------------------
   // In table order: entry u = C*base_r + c*n_r + slot stands for the `halves` segments of one
@@ -1615,13 +1631,14 @@ __global__ __launch_bounds__(kPlanThreads) void plan_resident_kernel(const PlanD
     const int rem = u - C * base;
     const int c = rem / n;
     const int pos = base + (rem - c * n);
-    const int32_t mi = s.st_m[pos];
-    const int64_t L = s.st_len[pos];
-    const int64_t src0 = s.st_src_row[pos];
+    const int seq = kStaged ? 0 : s.seq_ids[pos];
+    const int32_t mi = kStaged ? s.st_m[pos] : p.m[seq];
+    const int64_t L = kStaged ? s.st_len[pos] : p.lengths[seq];
+    const int64_t src0 = kStaged ? s.st_src_row[pos] : p.seq_row[seq];
     const int64_t dst0 = s.row_packed[pos];
-    const int32_t sh = s.st_shard[pos];
-    const int32_t k_in_group = s.st_k[pos];
-    const int32_t mb_i = s.st_mb[pos];
+    const int32_t sh = kStaged ? s.st_shard[pos] : p.seq_shard[seq];
+    const int32_t k_in_group = kStaged ? s.st_k[pos] : p.seq_k[seq];
+    const int32_t mb_i = kStaged ? s.st_mb[pos] : p.mb[seq];
     const int64_t e0 = (int64_t)halves * u;
     int64_t real = 0;
     for (int h = 0; h < halves; ++h) {
@@ -1686,13 +1703,15 @@ bool launch_plan(const PlanDev& p, hipStream_t stream) {
   const char* force = std::getenv("EARL_PLAN_KERNEL");
   const bool general = force && std::strcmp(force, "general") == 0;
   if (!general && fits_resident(p)) {
-    const int k_iters = p.N <= kPlanThreads ? 1 : 2;
+    const int k_iters = p.N <= kPlanThreads ? 1 : (p.N <= 2 * kPlanThreads ? 2 : 4);
     const int per = (p.N + k_iters - 1) / k_iters;
     const unsigned nt = (unsigned)((per + kWave - 1) / kWave * kWave);
     if (k_iters == 1)
-      hipLaunchKernelGGL(plan_resident_kernel<1>, dim3(1), dim3(nt), 0, stream, p);
+      hipLaunchKernelGGL((plan_resident_kernel<1, kResStagedSeqs, true>), dim3(1), dim3(nt), 0, stream, p);
+    else if (k_iters == 2)
+      hipLaunchKernelGGL((plan_resident_kernel<2, kResStagedSeqs, true>), dim3(1), dim3(nt), 0, stream, p);
     else
-      hipLaunchKernelGGL(plan_resident_kernel<2>, dim3(1), dim3(nt), 0, stream, p);
+      hipLaunchKernelGGL((plan_resident_kernel<4, kResMaxSeqs, false>), dim3(1), dim3(nt), 0, stream, p);
     return true;
   }
   hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, stream, p);

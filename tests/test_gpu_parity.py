@@ -232,6 +232,17 @@ def _dispatch_and_inverse_equal_oracle(H, w):
     H.B.plan_destroy(plan)
 
 
+@pytest.mark.parametrize("n,dp,sp,zigzag,groups,rep", [(2500, 8, 2, 1, 8, 1), (4096, 16, 1, 0, 4, 2)])
+def test_both_directions_beyond_2048_sequences(H, n, dp, sp, zigzag, groups, rep):
+    """Dispatch and reverse dispatch behind the plan kernel that keeps up to 4096 sequences in LDS
+    (its segment table reads the per-sequence outputs back from the workspace)."""
+    w = synth.custom_workload([(i * 7919) % 211 + 1 for i in range(n)], n_groups=groups, replication=rep,
+                              dp=dp, sp=sp, zigzag=zigzag, pad_multiple=2, mb_token_budget=4096,
+                              fields=(synth.F_ID, synth.F_MASK, synth.bytes_field("w40", 8, 5, 0x0102030405060708)),
+                              seed=n)
+    _dispatch_and_inverse_equal_oracle(H, w)
+
+
 @pytest.mark.parametrize("n,dp,sp,zigzag,groups,rep", [(300, 3, 2, 1, 4, 1), (2500, 8, 2, 1, 8, 1),
                                                       (700, 5, 4, 0, 2, 3)])
 def test_both_directions_behind_the_general_plan_kernel(H, monkeypatch, n, dp, sp, zigzag, groups, rep):
@@ -381,6 +392,15 @@ def test_explicit_source_rows_with_gaps(H):
                                         B=1 << 30)),
     ("narrow_keys_at_their_limit_dp_9", dict(L=[(1 << 21) - 1 - i for i in range(70)] +
                                              [(i * 13) % 999 + 1 for i in range(500)], dp=9, sp=1)),
+    # beyond 2048 sequences the batch still stays in LDS, with 12 index bits in the narrow keys
+    ("sequences_4096_ranks_64", dict(L=[(i * 7919) % 3001 + 1 for i in range(4096)], G=16, dp=64, sp=1,
+                                     B=1 << 17, packed=True)),
+    ("sequences_2049", dict(L=[(i * 104729) % 777 + 1 for i in range(2049)], G=4, R=2, dp=5, sp=2, zigzag=1,
+                            pad=4, B=1 << 15, packed=True)),
+    ("sequences_3000_wide_keys", dict(L=[(i * 31) % 4000 + 1 for i in range(2999)] + [1 << 20], dp=12, sp=2,
+                                      B=1 << 30)),
+    ("sequences_3000_narrow_keys_at_their_limit", dict(L=[(i * 31) % 4000 + 1 for i in range(2998)] +
+                                                       [(1 << 20) - 1, (1 << 20) - 2], dp=12, sp=1, B=1 << 30)),
     ("budget_exactly_one_sequence", dict(L=[16] * 40, dp=2, sp=2, zigzag=1, B=16)),
     ("sp_64_zigzag_128_chunks", dict(L=[(i * 37) % 900 + 1 for i in range(120)], G=3, dp=3, sp=64,
                                      zigzag=1, pad=2, B=40000)),
@@ -393,7 +413,7 @@ def test_plan_edge_cases(H, desc, kw):
     w = synth.custom_workload(kw["L"], n_groups=kw.get("G", 1), replication=kw.get("R", 1),
                               dp=kw["dp"], sp=kw["sp"], zigzag=kw.get("zigzag", 0),
                               pad_multiple=kw.get("pad", 1), mb_token_budget=kw.get("B", 1 << 40))
-    if kw.get("G", 1) > 1:
+    if kw.get("G", 1) > 1 and not kw.get("packed"):
         rng = np.random.default_rng(len(kw["L"]))
         w.seq_group = rng.integers(0, kw["G"], size=len(kw["L"])).astype(np.int32)
     plan = H.build_plan(w)
