@@ -1145,9 +1145,9 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(const PlanDev p) {
 }
 
 // ---------------------------------------------------------------------------------------
-// The same plan for batches of up to 4096 sequences on up to 64 ranks (every workload the
-// paper's setting produces: Section 3.1 trains with a few hundred to a few thousand episodes
-// per step), with another data flow: nothing is read back from global memory (beyond 2048
+// The same plan for batches of up to 4096 sequences on up to 64 ranks (the paper gives no batch
+// sizes; a few hundred to a few thousand sequences per step is what the synthetic workloads
+// assume), with another data flow: nothing is read back from global memory (beyond 2048
 // sequences: nothing but the per-sequence outputs, once, for the segment table).
 //
 // The kernel above keeps every intermediate array in the workspace, so each of its ~40
