@@ -163,7 +163,9 @@ typedef struct {
                                       sizes of the all-to-all of Section 2                     */
 } earl_plan_summary;
 
-/* Bytes of device workspace earl_plan_build needs for n_seqs sequences and these layouts. */
+/* Bytes of device workspace earl_plan_build needs for n_seqs sequences and these layouts.
+ * (This call, earl_plan_get_summary, the two exports, earl_plan_destroy and the status texts are
+ * bookkeeping around the plan; no passage of the paper defines them.) */
 int32_t earl_plan_workspace_bytes(int32_t n_seqs, const earl_src_layout* src,
                                   const earl_dst_layout* dst, size_t* out_bytes);
 
@@ -324,8 +326,8 @@ int32_t earl_plan_set_dispatch_events(earl_plan* plan, void* event_before, void*
 
 /*
  * The reverse direction (training layout back to the rollout layout; Section 2 describes dispatches
- * between several stages of a step, so data also has to come back): every real row of every destination shard is copied back to the source
- * row it was read from.  Field descriptors as in earl_dispatch with the roles of the two pointer
+ * between several stages of a step, so data also has to come back): every real row of every
+ * destination shard is copied back to the source row it was read from.  Field descriptors as in earl_dispatch with the roles of the two pointer
  * arrays unchanged (dst_shard_ptrs is read, src_shard_ptrs is written; both only need alignment to
  * scalar_bytes).  Rows of the source buffers that the plan does not read are left untouched.
  * The scratch buffer holds the call's parameter block and one 16-byte record per tile of the
